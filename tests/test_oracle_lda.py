@@ -1,0 +1,275 @@
+"""Pins for the oracle's LDA sweep (Fig. 1; Sect. 4.2): brute-force enumeration of the
+z conditional, library histograms, the closed-form collapsed posterior, a joint-distribution
+(Geweke) test of the whole sweep, an independent evaluation of the log joint, recovery of
+generating parameters, determinism and the special cases."""
+import itertools
+
+import numpy as np
+from scipy import special, stats
+
+from oracle import oracle as O
+from paper_1312_3613_amd import synth
+
+
+def _small_model(seed=0, D=2, V=3, K=3, lens=(3, 2)):
+    rng = np.random.default_rng(seed)
+    theta = rng.dirichlet(np.ones(K), size=D).astype(np.float32)
+    phi = rng.dirichlet(np.ones(V), size=K).T.astype(np.float32).copy()       # [V][K]
+    w = rng.integers(0, V, size=sum(lens)).astype(np.int32)
+    return theta, phi, w, np.array(lens, dtype=np.int32)
+
+
+def test_z_conditional_equals_bruteforce_enumeration():
+    theta, phi, w, lens = _small_model()
+    K, N = theta.shape[1], w.size
+    doc = np.repeat(np.arange(len(lens)), lens)
+    th, ph = theta.astype(np.float64), phi.astype(np.float64)
+    # joint weight of every assignment: prod_i theta[d_i][z_i] phi[w_i][z_i]
+    joint = {}
+    for zz in itertools.product(range(K), repeat=N):
+        joint[zz] = np.prod([th[doc[i], zz[i]] * ph[w[i], zz[i]] for i in range(N)])
+    for i in range(N):
+        cdf, _ = O.lda_token_cdf(theta[doc[i]], phi[w[i]], seed=1, token=i, sweep=1)
+        p = np.diff(np.concatenate([[0.0], cdf])) / cdf[-1]
+        # conditional given every other configuration of z is the same and equals p
+        for rest in itertools.product(range(K), repeat=N - 1):
+            ws = np.array([joint[rest[:i] + (k,) + rest[i:]] for k in range(K)])
+            assert np.allclose(ws / ws.sum(), p, rtol=1e-12, atol=0)
+
+
+def test_z_draws_follow_conditional_and_are_independent():
+    theta, phi, w, lens = _small_model(seed=1)
+    K, N = theta.shape[1], w.size
+    off = O.doc_offsets(lens)
+    doc = np.repeat(np.arange(len(lens)), lens)
+    T = 40_000
+    zs = np.stack([O.lda_sample_z(off, w, theta, phi, seed=77, sweep=s)[0] for s in range(1, T + 1)])
+    ps = []
+    for i in range(N):
+        p = theta[doc[i]].astype(np.float64) * phi[w[i]].astype(np.float64)
+        p /= p.sum()
+        ps.append(p)
+        assert stats.chisquare(np.bincount(zs[:, i], minlength=K), p * T).pvalue > 1e-4
+    # tokens 0 and 1 (same block of the stream) are independent given theta, phi
+    joint = np.bincount(zs[:, 0] * K + zs[:, 1], minlength=K * K)
+    assert stats.chisquare(joint, np.outer(ps[0], ps[1]).ravel() * T).pvalue > 1e-4
+
+
+def test_inverse_cdf_rule_and_zero_mass_topics():
+    # z = smallest k with C_k > u S; topics of zero mass are never drawn
+    D, V, K = 3, 4, 5
+    rng = np.random.default_rng(3)
+    theta = rng.dirichlet(np.ones(K), size=D).astype(np.float32)
+    theta[:, 2] = 0.0
+    theta[1, 0] = 0.0
+    phi = rng.dirichlet(np.ones(V), size=K).T.astype(np.float32).copy()
+    lens = np.array([400, 300, 300], dtype=np.int32)
+    w = rng.integers(0, V, size=lens.sum()).astype(np.int32)
+    off = O.doc_offsets(lens)
+    z, deg = O.lda_sample_z(off, w, theta, phi, seed=5, sweep=3)
+    assert deg == 0 and (z != 2).all() and (z[400:700] != 0).all()
+    doc = np.repeat(np.arange(D), lens)
+    u = O.datum_uniforms(5, 0, w.size, 3, O.STREAM_Z)
+    for i in range(0, w.size, 7):
+        cdf, t = O.lda_token_cdf(theta[doc[i]], phi[w[i]], seed=5, token=i, sweep=3)
+        assert t == u[i] * cdf[-1]
+        assert z[i] == int((cdf <= t).sum())
+        want = np.cumsum(theta[doc[i]].astype(np.float64) * phi[w[i]].astype(np.float64))
+        assert np.allclose(cdf, want, rtol=1e-15)
+
+
+def test_degenerate_conditional_falls_back_to_uniform_index():
+    theta = np.zeros((1, 4), dtype=np.float32)
+    phi = np.full((2, 4), 0.25, dtype=np.float32)
+    w = np.array([0, 1, 1, 0, 1], dtype=np.int32)
+    z, deg = O.lda_sample_z(O.doc_offsets([5]), w, theta, phi, seed=2, sweep=1)
+    u = O.datum_uniforms(2, 0, 5, 1, O.STREAM_Z)
+    assert deg == 5 and (z == np.floor(u * 4).astype(int)).all()
+
+
+def test_counts_match_library_histograms_and_invariants():
+    cfg = dict(synth.LDA_CONFIGS["tiny"])
+    c = synth.lda_corpus(**cfg)
+    D, V, K = cfg["D"], cfg["V"], cfg["K"]
+    off = O.doc_offsets(c["doc_len"])
+    z = O.lda_init_z(c["N"], K, seed=1)
+    n_dk, n_wk = O.lda_count(off, c["w"], z, D, V, K)
+    doc = np.repeat(np.arange(D), c["doc_len"])
+    assert (n_dk == np.bincount(doc * K + z, minlength=D * K).reshape(D, K)).all()
+    assert (n_wk == np.bincount(c["w"].astype(np.int64) * K + z, minlength=V * K).reshape(V, K)).all()
+    assert (n_dk.sum(axis=1) == c["doc_len"]).all()
+    assert (n_wk.sum(axis=1) == np.bincount(c["w"], minlength=V)).all()
+    assert (n_dk.sum(axis=0) == n_wk.sum(axis=0)).all() and n_dk.sum() == c["N"]
+
+
+def test_init_z_is_scaled_random_word():
+    N, K, seed = 1000, 7, 99
+    z = O.lda_init_z(N, K, seed)
+    for i in range(0, N, 13):
+        r = int(O.random_block(seed, i >> 2, 0, O.STREAM_INIT_Z, 0)[i & 3])
+        assert z[i] == (r * K) >> 32
+    assert stats.chisquare(np.bincount(O.lda_init_z(70_000, K, seed), minlength=K)).pvalue > 1e-4
+
+
+def _batch_check(samples, exact, nbatch=40, z_tol=5.0):
+    """samples: [T][m] indicator/values; exact: [m].  Batch-means standard errors."""
+    T = samples.shape[0] // nbatch * nbatch
+    b = samples[:T].reshape(nbatch, -1, samples.shape[1]).mean(axis=1)
+    mean, se = b.mean(axis=0), b.std(axis=0, ddof=1) / np.sqrt(nbatch)
+    assert (np.abs(mean - exact) < z_tol * se + 1e-4).all(), (mean, exact, se)
+
+
+def test_sweep_targets_closed_form_collapsed_posterior():
+    # p(z | w) proportional to prod_d [prod_k G(alpha+n_dk)] / G(K alpha + N_d)
+    #                         * prod_k [prod_v G(beta+n_vk)] / G(V beta + n_k)
+    # (Dirichlet-multinomial integrals of the joint of Fig. 1)
+    D, V, K, alpha, beta = 2, 2, 2, 0.5, 0.7
+    lens = np.array([2, 2], dtype=np.int32)
+    w = np.array([0, 1, 1, 1], dtype=np.int32)
+    doc = np.repeat(np.arange(D), lens)
+    configs = list(itertools.product(range(K), repeat=4))
+    logp = []
+    for zz in configs:
+        zz = np.array(zz)
+        n_dk = np.bincount(doc * K + zz, minlength=D * K).reshape(D, K)
+        n_vk = np.bincount(w * K + zz, minlength=V * K).reshape(V, K)
+        lp = special.gammaln(alpha + n_dk).sum() - special.gammaln(K * alpha + n_dk.sum(1)).sum()
+        lp += special.gammaln(beta + n_vk).sum() - special.gammaln(V * beta + n_vk.sum(0)).sum()
+        logp.append(lp)
+    exact = np.exp(np.array(logp) - special.logsumexp(logp))
+    m = O.OracleLDA(D, V, K, alpha, beta, seed=123, doc_len=lens, w=w)
+    T = 120_000
+    ids = np.empty(T, dtype=np.int64)
+    for t in range(T):
+        m.sweep(1)
+        ids[t] = int(m.z[0]) * 8 + int(m.z[1]) * 4 + int(m.z[2]) * 2 + int(m.z[3])
+    onehot = np.zeros((T, 16))
+    onehot[np.arange(T), ids] = 1.0
+    _batch_check(onehot, exact)
+
+
+def test_geweke_joint_distribution_of_full_sweep():
+    # Alternating w | z, phi (the model's own generative step) with one Gibbs sweep leaves the
+    # prior over (theta, phi) invariant: any error in a conditional or in the order z, theta,
+    # phi shifts these moments.
+    D, V, K, alpha, beta = 2, 3, 2, 0.8, 1.3
+    lens = np.array([3, 2], dtype=np.int32)
+    off = O.doc_offsets(lens)
+    N = int(lens.sum())
+    rng = np.random.default_rng(5)
+    theta = rng.dirichlet(np.full(K, alpha), size=D).astype(np.float32)
+    phi = rng.dirichlet(np.full(V, beta), size=K).T.astype(np.float32).copy()
+    doc = np.repeat(np.arange(D), lens)
+    th64 = theta.astype(np.float64)
+    th64 /= th64.sum(axis=1, keepdims=True)
+    z = np.array([rng.choice(K, p=th64[d]) for d in doc], dtype=np.int32)
+    T = 60_000
+    g = np.empty((T, 6))
+    for t in range(1, T + 1):
+        cols = phi[:, z].astype(np.float64)                   # [V][N]
+        cols /= cols.sum(axis=0, keepdims=True)
+        w = (rng.random(N)[None, :] > np.cumsum(cols, axis=0)).sum(axis=0).clip(0, V - 1).astype(np.int32)
+        z, _ = O.lda_sample_z(off, w, theta, phi, seed=31, sweep=t)
+        n_dk, n_wk = O.lda_count(off, w, z, D, V, K)
+        theta = O.lda_resample_theta(n_dk, alpha, seed=31, sweep=t)
+        phi = O.lda_resample_phi(n_wk, beta, seed=31, sweep=t)
+        g[t - 1] = [theta[0, 0], theta[0, 0] ** 2, phi[0, 0], phi[0, 0] ** 2, phi[1, 1] * phi[2, 1],
+                    theta[1, 1]]
+    a0, b0 = K * alpha, V * beta
+    e_th2 = alpha * (alpha + 1) / (a0 * (a0 + 1))
+    e_ph2 = beta * (beta + 1) / (b0 * (b0 + 1))
+    e_cross = beta * beta / (b0 * (b0 + 1))
+    _batch_check(g, np.array([1 / K, e_th2, 1 / V, e_ph2, e_cross, 1 / K]))
+
+
+def test_log_joint_against_term_by_term_evaluation():
+    cfg = dict(synth.LDA_CONFIGS["tiny"], D=12, V=30, K=4, mean_len=9)
+    c = synth.lda_corpus(**cfg)
+    D, V, K, alpha, beta = cfg["D"], cfg["V"], cfg["K"], cfg["alpha"], cfg["beta"]
+    m = O.OracleLDA(D, V, K, alpha, beta, seed=4, doc_len=c["doc_len"], w=c["w"])
+    m.sweep(3)
+    lj, lm = m.loglik()
+    a, b = m.alpha, m.beta
+    th, ph = m.theta.astype(np.float64), m.phi.astype(np.float64)
+    # the generative program, statement by statement
+    want = 0.0
+    for k in range(K):      # phi = Dirichlet(V, beta).sample(K)
+        want += special.gammaln(V * b) - V * special.gammaln(b) + ((b - 1) * np.log(ph[:, k])).sum()
+    for d in range(D):      # theta = Dirichlet(K, alpha).sample(M)
+        want += special.gammaln(K * a) - K * special.gammaln(a) + ((a - 1) * np.log(th[d])).sum()
+    i = 0
+    marg = 0.0
+    for d in range(D):
+        for _ in range(c["doc_len"][d]):
+            want += np.log(th[d, m.z[i]])             # z ~ Categorical(theta(i))
+            want += np.log(ph[m.w[i], m.z[i]])        # w ~ Categorical(phi(z))
+            marg += np.log(th[d] @ ph[m.w[i]])
+            i += 1
+    assert abs(lj - want) < 1e-9 * abs(want)
+    assert abs(lm - marg) < 1e-9 * abs(marg)
+
+
+def test_recovers_generating_parameters_on_tiny_config():
+    cfg = dict(synth.LDA_CONFIGS["tiny"])
+    c = synth.lda_corpus(return_truth=True, **cfg)
+    D, V, K = cfg["D"], cfg["V"], cfg["K"]
+    off = O.doc_offsets(c["doc_len"])
+    floor = np.float32(np.finfo(np.float32).tiny)
+    th_true, ph_true = np.maximum(c["theta"], floor), np.maximum(c["phi"], floor)
+    _, lm_true = O.lda_loglik(off, c["w"], c["z"], th_true, ph_true, cfg["alpha"], cfg["beta"])
+    m = O.OracleLDA(D, V, K, cfg["alpha"], cfg["beta"], seed=2024, doc_len=c["doc_len"], w=c["w"])
+    _, lm0 = m.loglik()
+    m.sweep(200)
+    _, lm = m.loglik()
+    per_tok0, per_tok, per_tok_true = lm0 / c["N"], lm / c["N"], lm_true / c["N"]
+    # the chain climbs from the random start to the neighbourhood of the generating parameters
+    assert per_tok > per_tok0 + 0.5
+    assert per_tok > per_tok_true - 0.25, (per_tok, per_tok_true)
+    # topics match the generating ones: greedy matching by total-variation distance
+    ph = m.phi.astype(np.float64)
+    used, tv = set(), []
+    for k in range(K):
+        d = [0.5 * np.abs(ph[:, j] - c["phi"][:, k]).sum() if j not in used else 9.0 for j in range(K)]
+        j = int(np.argmin(d))
+        used.add(j)
+        tv.append(d[j])
+    assert np.median(tv) < 0.35, tv
+    assert m.degenerate == 0
+
+
+def test_determinism_and_resume():
+    cfg = dict(synth.LDA_CONFIGS["tiny"], D=20, V=50, K=5)
+    c = synth.lda_corpus(**cfg)
+    args = (cfg["D"], cfg["V"], cfg["K"], cfg["alpha"], cfg["beta"], 7, c["doc_len"], c["w"])
+    a, b = O.OracleLDA(*args), O.OracleLDA(*args)
+    a.sweep(6)
+    b.sweep(3)
+    z, th, ph, t = b.get_state()
+    r = O.OracleLDA(*args)
+    r.set_state(z, th, ph, t)
+    r.sweep(3)
+    for x, y in zip(a.get_state(), r.get_state()):
+        assert np.array_equal(x, y)
+    # step-level calls are the sweep
+    s = O.OracleLDA(*args)
+    for _ in range(6):
+        s.step_sample_z(); s.step_count(); s.step_resample_theta(); s.step_resample_phi(); s.step_finish()
+    for x, y in zip(a.get_state(), s.get_state()):
+        assert np.array_equal(x, y)
+    assert all(np.array_equal(x, y) for x, y in zip(a.get_counts(), s.get_counts()))
+    # another seed gives another chain
+    d = O.OracleLDA(*(args[:5] + (8,) + args[6:]))
+    d.sweep(6)
+    assert not np.array_equal(d.z, a.z)
+
+
+def test_flat_phi_reduces_z_to_draws_from_theta():
+    # with phi constant over topics the conditional of z is theta_d itself
+    D, V, K = 1, 3, 4
+    theta = np.array([[0.1, 0.2, 0.3, 0.4]], dtype=np.float32)
+    phi = np.full((V, K), 1 / 3, dtype=np.float32)
+    n = 40_000
+    w = np.zeros(n, dtype=np.int32)
+    z, _ = O.lda_sample_z(O.doc_offsets([n]), w, theta, phi, seed=12, sweep=1)
+    p = theta[0].astype(np.float64)
+    assert stats.chisquare(np.bincount(z, minlength=K), p / p.sum() * n).pvalue > 1e-4
