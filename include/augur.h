@@ -1,0 +1,148 @@
+/*
+ * augur.h - C ABI of the MI355X (gfx950) uncollapsed Gibbs sweep for the two
+ * latent-variable models of Augur (arXiv 1312.3613): latent Dirichlet allocation
+ * (Fig. 1) and a Gaussian mixture (supplementary material, known-covariance
+ * variant).  One process, one GPU.  Every step of the sweep runs in HIP kernels;
+ * there is no CPU fallback.
+ *
+ * Conventions (all entry points)
+ *   - Return value: AUGUR_OK (0) or a negative AUGUR_ERR_* code.  Nothing throws
+ *     or aborts.  augur_last_error() gives the message of the last failing call
+ *     on the calling thread.
+ *   - Data pointers are HOST pointers unless the handle was created with
+ *     AUGUR_PTRS_DEVICE in config.flags, in which case every data pointer passed
+ *     to create/get_x/set_x of that handle is a DEVICE pointer on config.device.
+ *     Scalar outputs (double*, int64_t*) are always host pointers.
+ *   - create copies its inputs; the caller keeps ownership of every buffer it
+ *     passes and may free it on return.  get_x copies into caller-allocated
+ *     buffers; a NULL data pointer means "skip this array".
+ *   - Work is enqueued on config.stream (a hipStream_t; NULL = the default
+ *     stream).  sweep and step_x do not synchronise; loglik, get_x, set_x and
+ *     sync do.  A handle must not be used from two threads at once; distinct
+ *     handles are independent.
+ *   - Random numbers: Philox4x32-10 with key = seed and counter =
+ *     (variable index lo, hi, sweep index, stream<<24 | attempt), so a state and
+ *     a sweep index determine every draw.  Sweep index 0 initialises; sweep()
+ *     advances the index by one per sweep, starting at 1.
+ */
+#ifndef AUGUR_H
+#define AUGUR_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define AUGUR_OK 0
+#define AUGUR_ERR_INVALID_ARG (-1)   /* NULL, non-positive size, out-of-range word, ... */
+#define AUGUR_ERR_HIP (-2)           /* HIP runtime failure; message has hipGetErrorString */
+#define AUGUR_ERR_DEGENERATE (-3)    /* non-fatal: some conditional had zero/non-finite mass */
+#define AUGUR_ERR_UNIMPLEMENTED (-4)
+
+#define AUGUR_PTRS_DEVICE 1u
+
+const char* augur_last_error(void); /* thread-local; valid until the next call on this thread */
+const char* augur_version(void);
+
+/* ------------------------------------------------------------------ LDA (Fig. 1)
+ * phi_k ~ Dirichlet(beta 1_V), theta_d ~ Dirichlet(alpha 1_K),
+ * z_i ~ Categorical(theta_d), w_i ~ Categorical(phi_{z_i}); w observed.
+ * Layout: w, z flat doc-major int32[N]; theta float[D][K]; phi float[V][K]
+ * (row = word, i.e. the transpose of the paper's K x V array); counts
+ * n_dk int32[D][K] (the paper's c_m), n_wk int32[V][K] (the paper's c_k). */
+typedef struct augur_lda augur_lda;
+
+typedef struct {
+  int32_t D, V, K;      /* documents (paper: M), vocabulary size, topics */
+  float alpha, beta;    /* symmetric Dirichlet hyper-parameters, > 0, finite */
+  uint64_t seed;
+  int32_t device;       /* HIP device ordinal */
+  void* stream;         /* hipStream_t or NULL */
+  uint32_t flags;       /* AUGUR_PTRS_DEVICE or 0 */
+} augur_lda_config;
+
+/* Builds the sampler state for a corpus.  doc_len[D] >= 0 (empty documents
+ * allowed), w[N] with N = sum(doc_len) <= 2^31-1 and 0 <= w[i] < V.  The
+ * initial state is z_i = floor(K r_i / 2^32) from the init stream, the counts of
+ * that z, then theta and phi drawn from their conditionals with sweep index 0.
+ * Errors: INVALID_ARG for bad sizes/values (nothing is allocated), HIP. */
+int augur_lda_create(const augur_lda_config* cfg, const int32_t* doc_len, const int32_t* w,
+                     augur_lda** out);
+void augur_lda_destroy(augur_lda* h); /* NULL is a no-op */
+
+/* n_sweeps Gibbs sweeps (Sect. 4.2), each in the order: draw every z_i from
+ * p(k) ~ theta_d[k] phi[w_i][k]; count n_dk, n_wk; theta_d ~ Dirichlet(alpha +
+ * n_dk[d]); phi_k ~ Dirichlet(beta + n_wk[.][k]).  Asynchronous. */
+int augur_lda_sweep(augur_lda* h, int32_t n_sweeps);
+
+/* Same as sweep, but brackets each step with events on the handle's stream and
+ * returns the summed device time of each step over the n_sweeps, in ms:
+ * ms[0] sample_z, ms[1] count_accumulate, ms[2] resample theta, ms[3] resample
+ * phi, ms[4] whole loop.  Synchronises. */
+#define AUGUR_LDA_NSTEPS 5
+int augur_lda_sweep_profile(augur_lda* h, int32_t n_sweeps, double* ms);
+
+/* Steps of one sweep, for lock-step checking.  Each uses sweep index
+ * (completed sweeps + 1); step_finish adds one to the completed count. */
+int augur_lda_step_sample_z(augur_lda* h);
+int augur_lda_step_count(augur_lda* h);
+int augur_lda_step_resample_theta(augur_lda* h);
+int augur_lda_step_resample_phi(augur_lda* h);
+int augur_lda_step_finish(augur_lda* h);
+
+/* log_joint = ln p(phi, theta, z, w) of Fig. 1's program; log_marginal_w =
+ * sum_i ln sum_k theta_d[k] phi[w_i][k].  Log-space sums (Sect. 4.1), fp64.
+ * Either output may be NULL.  Returns AUGUR_ERR_DEGENERATE once (with the
+ * outputs still written) if a sweep since the last report met a token whose
+ * conditional had zero or non-finite mass. */
+int augur_lda_loglik(augur_lda* h, double* log_joint, double* log_marginal_w);
+
+int augur_lda_get_state(augur_lda* h, int32_t* z, float* theta, float* phi, int64_t* sweep);
+/* Any of z/theta/phi may be NULL (left as is); sweep < 0 leaves the index.
+ * Setting z recomputes the counts.  z[i] must lie in [0,K). */
+int augur_lda_set_state(augur_lda* h, const int32_t* z, const float* theta, const float* phi,
+                        int64_t sweep);
+int augur_lda_get_counts(augur_lda* h, int32_t* n_dk, int32_t* n_wk);
+/* Number of tokens, over all sweeps so far, whose conditional was degenerate. */
+int augur_lda_get_degenerate(augur_lda* h, int64_t* count);
+int augur_lda_sync(augur_lda* h);
+
+/* ------------------------------------------------ Gaussian mixture (supplement)
+ * pi ~ Dirichlet(alpha 1_K), mu_k ~ N(0, prior_sd^2 I), z_i ~ Categorical(pi),
+ * x_i ~ N(mu_{z_i}, sigma^2 I); x observed.  Layout: x float[N][dim],
+ * z int32[N], pi float[K], mu float[K][dim], n_k int32[K], s_k double[K][dim]. */
+typedef struct augur_gmm augur_gmm;
+
+typedef struct {
+  int64_t N;
+  int32_t dim, K;
+  float alpha, prior_sd, sigma; /* all > 0, finite */
+  uint64_t seed;
+  int32_t device;
+  void* stream;
+  uint32_t flags;
+} augur_gmm_config;
+
+int augur_gmm_create(const augur_gmm_config* cfg, const float* x, augur_gmm** out);
+void augur_gmm_destroy(augur_gmm* h);
+/* One sweep: z_i from p(k) ~ pi_k exp(-|x_i - mu_k|^2 / (2 sigma^2)); n_k and
+ * s_k = sum of x_i with z_i = k; pi ~ Dirichlet(alpha + n); mu_kj ~ Normal with
+ * precision 1/prior_sd^2 + n_k/sigma^2 and mean (s_kj/sigma^2)/precision. */
+int augur_gmm_sweep(augur_gmm* h, int32_t n_sweeps);
+int augur_gmm_step_sample_z(augur_gmm* h);
+int augur_gmm_step_stats(augur_gmm* h);
+int augur_gmm_step_resample(augur_gmm* h);
+int augur_gmm_step_finish(augur_gmm* h);
+int augur_gmm_loglik(augur_gmm* h, double* log_joint);
+int augur_gmm_get_state(augur_gmm* h, int32_t* z, float* pi, float* mu, int64_t* sweep);
+int augur_gmm_set_state(augur_gmm* h, const int32_t* z, const float* pi, const float* mu,
+                        int64_t sweep);
+int augur_gmm_get_stats(augur_gmm* h, int32_t* n_k, double* s_k);
+int augur_gmm_get_degenerate(augur_gmm* h, int64_t* count);
+int augur_gmm_sync(augur_gmm* h);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AUGUR_H */

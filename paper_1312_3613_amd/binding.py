@@ -1,0 +1,311 @@
+"""Python face of the C ABI in include/augur.h: argument marshalling only.
+
+Every computation happens in the HIP library (libaugur_hip.so).  Arrays cross the boundary
+either as numpy arrays (host pointers) or, for handles created with device_ptrs=True, as torch
+CUDA tensors (device pointers); torch is used for nothing but device memory and streams.
+There is no fallback: if the library is absent and cannot be built, loading raises.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+
+from . import build as _build
+
+OK, ERR_INVALID_ARG, ERR_HIP, ERR_DEGENERATE, ERR_UNIMPLEMENTED = 0, -1, -2, -3, -4
+PTRS_DEVICE = 1
+LDA_NSTEPS = 5
+
+_LIB = None
+
+
+class AugurError(RuntimeError):
+    def __init__(self, code, message):
+        super().__init__(f"augur error {code}: {message}")
+        self.code = code
+
+
+class LdaConfig(C.Structure):
+    _fields_ = [("D", C.c_int32), ("V", C.c_int32), ("K", C.c_int32), ("alpha", C.c_float),
+                ("beta", C.c_float), ("seed", C.c_uint64), ("device", C.c_int32),
+                ("stream", C.c_void_p), ("flags", C.c_uint32)]
+
+
+class GmmConfig(C.Structure):
+    _fields_ = [("N", C.c_int64), ("dim", C.c_int32), ("K", C.c_int32), ("alpha", C.c_float),
+                ("prior_sd", C.c_float), ("sigma", C.c_float), ("seed", C.c_uint64),
+                ("device", C.c_int32), ("stream", C.c_void_p), ("flags", C.c_uint32)]
+
+
+def lib():
+    """Load libaugur_hip.so (building it first only if it does not exist)."""
+    global _LIB
+    if _LIB is None:
+        if not os.path.exists(_build.LIB):
+            _build.build()
+        if not os.path.exists(_build.LIB):
+            raise RuntimeError("HIP library libaugur_hip.so is missing and could not be built")
+        # One HIP runtime per process: torch ships its own libamdhip64 (same soname as the
+        # system one).  Loading torch first makes the dynamic linker bind this library to the
+        # runtime torch uses, so device pointers and streams are shared; two runtimes in one
+        # process do not see each other's devices.
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
+        L = C.CDLL(_build.LIB)
+        L.augur_last_error.restype = C.c_char_p
+        L.augur_version.restype = C.c_char_p
+        vp = C.c_void_p
+        L.augur_lda_create.argtypes = [C.POINTER(LdaConfig), vp, vp, C.POINTER(vp)]
+        L.augur_lda_destroy.argtypes = [vp]
+        L.augur_lda_destroy.restype = None
+        L.augur_lda_sweep.argtypes = [vp, C.c_int32]
+        L.augur_lda_sweep_profile.argtypes = [vp, C.c_int32, C.POINTER(C.c_double)]
+        for name in ("step_sample_z", "step_count", "step_resample_theta", "step_resample_phi",
+                     "step_finish", "sync"):
+            getattr(L, "augur_lda_" + name).argtypes = [vp]
+        L.augur_lda_loglik.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_double)]
+        L.augur_lda_get_state.argtypes = [vp, vp, vp, vp, C.POINTER(C.c_int64)]
+        L.augur_lda_set_state.argtypes = [vp, vp, vp, vp, C.c_int64]
+        L.augur_lda_get_counts.argtypes = [vp, vp, vp]
+        L.augur_lda_get_degenerate.argtypes = [vp, C.POINTER(C.c_int64)]
+        L.augur_gmm_create.argtypes = [C.POINTER(GmmConfig), vp, C.POINTER(vp)]
+        L.augur_gmm_destroy.argtypes = [vp]
+        L.augur_gmm_destroy.restype = None
+        L.augur_gmm_sweep.argtypes = [vp, C.c_int32]
+        for name in ("step_sample_z", "step_stats", "step_resample", "step_finish", "sync"):
+            getattr(L, "augur_gmm_" + name).argtypes = [vp]
+        L.augur_gmm_loglik.argtypes = [vp, C.POINTER(C.c_double)]
+        L.augur_gmm_get_state.argtypes = [vp, vp, vp, vp, C.POINTER(C.c_int64)]
+        L.augur_gmm_set_state.argtypes = [vp, vp, vp, vp, C.c_int64]
+        L.augur_gmm_get_stats.argtypes = [vp, vp, vp]
+        L.augur_gmm_get_degenerate.argtypes = [vp, C.POINTER(C.c_int64)]
+        _LIB = L
+    return _LIB
+
+
+def last_error():
+    return lib().augur_last_error().decode()
+
+
+def _check(rc, allow=()):
+    if rc != OK and rc not in allow:
+        raise AugurError(rc, last_error())
+    return rc
+
+
+def _ptr(a):
+    """Raw address of a numpy array or torch tensor (None -> NULL)."""
+    if a is None:
+        return None
+    if isinstance(a, np.ndarray):
+        return a.ctypes.data
+    return a.data_ptr()
+
+
+def _stream_handle(stream):
+    if stream is None:
+        return None
+    return getattr(stream, "cuda_stream", stream)
+
+
+class _Arrays:
+    """Allocates output buffers and normalises inputs on the side of the boundary the handle
+    was created for: numpy (host) or torch CUDA tensors (device)."""
+
+    def __init__(self, device_ptrs, device):
+        self.device_ptrs = device_ptrs
+        self.device = device
+        if device_ptrs:
+            import torch
+            self.torch = torch
+            self.tdev = torch.device("cuda", device)
+
+    _np = {"i32": np.int32, "f32": np.float32, "f64": np.float64}
+
+    def empty(self, shape, kind):
+        if self.device_ptrs:
+            dt = {"i32": self.torch.int32, "f32": self.torch.float32, "f64": self.torch.float64}[kind]
+            return self.torch.empty(shape, dtype=dt, device=self.tdev)
+        return np.empty(shape, dtype=self._np[kind])
+
+    def input(self, a, kind, size=None):
+        if a is None:
+            return None
+        if self.device_ptrs:
+            dt = {"i32": self.torch.int32, "f32": self.torch.float32, "f64": self.torch.float64}[kind]
+            t = a if self.torch.is_tensor(a) else self.torch.as_tensor(np.asarray(a))
+            t = t.to(device=self.tdev, dtype=dt).contiguous()
+        else:
+            t = np.ascontiguousarray(a, dtype=self._np[kind])
+        n = t.numel() if self.device_ptrs else t.size
+        if size is not None and n != size:
+            raise ValueError(f"array has {n} elements, expected {size}")
+        return t
+
+
+class LDA:
+    """augur_lda_* handle.  Method names are the ABI's."""
+
+    def __init__(self, D, V, K, alpha, beta, seed, doc_len, w, device=0, stream=None,
+                 device_ptrs=False):
+        self._h = None
+        self.D, self.V, self.K = int(D), int(V), int(K)
+        self._arr = _Arrays(device_ptrs, device)
+        doc_len_a = self._arr.input(doc_len, "i32")
+        w_a = self._arr.input(w, "i32")
+        n_docs = doc_len_a.numel() if device_ptrs else doc_len_a.size
+        if n_docs != self.D:
+            raise ValueError(f"doc_len has {n_docs} entries, expected D = {self.D}")
+        n_tok = w_a.numel() if device_ptrs else w_a.size
+        self.N = int(doc_len_a.sum())
+        if n_tok != self.N:
+            raise ValueError(f"w has {n_tok} entries, sum(doc_len) = {self.N}")
+        cfg = LdaConfig(self.D, self.V, self.K, float(alpha), float(beta), int(seed), int(device),
+                        _stream_handle(stream), PTRS_DEVICE if device_ptrs else 0)
+        h = C.c_void_p()
+        _check(lib().augur_lda_create(C.byref(cfg), _ptr(doc_len_a), _ptr(w_a), C.byref(h)))
+        self._h = h
+
+    def close(self):
+        if self._h is not None:
+            lib().augur_lda_destroy(self._h)
+            self._h = None
+
+    __del__ = close
+
+    def sweep(self, n=1):
+        _check(lib().augur_lda_sweep(self._h, int(n)))
+
+    def sweep_profile(self, n=1):
+        ms = (C.c_double * LDA_NSTEPS)()
+        _check(lib().augur_lda_sweep_profile(self._h, int(n), ms))
+        return dict(zip(("sample_z", "count_accumulate", "resample_theta", "resample_phi", "sweep"),
+                        list(ms)))
+
+    def step_sample_z(self):
+        _check(lib().augur_lda_step_sample_z(self._h))
+
+    def step_count(self):
+        _check(lib().augur_lda_step_count(self._h))
+
+    def step_resample_theta(self):
+        _check(lib().augur_lda_step_resample_theta(self._h))
+
+    def step_resample_phi(self):
+        _check(lib().augur_lda_step_resample_phi(self._h))
+
+    def step_finish(self):
+        _check(lib().augur_lda_step_finish(self._h))
+
+    def sync(self):
+        _check(lib().augur_lda_sync(self._h))
+
+    def loglik(self, raise_on_degenerate=False):
+        lj, lm = C.c_double(), C.c_double()
+        _check(lib().augur_lda_loglik(self._h, C.byref(lj), C.byref(lm)),
+               allow=() if raise_on_degenerate else (ERR_DEGENERATE,))
+        return lj.value, lm.value
+
+    def get_state(self, z=True, theta=True, phi=True):
+        za = self._arr.empty((self.N,), "i32") if z else None
+        ta = self._arr.empty((self.D, self.K), "f32") if theta else None
+        pa = self._arr.empty((self.V, self.K), "f32") if phi else None
+        sw = C.c_int64()
+        _check(lib().augur_lda_get_state(self._h, _ptr(za), _ptr(ta), _ptr(pa), C.byref(sw)))
+        return za, ta, pa, sw.value
+
+    def set_state(self, z=None, theta=None, phi=None, sweep=None):
+        za = self._arr.input(z, "i32", self.N)
+        ta = self._arr.input(theta, "f32", self.D * self.K)
+        pa = self._arr.input(phi, "f32", self.V * self.K)
+        _check(lib().augur_lda_set_state(self._h, _ptr(za), _ptr(ta), _ptr(pa),
+                                         -1 if sweep is None else int(sweep)))
+
+    def get_counts(self):
+        n_dk = self._arr.empty((self.D, self.K), "i32")
+        n_wk = self._arr.empty((self.V, self.K), "i32")
+        _check(lib().augur_lda_get_counts(self._h, _ptr(n_dk), _ptr(n_wk)))
+        return n_dk, n_wk
+
+    def get_degenerate(self):
+        c = C.c_int64()
+        _check(lib().augur_lda_get_degenerate(self._h, C.byref(c)))
+        return c.value
+
+
+class GMM:
+    """augur_gmm_* handle."""
+
+    def __init__(self, K, alpha, prior_sd, sigma, seed, x, device=0, stream=None,
+                 device_ptrs=False):
+        self._h = None
+        self._arr = _Arrays(device_ptrs, device)
+        xa = self._arr.input(x, "f32")
+        if xa.ndim != 2:
+            raise ValueError("x must be [N][dim]")
+        self.N, self.dim, self.K = int(xa.shape[0]), int(xa.shape[1]), int(K)
+        cfg = GmmConfig(self.N, self.dim, self.K, float(alpha), float(prior_sd), float(sigma),
+                        int(seed), int(device), _stream_handle(stream),
+                        PTRS_DEVICE if device_ptrs else 0)
+        h = C.c_void_p()
+        _check(lib().augur_gmm_create(C.byref(cfg), _ptr(xa), C.byref(h)))
+        self._h = h
+
+    def close(self):
+        if self._h is not None:
+            lib().augur_gmm_destroy(self._h)
+            self._h = None
+
+    __del__ = close
+
+    def sweep(self, n=1):
+        _check(lib().augur_gmm_sweep(self._h, int(n)))
+
+    def step_sample_z(self):
+        _check(lib().augur_gmm_step_sample_z(self._h))
+
+    def step_stats(self):
+        _check(lib().augur_gmm_step_stats(self._h))
+
+    def step_resample(self):
+        _check(lib().augur_gmm_step_resample(self._h))
+
+    def step_finish(self):
+        _check(lib().augur_gmm_step_finish(self._h))
+
+    def sync(self):
+        _check(lib().augur_gmm_sync(self._h))
+
+    def loglik(self, raise_on_degenerate=False):
+        lj = C.c_double()
+        _check(lib().augur_gmm_loglik(self._h, C.byref(lj)),
+               allow=() if raise_on_degenerate else (ERR_DEGENERATE,))
+        return lj.value
+
+    def get_state(self):
+        z = self._arr.empty((self.N,), "i32")
+        pi = self._arr.empty((self.K,), "f32")
+        mu = self._arr.empty((self.K, self.dim), "f32")
+        sw = C.c_int64()
+        _check(lib().augur_gmm_get_state(self._h, _ptr(z), _ptr(pi), _ptr(mu), C.byref(sw)))
+        return z, pi, mu, sw.value
+
+    def set_state(self, z=None, pi=None, mu=None, sweep=None):
+        za = self._arr.input(z, "i32", self.N)
+        pa = self._arr.input(pi, "f32", self.K)
+        ma = self._arr.input(mu, "f32", self.K * self.dim)
+        _check(lib().augur_gmm_set_state(self._h, _ptr(za), _ptr(pa), _ptr(ma),
+                                         -1 if sweep is None else int(sweep)))
+
+    def get_stats(self):
+        n_k = self._arr.empty((self.K,), "i32")
+        s_k = self._arr.empty((self.K, self.dim), "f64")
+        _check(lib().augur_gmm_get_stats(self._h, _ptr(n_k), _ptr(s_k)))
+        return n_k, s_k
+
+    def get_degenerate(self):
+        c = C.c_int64()
+        _check(lib().augur_gmm_get_degenerate(self._h, C.byref(c)))
+        return c.value

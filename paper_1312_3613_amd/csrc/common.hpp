@@ -1,0 +1,178 @@
+// Shared pieces of the HIP library: error plumbing, device random streams,
+// Gamma draws, wave-level helpers.  gfx950 (CDNA4, wave64) only.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cfloat>
+#include <cmath>
+#include <cstdarg>
+#include <cstdint>
+#include <cstdio>
+#include <string>
+
+#include "../../include/augur.h"
+
+namespace augur {
+
+// ------------------------------------------------------------------ host errors
+void set_error(const char* fmt, ...);
+
+#define AUGUR_HIP_TRY(expr)                                                              \
+  do {                                                                                   \
+    hipError_t e_ = (expr);                                                              \
+    if (e_ != hipSuccess) {                                                              \
+      ::augur::set_error("%s failed: %s (%s:%d)", #expr, hipGetErrorString(e_), __FILE__, \
+                         __LINE__);                                                      \
+      return AUGUR_ERR_HIP;                                                              \
+    }                                                                                    \
+  } while (0)
+
+#define AUGUR_REQUIRE(cond, ...)            \
+  do {                                      \
+    if (!(cond)) {                          \
+      ::augur::set_error(__VA_ARGS__);      \
+      return AUGUR_ERR_INVALID_ARG;         \
+    }                                       \
+  } while (0)
+
+// Restores the caller's current device when it goes out of scope.
+struct DeviceGuard {
+  int prev = -1;
+  bool ok = false;
+  explicit DeviceGuard(int dev) {
+    if (hipGetDevice(&prev) != hipSuccess) prev = -1;
+    ok = hipSetDevice(dev) == hipSuccess;
+  }
+  ~DeviceGuard() {
+    if (prev >= 0) (void)hipSetDevice(prev);
+  }
+};
+
+// ------------------------------------------------------------ random streams
+enum : uint32_t {
+  kStreamInitZ = 0, kStreamZ = 1, kStreamTheta = 2, kStreamPhi = 3, kStreamGmmPi = 4,
+  kStreamGmmMu = 5
+};
+
+struct U4 { uint32_t x, y, z, w; };
+
+// Philox4x32 with ten rounds (Salmon, Moraes, Dror, Shaw; SC'11).
+__device__ __forceinline__ U4 philox10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                       uint32_t k0, uint32_t k1) {
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+    const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+    c0 = hi1 ^ c1 ^ k0;
+    c1 = lo1;
+    c2 = hi0 ^ c3 ^ k1;
+    c3 = lo0;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+  return U4{c0, c1, c2, c3};
+}
+
+// Block of (seed, variable index, sweep, stream, attempt).
+__device__ __forceinline__ U4 random_block(uint64_t seed, uint64_t index, uint32_t sweep,
+                                           uint32_t stream, uint32_t attempt) {
+  return philox10((uint32_t)index, (uint32_t)(index >> 32), sweep, (stream << 24) | attempt,
+                  (uint32_t)seed, (uint32_t)(seed >> 32));
+}
+
+__device__ __forceinline__ uint32_t word_of(const U4& b, uint32_t i) {
+  return i == 0 ? b.x : i == 1 ? b.y : i == 2 ? b.z : b.w;
+}
+
+// 23 random bits -> odd multiple of 2^-24 in (0,1): exact in fp32.
+__device__ __forceinline__ float u24(uint32_t r) {
+  return (float)(2u * (r >> 9) + 1u) * 0x1p-24f;
+}
+// floor(u24(r) * K) in integers.
+__device__ __forceinline__ int u24_times(uint32_t r, int K) {
+  return (int)(((uint64_t)(2u * (r >> 9) + 1u) * (uint64_t)K) >> 24);
+}
+// 32 random bits -> (r + 1/2) 2^-32 in (0,1): exact in fp64.
+__device__ __forceinline__ double u32d(uint32_t r) { return ((double)r + 0.5) * 0x1p-32; }
+
+__device__ __forceinline__ double normal_from(const U4& b) {
+  return sqrt(-2.0 * log(u32d(b.x))) * cospi(2.0 * u32d(b.y));
+}
+
+constexpr int kGammaAttemptCap = 64;
+
+// ln of a Gamma(a,1) draw by Marsaglia & Tsang's squeeze-rejection method
+// (2000), fp64: d = a' - 1/3, c = 1/sqrt(9 d), v = (1 + c x)^3 with x normal;
+// accept if U < 1 - 0.0331 x^4 or ln U < x^2/2 + d (1 - v + ln v); a < 1 draws
+// for a' = a + 1 and adds ln(U')/a.  Attempt j of the variable reads Philox
+// block j (words: x from 0 and 1, U from 2, U' from 3).  `capped` is raised if
+// the attempt cap is reached.
+__device__ __forceinline__ double gamma_log_draw(double a, uint64_t seed, uint64_t index,
+                                                 uint32_t sweep, uint32_t stream, bool& capped) {
+  const bool boost = a < 1.0;
+  const double a1 = boost ? a + 1.0 : a;
+  const double d = a1 - 1.0 / 3.0;
+  const double c = 1.0 / sqrt(9.0 * d);
+  for (uint32_t j = 0; j < (uint32_t)kGammaAttemptCap; ++j) {
+    const U4 b = random_block(seed, index, sweep, stream, j);
+    const double x = normal_from(b);
+    const double t = 1.0 + c * x;
+    if (t <= 0.0) continue;
+    const double v = t * t * t;
+    const double U = u32d(b.z);
+    const double x2 = x * x;
+    const double lv = log(v);
+    if (U < 1.0 - 0.0331 * x2 * x2 || log(U) < 0.5 * x2 + d * (1.0 - v + lv)) {
+      double lg = log(d) + lv;
+      if (boost) lg += log(u32d(b.w)) / a;
+      return lg;
+    }
+  }
+  capped = true;
+  return log(d);
+}
+
+// --------------------------------------------------------------- wave helpers
+// Orders LDS traffic between lanes of one wave (no cross-wave barrier).
+__device__ __forceinline__ void wave_lds_fence() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+template <typename T>
+__device__ __forceinline__ T wave_allreduce_sum(T v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+template <typename T>
+__device__ __forceinline__ T wave_allreduce_max(T v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const T other = __shfl_xor(v, o, 64);
+    v = other > v ? other : v;
+  }
+  return v;
+}
+
+// Deterministic grid-wide fp64 sum: every block writes one partial (sum of its
+// threads in a fixed tree order); the host adds the partials in index order.
+__device__ __forceinline__ void block_partial_sum(double v, double* partials, double* smem) {
+  v = wave_allreduce_sum(v);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (lane == 0) smem[wave] = v;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double s = 0.0;
+    const int nw = (blockDim.x + 63) >> 6;
+    for (int i = 0; i < nw; ++i) s += smem[i];
+    partials[blockIdx.x] = s;
+  }
+  __syncthreads();
+}
+
+inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
+
+}  // namespace augur

@@ -1,0 +1,500 @@
+// Gaussian mixture with known covariance sigma^2 I (the supplementary Gaussian
+// mixture model of arXiv 1312.3613 with the variance fixed): Gibbs sweep over
+// z, the weights pi (Dirichlet-categorical conjugacy) and the means mu
+// (Normal-Normal conjugacy), as HIP kernels behind the augur_gmm_* C ABI.
+//
+// Device layout: x float[N][dim], z int32[N], pi float[K], mu float[K][dim],
+// n_k int32[K], s_k double[K][dim].  The z conditional is evaluated in fp64 from
+// the fp32 state (N * K * dim fused multiply-adds per sweep is small).
+#include "common.hpp"
+
+#include <algorithm>
+#include <new>
+#include <vector>
+
+using namespace augur;
+
+namespace {
+
+constexpr int kRedBlocks = 512;
+constexpr int kStatChunk = 1024;  // points per block of the statistics kernel
+
+__global__ __launch_bounds__(256) void gmm_init_z_kernel(int32_t* __restrict__ z, int64_t N, int K,
+                                                          uint64_t seed) {
+  const int64_t b = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (b * 4 >= N) return;
+  const U4 r = random_block(seed, (uint64_t)b, 0, kStreamInitZ, 0);
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const int64_t i = b * 4 + e;
+    if (i < N) z[i] = (int32_t)(((uint64_t)word_of(r, e) * (uint64_t)K) >> 32);
+  }
+}
+
+// ln pi_k - |x - mu_k|^2 / (2 sigma^2) for one point; mu and ln pi in LDS.
+__device__ __forceinline__ double gmm_logw(const float* __restrict__ xi, const double* mu_s,
+                                           const double* lpi_s, int k, int dim, double inv2s2) {
+  double q = 0.0;
+  for (int j = 0; j < dim; ++j) {
+    const double df = (double)xi[j] - mu_s[k * dim + j];
+    q += df * df;
+  }
+  return lpi_s[k] - q * inv2s2;
+}
+
+// Gibbs step for z: p(k) proportional to pi_k N(x_i; mu_k, sigma^2 I), drawn by
+// inverse CDF over the weights exp(l_k - max l), running sum in index order.
+// One thread per point; three passes over the K components (max, total, search)
+// so that no per-thread array is needed.  Thread t of a group of four computes
+// the Philox block shared by points 4b..4b+3 redundantly (cheap at this size).
+__global__ __launch_bounds__(256) void gmm_sample_z_kernel(
+    const float* __restrict__ x, const float* __restrict__ pi, const float* __restrict__ mu,
+    int32_t* __restrict__ z, int64_t N, int dim, int K, double sigma, uint64_t seed, uint32_t sweep,
+    unsigned long long* __restrict__ n_degenerate) {
+  extern __shared__ double sh[];
+  double* mu_s = sh;              // [K][dim]
+  double* lpi_s = sh + K * dim;   // [K]
+  for (int e = threadIdx.x; e < K * dim; e += blockDim.x) mu_s[e] = (double)mu[e];
+  for (int k = threadIdx.x; k < K; k += blockDim.x) lpi_s[k] = log((double)pi[k]);
+  __syncthreads();
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= N) return;
+  const float* xi = x + i * dim;
+  const double inv2s2 = 1.0 / (2.0 * sigma * sigma);
+  double m = -INFINITY;
+  for (int k = 0; k < K; ++k) {
+    const double l = gmm_logw(xi, mu_s, lpi_s, k, dim, inv2s2);
+    m = l > m ? l : m;
+  }
+  double S = 0.0;
+  for (int k = 0; k < K; ++k) S += exp(gmm_logw(xi, mu_s, lpi_s, k, dim, inv2s2) - m);
+  const U4 blk = random_block(seed, (uint64_t)(i >> 2), sweep, kStreamZ, 0);
+  const uint32_t r = word_of(blk, (uint32_t)(i & 3));
+  int zi;
+  if (!(S > 0.0) || !(S <= DBL_MAX)) {
+    zi = u24_times(r, K);
+    atomicAdd(n_degenerate, 1ULL);
+  } else {
+    const double t = (double)u24(r) * S;
+    double C = 0.0;
+    int last = 0;
+    zi = -1;
+    for (int k = 0; k < K; ++k) {
+      const double p = exp(gmm_logw(xi, mu_s, lpi_s, k, dim, inv2s2) - m);
+      const double Cn = C + p;
+      if (Cn > C) last = k;
+      C = Cn;
+      if (zi < 0 && C > t) zi = k;
+    }
+    if (zi < 0) zi = last;
+  }
+  z[i] = zi;
+}
+
+// Sufficient statistics, deterministic: a block stages a chunk of points in
+// LDS; thread (k, j) walks the chunk in index order and adds x_i[j] when
+// z_i = k, thread k also counts.  Per-block partials are merged in block order
+// by the second kernel.
+__global__ __launch_bounds__(256) void gmm_stats_partial_kernel(
+    const float* __restrict__ x, const int32_t* __restrict__ z, int64_t N, int dim, int K,
+    double* __restrict__ part_s, int32_t* __restrict__ part_n) {
+  extern __shared__ unsigned char raw[];
+  float* xs = reinterpret_cast<float*>(raw);                               // [chunk][dim]
+  int32_t* zs = reinterpret_cast<int32_t*>(xs + (size_t)kStatChunk * dim);  // [chunk]
+  const int64_t p0 = (int64_t)blockIdx.x * kStatChunk;
+  const int n = (int)std::min<int64_t>(kStatChunk, N - p0);
+  for (int e = threadIdx.x; e < n * dim; e += blockDim.x) xs[e] = x[p0 * dim + e];
+  for (int e = threadIdx.x; e < n; e += blockDim.x) zs[e] = z[p0 + e];
+  __syncthreads();
+  for (int pair = threadIdx.x; pair < K * dim; pair += blockDim.x) {
+    const int k = pair / dim, j = pair - k * dim;
+    double s = 0.0;
+    int32_t c = 0;
+    for (int e = 0; e < n; ++e)
+      if (zs[e] == k) {
+        s += (double)xs[e * dim + j];
+        ++c;
+      }
+    part_s[(size_t)blockIdx.x * K * dim + pair] = s;
+    if (j == 0) part_n[(size_t)blockIdx.x * K + k] = c;
+  }
+}
+
+__global__ __launch_bounds__(256) void gmm_stats_merge_kernel(const double* __restrict__ part_s,
+                                                               const int32_t* __restrict__ part_n,
+                                                               int nblk, int dim, int K,
+                                                               double* __restrict__ s_k,
+                                                               int32_t* __restrict__ n_k) {
+  const int pair = blockIdx.x * blockDim.x + threadIdx.x;
+  if (pair >= K * dim) return;
+  double s = 0.0;
+  for (int b = 0; b < nblk; ++b) s += part_s[(size_t)b * K * dim + pair];
+  s_k[pair] = s;
+  const int k = pair / dim;
+  if (pair - k * dim == 0) {
+    int32_t c = 0;
+    for (int b = 0; b < nblk; ++b) c += part_n[(size_t)b * K + k];
+    n_k[k] = c;
+  }
+}
+
+// pi ~ Dirichlet(alpha + n) from K log-domain Gamma draws normalised in index
+// order; mu_kj ~ N(mean, 1/lambda), lambda = 1/prior_sd^2 + n_k/sigma^2,
+// mean = (s_kj / sigma^2) / lambda.  One block.
+__global__ __launch_bounds__(256) void gmm_resample_kernel(
+    const int32_t* __restrict__ n_k, const double* __restrict__ s_k, float* __restrict__ pi,
+    float* __restrict__ mu, int dim, int K, double alpha, double prior_sd, double sigma,
+    uint64_t seed, uint32_t sweep, unsigned long long* __restrict__ n_capped) {
+  extern __shared__ double lg[];  // [K]
+  bool capped = false;
+  for (int k = threadIdx.x; k < K; k += blockDim.x)
+    lg[k] = gamma_log_draw(alpha + (double)n_k[k], seed, (uint64_t)k, sweep, kStreamGmmPi, capped);
+  __syncthreads();
+  for (int k = threadIdx.x; k < K; k += blockDim.x) {
+    double m = lg[0];
+    for (int q = 1; q < K; ++q) m = lg[q] > m ? lg[q] : m;
+    double s = 0.0;
+    for (int q = 0; q < K; ++q) s += exp(lg[q] - m);
+    double p = exp(lg[k] - (m + log(s)));
+    p = p < (double)FLT_MIN ? (double)FLT_MIN : p;
+    pi[k] = (float)p;
+  }
+  for (int e = threadIdx.x; e < K * dim; e += blockDim.x) {
+    const int k = e / dim;
+    const double lambda = 1.0 / (prior_sd * prior_sd) + (double)n_k[k] / (sigma * sigma);
+    const double mean = (s_k[e] / (sigma * sigma)) / lambda;
+    const U4 b = random_block(seed, (uint64_t)e, sweep, kStreamGmmMu, 0);
+    mu[e] = (float)(mean + normal_from(b) / sqrt(lambda));
+  }
+  if (capped) atomicAdd(n_capped, 1ULL);
+}
+
+// Per-point terms of the log joint: ln pi_z + ln N(x_i; mu_z, sigma^2 I).
+__global__ __launch_bounds__(256) void gmm_loglik_kernel(
+    const float* __restrict__ x, const int32_t* __restrict__ z, const float* __restrict__ pi,
+    const float* __restrict__ mu, int64_t N, int dim, double sigma, double* __restrict__ part) {
+  __shared__ double smem[8];
+  const double LN_2PI = 1.8378770664093454835606594728112;
+  double s = 0.0;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < N;
+       i += (int64_t)gridDim.x * blockDim.x) {
+    const int k = z[i];
+    double q = 0.0;
+    for (int j = 0; j < dim; ++j) {
+      const double df = (double)x[i * dim + j] - (double)mu[k * dim + j];
+      q += df * df;
+    }
+    s += log((double)pi[k]) - 0.5 * (double)dim * LN_2PI - (double)dim * log(sigma) -
+         q / (2.0 * sigma * sigma);
+  }
+  block_partial_sum(s, part, smem);
+}
+
+__global__ __launch_bounds__(256) void gmm_check_range_kernel(const int32_t* __restrict__ a,
+                                                               int64_t n, int32_t hi,
+                                                               unsigned long long* __restrict__ bad) {
+  unsigned long long c = 0;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
+       i += (int64_t)gridDim.x * blockDim.x)
+    if (a[i] < 0 || a[i] >= hi) ++c;
+  if (c) atomicAdd(bad, c);
+}
+
+}  // namespace
+
+struct augur_gmm {
+  augur_gmm_config cfg{};
+  hipStream_t stream = nullptr;
+  double alpha = 0, prior_sd = 0, sigma = 0;
+  float *x = nullptr, *pi = nullptr, *mu = nullptr;
+  int32_t *z = nullptr, *n_k = nullptr, *part_n = nullptr;
+  double *s_k = nullptr, *part_s = nullptr, *red = nullptr;
+  unsigned long long* counters = nullptr;  // [0] degenerate [1] capped [2] bad input
+  int stat_blocks = 0;
+  int64_t sweep = 0;
+  unsigned long long degenerate_reported = 0;
+};
+
+namespace {
+
+bool device_ptrs(const augur_gmm* h) { return (h->cfg.flags & AUGUR_PTRS_DEVICE) != 0; }
+
+void free_all(augur_gmm* h) {
+  (void)hipFree(h->x); (void)hipFree(h->pi); (void)hipFree(h->mu); (void)hipFree(h->z);
+  (void)hipFree(h->n_k); (void)hipFree(h->part_n); (void)hipFree(h->s_k); (void)hipFree(h->part_s);
+  (void)hipFree(h->red); (void)hipFree(h->counters);
+}
+
+int launch_z(augur_gmm* h, uint32_t sweep) {
+  const int K = h->cfg.K, dim = h->cfg.dim;
+  const int64_t N = h->cfg.N;
+  hipLaunchKernelGGL(gmm_sample_z_kernel, dim3((unsigned)((N + 255) / 256)), dim3(256),
+                     sizeof(double) * ((size_t)K * dim + K), h->stream, h->x, h->pi, h->mu, h->z, N,
+                     dim, K, h->sigma, h->cfg.seed, sweep, h->counters);
+  AUGUR_HIP_TRY(hipGetLastError());
+  return AUGUR_OK;
+}
+
+int launch_stats(augur_gmm* h) {
+  const int K = h->cfg.K, dim = h->cfg.dim;
+  const size_t shm = sizeof(float) * (size_t)kStatChunk * dim + sizeof(int32_t) * kStatChunk;
+  hipLaunchKernelGGL(gmm_stats_partial_kernel, dim3(h->stat_blocks), dim3(256), shm, h->stream, h->x,
+                     h->z, h->cfg.N, dim, K, h->part_s, h->part_n);
+  hipLaunchKernelGGL(gmm_stats_merge_kernel, dim3((K * dim + 255) / 256), dim3(256), 0, h->stream,
+                     h->part_s, h->part_n, h->stat_blocks, dim, K, h->s_k, h->n_k);
+  AUGUR_HIP_TRY(hipGetLastError());
+  return AUGUR_OK;
+}
+
+int launch_resample(augur_gmm* h, uint32_t sweep) {
+  hipLaunchKernelGGL(gmm_resample_kernel, dim3(1), dim3(256), sizeof(double) * (size_t)h->cfg.K,
+                     h->stream, h->n_k, h->s_k, h->pi, h->mu, h->cfg.dim, h->cfg.K, h->alpha,
+                     h->prior_sd, h->sigma, h->cfg.seed, sweep, h->counters + 1);
+  AUGUR_HIP_TRY(hipGetLastError());
+  return AUGUR_OK;
+}
+
+int read_counter(augur_gmm* h, int which, unsigned long long* out) {
+  AUGUR_HIP_TRY(hipMemcpyAsync(out, h->counters + which, sizeof(unsigned long long),
+                               hipMemcpyDeviceToHost, h->stream));
+  AUGUR_HIP_TRY(hipStreamSynchronize(h->stream));
+  return AUGUR_OK;
+}
+
+#define AUGUR_CHECK_HANDLE(h)                      \
+  AUGUR_REQUIRE((h) != nullptr, "handle is NULL"); \
+  DeviceGuard guard_((h)->cfg.device);             \
+  AUGUR_REQUIRE(guard_.ok, "cannot select device %d", (h)->cfg.device)
+
+#define AUGUR_TRY(expr)              \
+  do {                               \
+    const int rc_ = (expr);          \
+    if (rc_ != AUGUR_OK) return rc_; \
+  } while (0)
+
+}  // namespace
+
+extern "C" {
+
+int augur_gmm_create(const augur_gmm_config* cfg, const float* x, augur_gmm** out) {
+  AUGUR_REQUIRE(out != nullptr, "out is NULL");
+  *out = nullptr;
+  AUGUR_REQUIRE(cfg != nullptr && x != nullptr, "config or x is NULL");
+  AUGUR_REQUIRE(cfg->N > 0 && cfg->N <= 2147483647LL && cfg->dim > 0 && cfg->K > 0,
+                "N, dim, K must be positive and N <= 2^31-1 (got %lld, %d, %d)", (long long)cfg->N,
+                cfg->dim, cfg->K);
+  AUGUR_REQUIRE((int64_t)cfg->K * cfg->dim <= 4096 && cfg->dim <= 14,
+                "supported sizes: dim <= 14 and K * dim <= 4096 (got dim %d, K %d)", cfg->dim,
+                cfg->K);
+  AUGUR_REQUIRE(std::isfinite(cfg->alpha) && cfg->alpha > 0.f && std::isfinite(cfg->prior_sd) &&
+                    cfg->prior_sd > 0.f && std::isfinite(cfg->sigma) && cfg->sigma > 0.f,
+                "alpha, prior_sd and sigma must be positive and finite");
+  AUGUR_REQUIRE((cfg->flags & ~AUGUR_PTRS_DEVICE) == 0, "unknown flag bits 0x%x", cfg->flags);
+  int ndev = 0;
+  AUGUR_HIP_TRY(hipGetDeviceCount(&ndev));
+  AUGUR_REQUIRE(cfg->device >= 0 && cfg->device < ndev, "device %d out of range (%d present)",
+                cfg->device, ndev);
+  DeviceGuard guard(cfg->device);
+  AUGUR_REQUIRE(guard.ok, "cannot select device %d", cfg->device);
+
+  augur_gmm* h = new (std::nothrow) augur_gmm();
+  AUGUR_REQUIRE(h != nullptr, "out of host memory");
+  h->cfg = *cfg;
+  h->stream = (hipStream_t)cfg->stream;
+  h->alpha = (double)cfg->alpha;
+  h->prior_sd = (double)cfg->prior_sd;
+  h->sigma = (double)cfg->sigma;
+  const int64_t N = cfg->N;
+  const int K = cfg->K, dim = cfg->dim;
+  h->stat_blocks = (int)((N + kStatChunk - 1) / kStatChunk);
+
+#define AUGUR_CREATE_TRY(expr)                                                              \
+  do {                                                                                      \
+    hipError_t e_ = (expr);                                                                 \
+    if (e_ != hipSuccess) {                                                                 \
+      set_error("%s failed: %s (%s:%d)", #expr, hipGetErrorString(e_), __FILE__, __LINE__); \
+      free_all(h);                                                                          \
+      delete h;                                                                             \
+      return AUGUR_ERR_HIP;                                                                 \
+    }                                                                                       \
+  } while (0)
+
+  AUGUR_CREATE_TRY(hipMalloc(&h->counters, 4 * sizeof(unsigned long long)));
+  AUGUR_CREATE_TRY(hipMemsetAsync(h->counters, 0, 4 * sizeof(unsigned long long), h->stream));
+  AUGUR_CREATE_TRY(hipMalloc(&h->x, sizeof(float) * (size_t)N * dim));
+  AUGUR_CREATE_TRY(hipMalloc(&h->z, sizeof(int32_t) * (size_t)N));
+  AUGUR_CREATE_TRY(hipMalloc(&h->pi, sizeof(float) * (size_t)K));
+  AUGUR_CREATE_TRY(hipMalloc(&h->mu, sizeof(float) * (size_t)K * dim));
+  AUGUR_CREATE_TRY(hipMalloc(&h->n_k, sizeof(int32_t) * (size_t)K));
+  AUGUR_CREATE_TRY(hipMalloc(&h->s_k, sizeof(double) * (size_t)K * dim));
+  AUGUR_CREATE_TRY(hipMalloc(&h->part_s, sizeof(double) * (size_t)h->stat_blocks * K * dim));
+  AUGUR_CREATE_TRY(hipMalloc(&h->part_n, sizeof(int32_t) * (size_t)h->stat_blocks * K));
+  AUGUR_CREATE_TRY(hipMalloc(&h->red, sizeof(double) * kRedBlocks));
+  AUGUR_CREATE_TRY(hipMemcpyAsync(h->x, x, sizeof(float) * (size_t)N * dim,
+                                  device_ptrs(h) ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice,
+                                  h->stream));
+  const int64_t blocks4 = (N + 3) / 4;
+  hipLaunchKernelGGL(gmm_init_z_kernel, dim3((unsigned)((blocks4 + 255) / 256)), dim3(256), 0,
+                     h->stream, h->z, N, K, cfg->seed);
+  AUGUR_CREATE_TRY(hipGetLastError());
+  int rc = launch_stats(h);
+  if (rc == AUGUR_OK) rc = launch_resample(h, 0);
+  if (rc == AUGUR_OK && hipStreamSynchronize(h->stream) != hipSuccess) {
+    set_error("initial sweep failed: %s", hipGetErrorString(hipGetLastError()));
+    rc = AUGUR_ERR_HIP;
+  }
+  if (rc != AUGUR_OK) {
+    free_all(h);
+    delete h;
+    return rc;
+  }
+  *out = h;
+  return AUGUR_OK;
+#undef AUGUR_CREATE_TRY
+}
+
+void augur_gmm_destroy(augur_gmm* h) {
+  if (!h) return;
+  DeviceGuard guard(h->cfg.device);
+  (void)hipStreamSynchronize(h->stream);
+  free_all(h);
+  delete h;
+}
+
+int augur_gmm_step_sample_z(augur_gmm* h) {
+  AUGUR_CHECK_HANDLE(h);
+  return launch_z(h, (uint32_t)(h->sweep + 1));
+}
+int augur_gmm_step_stats(augur_gmm* h) {
+  AUGUR_CHECK_HANDLE(h);
+  return launch_stats(h);
+}
+int augur_gmm_step_resample(augur_gmm* h) {
+  AUGUR_CHECK_HANDLE(h);
+  return launch_resample(h, (uint32_t)(h->sweep + 1));
+}
+int augur_gmm_step_finish(augur_gmm* h) {
+  AUGUR_REQUIRE(h != nullptr, "handle is NULL");
+  h->sweep += 1;
+  return AUGUR_OK;
+}
+
+int augur_gmm_sweep(augur_gmm* h, int32_t n_sweeps) {
+  AUGUR_CHECK_HANDLE(h);
+  AUGUR_REQUIRE(n_sweeps >= 0, "n_sweeps = %d is negative", n_sweeps);
+  for (int32_t s = 0; s < n_sweeps; ++s) {
+    const uint32_t t = (uint32_t)(h->sweep + 1);
+    AUGUR_TRY(launch_z(h, t));
+    AUGUR_TRY(launch_stats(h));
+    AUGUR_TRY(launch_resample(h, t));
+    h->sweep += 1;
+  }
+  return AUGUR_OK;
+}
+
+int augur_gmm_loglik(augur_gmm* h, double* log_joint) {
+  AUGUR_CHECK_HANDLE(h);
+  AUGUR_REQUIRE(log_joint != nullptr, "log_joint is NULL");
+  const int K = h->cfg.K, dim = h->cfg.dim;
+  hipLaunchKernelGGL(gmm_loglik_kernel, dim3(kRedBlocks), dim3(256), 0, h->stream, h->x, h->z, h->pi,
+                     h->mu, h->cfg.N, dim, h->sigma, h->red);
+  AUGUR_HIP_TRY(hipGetLastError());
+  std::vector<double> part(kRedBlocks);
+  std::vector<float> pi(K), mu((size_t)K * dim);
+  AUGUR_HIP_TRY(hipMemcpyAsync(part.data(), h->red, sizeof(double) * kRedBlocks,
+                               hipMemcpyDeviceToHost, h->stream));
+  AUGUR_HIP_TRY(hipMemcpyAsync(pi.data(), h->pi, sizeof(float) * K, hipMemcpyDeviceToHost,
+                               h->stream));
+  AUGUR_HIP_TRY(hipMemcpyAsync(mu.data(), h->mu, sizeof(float) * mu.size(), hipMemcpyDeviceToHost,
+                               h->stream));
+  AUGUR_HIP_TRY(hipStreamSynchronize(h->stream));
+  // the K + K*dim prior terms are a handful of scalars: summed on the host
+  const double LN_2PI = 1.8378770664093454835606594728112;
+  double lj = std::lgamma(K * h->alpha) - K * std::lgamma(h->alpha);
+  for (int k = 0; k < K; ++k) lj += (h->alpha - 1.0) * std::log((double)pi[k]);
+  for (size_t e = 0; e < mu.size(); ++e) {
+    const double m = (double)mu[e];
+    lj += -0.5 * LN_2PI - std::log(h->prior_sd) - m * m / (2.0 * h->prior_sd * h->prior_sd);
+  }
+  for (int i = 0; i < kRedBlocks; ++i) lj += part[i];
+  *log_joint = lj;
+  unsigned long long deg = 0;
+  AUGUR_TRY(read_counter(h, 0, &deg));
+  if (deg > h->degenerate_reported) {
+    set_error("%llu points met a conditional of zero or non-finite mass since the last report",
+              deg - h->degenerate_reported);
+    h->degenerate_reported = deg;
+    return AUGUR_ERR_DEGENERATE;
+  }
+  return AUGUR_OK;
+}
+
+int augur_gmm_get_state(augur_gmm* h, int32_t* z, float* pi, float* mu, int64_t* sweep) {
+  AUGUR_CHECK_HANDLE(h);
+  const hipMemcpyKind kind = device_ptrs(h) ? hipMemcpyDeviceToDevice : hipMemcpyDeviceToHost;
+  if (z) AUGUR_HIP_TRY(hipMemcpyAsync(z, h->z, sizeof(int32_t) * (size_t)h->cfg.N, kind, h->stream));
+  if (pi) AUGUR_HIP_TRY(hipMemcpyAsync(pi, h->pi, sizeof(float) * (size_t)h->cfg.K, kind, h->stream));
+  if (mu)
+    AUGUR_HIP_TRY(hipMemcpyAsync(mu, h->mu, sizeof(float) * (size_t)h->cfg.K * h->cfg.dim, kind,
+                                 h->stream));
+  AUGUR_HIP_TRY(hipStreamSynchronize(h->stream));
+  if (sweep) *sweep = h->sweep;
+  return AUGUR_OK;
+}
+
+int augur_gmm_set_state(augur_gmm* h, const int32_t* z, const float* pi, const float* mu,
+                        int64_t sweep) {
+  AUGUR_CHECK_HANDLE(h);
+  const hipMemcpyKind kind = device_ptrs(h) ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice;
+  if (z) {
+    if (!device_ptrs(h)) {
+      for (int64_t i = 0; i < h->cfg.N; ++i)
+        AUGUR_REQUIRE(z[i] >= 0 && z[i] < h->cfg.K, "z[%lld] = %d is outside [0, %d)",
+                      (long long)i, z[i], h->cfg.K);
+    } else {
+      AUGUR_HIP_TRY(hipMemsetAsync(h->counters + 2, 0, sizeof(unsigned long long), h->stream));
+      hipLaunchKernelGGL(gmm_check_range_kernel, dim3(512), dim3(256), 0, h->stream, z, h->cfg.N,
+                         h->cfg.K, h->counters + 2);
+      unsigned long long bad = 0;
+      AUGUR_TRY(read_counter(h, 2, &bad));
+      AUGUR_REQUIRE(bad == 0, "%llu entries of z are outside [0, %d)", bad, h->cfg.K);
+    }
+    AUGUR_HIP_TRY(hipMemcpyAsync(h->z, z, sizeof(int32_t) * (size_t)h->cfg.N, kind, h->stream));
+    AUGUR_TRY(launch_stats(h));
+  }
+  if (pi) AUGUR_HIP_TRY(hipMemcpyAsync(h->pi, pi, sizeof(float) * (size_t)h->cfg.K, kind, h->stream));
+  if (mu)
+    AUGUR_HIP_TRY(hipMemcpyAsync(h->mu, mu, sizeof(float) * (size_t)h->cfg.K * h->cfg.dim, kind,
+                                 h->stream));
+  AUGUR_HIP_TRY(hipStreamSynchronize(h->stream));
+  if (sweep >= 0) h->sweep = sweep;
+  return AUGUR_OK;
+}
+
+int augur_gmm_get_stats(augur_gmm* h, int32_t* n_k, double* s_k) {
+  AUGUR_CHECK_HANDLE(h);
+  const hipMemcpyKind kind = device_ptrs(h) ? hipMemcpyDeviceToDevice : hipMemcpyDeviceToHost;
+  if (n_k) AUGUR_HIP_TRY(hipMemcpyAsync(n_k, h->n_k, sizeof(int32_t) * (size_t)h->cfg.K, kind, h->stream));
+  if (s_k)
+    AUGUR_HIP_TRY(hipMemcpyAsync(s_k, h->s_k, sizeof(double) * (size_t)h->cfg.K * h->cfg.dim, kind,
+                                 h->stream));
+  AUGUR_HIP_TRY(hipStreamSynchronize(h->stream));
+  return AUGUR_OK;
+}
+
+int augur_gmm_get_degenerate(augur_gmm* h, int64_t* count) {
+  AUGUR_CHECK_HANDLE(h);
+  AUGUR_REQUIRE(count != nullptr, "count is NULL");
+  unsigned long long c = 0;
+  AUGUR_TRY(read_counter(h, 0, &c));
+  *count = (int64_t)c;
+  return AUGUR_OK;
+}
+
+int augur_gmm_sync(augur_gmm* h) {
+  AUGUR_CHECK_HANDLE(h);
+  AUGUR_HIP_TRY(hipStreamSynchronize(h->stream));
+  return AUGUR_OK;
+}
+
+}  // extern "C"

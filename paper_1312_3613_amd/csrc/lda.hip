@@ -1,0 +1,893 @@
+// LDA (Fig. 1 of arXiv 1312.3613): the uncollapsed Gibbs sweep of Sect. 4.2 as
+// HIP kernels for gfx950, behind the augur_lda_* C ABI.
+//
+// Device layout (all row strides are ldk = K rounded up to a multiple of 4, so
+// every row starts 16-byte aligned; padding columns hold 0):
+//   w, z      int32[N]     doc-major
+//   doc_off   int64[D+1]
+//   theta     float[D][ldk]     n_dk int32[D][ldk]
+//   phi       float[V][ldk]     n_wk int32[V][ldk]
+#include "common.hpp"
+
+#include <algorithm>
+#include <new>
+#include <vector>
+
+using namespace augur;
+
+namespace {
+
+constexpr int kRedBlocks = 1024;       // partial sums of the log-likelihood reductions
+constexpr int kPhiRowsPerBlock = 32;   // rows of the Gamma matrix handled by one block
+
+// ------------------------------------------------------------------ DPP rows
+// A "row" is 16 consecutive lanes; DPP moves data inside rows at VALU speed.
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float x) {  // out-of-row sources read 0
+  return __builtin_bit_cast(
+      float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xF, 0xF, true));
+}
+template <int CTRL>
+__device__ __forceinline__ int dpp_i32_keep(int x) {  // out-of-row sources keep x
+  return __builtin_amdgcn_update_dpp(x, x, CTRL, 0xF, 0xF, false);
+}
+constexpr int kRowShr1 = 0x111, kRowShr2 = 0x112, kRowShr4 = 0x114, kRowShr8 = 0x118;
+constexpr int kRowRor1 = 0x121, kRowRor2 = 0x122, kRowRor4 = 0x124, kRowRor8 = 0x128;
+constexpr int kRowBcast15 = 0x15F;  // lane 15 of the row to the whole row
+
+__device__ __forceinline__ float row_inclusive_scan(float x) {
+  x += dpp_f32<kRowShr1>(x);
+  x += dpp_f32<kRowShr2>(x);
+  x += dpp_f32<kRowShr4>(x);
+  x += dpp_f32<kRowShr8>(x);
+  return x;
+}
+__device__ __forceinline__ int row_allreduce_min(int x) {
+  x = min(x, dpp_i32_keep<kRowRor8>(x));
+  x = min(x, dpp_i32_keep<kRowRor4>(x));
+  x = min(x, dpp_i32_keep<kRowRor2>(x));
+  x = min(x, dpp_i32_keep<kRowRor1>(x));
+  return x;
+}
+__device__ __forceinline__ int row_allreduce_max(int x) {
+  x = max(x, dpp_i32_keep<kRowRor8>(x));
+  x = max(x, dpp_i32_keep<kRowRor4>(x));
+  x = max(x, dpp_i32_keep<kRowRor2>(x));
+  x = max(x, dpp_i32_keep<kRowRor1>(x));
+  return x;
+}
+
+// ------------------------------------------------------------------- init z
+// z_i = floor(K r / 2^32), r = word (i & 3) of block i >> 2 of the init stream.
+__global__ __launch_bounds__(256) void lda_init_z_kernel(int32_t* __restrict__ z, int64_t N, int K,
+                                                          uint64_t seed) {
+  const int64_t b = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;  // one Philox block each
+  if (b * 4 >= N) return;
+  const U4 r = random_block(seed, (uint64_t)b, 0, kStreamInitZ, 0);
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const int64_t i = b * 4 + e;
+    if (i < N) z[i] = (int32_t)(((uint64_t)word_of(r, e) * (uint64_t)K) >> 32);
+  }
+}
+
+// ----------------------------------------------------------------- sample z
+// Gibbs step for the assignments (Sect. 4.2): token i of document d with word v
+// draws z_i = first k with C_k > u_i * S, C_k the running sum of
+// theta[d][k] * phi[v][k] and S = C_{K-1}; fp32 throughout.
+//
+// One wave owns one document.  The wave is four 16-lane rows; each row draws one
+// token per iteration.  A row covers the K topics in NS stripes of 64: lane j
+// holds topics 64 m + 4 j + {0,1,2,3} of stripe m, so a row reads 256 contiguous
+// bytes of the phi row per load.  theta_d lives in registers for the whole
+// document.  Per stripe the lane sums its four products, the row scans the lane
+// sums with DPP, and the stripe total is carried into the next stripe.  The
+// crossing topic is found by every lane testing its own chunks against the
+// threshold and the row taking the minimum candidate index; a chunk or topic of
+// zero mass is never a candidate.
+//
+// Random numbers: lane L computes the Philox block of tokens
+// base + 4 L .. base + 4 L + 3 (base a multiple of 4), parks the four words in
+// the wave's LDS strip, and each row then picks the word of its token: one
+// Philox evaluation per wave serves 256 tokens.
+template <int NS>
+__global__ __launch_bounds__(256) void lda_sample_z_kernel(
+    const int32_t* __restrict__ w, const int64_t* __restrict__ doc_off,
+    const float* __restrict__ theta, const float* __restrict__ phi, int32_t* __restrict__ z, int D,
+    int K, int ldk, uint64_t seed, uint32_t sweep, unsigned long long* __restrict__ n_degenerate) {
+  __shared__ uint32_t rnd[4][256];
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const int d = blockIdx.x * 4 + wave;
+  if (d >= D) return;
+  const int row = lane >> 4, j = lane & 15;
+
+  float4 th[NS];
+#pragma unroll
+  for (int m = 0; m < NS; ++m) {
+    const int col = 64 * m + 4 * j;
+    th[m] = col < ldk ? *reinterpret_cast<const float4*>(theta + (size_t)d * ldk + col)
+                      : make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+
+  const int64_t a = doc_off[d], b = doc_off[d + 1];
+  for (int64_t base = a & ~(int64_t)3; base < b; base += 256) {
+    {
+      const U4 r = random_block(seed, (uint64_t)(base >> 2) + (uint64_t)lane, sweep, kStreamZ, 0);
+      wave_lds_fence();  // earlier reads of the strip are done
+      *reinterpret_cast<uint4*>(&rnd[wave][4 * lane]) = make_uint4(r.x, r.y, r.z, r.w);
+      wave_lds_fence();
+    }
+    const int64_t lo = a > base ? a : base;
+    const int64_t hi = b < base + 256 ? b : base + 256;
+    for (int64_t i0 = lo; i0 < hi; i0 += 4) {
+      const int64_t i = i0 + row;
+      const bool valid = i < hi;
+      const int32_t v = valid ? w[i] : 0;
+      const uint32_t r = rnd[wave][valid ? (int)(i - base) : 0];
+      const float* prow = phi + (size_t)v * ldk;
+
+      float4 q[NS];
+#pragma unroll
+      for (int m = 0; m < NS; ++m) {
+        const int col = 64 * m + 4 * j;
+        q[m] = col < ldk ? *reinterpret_cast<const float4*>(prow + col)
+                         : make_float4(0.f, 0.f, 0.f, 0.f);
+      }
+
+      // running sums: l?[m] = lane-local inclusive sums of stripe m, base[m] =
+      // sum of everything before this lane's chunk of stripe m
+      float l0[NS], l1[NS], l2[NS], l3[NS], cbase[NS];
+      float carry = 0.f;
+#pragma unroll
+      for (int m = 0; m < NS; ++m) {
+        l0[m] = th[m].x * q[m].x;
+        l1[m] = fmaf(th[m].y, q[m].y, l0[m]);
+        l2[m] = fmaf(th[m].z, q[m].z, l1[m]);
+        l3[m] = fmaf(th[m].w, q[m].w, l2[m]);
+        const float incl = row_inclusive_scan(l3[m]);
+        const float excl = dpp_f32<kRowShr1>(incl);
+        cbase[m] = carry + excl;
+        carry += dpp_f32<kRowBcast15>(incl);
+      }
+      const float S = carry;
+      const float t = u24(r) * S;
+
+      // candidate = global topic index of the first topic of this lane's chunks
+      // whose running sum exceeds t and whose mass is positive
+      int cand = 0x7FFFFFFF;
+#pragma unroll
+      for (int m = NS - 1; m >= 0; --m) {
+        const float tt = fmaxf(t - cbase[m], 0.f);
+        const int e = (l0[m] <= tt) + (l1[m] <= tt) + (l2[m] <= tt);
+        cand = l3[m] > tt ? 64 * m + 4 * j + e : cand;
+      }
+      int k = row_allreduce_min(cand);
+
+      const bool ok = S > 0.f && S <= FLT_MAX;  // false for 0, inf and NaN
+      if (__builtin_expect(__any(valid && (!ok || k == 0x7FFFFFFF)), 0)) {
+        if (!ok) {
+          // zero or non-finite mass: z = floor(u K)
+          k = u24_times(r, K);
+          if (valid && j == 0) atomicAdd(n_degenerate, 1ULL);
+        } else if (k == 0x7FFFFFFF) {
+          // rounding pushed t to S: the last topic of positive mass
+          int last = -1;
+#pragma unroll
+          for (int m = 0; m < NS; ++m) {
+            const int kk = 64 * m + 4 * j;
+            if (l0[m] > 0.f) last = kk;
+            if (l1[m] > l0[m]) last = kk + 1;
+            if (l2[m] > l1[m]) last = kk + 2;
+            if (l3[m] > l2[m]) last = kk + 3;
+          }
+          k = row_allreduce_max(last);
+        }
+      }
+      // garbage parameters (negative or NaN entries) must not yield an index outside the tables
+      if (valid && j == 0) z[i] = min(max(k, 0), K - 1);
+    }
+  }
+}
+
+// --------------------------------------------------------------- count step
+// Counting phase (Sect. 4.2): n_dk[d][k] = tokens of document d with z = k;
+// n_wk[v][k] = tokens of word v with z = k.  One wave per document builds the
+// document's row in an LDS histogram and stores it whole (no zero-fill of n_dk
+// needed); word counts go to global memory with atomics (n_wk zeroed before).
+__global__ __launch_bounds__(256) void lda_count_kernel(
+    const int32_t* __restrict__ w, const int32_t* __restrict__ z,
+    const int64_t* __restrict__ doc_off, int32_t* __restrict__ n_dk, int32_t* __restrict__ n_wk,
+    int D, int K, int ldk) {
+  extern __shared__ int32_t hist_all[];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int d = blockIdx.x * 4 + wave;
+  if (d >= D) return;
+  int32_t* hist = hist_all + (size_t)wave * ldk;
+  for (int k = lane; k < ldk; k += 64) hist[k] = 0;
+  wave_lds_fence();
+  const int64_t a = doc_off[d], b = doc_off[d + 1];
+  for (int64_t i = a + lane; i < b; i += 64) {
+    const int32_t zi = z[i];
+    atomicAdd(&hist[zi], 1);
+    atomicAdd(&n_wk[(size_t)w[i] * ldk + zi], 1);
+  }
+  wave_lds_fence();
+  for (int k = lane; k < ldk; k += 64) n_dk[(size_t)d * ldk + k] = hist[k];
+}
+
+// ------------------------------------------------------------ resample theta
+// theta_d ~ Dirichlet(alpha + n_dk[d][.]) for every document in parallel
+// (Sect. 4.3; App. B, Alg. 2): K Gamma draws in the log domain, normalised by
+// their sum (log-sum-exp in fp64), stored as fp32 floored at FLT_MIN.  One wave
+// per document, lanes over topics; the draws wait in LDS between the passes.
+__global__ __launch_bounds__(256) void lda_resample_theta_kernel(
+    const int32_t* __restrict__ n_dk, float* __restrict__ theta, int D, int K, int ldk,
+    double alpha, uint64_t seed, uint32_t sweep, unsigned long long* __restrict__ n_capped) {
+  extern __shared__ double lg_all[];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int d = blockIdx.x * 4 + wave;
+  if (d >= D) return;
+  double* lg = lg_all + (size_t)wave * K;
+  bool capped = false;
+  double m = -INFINITY;
+  for (int k = lane; k < K; k += 64) {
+    const double a = alpha + (double)n_dk[(size_t)d * ldk + k];
+    const double v = gamma_log_draw(a, seed, (uint64_t)d * (uint64_t)K + (uint64_t)k, sweep,
+                                    kStreamTheta, capped);
+    lg[k] = v;
+    m = v > m ? v : m;
+  }
+  m = wave_allreduce_max(m);
+  double s = 0.0;
+  for (int k = lane; k < K; k += 64) s += exp(lg[k] - m);
+  s = wave_allreduce_sum(s);
+  const double L = m + log(s);
+  for (int k = lane; k < K; k += 64) {
+    double p = exp(lg[k] - L);
+    p = p < (double)FLT_MIN ? (double)FLT_MIN : p;
+    theta[(size_t)d * ldk + k] = (float)p;
+  }
+  if (capped) atomicAdd(n_capped, 1ULL);
+}
+
+// -------------------------------------------------------------- resample phi
+// phi_k ~ Dirichlet(beta + n_wk[.][k]) for every topic (Sect. 4.3, Alg. 1): a
+// V x K matrix of Gamma draws, element-parallel because K is small, then one
+// normaliser per topic.  Here the normaliser is a column log-sum-exp: pass 1
+// draws and keeps a running (max, sum) per column per block of rows, pass 2
+// merges the blocks, pass 3 writes exp(lg - L_k).
+__global__ __launch_bounds__(256) void lda_phi_draw_kernel(
+    const int32_t* __restrict__ n_wk, double* __restrict__ lg, double2* __restrict__ partial, int V,
+    int K, int ldk, double beta, uint64_t seed, uint32_t sweep,
+    unsigned long long* __restrict__ n_capped) {
+  const int v0 = blockIdx.x * kPhiRowsPerBlock;
+  const int v1 = min(V, v0 + kPhiRowsPerBlock);
+  bool capped = false;
+  for (int k = threadIdx.x; k < K; k += blockDim.x) {
+    double m = -INFINITY, s = 0.0;
+    for (int v = v0; v < v1; ++v) {
+      const size_t e = (size_t)v * ldk + k;
+      const double a = beta + (double)n_wk[e];
+      const double x = gamma_log_draw(a, seed, (uint64_t)v * (uint64_t)K + (uint64_t)k, sweep,
+                                      kStreamPhi, capped);
+      lg[e] = x;
+      if (x > m) {
+        s = s * exp(m - x) + 1.0;  // exp(-inf) = 0 on the first row
+        m = x;
+      } else {
+        s += exp(x - m);
+      }
+    }
+    partial[(size_t)blockIdx.x * K + k] = make_double2(m, s);
+  }
+  if (capped) atomicAdd(n_capped, 1ULL);
+}
+
+// One block per topic: merge the per-block (max, sum) pairs in a fixed order.
+__global__ __launch_bounds__(256) void lda_phi_norm_kernel(const double2* __restrict__ partial,
+                                                            double* __restrict__ logZ, int nblk,
+                                                            int K) {
+  __shared__ double sm[256], ss[256];
+  const int k = blockIdx.x;
+  double m = -INFINITY, s = 0.0;
+  for (int b = threadIdx.x; b < nblk; b += 256) {
+    const double2 p = partial[(size_t)b * K + k];
+    if (p.x > m) {
+      s = s * exp(m - p.x) + p.y;
+      m = p.x;
+    } else {
+      s += p.y * exp(p.x - m);
+    }
+  }
+  sm[threadIdx.x] = m;
+  ss[threadIdx.x] = s;
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) {
+    if ((int)threadIdx.x < o) {
+      const double m2 = sm[threadIdx.x + o], s2 = ss[threadIdx.x + o];
+      double m1 = sm[threadIdx.x], s1 = ss[threadIdx.x];
+      if (m2 > m1) {
+        s1 = s1 * exp(m1 - m2) + s2;
+        m1 = m2;
+      } else if (m2 > -INFINITY) {
+        s1 += s2 * exp(m2 - m1);
+      }
+      sm[threadIdx.x] = m1;
+      ss[threadIdx.x] = s1;
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) logZ[k] = sm[0] + log(ss[0]);
+}
+
+__global__ __launch_bounds__(256) void lda_phi_write_kernel(const double* __restrict__ lg,
+                                                             const double* __restrict__ logZ,
+                                                             float* __restrict__ phi, int V, int K,
+                                                             int ldk) {
+  const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= (int64_t)V * ldk) return;
+  const int k = (int)(e % ldk);
+  if (k >= K) return;
+  double p = exp(lg[e] - logZ[k]);
+  p = p < (double)FLT_MIN ? (double)FLT_MIN : p;
+  phi[e] = (float)p;
+}
+
+// -------------------------------------------------------------------- loglik
+// Per-token terms of the log joint (Sect. 4.1: log space, terms evaluated in
+// parallel and summed): ln theta[d][z_i] + ln phi[w_i][z_i], and
+// ln sum_k theta[d][k] phi[w_i][k] for the marginal.  One wave per document
+// slot, a 16-lane row per token, fp64 accumulation.
+__global__ __launch_bounds__(256) void lda_loglik_tokens_kernel(
+    const int32_t* __restrict__ w, const int32_t* __restrict__ z,
+    const int64_t* __restrict__ doc_off, const float* __restrict__ theta,
+    const float* __restrict__ phi, int D, int ldk, double* __restrict__ part_lik,
+    double* __restrict__ part_marg) {
+  __shared__ double smem[8];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int row = lane >> 4, j = lane & 15;
+  double lik = 0.0, marg = 0.0;
+  for (int d = blockIdx.x * 4 + wave; d < D; d += gridDim.x * 4) {
+    const float* th = theta + (size_t)d * ldk;
+    const int64_t a = doc_off[d], b = doc_off[d + 1];
+    for (int64_t i0 = a; i0 < b; i0 += 4) {
+      const int64_t i = i0 + row;
+      const bool valid = i < b;
+      const float* ph = phi + (size_t)(valid ? w[i] : 0) * ldk;
+      double s = 0.0;
+      for (int col = 4 * j; col < ldk; col += 64) {
+        const float4 x = *reinterpret_cast<const float4*>(th + col);
+        const float4 y = *reinterpret_cast<const float4*>(ph + col);
+        s += (double)x.x * (double)y.x + (double)x.y * (double)y.y + (double)x.z * (double)y.z +
+             (double)x.w * (double)y.w;
+      }
+#pragma unroll
+      for (int o = 8; o > 0; o >>= 1) s += __shfl_xor(s, o, 16);
+      if (valid && j == 0) {
+        const int zi = z[i];
+        marg += log(s);
+        lik += log((double)th[zi]) + log((double)ph[zi]);
+      }
+    }
+  }
+  block_partial_sum(lik, part_lik, smem);
+  block_partial_sum(marg, part_marg, smem);
+}
+
+// Sum of ln x over the K real columns of a [rows][ldk] matrix.
+__global__ __launch_bounds__(256) void sum_log_kernel(const float* __restrict__ x, int64_t rows,
+                                                       int K, int ldk, double* __restrict__ part) {
+  __shared__ double smem[8];
+  double s = 0.0;
+  const int64_t total = rows * ldk;
+  for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total;
+       e += (int64_t)gridDim.x * blockDim.x) {
+    if ((int)(e % ldk) < K) s += log((double)x[e]);
+  }
+  block_partial_sum(s, part, smem);
+}
+
+// --------------------------------------------------------------- validation
+__global__ __launch_bounds__(256) void check_range_kernel(const int32_t* __restrict__ a, int64_t n,
+                                                           int32_t lo, int32_t hi,
+                                                           unsigned long long* __restrict__ bad) {
+  unsigned long long c = 0;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
+       i += (int64_t)gridDim.x * blockDim.x)
+    if (a[i] < lo || a[i] >= hi) ++c;
+  if (c) atomicAdd(bad, c);
+}
+
+// doc_off[d+1] = inclusive prefix of doc_len on the host for host pointers; for
+// device pointers a single block scans (D is at most a few 10^5).
+__global__ __launch_bounds__(1024) void doc_offsets_kernel(const int32_t* __restrict__ doc_len,
+                                                            int64_t* __restrict__ doc_off, int D,
+                                                            unsigned long long* __restrict__ bad) {
+  __shared__ int64_t chunk_sum[1024];
+  const int t = threadIdx.x;
+  const int per = (D + 1023) / 1024;
+  const int lo = min(D, t * per), hi = min(D, lo + per);
+  int64_t s = 0;
+  unsigned long long neg = 0;
+  for (int d = lo; d < hi; ++d) {
+    if (doc_len[d] < 0) ++neg;
+    s += doc_len[d];
+  }
+  chunk_sum[t] = s;
+  __syncthreads();
+  if (t == 0) {
+    int64_t run = 0;
+    for (int c = 0; c < 1024; ++c) {
+      const int64_t x = chunk_sum[c];
+      chunk_sum[c] = run;
+      run += x;
+    }
+    doc_off[0] = 0;
+  }
+  __syncthreads();
+  int64_t run = chunk_sum[t];
+  for (int d = lo; d < hi; ++d) {
+    run += doc_len[d];
+    doc_off[d + 1] = run;
+  }
+  if (neg) atomicAdd(bad, neg);
+}
+
+}  // namespace
+
+// ======================================================================= host
+struct augur_lda {
+  augur_lda_config cfg{};
+  int64_t N = 0;
+  int ldk = 0;
+  int ns = 0;  // stripes of 64 topics per token row
+  hipStream_t stream = nullptr;
+  double alpha = 0, beta = 0;
+  int32_t *w = nullptr, *z = nullptr, *n_dk = nullptr, *n_wk = nullptr;
+  int64_t* doc_off = nullptr;
+  float *theta = nullptr, *phi = nullptr;
+  double* lg = nullptr;          // [V][ldk] ln Gamma draws of the phi step
+  double2* col_partial = nullptr;  // [phi row blocks][K]
+  double* col_logZ = nullptr;    // [K]
+  double* red = nullptr;         // [4][kRedBlocks] reduction partials
+  unsigned long long* counters = nullptr;  // [0] degenerate tokens [1] capped draws [2] bad input
+  int phi_blocks = 0;
+  int64_t sweep = 0;
+  unsigned long long degenerate_reported = 0;
+  hipEvent_t ev[6] = {};
+  bool have_events = false;
+};
+
+namespace {
+
+bool device_ptrs(const augur_lda* h) { return (h->cfg.flags & AUGUR_PTRS_DEVICE) != 0; }
+
+void free_all(augur_lda* h) {
+  (void)hipFree(h->w); (void)hipFree(h->z); (void)hipFree(h->n_dk); (void)hipFree(h->n_wk);
+  (void)hipFree(h->doc_off); (void)hipFree(h->theta); (void)hipFree(h->phi); (void)hipFree(h->lg);
+  (void)hipFree(h->col_partial); (void)hipFree(h->col_logZ); (void)hipFree(h->red);
+  (void)hipFree(h->counters);
+  if (h->have_events)
+    for (auto& e : h->ev) (void)hipEventDestroy(e);
+}
+
+int launch_sample_z(augur_lda* h, uint32_t sweep) {
+  const int D = h->cfg.D;
+  if (D == 0 || h->N == 0) return AUGUR_OK;
+  const dim3 grid((D + 3) / 4), block(256);
+#define AUGUR_Z_CASE(NSV)                                                                      \
+  case NSV:                                                                                    \
+    hipLaunchKernelGGL(lda_sample_z_kernel<NSV>, grid, block, 0, h->stream, h->w, h->doc_off,  \
+                       h->theta, h->phi, h->z, D, h->cfg.K, h->ldk, h->cfg.seed, sweep,        \
+                       h->counters);                                                           \
+    break;
+  switch (h->ns) {
+    AUGUR_Z_CASE(1) AUGUR_Z_CASE(2) AUGUR_Z_CASE(3) AUGUR_Z_CASE(4) AUGUR_Z_CASE(5)
+    AUGUR_Z_CASE(6) AUGUR_Z_CASE(7) AUGUR_Z_CASE(8) AUGUR_Z_CASE(9) AUGUR_Z_CASE(10)
+    AUGUR_Z_CASE(11) AUGUR_Z_CASE(12) AUGUR_Z_CASE(13) AUGUR_Z_CASE(14) AUGUR_Z_CASE(15)
+    AUGUR_Z_CASE(16)
+    default:
+      set_error("K = %d is above the supported maximum of 1024 topics", h->cfg.K);
+      return AUGUR_ERR_UNIMPLEMENTED;
+  }
+#undef AUGUR_Z_CASE
+  AUGUR_HIP_TRY(hipGetLastError());
+  return AUGUR_OK;
+}
+
+int launch_count(augur_lda* h) {
+  const int D = h->cfg.D;
+  AUGUR_HIP_TRY(hipMemsetAsync(h->n_wk, 0, sizeof(int32_t) * (size_t)h->cfg.V * h->ldk, h->stream));
+  if (D == 0) return AUGUR_OK;
+  hipLaunchKernelGGL(lda_count_kernel, dim3((D + 3) / 4), dim3(256),
+                     sizeof(int32_t) * 4 * (size_t)h->ldk, h->stream, h->w, h->z, h->doc_off,
+                     h->n_dk, h->n_wk, D, h->cfg.K, h->ldk);
+  AUGUR_HIP_TRY(hipGetLastError());
+  return AUGUR_OK;
+}
+
+int launch_theta(augur_lda* h, uint32_t sweep) {
+  const int D = h->cfg.D;
+  if (D == 0) return AUGUR_OK;
+  hipLaunchKernelGGL(lda_resample_theta_kernel, dim3((D + 3) / 4), dim3(256),
+                     sizeof(double) * 4 * (size_t)h->cfg.K, h->stream, h->n_dk, h->theta, D,
+                     h->cfg.K, h->ldk, h->alpha, h->cfg.seed, sweep, h->counters + 1);
+  AUGUR_HIP_TRY(hipGetLastError());
+  return AUGUR_OK;
+}
+
+int launch_phi(augur_lda* h, uint32_t sweep) {
+  const int V = h->cfg.V, K = h->cfg.K;
+  const int threads = (int)std::min<int64_t>(256, round_up(K, 64));
+  hipLaunchKernelGGL(lda_phi_draw_kernel, dim3(h->phi_blocks), dim3(threads), 0, h->stream, h->n_wk,
+                     h->lg, h->col_partial, V, K, h->ldk, h->beta, h->cfg.seed, sweep,
+                     h->counters + 1);
+  hipLaunchKernelGGL(lda_phi_norm_kernel, dim3(K), dim3(256), 0, h->stream, h->col_partial,
+                     h->col_logZ, h->phi_blocks, K);
+  const int64_t total = (int64_t)V * h->ldk;
+  hipLaunchKernelGGL(lda_phi_write_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0,
+                     h->stream, h->lg, h->col_logZ, h->phi, V, K, h->ldk);
+  AUGUR_HIP_TRY(hipGetLastError());
+  return AUGUR_OK;
+}
+
+// Strided copies between the caller's dense [rows][K] arrays and the padded
+// device arrays.
+int copy_in(augur_lda* h, void* dst, const void* src, size_t elem, int64_t rows) {
+  AUGUR_HIP_TRY(hipMemcpy2DAsync(dst, elem * h->ldk, src, elem * h->cfg.K, elem * h->cfg.K,
+                                 (size_t)rows,
+                                 device_ptrs(h) ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice,
+                                 h->stream));
+  return AUGUR_OK;
+}
+int copy_out(augur_lda* h, void* dst, const void* src, size_t elem, int64_t rows) {
+  AUGUR_HIP_TRY(hipMemcpy2DAsync(dst, elem * h->cfg.K, src, elem * h->ldk, elem * h->cfg.K,
+                                 (size_t)rows,
+                                 device_ptrs(h) ? hipMemcpyDeviceToDevice : hipMemcpyDeviceToHost,
+                                 h->stream));
+  return AUGUR_OK;
+}
+
+int read_counter(augur_lda* h, int which, unsigned long long* out) {
+  AUGUR_HIP_TRY(hipMemcpyAsync(out, h->counters + which, sizeof(unsigned long long),
+                               hipMemcpyDeviceToHost, h->stream));
+  AUGUR_HIP_TRY(hipStreamSynchronize(h->stream));
+  return AUGUR_OK;
+}
+
+#define AUGUR_CHECK_HANDLE(h)                              \
+  AUGUR_REQUIRE((h) != nullptr, "handle is NULL");         \
+  DeviceGuard guard_((h)->cfg.device);                     \
+  AUGUR_REQUIRE(guard_.ok, "cannot select device %d", (h)->cfg.device)
+
+#define AUGUR_TRY(expr)              \
+  do {                               \
+    const int rc_ = (expr);          \
+    if (rc_ != AUGUR_OK) return rc_; \
+  } while (0)
+
+}  // namespace
+
+extern "C" {
+
+int augur_lda_create(const augur_lda_config* cfg, const int32_t* doc_len, const int32_t* w,
+                     augur_lda** out) {
+  AUGUR_REQUIRE(out != nullptr, "out is NULL");
+  *out = nullptr;
+  AUGUR_REQUIRE(cfg != nullptr, "config is NULL");
+  AUGUR_REQUIRE(cfg->D > 0 && cfg->V > 0 && cfg->K > 0, "D, V, K must be positive (got %d, %d, %d)",
+                cfg->D, cfg->V, cfg->K);
+  AUGUR_REQUIRE(cfg->K <= 1024, "K = %d is above the supported maximum of 1024 topics", cfg->K);
+  AUGUR_REQUIRE(std::isfinite(cfg->alpha) && cfg->alpha > 0.f && std::isfinite(cfg->beta) &&
+                    cfg->beta > 0.f,
+                "alpha and beta must be positive and finite");
+  AUGUR_REQUIRE((cfg->flags & ~AUGUR_PTRS_DEVICE) == 0, "unknown flag bits 0x%x", cfg->flags);
+  AUGUR_REQUIRE(doc_len != nullptr, "doc_len is NULL");
+  int ndev = 0;
+  AUGUR_HIP_TRY(hipGetDeviceCount(&ndev));
+  AUGUR_REQUIRE(cfg->device >= 0 && cfg->device < ndev, "device %d out of range (%d present)",
+                cfg->device, ndev);
+  DeviceGuard guard(cfg->device);
+  AUGUR_REQUIRE(guard.ok, "cannot select device %d", cfg->device);
+  const bool dev = (cfg->flags & AUGUR_PTRS_DEVICE) != 0;
+  const int D = cfg->D, V = cfg->V, K = cfg->K;
+
+  augur_lda* h = new (std::nothrow) augur_lda();
+  AUGUR_REQUIRE(h != nullptr, "out of host memory");
+  h->cfg = *cfg;
+  h->stream = (hipStream_t)cfg->stream;
+  h->alpha = (double)cfg->alpha;
+  h->beta = (double)cfg->beta;
+  h->ldk = (int)round_up(K, 4);
+  h->ns = (h->ldk + 63) / 64;
+  h->phi_blocks = (V + kPhiRowsPerBlock - 1) / kPhiRowsPerBlock;
+
+#define AUGUR_CREATE_TRY(expr)                                                              \
+  do {                                                                                      \
+    hipError_t e_ = (expr);                                                                 \
+    if (e_ != hipSuccess) {                                                                 \
+      set_error("%s failed: %s (%s:%d)", #expr, hipGetErrorString(e_), __FILE__, __LINE__); \
+      free_all(h);                                                                          \
+      delete h;                                                                             \
+      return AUGUR_ERR_HIP;                                                                 \
+    }                                                                                       \
+  } while (0)
+#define AUGUR_CREATE_FAIL(...)  \
+  do {                          \
+    set_error(__VA_ARGS__);     \
+    free_all(h);                \
+    delete h;                   \
+    return AUGUR_ERR_INVALID_ARG; \
+  } while (0)
+
+  AUGUR_CREATE_TRY(hipMalloc(&h->counters, 4 * sizeof(unsigned long long)));
+  AUGUR_CREATE_TRY(hipMemsetAsync(h->counters, 0, 4 * sizeof(unsigned long long), h->stream));
+  AUGUR_CREATE_TRY(hipMalloc(&h->doc_off, sizeof(int64_t) * ((size_t)D + 1)));
+
+  // document offsets and N
+  if (dev) {
+    hipLaunchKernelGGL(doc_offsets_kernel, dim3(1), dim3(1024), 0, h->stream, doc_len, h->doc_off, D,
+                       h->counters + 2);
+    AUGUR_CREATE_TRY(hipGetLastError());
+    int64_t n = 0;
+    unsigned long long bad = 0;
+    AUGUR_CREATE_TRY(hipMemcpyAsync(&n, h->doc_off + D, sizeof(int64_t), hipMemcpyDeviceToHost,
+                                    h->stream));
+    AUGUR_CREATE_TRY(hipMemcpyAsync(&bad, h->counters + 2, sizeof(bad), hipMemcpyDeviceToHost,
+                                    h->stream));
+    AUGUR_CREATE_TRY(hipStreamSynchronize(h->stream));
+    if (bad) AUGUR_CREATE_FAIL("doc_len has %llu negative entries", bad);
+    h->N = n;
+  } else {
+    std::vector<int64_t> off((size_t)D + 1, 0);
+    for (int d = 0; d < D; ++d) {
+      if (doc_len[d] < 0) AUGUR_CREATE_FAIL("doc_len[%d] = %d is negative", d, doc_len[d]);
+      off[d + 1] = off[d] + doc_len[d];
+    }
+    h->N = off[D];
+    AUGUR_CREATE_TRY(hipMemcpy(h->doc_off, off.data(), sizeof(int64_t) * off.size(),
+                               hipMemcpyHostToDevice));
+  }
+  if (h->N > 2147483647LL) AUGUR_CREATE_FAIL("N = %lld tokens exceeds 2^31-1", (long long)h->N);
+  if (h->N > 0 && w == nullptr) AUGUR_CREATE_FAIL("w is NULL");
+  const size_t n_alloc = (size_t)std::max<int64_t>(h->N, 1);
+
+  if (!dev)
+    for (int64_t i = 0; i < h->N; ++i)
+      if (w[i] < 0 || w[i] >= V)
+        AUGUR_CREATE_FAIL("w[%lld] = %d is outside [0, %d)", (long long)i, w[i], V);
+
+  AUGUR_CREATE_TRY(hipMalloc(&h->w, sizeof(int32_t) * n_alloc));
+  AUGUR_CREATE_TRY(hipMalloc(&h->z, sizeof(int32_t) * n_alloc));
+  if (h->N > 0)
+    AUGUR_CREATE_TRY(hipMemcpyAsync(h->w, w, sizeof(int32_t) * (size_t)h->N,
+                                    dev ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice,
+                                    h->stream));
+  if (dev && h->N > 0) {
+    hipLaunchKernelGGL(check_range_kernel, dim3(1024), dim3(256), 0, h->stream, h->w, h->N, 0, V,
+                       h->counters + 2);
+    unsigned long long bad = 0;
+    AUGUR_CREATE_TRY(hipMemcpyAsync(&bad, h->counters + 2, sizeof(bad), hipMemcpyDeviceToHost,
+                                    h->stream));
+    AUGUR_CREATE_TRY(hipStreamSynchronize(h->stream));
+    if (bad) AUGUR_CREATE_FAIL("%llu entries of w are outside [0, %d)", bad, V);
+  }
+
+  const size_t dk = (size_t)D * h->ldk, vk = (size_t)V * h->ldk;
+  AUGUR_CREATE_TRY(hipMalloc(&h->theta, sizeof(float) * dk));
+  AUGUR_CREATE_TRY(hipMalloc(&h->n_dk, sizeof(int32_t) * dk));
+  AUGUR_CREATE_TRY(hipMalloc(&h->phi, sizeof(float) * vk));
+  AUGUR_CREATE_TRY(hipMalloc(&h->n_wk, sizeof(int32_t) * vk));
+  AUGUR_CREATE_TRY(hipMalloc(&h->lg, sizeof(double) * vk));
+  AUGUR_CREATE_TRY(hipMalloc(&h->col_partial, sizeof(double2) * (size_t)h->phi_blocks * K));
+  AUGUR_CREATE_TRY(hipMalloc(&h->col_logZ, sizeof(double) * (size_t)K));
+  AUGUR_CREATE_TRY(hipMalloc(&h->red, sizeof(double) * 4 * kRedBlocks));
+  AUGUR_CREATE_TRY(hipMemsetAsync(h->theta, 0, sizeof(float) * dk, h->stream));
+  AUGUR_CREATE_TRY(hipMemsetAsync(h->phi, 0, sizeof(float) * vk, h->stream));
+  AUGUR_CREATE_TRY(hipMemsetAsync(h->n_dk, 0, sizeof(int32_t) * dk, h->stream));
+  for (auto& e : h->ev) AUGUR_CREATE_TRY(hipEventCreate(&e));
+  h->have_events = true;
+
+  // initial state (sweep index 0)
+  if (h->N > 0) {
+    const int64_t blocks4 = (h->N + 3) / 4;
+    hipLaunchKernelGGL(lda_init_z_kernel, dim3((unsigned)((blocks4 + 255) / 256)), dim3(256), 0,
+                       h->stream, h->z, h->N, K, cfg->seed);
+    AUGUR_CREATE_TRY(hipGetLastError());
+  }
+  int rc = launch_count(h);
+  if (rc == AUGUR_OK) rc = launch_theta(h, 0);
+  if (rc == AUGUR_OK) rc = launch_phi(h, 0);
+  if (rc == AUGUR_OK && hipStreamSynchronize(h->stream) != hipSuccess) {
+    set_error("initial sweep failed: %s", hipGetErrorString(hipGetLastError()));
+    rc = AUGUR_ERR_HIP;
+  }
+  if (rc != AUGUR_OK) {
+    free_all(h);
+    delete h;
+    return rc;
+  }
+  h->sweep = 0;
+  *out = h;
+  return AUGUR_OK;
+#undef AUGUR_CREATE_TRY
+#undef AUGUR_CREATE_FAIL
+}
+
+void augur_lda_destroy(augur_lda* h) {
+  if (!h) return;
+  DeviceGuard guard(h->cfg.device);
+  (void)hipStreamSynchronize(h->stream);
+  free_all(h);
+  delete h;
+}
+
+int augur_lda_step_sample_z(augur_lda* h) {
+  AUGUR_CHECK_HANDLE(h);
+  return launch_sample_z(h, (uint32_t)(h->sweep + 1));
+}
+int augur_lda_step_count(augur_lda* h) {
+  AUGUR_CHECK_HANDLE(h);
+  return launch_count(h);
+}
+int augur_lda_step_resample_theta(augur_lda* h) {
+  AUGUR_CHECK_HANDLE(h);
+  return launch_theta(h, (uint32_t)(h->sweep + 1));
+}
+int augur_lda_step_resample_phi(augur_lda* h) {
+  AUGUR_CHECK_HANDLE(h);
+  return launch_phi(h, (uint32_t)(h->sweep + 1));
+}
+int augur_lda_step_finish(augur_lda* h) {
+  AUGUR_REQUIRE(h != nullptr, "handle is NULL");
+  h->sweep += 1;
+  return AUGUR_OK;
+}
+
+int augur_lda_sweep(augur_lda* h, int32_t n_sweeps) {
+  AUGUR_CHECK_HANDLE(h);
+  AUGUR_REQUIRE(n_sweeps >= 0, "n_sweeps = %d is negative", n_sweeps);
+  for (int32_t s = 0; s < n_sweeps; ++s) {
+    const uint32_t t = (uint32_t)(h->sweep + 1);
+    AUGUR_TRY(launch_sample_z(h, t));
+    AUGUR_TRY(launch_count(h));
+    AUGUR_TRY(launch_theta(h, t));
+    AUGUR_TRY(launch_phi(h, t));
+    h->sweep += 1;
+  }
+  return AUGUR_OK;
+}
+
+int augur_lda_sweep_profile(augur_lda* h, int32_t n_sweeps, double* ms) {
+  AUGUR_CHECK_HANDLE(h);
+  AUGUR_REQUIRE(n_sweeps >= 0 && ms != nullptr, "bad arguments");
+  for (int i = 0; i < AUGUR_LDA_NSTEPS; ++i) ms[i] = 0.0;
+  AUGUR_HIP_TRY(hipStreamSynchronize(h->stream));
+  for (int32_t s = 0; s < n_sweeps; ++s) {
+    const uint32_t t = (uint32_t)(h->sweep + 1);
+    AUGUR_HIP_TRY(hipEventRecord(h->ev[0], h->stream));
+    AUGUR_TRY(launch_sample_z(h, t));
+    AUGUR_HIP_TRY(hipEventRecord(h->ev[1], h->stream));
+    AUGUR_TRY(launch_count(h));
+    AUGUR_HIP_TRY(hipEventRecord(h->ev[2], h->stream));
+    AUGUR_TRY(launch_theta(h, t));
+    AUGUR_HIP_TRY(hipEventRecord(h->ev[3], h->stream));
+    AUGUR_TRY(launch_phi(h, t));
+    AUGUR_HIP_TRY(hipEventRecord(h->ev[4], h->stream));
+    AUGUR_HIP_TRY(hipEventSynchronize(h->ev[4]));
+    for (int i = 0; i < 4; ++i) {
+      float x = 0.f;
+      AUGUR_HIP_TRY(hipEventElapsedTime(&x, h->ev[i], h->ev[i + 1]));
+      ms[i] += (double)x;
+    }
+    float x = 0.f;
+    AUGUR_HIP_TRY(hipEventElapsedTime(&x, h->ev[0], h->ev[4]));
+    ms[4] += (double)x;
+    h->sweep += 1;
+  }
+  return AUGUR_OK;
+}
+
+int augur_lda_loglik(augur_lda* h, double* log_joint, double* log_marginal_w) {
+  AUGUR_CHECK_HANDLE(h);
+  const int D = h->cfg.D, V = h->cfg.V, K = h->cfg.K;
+  double* p_lik = h->red;
+  double* p_marg = h->red + kRedBlocks;
+  double* p_th = h->red + 2 * kRedBlocks;
+  double* p_ph = h->red + 3 * kRedBlocks;
+  hipLaunchKernelGGL(lda_loglik_tokens_kernel, dim3(kRedBlocks), dim3(256), 0, h->stream, h->w, h->z,
+                     h->doc_off, h->theta, h->phi, D, h->ldk, p_lik, p_marg);
+  hipLaunchKernelGGL(sum_log_kernel, dim3(kRedBlocks), dim3(256), 0, h->stream, h->theta,
+                     (int64_t)D, K, h->ldk, p_th);
+  hipLaunchKernelGGL(sum_log_kernel, dim3(kRedBlocks), dim3(256), 0, h->stream, h->phi, (int64_t)V,
+                     K, h->ldk, p_ph);
+  AUGUR_HIP_TRY(hipGetLastError());
+  std::vector<double> host(4 * kRedBlocks);
+  AUGUR_HIP_TRY(hipMemcpyAsync(host.data(), h->red, sizeof(double) * host.size(),
+                               hipMemcpyDeviceToHost, h->stream));
+  AUGUR_HIP_TRY(hipStreamSynchronize(h->stream));
+  double s[4] = {0, 0, 0, 0};
+  for (int g = 0; g < 4; ++g)
+    for (int i = 0; i < kRedBlocks; ++i) s[g] += host[(size_t)g * kRedBlocks + i];
+  const double a = h->alpha, b = h->beta;
+  const double prior_theta = (double)D * (std::lgamma(K * a) - K * std::lgamma(a)) + (a - 1.0) * s[2];
+  const double prior_phi = (double)K * (std::lgamma(V * b) - V * std::lgamma(b)) + (b - 1.0) * s[3];
+  if (log_joint) *log_joint = prior_theta + prior_phi + s[0];
+  if (log_marginal_w) *log_marginal_w = s[1];
+  unsigned long long deg = 0;
+  AUGUR_TRY(read_counter(h, 0, &deg));
+  if (deg > h->degenerate_reported) {
+    set_error("%llu tokens met a conditional of zero or non-finite mass since the last report",
+              deg - h->degenerate_reported);
+    h->degenerate_reported = deg;
+    return AUGUR_ERR_DEGENERATE;
+  }
+  return AUGUR_OK;
+}
+
+int augur_lda_get_state(augur_lda* h, int32_t* z, float* theta, float* phi, int64_t* sweep) {
+  AUGUR_CHECK_HANDLE(h);
+  if (z && h->N > 0)
+    AUGUR_HIP_TRY(hipMemcpyAsync(z, h->z, sizeof(int32_t) * (size_t)h->N,
+                                 device_ptrs(h) ? hipMemcpyDeviceToDevice : hipMemcpyDeviceToHost,
+                                 h->stream));
+  if (theta) AUGUR_TRY(copy_out(h, theta, h->theta, sizeof(float), h->cfg.D));
+  if (phi) AUGUR_TRY(copy_out(h, phi, h->phi, sizeof(float), h->cfg.V));
+  AUGUR_HIP_TRY(hipStreamSynchronize(h->stream));
+  if (sweep) *sweep = h->sweep;
+  return AUGUR_OK;
+}
+
+int augur_lda_set_state(augur_lda* h, const int32_t* z, const float* theta, const float* phi,
+                        int64_t sweep) {
+  AUGUR_CHECK_HANDLE(h);
+  if (z && h->N > 0) {
+    if (!device_ptrs(h)) {
+      for (int64_t i = 0; i < h->N; ++i)
+        AUGUR_REQUIRE(z[i] >= 0 && z[i] < h->cfg.K, "z[%lld] = %d is outside [0, %d)",
+                      (long long)i, z[i], h->cfg.K);
+    } else {
+      AUGUR_HIP_TRY(hipMemsetAsync(h->counters + 2, 0, sizeof(unsigned long long), h->stream));
+      hipLaunchKernelGGL(check_range_kernel, dim3(1024), dim3(256), 0, h->stream, z, h->N, 0,
+                         h->cfg.K, h->counters + 2);
+      unsigned long long bad = 0;
+      AUGUR_TRY(read_counter(h, 2, &bad));
+      AUGUR_REQUIRE(bad == 0, "%llu entries of z are outside [0, %d)", bad, h->cfg.K);
+    }
+    AUGUR_HIP_TRY(hipMemcpyAsync(h->z, z, sizeof(int32_t) * (size_t)h->N,
+                                 device_ptrs(h) ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice,
+                                 h->stream));
+    AUGUR_TRY(launch_count(h));
+  }
+  if (theta) AUGUR_TRY(copy_in(h, h->theta, theta, sizeof(float), h->cfg.D));
+  if (phi) AUGUR_TRY(copy_in(h, h->phi, phi, sizeof(float), h->cfg.V));
+  AUGUR_HIP_TRY(hipStreamSynchronize(h->stream));
+  if (sweep >= 0) h->sweep = sweep;
+  return AUGUR_OK;
+}
+
+int augur_lda_get_counts(augur_lda* h, int32_t* n_dk, int32_t* n_wk) {
+  AUGUR_CHECK_HANDLE(h);
+  if (n_dk) AUGUR_TRY(copy_out(h, n_dk, h->n_dk, sizeof(int32_t), h->cfg.D));
+  if (n_wk) AUGUR_TRY(copy_out(h, n_wk, h->n_wk, sizeof(int32_t), h->cfg.V));
+  AUGUR_HIP_TRY(hipStreamSynchronize(h->stream));
+  return AUGUR_OK;
+}
+
+int augur_lda_get_degenerate(augur_lda* h, int64_t* count) {
+  AUGUR_CHECK_HANDLE(h);
+  AUGUR_REQUIRE(count != nullptr, "count is NULL");
+  unsigned long long c = 0;
+  AUGUR_TRY(read_counter(h, 0, &c));
+  *count = (int64_t)c;
+  return AUGUR_OK;
+}
+
+int augur_lda_sync(augur_lda* h) {
+  AUGUR_CHECK_HANDLE(h);
+  AUGUR_HIP_TRY(hipStreamSynchronize(h->stream));
+  return AUGUR_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,60 @@
+"""Acceptance rules shared by the GPU parity tests (stated in the benchmark contract):
+integer tables bit-exact; z equal on >= 99.99 % of variables per sweep, every disagreement only
+where the threshold u*S lies within 1e-6 relative of the CDF boundaries that separate the two
+answers; theta/phi/pi/mu and log densities within 1e-5 relative."""
+import numpy as np
+
+from oracle import oracle as O
+
+FLT_MIN = float(np.finfo(np.float32).tiny)
+Z_AGREE = 0.9999
+Z_BOUNDARY_RTOL = 1e-6
+REAL_RTOL = 1e-5
+
+
+def assert_real_close(got, want, what, rtol=REAL_RTOL, floor=FLT_MIN):
+    got = np.asarray(got, dtype=np.float64)
+    want = np.asarray(want, dtype=np.float64)
+    assert got.shape == want.shape, (what, got.shape, want.shape)
+    err = np.abs(got - want)
+    bound = rtol * np.maximum(np.abs(want), floor)
+    bad = np.nonzero(err > bound)
+    assert bad[0].size == 0, (what, bad[0].size, "worst rel", float((err / np.maximum(np.abs(want), floor)).max()))
+
+
+def assert_z_lda(z_gpu, z_orc, doc_off, w, theta, phi, seed, sweep):
+    """theta [D][K], phi [V][K]: the shared state both sides drew from."""
+    z_gpu, z_orc = np.asarray(z_gpu), np.asarray(z_orc)
+    N = z_orc.size
+    K = theta.shape[1]
+    assert z_gpu.shape == z_orc.shape
+    assert N == 0 or (z_gpu.min() >= 0 and z_gpu.max() < K)
+    mism = np.nonzero(z_gpu != z_orc)[0]
+    assert mism.size <= (1.0 - Z_AGREE) * N, f"{mism.size} of {N} z differ"
+    if mism.size == 0:
+        return 0
+    doc_of = np.searchsorted(doc_off, mism, side="right") - 1
+    for i, d in zip(mism, doc_of):
+        cdf, t = O.lda_token_cdf(theta[d], phi[w[i]], seed, int(i), sweep)
+        _assert_boundary(cdf, t, int(z_gpu[i]), int(z_orc[i]), f"token {i}")
+    return mism.size
+
+
+def assert_z_gmm(z_gpu, z_orc, x, pi, mu, sigma, seed, sweep):
+    z_gpu, z_orc = np.asarray(z_gpu), np.asarray(z_orc)
+    N = z_orc.size
+    assert z_gpu.min() >= 0 and z_gpu.max() < pi.size
+    mism = np.nonzero(z_gpu != z_orc)[0]
+    assert mism.size <= (1.0 - Z_AGREE) * N, f"{mism.size} of {N} z differ"
+    for i in mism:
+        cdf, t = O.gmm_point_cdf(x[i], pi, mu, sigma, seed, int(i), sweep)
+        _assert_boundary(cdf, t, int(z_gpu[i]), int(z_orc[i]), f"point {i}")
+    return mism.size
+
+
+def _assert_boundary(cdf, t, zg, zo, what):
+    lo, hi = min(zg, zo), max(zg, zo)
+    between = cdf[lo:hi]                       # boundaries C_lo .. C_{hi-1} separate the answers
+    assert (np.abs(t - between) <= Z_BOUNDARY_RTOL * between).all(), (what, zg, zo, t, between)
+    prev = cdf[zg - 1] if zg > 0 else 0.0
+    assert cdf[zg] > prev, (what, "GPU chose a topic of zero mass", zg)

@@ -1,0 +1,109 @@
+"""GPU parity of the Gaussian-mixture sweep against the oracle, step by step from a shared state."""
+import numpy as np
+import pytest
+
+from oracle import oracle as O
+from paper_1312_3613_amd import synth
+from tests import parity as P
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_1312_3613_amd import binding
+    binding.lib()
+    return binding
+
+
+def lockstep(g, o, check_loglik=True):
+    t = o.sweep_index + 1
+    pi0, mu0 = o.pi.copy(), o.mu.copy()
+    g.set_state(z=o.z, pi=o.pi, mu=o.mu, sweep=o.sweep_index)
+    g.step_sample_z(); o.step_sample_z()
+    zg = g.get_state()[0]
+    nm = P.assert_z_gmm(zg, o.z, o.x, pi0, mu0, o.sigma, o.seed, t)
+    g.set_state(z=o.z)
+    g.step_stats(); o.step_stats()
+    n_k, s_k = g.get_stats()
+    assert np.array_equal(n_k, o.n_k)
+    assert np.allclose(s_k, o.s_k, rtol=1e-12, atol=1e-9)
+    g.step_resample(); o.step_resample()
+    _, pi, mu, _ = g.get_state()
+    P.assert_real_close(pi, o.pi, "pi")
+    lam = 1.0 / o.prior_sd ** 2 + o.n_k / o.sigma ** 2
+    err = np.abs(mu.astype(np.float64) - o.mu)
+    assert (err <= P.REAL_RTOL * np.maximum(np.abs(o.mu), (lam ** -0.5)[:, None])).all()
+    g.step_finish(); o.step_finish()
+    if check_loglik:
+        g.set_state(pi=o.pi, mu=o.mu)
+        lj, olj = g.loglik(), o.loglik()
+        assert abs(lj - olj) <= P.REAL_RTOL * abs(olj)
+    return nm
+
+
+def test_gmm_initial_state_and_lockstep(B):
+    cfg = dict(synth.GMM_CONFIG, N=50_001)
+    d = synth.gmm_points(**cfg)
+    g = B.GMM(cfg["K"], cfg["alpha"], cfg["prior_sd"], cfg["sigma"], 21, d["x"])
+    o = O.OracleGMM(cfg["K"], cfg["alpha"], cfg["prior_sd"], cfg["sigma"], 21, d["x"])
+    z, pi, mu, sw = g.get_state()
+    assert sw == 0 and np.array_equal(z, o.z)
+    P.assert_real_close(pi, o.pi, "pi0")
+    n_k, s_k = g.get_stats()
+    assert np.array_equal(n_k, o.n_k) and np.allclose(s_k, o.s_k, rtol=1e-12, atol=1e-9)
+    total = sum(lockstep(g, o) for _ in range(10))
+    print("gmm: z mismatches over 10 sweeps", total)
+    assert g.get_degenerate() == 0
+    g.close()
+
+
+@pytest.mark.parametrize("N,dim,K", [(1, 1, 1), (5, 3, 2), (1023, 8, 16), (1025, 2, 5), (4099, 14, 33)])
+def test_gmm_shapes(B, N, dim, K):
+    d = synth.gmm_points(N=N, dim=dim, K=K, seed=N + K)
+    g = B.GMM(K, 1.0, 10.0, 1.0, 5, d["x"])
+    o = O.OracleGMM(K, 1.0, 10.0, 1.0, 5, d["x"])
+    for _ in range(3):
+        lockstep(g, o)
+    g.close()
+
+
+def test_gmm_full_config_free_running_and_resume(B):
+    cfg = synth.GMM_CONFIG
+    d = synth.gmm_points(return_truth=True, **cfg)
+    args = (cfg["K"], cfg["alpha"], cfg["prior_sd"], cfg["sigma"], cfg["seed"], d["x"])
+    g, o = B.GMM(*args), O.OracleGMM(*args)
+    lockstep(g, o)
+    lockstep(g, o)
+    a, b = B.GMM(*args), B.GMM(*args)
+    a.sweep(6)
+    b.sweep(3)
+    st = b.get_state()
+    r = B.GMM(*args)
+    r.set_state(*st)
+    r.sweep(3)
+    for x, y in zip(a.get_state(), r.get_state()):
+        assert np.array_equal(x, y)
+    # statistics invariants at full size
+    n_k, s_k = a.get_stats()
+    assert n_k.sum() == cfg["N"]
+    assert np.allclose(s_k.sum(0), d["x"].astype(np.float64).sum(0), rtol=1e-10)
+    for h in (g, a, b, r):
+        h.close()
+
+
+def test_gmm_degenerate_and_errors(B):
+    d = synth.gmm_points(N=100, dim=2, K=3, seed=1)
+    g = B.GMM(3, 1.0, 10.0, 1.0, 5, d["x"])
+    o = O.OracleGMM(3, 1.0, 10.0, 1.0, 5, d["x"])
+    pi = np.array([np.nan, 0.5, 0.5], dtype=np.float32)
+    o.set_state(pi=pi)
+    g.set_state(z=o.z, pi=pi, mu=o.mu)
+    g.step_sample_z(); o.step_sample_z()
+    assert np.array_equal(g.get_state()[0], o.z)
+    assert g.get_degenerate() == 100 == o.degenerate
+    with pytest.raises(B.AugurError):
+        g.set_state(z=np.full(100, 3, dtype=np.int32))
+    with pytest.raises(B.AugurError):
+        B.GMM(3, -1.0, 10.0, 1.0, 5, d["x"])
+    g.close()

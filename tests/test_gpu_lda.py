@@ -1,0 +1,248 @@
+"""GPU parity of the LDA sweep: the HIP path (through the C ABI) against the oracle, element by
+element, from the same state and the same random streams."""
+import ctypes as C
+
+import numpy as np
+import pytest
+
+from oracle import oracle as O
+from paper_1312_3613_amd import synth
+from tests import parity as P
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_1312_3613_amd import binding
+    binding.lib()
+    return binding
+
+
+def ragged_corpus(D, V, K, seed, lens=None, mean_len=40):
+    rng = np.random.default_rng(seed)
+    if lens is None:
+        lens = rng.poisson(mean_len, size=D)
+        special = [0, 1, 3, 4, 5, 255, 256, 257, 0, 600]
+        lens[:len(special)] = special[:D]
+    lens = np.asarray(lens, dtype=np.int32)
+    zipf = (np.arange(1, V + 1) ** -1.1)
+    w = rng.choice(V, size=int(lens.sum()), p=zipf / zipf.sum()).astype(np.int32)
+    return lens, w
+
+
+def make_pair(B, D, V, K, alpha, beta, seed, lens, w, **kw):
+    g = B.LDA(D, V, K, alpha, beta, seed, lens, w, **kw)
+    o = O.OracleLDA(D, V, K, alpha, beta, seed, lens, w)
+    return g, o
+
+
+def np_(a):
+    return a.cpu().numpy() if hasattr(a, "cpu") else a
+
+
+def lockstep_sweep(g, o, check_loglik=False):
+    """One sweep, both sides restarted from the oracle's state before every step."""
+    t = o.sweep_index + 1
+    theta0, phi0 = o.theta.copy(), o.phi.copy()
+    g.set_state(z=o.z, theta=o.theta, phi=o.phi, sweep=o.sweep_index)
+    g.step_sample_z(); o.step_sample_z()
+    zg = np_(g.get_state(theta=False, phi=False)[0])
+    nm = P.assert_z_lda(zg, o.z, o.doc_off, o.w, theta0, phi0, o.seed, t)
+    g.set_state(z=o.z)                        # identical z from here on
+    g.step_count(); o.step_count()
+    n_dk, n_wk = (np_(a) for a in g.get_counts())
+    assert np.array_equal(n_dk, o.n_dk) and np.array_equal(n_wk, o.n_wk)
+    g.step_resample_theta(); o.step_resample_theta()
+    g.step_resample_phi(); o.step_resample_phi()
+    _, th, ph, _ = g.get_state(z=False)
+    P.assert_real_close(np_(th), o.theta, "theta")
+    P.assert_real_close(np_(ph), o.phi, "phi")
+    g.step_finish(); o.step_finish()
+    if check_loglik:
+        g.set_state(theta=o.theta, phi=o.phi)
+        lj, lm = g.loglik()
+        olj, olm = o.loglik()
+        assert abs(lj - olj) <= P.REAL_RTOL * abs(olj) and abs(lm - olm) <= P.REAL_RTOL * abs(olm)
+    return nm
+
+
+def test_initial_state_matches_oracle(B):
+    cfg = synth.LDA_CONFIGS["tiny"]
+    c = synth.lda_corpus(**cfg)
+    g, o = make_pair(B, cfg["D"], cfg["V"], cfg["K"], cfg["alpha"], cfg["beta"], 11, c["doc_len"], c["w"])
+    z, th, ph, sw = g.get_state()
+    assert sw == 0 and np.array_equal(z, o.z)
+    n_dk, n_wk = g.get_counts()
+    assert np.array_equal(n_dk, o.n_dk) and np.array_equal(n_wk, o.n_wk)
+    P.assert_real_close(th, o.theta, "theta0")
+    P.assert_real_close(ph, o.phi, "phi0")
+    g.close()
+
+
+def test_tiny_config_twenty_lockstep_sweeps(B):
+    cfg = synth.LDA_CONFIGS["tiny"]
+    c = synth.lda_corpus(**cfg)
+    g, o = make_pair(B, cfg["D"], cfg["V"], cfg["K"], cfg["alpha"], cfg["beta"], cfg["seed"],
+                     c["doc_len"], c["w"])
+    total = 0
+    for s in range(cfg["sweeps"]):
+        total += lockstep_sweep(g, o, check_loglik=(s % 5 == 4))
+    assert o.sweep_index == 20 and g.get_state(False, False, False)[3] == 20
+    assert g.get_degenerate() == 0 and o.degenerate == 0
+    print("tiny: z mismatches over 20 sweeps:", total)
+    g.close()
+
+
+def test_tiny_config_free_running(B):
+    cfg = synth.LDA_CONFIGS["tiny"]
+    c = synth.lda_corpus(**cfg)
+    g, o = make_pair(B, cfg["D"], cfg["V"], cfg["K"], cfg["alpha"], cfg["beta"], cfg["seed"],
+                     c["doc_len"], c["w"])
+    g.sweep(20); o.sweep(20)
+    z, th, ph, sw = g.get_state()
+    assert sw == 20
+    # chains may part ways after a single boundary decision; they must stay statistically alike
+    agree = (z == o.z).mean()
+    lj, lm = g.loglik()
+    olj, olm = o.loglik()
+    print("free-running agreement", agree, lm, olm)
+    assert agree > 0.9 and abs(lm - olm) < 0.02 * abs(olm)
+    n_dk, n_wk = g.get_counts()
+    assert (n_dk.sum(1) == c["doc_len"]).all() and n_wk.sum() == c["N"]
+    g.close()
+
+
+@pytest.mark.parametrize("K", [1, 2, 7, 10, 64, 65, 100, 200, 257, 1000, 1024])
+def test_topic_counts_span_stripes_and_tails(B, K):
+    D, V = 40, 300
+    lens, w = ragged_corpus(D, V, K, seed=K)
+    g, o = make_pair(B, D, V, K, 0.1, 0.01, 1000 + K, lens, w)
+    z0 = g.get_state(theta=False, phi=False)[0]
+    assert np.array_equal(z0, o.z)
+    for _ in range(2):
+        lockstep_sweep(g, o, check_loglik=True)
+    g.close()
+
+
+def test_dense_parameters_many_live_topics(B):
+    # alpha = beta = 1: every topic carries mass, the hard case for fp32 running sums
+    D, V, K = 64, 500, 200
+    lens, w = ragged_corpus(D, V, K, seed=5, mean_len=300)
+    g, o = make_pair(B, D, V, K, 1.0, 1.0, 77, lens, w)
+    for _ in range(3):
+        lockstep_sweep(g, o)
+    g.close()
+
+
+def test_edge_corpora(B):
+    # one token; all documents empty; V = 1
+    for lens, w, V, K in [([1], [2], 5, 3), ([0, 0, 0], [], 4, 3), ([3, 0, 2], [0, 0, 0, 0, 0], 1, 4)]:
+        lens, w = np.array(lens, dtype=np.int32), np.array(w, dtype=np.int32)
+        g, o = make_pair(B, len(lens), V, K, 0.5, 0.5, 3, lens, w)
+        lockstep_sweep(g, o, check_loglik=w.size > 0)
+        g.sweep(2); o.sweep(2)
+        g.close()
+
+
+def test_zero_mass_topics_and_degenerate_rows(B):
+    D, V, K = 6, 50, 12
+    lens, w = ragged_corpus(D, V, K, seed=9, lens=[40, 40, 40, 40, 40, 40])
+    g, o = make_pair(B, D, V, K, 0.1, 0.1, 5, lens, w)
+    theta = o.theta.copy()
+    theta[:, 3] = 0.0            # a topic of zero mass everywhere
+    theta[1, :] = 0.0            # a document whose conditional has no mass at all
+    theta[2, :] = np.nan
+    o.set_state(theta=theta)
+    g.set_state(z=o.z, theta=theta, phi=o.phi, sweep=o.sweep_index)
+    g.step_sample_z(); o.step_sample_z()
+    zg = g.get_state(theta=False, phi=False)[0]
+    assert np.array_equal(zg, o.z)
+    live = np.r_[0:40, 120:240]
+    assert (zg[live] != 3).all()
+    assert g.get_degenerate() == 80 == o.degenerate
+    lj = C.c_double()
+    assert B.lib().augur_lda_loglik(g._h, C.byref(lj), None) == B.ERR_DEGENERATE
+    assert "zero or non-finite" in B.last_error()
+    assert B.lib().augur_lda_loglik(g._h, C.byref(lj), None) == B.OK     # reported once
+    g.close()
+
+
+def test_resume_is_bit_exact_and_deterministic(B):
+    cfg = dict(synth.LDA_CONFIGS["tiny"], D=60, V=200, K=20)
+    c = synth.lda_corpus(**cfg)
+    args = (cfg["D"], cfg["V"], cfg["K"], cfg["alpha"], cfg["beta"], 4242, c["doc_len"], c["w"])
+    a, b = B.LDA(*args), B.LDA(*args)
+    a.sweep(10)
+    b.sweep(5)
+    z, th, ph, sw = b.get_state()
+    r = B.LDA(*args)
+    r.set_state(z, th, ph, sw)
+    r.sweep(5)
+    for x, y in zip(a.get_state(), r.get_state()):
+        assert np.array_equal(x, y)
+    for x, y in zip(a.get_counts(), r.get_counts()):
+        assert np.array_equal(x, y)
+    assert a.loglik() == r.loglik()
+    for h in (a, b, r):
+        h.close()
+
+
+def test_device_pointer_mode_and_stream(B):
+    import torch
+    cfg = dict(synth.LDA_CONFIGS["tiny"], D=50, V=120, K=10)
+    c = synth.lda_corpus(**cfg)
+    args = (cfg["D"], cfg["V"], cfg["K"], cfg["alpha"], cfg["beta"], 99)
+    host = B.LDA(*args, c["doc_len"], c["w"])
+    stream = torch.cuda.Stream()
+    dev = B.LDA(*args, torch.as_tensor(c["doc_len"]).cuda(), torch.as_tensor(c["w"]).cuda(),
+                stream=stream, device_ptrs=True)
+    host.sweep(4); dev.sweep(4)
+    for x, y in zip(host.get_state(), dev.get_state()):
+        assert np.array_equal(np_(x), np_(y))
+    for x, y in zip(host.get_counts(), dev.get_counts()):
+        assert np.array_equal(x, np_(y))
+    z, th, ph, sw = dev.get_state()
+    assert z.is_cuda and th.shape == (cfg["D"], cfg["K"])
+    dev.set_state(z=z, theta=th, phi=ph, sweep=sw)
+    bad = z.clone(); bad[0] = cfg["K"]
+    with pytest.raises(B.AugurError):
+        dev.set_state(z=bad)
+    host.close(); dev.close()
+
+
+def test_invalid_inputs_are_rejected(B):
+    lens = np.array([2, 2], dtype=np.int32)
+    with pytest.raises(B.AugurError) as e:
+        B.LDA(2, 5, 3, 0.1, 0.1, 1, lens, np.array([0, 1, 5, 2], dtype=np.int32))
+    assert e.value.code == B.ERR_INVALID_ARG and "outside" in str(e.value)
+    with pytest.raises(B.AugurError):
+        B.LDA(2, 5, 3, 0.1, 0.1, 1, np.array([2, -1], dtype=np.int32), np.array([0], dtype=np.int32))
+    with pytest.raises(B.AugurError):
+        B.LDA(2, 5, 2000, 0.1, 0.1, 1, lens, np.array([0, 1, 2, 3], dtype=np.int32))
+    g = B.LDA(2, 5, 3, 0.1, 0.1, 1, lens, np.array([0, 1, 4, 2], dtype=np.int32))
+    with pytest.raises(B.AugurError):
+        g.set_state(z=np.array([0, 1, 3, 0], dtype=np.int32))
+    with pytest.raises(B.AugurError):
+        g.sweep(-1)
+    g.close()
+
+
+def test_medium_config_full_parity(B):
+    cfg = synth.LDA_CONFIGS["medium"]
+    c = synth.lda_corpus(**cfg)
+    g, o = make_pair(B, cfg["D"], cfg["V"], cfg["K"], cfg["alpha"], cfg["beta"], cfg["seed"],
+                     c["doc_len"], c["w"])
+    assert np.array_equal(g.get_state(theta=False, phi=False)[0], o.z)
+    nm = [lockstep_sweep(g, o, check_loglik=(s == 1)) for s in range(2)]
+    print("medium: z mismatches per sweep", nm, "of", c["N"])
+    # a few more sweeps the way the benchmark runs them, then invariants at this size
+    g.sweep(3)
+    n_dk, n_wk = g.get_counts()
+    assert (n_dk.sum(1) == c["doc_len"]).all()
+    assert (n_wk.sum(1) == np.bincount(c["w"], minlength=cfg["V"])).all()
+    assert (n_dk.sum(0) == n_wk.sum(0)).all()
+    z, th, ph, sw = g.get_state()
+    assert sw == 5 and np.abs(th.astype(np.float64).sum(1) - 1).max() < 1e-5
+    assert np.abs(ph.astype(np.float64).sum(0) - 1).max() < 1e-4 and th.min() > 0 and ph.min() > 0
+    g.close()
