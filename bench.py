@@ -1,0 +1,138 @@
+#!/usr/bin/env python3
+"""Benchmark of the LDA Gibbs sweep on one MI355X.
+
+A step is one whole sweep (sample_z, count_accumulate, resample theta, resample phi) over a
+synthetic corpus that is already resident in HBM.  Prints ONE JSON line: whole-sweep tokens/s,
+the HBM-roofline figures of the dominant kernel (sample_z) from HIP events recorded on the
+library's stream inside the timed region, and the oracle's throughput on this machine's host cores
+(bounded sample) as cpu_baseline.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+
+# HBM bytes per sample_z launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see
+# profiles/), scaled by the copy-kernel factor; None until measured for that workload.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def sample_z_algorithmic_bytes(N, D, K):
+    """Per launch: every token reads its word id, its phi row and writes z; every document reads
+    its theta row and its two offsets."""
+    return N * (8 + 4 * K) + D * (4 * K + 8)
+
+
+def cpu_baseline(cfg, corpus, budget_s=20.0):
+    """Oracle sweeps on a bounded sample of the same corpus (its first documents, full
+    vocabulary), single thread."""
+    import numpy as np
+    from oracle import oracle as O
+    target_tokens = 1_500_000 if cfg["K"] <= 256 else 300_000
+    doc_len = corpus["doc_len"]
+    cum = np.cumsum(doc_len.astype(np.int64))
+    nd = int(min(len(doc_len), np.searchsorted(cum, target_tokens) + 1))
+    ntok = int(cum[nd - 1])
+    o = O.OracleLDA(nd, cfg["V"], cfg["K"], cfg["alpha"], cfg["beta"], cfg["seed"], doc_len[:nd],
+                    corpus["w"][:ntok])
+    sweeps, t0 = 0, time.perf_counter()
+    while True:
+        o.sweep(1)
+        sweeps += 1
+        el = time.perf_counter() - t0
+        if sweeps >= 2 and (el > budget_s / 2 or sweeps >= 5):
+            break
+    return {"value": ntok * sweeps / el, "unit": "tokens/s", "cores": 1, "kind": "oracle",
+            "sample": f"first {nd} documents ({ntok} tokens) of the same corpus, full V={cfg['V']} "
+                      f"and K={cfg['K']}, {sweeps} whole sweeps, single thread of {os.cpu_count()} visible"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="large", choices=["tiny", "medium", "large", "widek"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_1312_3613_amd import binding as B, synth
+
+    cfg = synth.LDA_CONFIGS[args.workload]
+    steps = args.steps if args.steps is not None else cfg["sweeps"]
+    t0 = time.perf_counter()
+    corpus = synth.lda_corpus(**cfg)
+    t_gen = time.perf_counter() - t0
+    N, D, V, K = corpus["N"], cfg["D"], cfg["V"], cfg["K"]
+
+    torch.cuda.set_device(0)
+    stream = torch.cuda.Stream()
+    doc_len_d = torch.as_tensor(corpus["doc_len"]).cuda()
+    w_d = torch.as_tensor(corpus["w"]).cuda()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    h = B.LDA(D, V, K, cfg["alpha"], cfg["beta"], cfg["seed"], doc_len_d, w_d, stream=stream,
+              device_ptrs=True)
+    t_create = time.perf_counter() - t0
+
+    h.sweep(args.warmup)
+    h.sync()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ms = h.sweep_profile(steps)  # the timed region; HIP events on the library's stream inside
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    lj, lm = h.loglik()
+    degenerate = h.get_degenerate()
+    h.close()
+
+    t_z = ms["sample_z"] / steps * 1e-3
+    bytes_z = sample_z_algorithmic_bytes(N, D, K)
+    achieved = bytes_z / t_z / 1e9
+    traffic = MEASURED_TRAFFIC_BYTES.get(args.workload)
+    out = {
+        "metric": "Gibbs sweep tokens/sec (LDA K=100/200) + achieved HBM GB/s vs peak",
+        "value": N * steps / elapsed,
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": steps,
+        "warmup": args.warmup,
+        "ms_per_step": elapsed / steps * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"LDA {args.workload}: D={D} V={V} K={K} N={N} alpha={cfg['alpha']} "
+                               f"beta={cfg['beta']}, corpus from the LDA generative process "
+                               f"(seed {cfg['seed']}), inputs resident in HBM"},
+        "roofline": {"bound": "hbm", "kernel": "lda_sample_z", "achieved": achieved,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": traffic, "algorithmic_bytes_per_launch": bytes_z,
+                     "avg_launch_ms": t_z * 1e3},
+        "kernel_ms_per_sweep": {k: v / steps for k, v in ms.items()},
+        "log_marginal_per_token": lm / max(N, 1),
+        "degenerate_tokens": degenerate,
+        "setup_s": {"generate_corpus": t_gen, "create": t_create},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, corpus)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -79,7 +79,8 @@ int augur_lda_sweep(augur_lda* h, int32_t n_sweeps);
 /* Same as sweep, but brackets each step with events on the handle's stream and
  * returns the summed device time of each step over the n_sweeps, in ms:
  * ms[0] sample_z, ms[1] count_accumulate, ms[2] resample theta, ms[3] resample
- * phi, ms[4] whole loop.  Synchronises. */
+ * phi, ms[4] whole sweep (first event to last).  Events are recorded without host waits;
+ * the call synchronises once at the end.  n_sweeps <= 4096. */
 #define AUGUR_LDA_NSTEPS 5
 int augur_lda_sweep_profile(augur_lda* h, int32_t n_sweeps, double* ms);
 

@@ -57,17 +57,18 @@ enum : uint32_t {
 
 struct U4 { uint32_t x, y, z, w; };
 
-// Philox4x32 with ten rounds (Salmon, Moraes, Dror, Shaw; SC'11).
+// Philox4x32 with ten rounds (Salmon, Moraes, Dror, Shaw; SC'11).  Each round
+// needs two full 32x32->64 products.
 __device__ __forceinline__ U4 philox10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
                                        uint32_t k0, uint32_t k1) {
 #pragma unroll
   for (int r = 0; r < 10; ++r) {
-    const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
-    const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
-    c0 = hi1 ^ c1 ^ k0;
-    c1 = lo1;
-    c2 = hi0 ^ c3 ^ k1;
-    c3 = lo0;
+    const uint64_t p0 = (uint64_t)0xD2511F53u * (uint64_t)c0;
+    const uint64_t p1 = (uint64_t)0xCD9E8D57u * (uint64_t)c2;
+    c0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+    c1 = (uint32_t)p1;
+    c2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+    c3 = (uint32_t)p0;
     k0 += 0x9E3779B9u;
     k1 += 0xBB67AE85u;
   }
@@ -102,35 +103,50 @@ __device__ __forceinline__ double normal_from(const U4& b) {
 
 constexpr int kGammaAttemptCap = 64;
 
-// ln of a Gamma(a,1) draw by Marsaglia & Tsang's squeeze-rejection method
-// (2000), fp64: d = a' - 1/3, c = 1/sqrt(9 d), v = (1 + c x)^3 with x normal;
-// accept if U < 1 - 0.0331 x^4 or ln U < x^2/2 + d (1 - v + ln v); a < 1 draws
-// for a' = a + 1 and adds ln(U')/a.  Attempt j of the variable reads Philox
-// block j (words: x from 0 and 1, U from 2, U' from 3).  `capped` is raised if
-// the attempt cap is reached.
+// Gamma(a,1) draws in the log domain by Marsaglia & Tsang's squeeze-rejection
+// method (2000), fp64: d = a' - 1/3, c = 1/sqrt(9 d), v = (1 + c x)^3 with x
+// normal; accept if U < 1 - 0.0331 x^4 or ln U < x^2/2 + d (1 - v + ln v); the
+// draw is d v.  a < 1 draws for a' = a + 1 and multiplies by U'^(1/a).  Attempt
+// j of a variable reads Philox block j (x from words 0 and 1, U from 2, U' from
+// 3).  Split into per-variable constants and a single attempt so that callers
+// can let every lane retry on its own variable instead of waiting for the
+// slowest lane of the wave.
+struct GammaShape {
+  double a, d, c, ln_d;
+};
+__device__ __forceinline__ GammaShape gamma_shape(double a) {
+  GammaShape g;
+  g.a = a;
+  g.d = (a < 1.0 ? a + 1.0 : a) - 1.0 / 3.0;
+  g.c = 1.0 / sqrt(9.0 * g.d);
+  g.ln_d = log(g.d);
+  return g;
+}
+// One attempt; on acceptance writes ln(draw) and returns true.
+__device__ __forceinline__ bool gamma_attempt(const GammaShape& g, const U4& b, double& lg) {
+  const double x = normal_from(b);
+  const double t = 1.0 + g.c * x;
+  const double v = t * t * t;
+  const double U = u32d(b.z);
+  const double x2 = x * x;
+  const double lv = log(fabs(v));  // only used when t > 0
+  bool accept = U < 1.0 - 0.0331 * x2 * x2;
+  if (!accept) accept = log(U) < 0.5 * x2 + g.d * (1.0 - v + lv);
+  accept = accept && t > 0.0;
+  lg = g.ln_d + lv;
+  if (g.a < 1.0) lg += log(u32d(b.w)) / g.a;
+  return accept;
+}
+// Loop form: attempts until accepted.  `capped` is raised if the cap is reached.
 __device__ __forceinline__ double gamma_log_draw(double a, uint64_t seed, uint64_t index,
                                                  uint32_t sweep, uint32_t stream, bool& capped) {
-  const bool boost = a < 1.0;
-  const double a1 = boost ? a + 1.0 : a;
-  const double d = a1 - 1.0 / 3.0;
-  const double c = 1.0 / sqrt(9.0 * d);
+  const GammaShape g = gamma_shape(a);
   for (uint32_t j = 0; j < (uint32_t)kGammaAttemptCap; ++j) {
-    const U4 b = random_block(seed, index, sweep, stream, j);
-    const double x = normal_from(b);
-    const double t = 1.0 + c * x;
-    if (t <= 0.0) continue;
-    const double v = t * t * t;
-    const double U = u32d(b.z);
-    const double x2 = x * x;
-    const double lv = log(v);
-    if (U < 1.0 - 0.0331 * x2 * x2 || log(U) < 0.5 * x2 + d * (1.0 - v + lv)) {
-      double lg = log(d) + lv;
-      if (boost) lg += log(u32d(b.w)) / a;
-      return lg;
-    }
+    double lg;
+    if (gamma_attempt(g, random_block(seed, index, sweep, stream, j), lg)) return lg;
   }
   capped = true;
-  return log(d);
+  return g.ln_d;
 }
 
 // --------------------------------------------------------------- wave helpers

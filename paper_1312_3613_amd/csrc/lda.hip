@@ -7,7 +7,12 @@
 //   doc_off   int64[D+1]
 //   theta     float[D][ldk]     n_dk int32[D][ldk]
 //   phi       float[V][ldk]     n_wk int32[V][ldk]
+//   perm      int32[N]     token indices sorted by word (built once: w never changes)
+//   word_off  int32[V+1]   start of each word's run in perm
+//   slice_base int32[V+1]  first slice id of each word (a word's run is cut into slices)
 #include "common.hpp"
+
+#include <hipcub/hipcub.hpp>
 
 #include <algorithm>
 #include <new>
@@ -28,6 +33,11 @@ __device__ __forceinline__ float dpp_f32(float x) {  // out-of-row sources read 
       float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xF, 0xF, true));
 }
 template <int CTRL>
+__device__ __forceinline__ float dpp_mov_f32(float x) {  // plain move, out-of-row sources read 0
+  return __builtin_bit_cast(float,
+                            __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, x), CTRL, 0xF, 0xF, true));
+}
+template <int CTRL>
 __device__ __forceinline__ int dpp_i32_keep(int x) {  // out-of-row sources keep x
   return __builtin_amdgcn_update_dpp(x, x, CTRL, 0xF, 0xF, false);
 }
@@ -35,13 +45,6 @@ constexpr int kRowShr1 = 0x111, kRowShr2 = 0x112, kRowShr4 = 0x114, kRowShr8 = 0
 constexpr int kRowRor1 = 0x121, kRowRor2 = 0x122, kRowRor4 = 0x124, kRowRor8 = 0x128;
 constexpr int kRowBcast15 = 0x15F;  // lane 15 of the row to the whole row
 
-__device__ __forceinline__ float row_inclusive_scan(float x) {
-  x += dpp_f32<kRowShr1>(x);
-  x += dpp_f32<kRowShr2>(x);
-  x += dpp_f32<kRowShr4>(x);
-  x += dpp_f32<kRowShr8>(x);
-  return x;
-}
 __device__ __forceinline__ int row_allreduce_min(int x) {
   x = min(x, dpp_i32_keep<kRowRor8>(x));
   x = min(x, dpp_i32_keep<kRowRor4>(x));
@@ -102,6 +105,10 @@ __global__ __launch_bounds__(256) void lda_sample_z_kernel(
   if (d >= D) return;
   const int row = lane >> 4, j = lane & 15;
 
+  // theta_d in registers; chunks past the last topic hold 0.  Every lane's byte
+  // offset inside a phi row is fixed: full stripes sit 256 B apart, and the last
+  // stripe's lanes beyond the row are pointed at the row's last chunk (their
+  // theta is 0), so all loads are unconditional and stay inside the row.
   float4 th[NS];
 #pragma unroll
   for (int m = 0; m < NS; ++m) {
@@ -109,6 +116,10 @@ __global__ __launch_bounds__(256) void lda_sample_z_kernel(
     th[m] = col < ldk ? *reinterpret_cast<const float4*>(theta + (size_t)d * ldk + col)
                       : make_float4(0.f, 0.f, 0.f, 0.f);
   }
+  const uint32_t lane_off = 16u * (uint32_t)j;
+  const uint32_t last_off = 4u * (uint32_t)min(64 * (NS - 1) + 4 * j, ldk - 4);
+  const char* phi_bytes = reinterpret_cast<const char*>(phi);
+  const uint32_t row_bytes = 4u * (uint32_t)ldk;
 
   const int64_t a = doc_off[d], b = doc_off[d + 1];
   for (int64_t base = a & ~(int64_t)3; base < b; base += 256) {
@@ -123,32 +134,41 @@ __global__ __launch_bounds__(256) void lda_sample_z_kernel(
     for (int64_t i0 = lo; i0 < hi; i0 += 4) {
       const int64_t i = i0 + row;
       const bool valid = i < hi;
-      const int32_t v = valid ? w[i] : 0;
+      const uint32_t v = valid ? (uint32_t)w[i] : 0u;
       const uint32_t r = rnd[wave][valid ? (int)(i - base) : 0];
-      const float* prow = phi + (size_t)v * ldk;
+      const uint32_t row_off = v * row_bytes;  // < 2^32: checked when the handle is created
 
       float4 q[NS];
 #pragma unroll
-      for (int m = 0; m < NS; ++m) {
-        const int col = 64 * m + 4 * j;
-        q[m] = col < ldk ? *reinterpret_cast<const float4*>(prow + col)
-                         : make_float4(0.f, 0.f, 0.f, 0.f);
-      }
+      for (int m = 0; m < NS - 1; ++m)
+        q[m] = *reinterpret_cast<const float4*>(phi_bytes + (row_off + lane_off + 256u * m));
+      q[NS - 1] = *reinterpret_cast<const float4*>(phi_bytes + (row_off + last_off));
 
-      // running sums: l?[m] = lane-local inclusive sums of stripe m, base[m] =
-      // sum of everything before this lane's chunk of stripe m
-      float l0[NS], l1[NS], l2[NS], l3[NS], cbase[NS];
-      float carry = 0.f;
+      // running sums: l?[m] = lane-local inclusive sums of stripe m, cbase[m] =
+      // sum of everything before this lane's chunk of stripe m.  The NS row
+      // scans are independent until the carries, so they are issued side by side.
+      float l0[NS], l1[NS], l2[NS], l3[NS], inc[NS], cbase[NS];
 #pragma unroll
       for (int m = 0; m < NS; ++m) {
         l0[m] = th[m].x * q[m].x;
         l1[m] = fmaf(th[m].y, q[m].y, l0[m]);
         l2[m] = fmaf(th[m].z, q[m].z, l1[m]);
         l3[m] = fmaf(th[m].w, q[m].w, l2[m]);
-        const float incl = row_inclusive_scan(l3[m]);
-        const float excl = dpp_f32<kRowShr1>(incl);
-        cbase[m] = carry + excl;
-        carry += dpp_f32<kRowBcast15>(incl);
+        inc[m] = l3[m];
+      }
+#pragma unroll
+      for (int m = 0; m < NS; ++m) inc[m] += dpp_f32<kRowShr1>(inc[m]);
+#pragma unroll
+      for (int m = 0; m < NS; ++m) inc[m] += dpp_f32<kRowShr2>(inc[m]);
+#pragma unroll
+      for (int m = 0; m < NS; ++m) inc[m] += dpp_f32<kRowShr4>(inc[m]);
+#pragma unroll
+      for (int m = 0; m < NS; ++m) inc[m] += dpp_f32<kRowShr8>(inc[m]);
+      float carry = 0.f;
+#pragma unroll
+      for (int m = 0; m < NS; ++m) {
+        cbase[m] = carry + dpp_mov_f32<kRowShr1>(inc[m]);
+        carry += dpp_mov_f32<kRowBcast15>(inc[m]);
       }
       const float S = carry;
       const float t = u24(r) * S;
@@ -192,13 +212,14 @@ __global__ __launch_bounds__(256) void lda_sample_z_kernel(
 
 // --------------------------------------------------------------- count step
 // Counting phase (Sect. 4.2): n_dk[d][k] = tokens of document d with z = k;
-// n_wk[v][k] = tokens of word v with z = k.  One wave per document builds the
-// document's row in an LDS histogram and stores it whole (no zero-fill of n_dk
-// needed); word counts go to global memory with atomics (n_wk zeroed before).
-__global__ __launch_bounds__(256) void lda_count_kernel(
-    const int32_t* __restrict__ w, const int32_t* __restrict__ z,
-    const int64_t* __restrict__ doc_off, int32_t* __restrict__ n_dk, int32_t* __restrict__ n_wk,
-    int D, int K, int ldk) {
+// n_wk[v][k] = tokens of word v with z = k.  No global atomics: both tables are
+// built from LDS histograms whose owner is fixed by the static structure of the
+// corpus.
+//
+// Documents: one wave per document builds the row in LDS and stores it whole.
+__global__ __launch_bounds__(256) void lda_count_docs_kernel(
+    const int32_t* __restrict__ z, const int64_t* __restrict__ doc_off, int32_t* __restrict__ n_dk,
+    int D, int ldk) {
   extern __shared__ int32_t hist_all[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int d = blockIdx.x * 4 + wave;
@@ -207,46 +228,164 @@ __global__ __launch_bounds__(256) void lda_count_kernel(
   for (int k = lane; k < ldk; k += 64) hist[k] = 0;
   wave_lds_fence();
   const int64_t a = doc_off[d], b = doc_off[d + 1];
-  for (int64_t i = a + lane; i < b; i += 64) {
-    const int32_t zi = z[i];
-    atomicAdd(&hist[zi], 1);
-    atomicAdd(&n_wk[(size_t)w[i] * ldk + zi], 1);
-  }
+  for (int64_t i = a + lane; i < b; i += 64) atomicAdd(&hist[z[i]], 1);
   wave_lds_fence();
   for (int k = lane; k < ldk; k += 64) n_dk[(size_t)d * ldk + k] = hist[k];
+}
+
+// Words: tokens were sorted by word once (perm).  A word's run of tokens is cut
+// into slices; one wave per slice gathers z through perm into an LDS histogram.
+// A word with a single slice stores its row directly; a word with several
+// slices stores one partial row per slice and lda_count_words_merge_kernel adds
+// them.  Every word has at least one slice, so every row is written each sweep.
+__device__ __forceinline__ int word_of_slice(const int32_t* __restrict__ slice_base, int V, int s) {
+  int lo = 0, hi = V;  // largest v with slice_base[v] <= s
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (slice_base[mid] <= s) lo = mid; else hi = mid;
+  }
+  return lo;
+}
+
+__global__ __launch_bounds__(256) void lda_count_words_kernel(
+    const int32_t* __restrict__ z, const int32_t* __restrict__ perm,
+    const int32_t* __restrict__ word_off, const int32_t* __restrict__ slice_base,
+    int32_t* __restrict__ n_wk, int32_t* __restrict__ part, int V, int ldk, int n_slices) {
+  extern __shared__ int32_t hist_all[];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int s = blockIdx.x * 4 + wave;
+  if (s >= n_slices) return;
+  int32_t* hist = hist_all + (size_t)wave * ldk;
+  for (int k = lane; k < ldk; k += 64) hist[k] = 0;
+  const int v = word_of_slice(slice_base, V, s);
+  const int ns = slice_base[v + 1] - slice_base[v];
+  const int q = s - slice_base[v];
+  const int w0 = word_off[v], w1 = word_off[v + 1];
+  const int len = (w1 - w0 + ns - 1) / ns;
+  const int start = min(w1, w0 + q * len), end = min(w1, start + len);
+  wave_lds_fence();
+  int j = start + lane;
+  for (; j + 192 < end; j += 256) {  // four gathers in flight per lane
+    const int p0 = perm[j], p1 = perm[j + 64], p2 = perm[j + 128], p3 = perm[j + 192];
+    const int z0 = z[p0], z1 = z[p1], z2 = z[p2], z3 = z[p3];
+    atomicAdd(&hist[z0], 1);
+    atomicAdd(&hist[z1], 1);
+    atomicAdd(&hist[z2], 1);
+    atomicAdd(&hist[z3], 1);
+  }
+  for (; j < end; j += 64) atomicAdd(&hist[z[perm[j]]], 1);
+  wave_lds_fence();
+  int32_t* dst = ns == 1 ? n_wk + (size_t)v * ldk : part + (size_t)s * ldk;
+  for (int k = lane; k < ldk; k += 64) dst[k] = hist[k];
+}
+
+__global__ __launch_bounds__(256) void lda_count_words_merge_kernel(
+    const int32_t* __restrict__ slice_base, const int32_t* __restrict__ part,
+    int32_t* __restrict__ n_wk, int V, int ldk) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int v = blockIdx.x * 4 + wave;
+  if (v >= V) return;
+  const int s0 = slice_base[v], s1 = slice_base[v + 1];
+  if (s1 - s0 == 1) return;
+  for (int k = lane; k < ldk; k += 64) {
+    int32_t c = 0;
+    for (int s = s0; s < s1; ++s) c += part[(size_t)s * ldk + k];
+    n_wk[(size_t)v * ldk + k] = c;
+  }
+}
+
+// ---- one-time structure of the corpus (create) ----
+__global__ __launch_bounds__(256) void iota_kernel(int32_t* __restrict__ a, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) a[i] = (int32_t)i;
+}
+// word_off[v] = first position of a key >= v in the sorted keys (v = 0..V).
+__global__ __launch_bounds__(256) void word_offsets_kernel(const int32_t* __restrict__ sorted_w,
+                                                            int64_t N, int V,
+                                                            int32_t* __restrict__ word_off) {
+  const int v = blockIdx.x * blockDim.x + threadIdx.x;
+  if (v > V) return;
+  int64_t lo = 0, hi = N;  // first index with sorted_w[index] >= v
+  while (lo < hi) {
+    const int64_t mid = (lo + hi) >> 1;
+    if (sorted_w[mid] < v) lo = mid + 1; else hi = mid;
+  }
+  word_off[v] = (int32_t)lo;
+}
+// Slices per word: runs are cut to about kSliceTokens tokens, at most
+// kMaxSlicesPerWord per word, at least one.
+constexpr int kSliceTokens = 4096;
+constexpr int kMaxSlicesPerWord = 512;
+__global__ __launch_bounds__(256) void slice_counts_kernel(const int32_t* __restrict__ word_off,
+                                                            int V, int32_t* __restrict__ ns) {
+  const int v = blockIdx.x * blockDim.x + threadIdx.x;
+  if (v > V) return;
+  if (v == V) { ns[v] = 0; return; }
+  const int f = word_off[v + 1] - word_off[v];
+  ns[v] = max(1, min(kMaxSlicesPerWord, (f + kSliceTokens - 1) / kSliceTokens));
 }
 
 // ------------------------------------------------------------ resample theta
 // theta_d ~ Dirichlet(alpha + n_dk[d][.]) for every document in parallel
 // (Sect. 4.3; App. B, Alg. 2): K Gamma draws in the log domain, normalised by
-// their sum (log-sum-exp in fp64), stored as fp32 floored at FLT_MIN.  One wave
-// per document, lanes over topics; the draws wait in LDS between the passes.
+// their sum (log-sum-exp in fp64), stored as fp32 floored at FLT_MIN.
+//
+// One wave owns `rows` consecutive documents (rows * K variables, about 25 per
+// lane).  Rejection sampling diverges, so each lane walks its own variables:
+// every trip of the loop is one attempt on the lane's current variable, and an
+// accepted lane moves on without waiting for the others.  The draws wait in the
+// wave's LDS strip; then each row is normalised by the whole wave.
 __global__ __launch_bounds__(256) void lda_resample_theta_kernel(
-    const int32_t* __restrict__ n_dk, float* __restrict__ theta, int D, int K, int ldk,
+    const int32_t* __restrict__ n_dk, float* __restrict__ theta, int D, int K, int ldk, int rows,
     double alpha, uint64_t seed, uint32_t sweep, unsigned long long* __restrict__ n_capped) {
   extern __shared__ double lg_all[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int d = blockIdx.x * 4 + wave;
-  if (d >= D) return;
-  double* lg = lg_all + (size_t)wave * K;
+  const int d0 = (blockIdx.x * 4 + wave) * rows;
+  if (d0 >= D) return;
+  const int nrows = min(rows, D - d0);
+  const int total = nrows * K;
+  double* lg = lg_all + (size_t)wave * rows * K;
+
+  int e = lane, r = 0, k = lane;  // variable e = row r, topic k
+  while (k >= K) { k -= K; ++r; }
+  uint32_t attempt = 0;
   bool capped = false;
-  double m = -INFINITY;
-  for (int k = lane; k < K; k += 64) {
-    const double a = alpha + (double)n_dk[(size_t)d * ldk + k];
-    const double v = gamma_log_draw(a, seed, (uint64_t)d * (uint64_t)K + (uint64_t)k, sweep,
-                                    kStreamTheta, capped);
-    lg[k] = v;
-    m = v > m ? v : m;
+  GammaShape g = gamma_shape(alpha + (double)(e < total ? n_dk[(size_t)(d0 + r) * ldk + k] : 0));
+  while (__any(e < total)) {
+    if (e < total) {
+      const uint64_t index = (uint64_t)(d0 + r) * (uint64_t)K + (uint64_t)k;
+      double x;
+      bool done = gamma_attempt(g, random_block(seed, index, sweep, kStreamTheta, attempt), x);
+      if (!done && ++attempt == (uint32_t)kGammaAttemptCap) {
+        done = true;
+        capped = true;
+        x = g.ln_d;
+      }
+      if (done) {
+        lg[e] = x;
+        e += 64;
+        k += 64;
+        while (k >= K) { k -= K; ++r; }
+        attempt = 0;
+        if (e < total) g = gamma_shape(alpha + (double)n_dk[(size_t)(d0 + r) * ldk + k]);
+      }
+    }
   }
-  m = wave_allreduce_max(m);
-  double s = 0.0;
-  for (int k = lane; k < K; k += 64) s += exp(lg[k] - m);
-  s = wave_allreduce_sum(s);
-  const double L = m + log(s);
-  for (int k = lane; k < K; k += 64) {
-    double p = exp(lg[k] - L);
-    p = p < (double)FLT_MIN ? (double)FLT_MIN : p;
-    theta[(size_t)d * ldk + k] = (float)p;
+  wave_lds_fence();
+  for (int rr = 0; rr < nrows; ++rr) {
+    const double* row = lg + (size_t)rr * K;
+    double m = -INFINITY;
+    for (int kk = lane; kk < K; kk += 64) m = row[kk] > m ? row[kk] : m;
+    m = wave_allreduce_max(m);
+    double sum = 0.0;
+    for (int kk = lane; kk < K; kk += 64) sum += exp(row[kk] - m);
+    sum = wave_allreduce_sum(sum);
+    const double L = m + log(sum);
+    for (int kk = lane; kk < K; kk += 64) {
+      double p = exp(row[kk] - L);
+      p = p < (double)FLT_MIN ? (double)FLT_MIN : p;
+      theta[(size_t)(d0 + rr) * ldk + kk] = (float)p;
+    }
   }
   if (capped) atomicAdd(n_capped, 1ULL);
 }
@@ -256,7 +395,8 @@ __global__ __launch_bounds__(256) void lda_resample_theta_kernel(
 // V x K matrix of Gamma draws, element-parallel because K is small, then one
 // normaliser per topic.  Here the normaliser is a column log-sum-exp: pass 1
 // draws and keeps a running (max, sum) per column per block of rows, pass 2
-// merges the blocks, pass 3 writes exp(lg - L_k).
+// merges the blocks, pass 3 writes exp(lg - L_k).  In pass 1 a thread owns one
+// column of its block of rows and retries on its own variable (see theta).
 __global__ __launch_bounds__(256) void lda_phi_draw_kernel(
     const int32_t* __restrict__ n_wk, double* __restrict__ lg, double2* __restrict__ partial, int V,
     int K, int ldk, double beta, uint64_t seed, uint32_t sweep,
@@ -264,22 +404,39 @@ __global__ __launch_bounds__(256) void lda_phi_draw_kernel(
   const int v0 = blockIdx.x * kPhiRowsPerBlock;
   const int v1 = min(V, v0 + kPhiRowsPerBlock);
   bool capped = false;
-  for (int k = threadIdx.x; k < K; k += blockDim.x) {
+  for (int k0 = 0; k0 < K; k0 += blockDim.x) {
+    const int k = k0 + threadIdx.x;
+    int v = k < K ? v0 : v1;
     double m = -INFINITY, s = 0.0;
-    for (int v = v0; v < v1; ++v) {
-      const size_t e = (size_t)v * ldk + k;
-      const double a = beta + (double)n_wk[e];
-      const double x = gamma_log_draw(a, seed, (uint64_t)v * (uint64_t)K + (uint64_t)k, sweep,
-                                      kStreamPhi, capped);
-      lg[e] = x;
-      if (x > m) {
-        s = s * exp(m - x) + 1.0;  // exp(-inf) = 0 on the first row
-        m = x;
-      } else {
-        s += exp(x - m);
+    uint32_t attempt = 0;
+    GammaShape g = gamma_shape(beta + (double)(v < v1 ? n_wk[(size_t)v * ldk + k] : 0));
+    while (__any(v < v1)) {
+      if (v < v1) {
+        const size_t e = (size_t)v * ldk + k;
+        double x;
+        bool done = gamma_attempt(
+            g, random_block(seed, (uint64_t)v * (uint64_t)K + (uint64_t)k, sweep, kStreamPhi, attempt),
+            x);
+        if (!done && ++attempt == (uint32_t)kGammaAttemptCap) {
+          done = true;
+          capped = true;
+          x = g.ln_d;
+        }
+        if (done) {
+          lg[e] = x;
+          if (x > m) {
+            s = s * exp(m - x) + 1.0;  // exp(-inf) = 0 on the first row
+            m = x;
+          } else {
+            s += exp(x - m);
+          }
+          ++v;
+          attempt = 0;
+          if (v < v1) g = gamma_shape(beta + (double)n_wk[(size_t)v * ldk + k]);
+        }
       }
     }
-    partial[(size_t)blockIdx.x * K + k] = make_double2(m, s);
+    if (k < K) partial[(size_t)blockIdx.x * K + k] = make_double2(m, s);
   }
   if (capped) atomicAdd(n_capped, 1ULL);
 }
@@ -446,6 +603,8 @@ struct augur_lda {
   double alpha = 0, beta = 0;
   int32_t *w = nullptr, *z = nullptr, *n_dk = nullptr, *n_wk = nullptr;
   int64_t* doc_off = nullptr;
+  int32_t *perm = nullptr, *word_off = nullptr, *slice_base = nullptr, *slice_part = nullptr;
+  int n_slices = 0;
   float *theta = nullptr, *phi = nullptr;
   double* lg = nullptr;          // [V][ldk] ln Gamma draws of the phi step
   double2* col_partial = nullptr;  // [phi row blocks][K]
@@ -455,8 +614,6 @@ struct augur_lda {
   int phi_blocks = 0;
   int64_t sweep = 0;
   unsigned long long degenerate_reported = 0;
-  hipEvent_t ev[6] = {};
-  bool have_events = false;
 };
 
 namespace {
@@ -467,9 +624,8 @@ void free_all(augur_lda* h) {
   (void)hipFree(h->w); (void)hipFree(h->z); (void)hipFree(h->n_dk); (void)hipFree(h->n_wk);
   (void)hipFree(h->doc_off); (void)hipFree(h->theta); (void)hipFree(h->phi); (void)hipFree(h->lg);
   (void)hipFree(h->col_partial); (void)hipFree(h->col_logZ); (void)hipFree(h->red);
-  (void)hipFree(h->counters);
-  if (h->have_events)
-    for (auto& e : h->ev) (void)hipEventDestroy(e);
+  (void)hipFree(h->counters); (void)hipFree(h->perm); (void)hipFree(h->word_off);
+  (void)hipFree(h->slice_base); (void)hipFree(h->slice_part);
 }
 
 int launch_sample_z(augur_lda* h, uint32_t sweep) {
@@ -497,22 +653,91 @@ int launch_sample_z(augur_lda* h, uint32_t sweep) {
 }
 
 int launch_count(augur_lda* h) {
-  const int D = h->cfg.D;
-  AUGUR_HIP_TRY(hipMemsetAsync(h->n_wk, 0, sizeof(int32_t) * (size_t)h->cfg.V * h->ldk, h->stream));
-  if (D == 0) return AUGUR_OK;
-  hipLaunchKernelGGL(lda_count_kernel, dim3((D + 3) / 4), dim3(256),
-                     sizeof(int32_t) * 4 * (size_t)h->ldk, h->stream, h->w, h->z, h->doc_off,
-                     h->n_dk, h->n_wk, D, h->cfg.K, h->ldk);
+  const int D = h->cfg.D, V = h->cfg.V;
+  const size_t shm = sizeof(int32_t) * 4 * (size_t)h->ldk;
+  hipLaunchKernelGGL(lda_count_docs_kernel, dim3((D + 3) / 4), dim3(256), shm, h->stream, h->z,
+                     h->doc_off, h->n_dk, D, h->ldk);
+  hipLaunchKernelGGL(lda_count_words_kernel, dim3((h->n_slices + 3) / 4), dim3(256), shm, h->stream,
+                     h->z, h->perm, h->word_off, h->slice_base, h->n_wk, h->slice_part, V, h->ldk,
+                     h->n_slices);
+  hipLaunchKernelGGL(lda_count_words_merge_kernel, dim3((V + 3) / 4), dim3(256), 0, h->stream,
+                     h->slice_base, h->slice_part, h->n_wk, V, h->ldk);
   AUGUR_HIP_TRY(hipGetLastError());
   return AUGUR_OK;
 }
 
+// Sort the tokens by word once and cut each word's run into slices.
+int build_word_major(augur_lda* h) {
+  const int64_t N = h->N;
+  const int V = h->cfg.V;
+  const size_t n_alloc = (size_t)std::max<int64_t>(N, 1);
+  int32_t *iota = nullptr, *sorted_w = nullptr, *ns = nullptr;
+  void* temp = nullptr;
+  int rc = AUGUR_OK;
+  auto check = [&](hipError_t e, const char* what) {
+    if (e != hipSuccess && rc == AUGUR_OK) {
+      set_error("%s failed: %s", what, hipGetErrorString(e));
+      rc = AUGUR_ERR_HIP;
+    }
+    return rc == AUGUR_OK;
+  };
+  do {
+    if (!check(hipMalloc(&h->perm, sizeof(int32_t) * n_alloc), "hipMalloc(perm)")) break;
+    if (!check(hipMalloc(&h->word_off, sizeof(int32_t) * ((size_t)V + 1)), "hipMalloc(word_off)")) break;
+    if (!check(hipMalloc(&h->slice_base, sizeof(int32_t) * ((size_t)V + 1)), "hipMalloc(slice_base)")) break;
+    if (!check(hipMalloc(&iota, sizeof(int32_t) * n_alloc), "hipMalloc(iota)")) break;
+    if (!check(hipMalloc(&sorted_w, sizeof(int32_t) * n_alloc), "hipMalloc(sorted_w)")) break;
+    if (!check(hipMalloc(&ns, sizeof(int32_t) * ((size_t)V + 1)), "hipMalloc(ns)")) break;
+    if (N > 0) {
+      hipLaunchKernelGGL(iota_kernel, dim3((unsigned)((N + 255) / 256)), dim3(256), 0, h->stream,
+                         iota, N);
+      int end_bit = 1;
+      while ((1LL << end_bit) < V) ++end_bit;
+      size_t temp_bytes = 0;
+      if (!check(hipcub::DeviceRadixSort::SortPairs(nullptr, temp_bytes, h->w, sorted_w, iota,
+                                                    h->perm, (int)N, 0, end_bit, h->stream),
+                 "radix sort (size query)")) break;
+      if (!check(hipMalloc(&temp, std::max<size_t>(temp_bytes, 16)), "hipMalloc(sort temp)")) break;
+      if (!check(hipcub::DeviceRadixSort::SortPairs(temp, temp_bytes, h->w, sorted_w, iota, h->perm,
+                                                    (int)N, 0, end_bit, h->stream),
+                 "radix sort")) break;
+      (void)hipFree(temp);
+      temp = nullptr;
+    }
+    hipLaunchKernelGGL(word_offsets_kernel, dim3((V + 256) / 256), dim3(256), 0, h->stream, sorted_w,
+                       N, V, h->word_off);
+    hipLaunchKernelGGL(slice_counts_kernel, dim3((V + 256) / 256), dim3(256), 0, h->stream,
+                       h->word_off, V, ns);
+    size_t temp_bytes = 0;
+    if (!check(hipcub::DeviceScan::ExclusiveSum(nullptr, temp_bytes, ns, h->slice_base, V + 1,
+                                                h->stream), "scan (size query)")) break;
+    if (!check(hipMalloc(&temp, std::max<size_t>(temp_bytes, 16)), "hipMalloc(scan temp)")) break;
+    if (!check(hipcub::DeviceScan::ExclusiveSum(temp, temp_bytes, ns, h->slice_base, V + 1,
+                                                h->stream), "scan")) break;
+    int32_t total = 0;
+    if (!check(hipMemcpyAsync(&total, h->slice_base + V, sizeof(int32_t), hipMemcpyDeviceToHost,
+                              h->stream), "hipMemcpyAsync")) break;
+    if (!check(hipStreamSynchronize(h->stream), "hipStreamSynchronize")) break;
+    h->n_slices = total;
+    if (!check(hipMalloc(&h->slice_part, sizeof(int32_t) * (size_t)total * h->ldk),
+               "hipMalloc(slice_part)")) break;
+  } while (false);
+  (void)hipFree(temp); (void)hipFree(iota); (void)hipFree(sorted_w); (void)hipFree(ns);
+  return rc;
+}
+
+// Documents per wave in the theta step: about 1000 variables per wave (16 per
+// lane keeps the lanes' retry loops balanced) and the four waves' LDS strips
+// (rows * K doubles each) at 32 KiB, so several workgroups share a CU.
+int theta_rows_per_wave(int K) { return std::max(1, std::min(16, 1024 / K)); }
+
 int launch_theta(augur_lda* h, uint32_t sweep) {
-  const int D = h->cfg.D;
-  if (D == 0) return AUGUR_OK;
-  hipLaunchKernelGGL(lda_resample_theta_kernel, dim3((D + 3) / 4), dim3(256),
-                     sizeof(double) * 4 * (size_t)h->cfg.K, h->stream, h->n_dk, h->theta, D,
-                     h->cfg.K, h->ldk, h->alpha, h->cfg.seed, sweep, h->counters + 1);
+  const int D = h->cfg.D, K = h->cfg.K;
+  const int rows = theta_rows_per_wave(K);
+  const int waves = (D + rows - 1) / rows;
+  hipLaunchKernelGGL(lda_resample_theta_kernel, dim3((waves + 3) / 4), dim3(256),
+                     sizeof(double) * 4 * (size_t)rows * K, h->stream, h->n_dk, h->theta, D, K,
+                     h->ldk, rows, h->alpha, h->cfg.seed, sweep, h->counters + 1);
   AUGUR_HIP_TRY(hipGetLastError());
   return AUGUR_OK;
 }
@@ -579,6 +804,9 @@ int augur_lda_create(const augur_lda_config* cfg, const int32_t* doc_len, const 
   AUGUR_REQUIRE(cfg->D > 0 && cfg->V > 0 && cfg->K > 0, "D, V, K must be positive (got %d, %d, %d)",
                 cfg->D, cfg->V, cfg->K);
   AUGUR_REQUIRE(cfg->K <= 1024, "K = %d is above the supported maximum of 1024 topics", cfg->K);
+  AUGUR_REQUIRE((int64_t)cfg->V * round_up(cfg->K, 4) <= (1LL << 30),
+                "V * K = %lld exceeds 2^30 table entries (phi rows are addressed with 32-bit "
+                "byte offsets)", (long long)cfg->V * cfg->K);
   AUGUR_REQUIRE(std::isfinite(cfg->alpha) && cfg->alpha > 0.f && std::isfinite(cfg->beta) &&
                     cfg->beta > 0.f,
                 "alpha and beta must be positive and finite");
@@ -686,8 +914,15 @@ int augur_lda_create(const augur_lda_config* cfg, const int32_t* doc_len, const 
   AUGUR_CREATE_TRY(hipMemsetAsync(h->theta, 0, sizeof(float) * dk, h->stream));
   AUGUR_CREATE_TRY(hipMemsetAsync(h->phi, 0, sizeof(float) * vk, h->stream));
   AUGUR_CREATE_TRY(hipMemsetAsync(h->n_dk, 0, sizeof(int32_t) * dk, h->stream));
-  for (auto& e : h->ev) AUGUR_CREATE_TRY(hipEventCreate(&e));
-  h->have_events = true;
+
+  {
+    const int rc_w = build_word_major(h);
+    if (rc_w != AUGUR_OK) {
+      free_all(h);
+      delete h;
+      return rc_w;
+    }
+  }
 
   // initial state (sweep index 0)
   if (h->N > 0) {
@@ -761,32 +996,52 @@ int augur_lda_sweep(augur_lda* h, int32_t n_sweeps) {
 
 int augur_lda_sweep_profile(augur_lda* h, int32_t n_sweeps, double* ms) {
   AUGUR_CHECK_HANDLE(h);
-  AUGUR_REQUIRE(n_sweeps >= 0 && ms != nullptr, "bad arguments");
+  AUGUR_REQUIRE(n_sweeps >= 0 && n_sweeps <= 4096 && ms != nullptr,
+                "n_sweeps must lie in [0, 4096] and ms must not be NULL");
   for (int i = 0; i < AUGUR_LDA_NSTEPS; ++i) ms[i] = 0.0;
-  AUGUR_HIP_TRY(hipStreamSynchronize(h->stream));
-  for (int32_t s = 0; s < n_sweeps; ++s) {
+  // five events per sweep, all recorded without a host wait; read back at the end
+  std::vector<hipEvent_t> ev((size_t)n_sweeps * 5, nullptr);
+  int rc = AUGUR_OK;
+  auto fail_hip = [&](hipError_t e, const char* what) {
+    if (e != hipSuccess && rc == AUGUR_OK) {
+      set_error("%s failed: %s", what, hipGetErrorString(e));
+      rc = AUGUR_ERR_HIP;
+    }
+    return e != hipSuccess;
+  };
+  for (auto& e : ev)
+    if (fail_hip(hipEventCreate(&e), "hipEventCreate")) break;
+  int done = 0;
+  for (int32_t s = 0; s < n_sweeps && rc == AUGUR_OK; ++s) {
     const uint32_t t = (uint32_t)(h->sweep + 1);
-    AUGUR_HIP_TRY(hipEventRecord(h->ev[0], h->stream));
-    AUGUR_TRY(launch_sample_z(h, t));
-    AUGUR_HIP_TRY(hipEventRecord(h->ev[1], h->stream));
-    AUGUR_TRY(launch_count(h));
-    AUGUR_HIP_TRY(hipEventRecord(h->ev[2], h->stream));
-    AUGUR_TRY(launch_theta(h, t));
-    AUGUR_HIP_TRY(hipEventRecord(h->ev[3], h->stream));
-    AUGUR_TRY(launch_phi(h, t));
-    AUGUR_HIP_TRY(hipEventRecord(h->ev[4], h->stream));
-    AUGUR_HIP_TRY(hipEventSynchronize(h->ev[4]));
+    hipEvent_t* e = &ev[(size_t)s * 5];
+    if (fail_hip(hipEventRecord(e[0], h->stream), "hipEventRecord")) break;
+    if ((rc = launch_sample_z(h, t)) != AUGUR_OK) break;
+    if (fail_hip(hipEventRecord(e[1], h->stream), "hipEventRecord")) break;
+    if ((rc = launch_count(h)) != AUGUR_OK) break;
+    if (fail_hip(hipEventRecord(e[2], h->stream), "hipEventRecord")) break;
+    if ((rc = launch_theta(h, t)) != AUGUR_OK) break;
+    if (fail_hip(hipEventRecord(e[3], h->stream), "hipEventRecord")) break;
+    if ((rc = launch_phi(h, t)) != AUGUR_OK) break;
+    if (fail_hip(hipEventRecord(e[4], h->stream), "hipEventRecord")) break;
+    h->sweep += 1;
+    ++done;
+  }
+  fail_hip(hipStreamSynchronize(h->stream), "hipStreamSynchronize");
+  for (int s = 0; s < done && rc == AUGUR_OK; ++s) {
+    hipEvent_t* e = &ev[(size_t)s * 5];
     for (int i = 0; i < 4; ++i) {
       float x = 0.f;
-      AUGUR_HIP_TRY(hipEventElapsedTime(&x, h->ev[i], h->ev[i + 1]));
+      if (fail_hip(hipEventElapsedTime(&x, e[i], e[i + 1]), "hipEventElapsedTime")) break;
       ms[i] += (double)x;
     }
     float x = 0.f;
-    AUGUR_HIP_TRY(hipEventElapsedTime(&x, h->ev[0], h->ev[4]));
+    if (fail_hip(hipEventElapsedTime(&x, e[0], e[4]), "hipEventElapsedTime")) break;
     ms[4] += (double)x;
-    h->sweep += 1;
   }
-  return AUGUR_OK;
+  for (auto& e : ev)
+    if (e) (void)hipEventDestroy(e);
+  return rc;
 }
 
 int augur_lda_loglik(augur_lda* h, double* log_joint, double* log_marginal_w) {
