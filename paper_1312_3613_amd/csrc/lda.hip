@@ -138,10 +138,10 @@ __global__ __launch_bounds__(256) void lda_sample_z_kernel(
       const uint32_t r = rnd[wave][valid ? (int)(i - base) : 0];
       const uint32_t row_off = v * row_bytes;  // < 2^32: checked when the handle is created
 
+      const char* rowp = phi_bytes + (size_t)(row_off + lane_off);  // constant offsets fold into the loads
       float4 q[NS];
 #pragma unroll
-      for (int m = 0; m < NS - 1; ++m)
-        q[m] = *reinterpret_cast<const float4*>(phi_bytes + (row_off + lane_off + 256u * m));
+      for (int m = 0; m < NS - 1; ++m) q[m] = *reinterpret_cast<const float4*>(rowp + 256 * m);
       q[NS - 1] = *reinterpret_cast<const float4*>(phi_bytes + (row_off + last_off));
 
       // running sums: l?[m] = lane-local inclusive sums of stripe m, cbase[m] =
@@ -206,6 +206,169 @@ __global__ __launch_bounds__(256) void lda_sample_z_kernel(
       }
       // garbage parameters (negative or NaN entries) must not yield an index outside the tables
       if (valid && j == 0) z[i] = min(max(k, 0), K - 1);
+    }
+  }
+}
+
+// ------------------------------------------------- sample z, up to 256 topics
+// Same draw as lda_sample_z_kernel with a finer grain: a QUAD (4 lanes) per
+// token, 16 tokens per wave and iteration.  The topics are cut into stripes of
+// 16; quad lane q holds topics 16 c + 4 q + {0..3} of stripe c, so a quad reads
+// 64 contiguous bytes of the phi row per load.
+//
+// Pass 1 keeps only the running stripe totals cum[c] (a quad-wide sum needs two
+// DPP adds and gives all four lanes the same bits).  With S = cum[last] and
+// t = u S the crossing stripe c* = #{c : cum[c] <= t} is found by comparing
+// registers.  Pass 2 reloads the 64 bytes of stripe c* (an L1 hit) and the
+// matching chunk of theta_d from LDS, rebuilds that stripe's running sums and
+// finds the topic.  Against the 16-lane form this removes the per-stripe
+// 16-lane scans and all but one of the per-stripe searches: about a third of
+// the vector instructions per token.
+//
+// The wave's LDS strip holds, for the 256 tokens of the current chunk, the
+// Philox word and the word id of each token, and theta_d padded with zeros to a
+// whole number of stripes.
+constexpr int kQpSwap1 = 0xB1;   // quad_perm [1,0,3,2]
+constexpr int kQpSwap2 = 0x4E;   // quad_perm [2,3,0,1]
+constexpr int kQpBcast0 = 0x00, kQpBcast1 = 0x55, kQpBcast2 = 0xAA;
+constexpr int kNoTopic = 0x7FFFFFFF;
+
+template <int NS16>
+__global__ __launch_bounds__(256) void lda_sample_z_quad_kernel(
+    const int32_t* __restrict__ w, const int64_t* __restrict__ doc_off,
+    const float* __restrict__ theta, const float* __restrict__ phi, int32_t* __restrict__ z, int D,
+    int K, int ldk, uint64_t seed, uint32_t sweep, unsigned long long* __restrict__ n_degenerate) {
+  __shared__ uint2 strip_all[4][256];            // {Philox word, word id} per token of the chunk
+  __shared__ __align__(16) float theta_all[4][16 * NS16];
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const int d = blockIdx.x * 4 + wave;
+  if (d >= D) return;
+  const int tq = lane >> 2, q = lane & 3;  // token slot of this quad, lane within the quad
+  uint2* strip = strip_all[wave];
+  float* theta_s = theta_all[wave];
+
+  // theta_d: registers for pass 1 (the quads all hold the same 16 NS16 values),
+  // LDS for the dynamically indexed read of pass 2
+  float4 th[NS16];
+#pragma unroll
+  for (int c = 0; c < NS16; ++c) {
+    const int col = 16 * c + 4 * q;
+    th[c] = col < ldk ? *reinterpret_cast<const float4*>(theta + (size_t)d * ldk + col)
+                      : make_float4(0.f, 0.f, 0.f, 0.f);
+    if (tq == 0) *reinterpret_cast<float4*>(theta_s + col) = th[c];
+  }
+  const uint32_t row_bytes = 4u * (uint32_t)ldk;
+  const uint32_t lane_off = 16u * (uint32_t)q;
+  const uint32_t last_off = min(64u * (NS16 - 1) + lane_off, row_bytes - 16u);
+  const char* phi_bytes = reinterpret_cast<const char*>(phi);
+
+  const int64_t a = doc_off[d], b = doc_off[d + 1];
+  for (int64_t base = a & ~(int64_t)3; base < b; base += 256) {
+    {
+      // tokens base + 4 lane .. + 3: one Philox block and four word ids (w is
+      // padded by 256 entries, so the vector load never leaves the allocation)
+      const U4 r = random_block(seed, (uint64_t)(base >> 2) + (uint64_t)lane, sweep, kStreamZ, 0);
+      const int4 wv = *reinterpret_cast<const int4*>(w + base + 4 * lane);
+      wave_lds_fence();  // earlier reads of the strip are done
+      uint4* dst = reinterpret_cast<uint4*>(strip + 4 * lane);
+      dst[0] = make_uint4(r.x, (uint32_t)wv.x, r.y, (uint32_t)wv.y);
+      dst[1] = make_uint4(r.z, (uint32_t)wv.z, r.w, (uint32_t)wv.w);
+      wave_lds_fence();
+    }
+    const int64_t lo = a > base ? a : base;
+    const int64_t hi = b < base + 256 ? b : base + 256;
+    for (int64_t i0 = lo; i0 < hi; i0 += 16) {
+      const int64_t i = i0 + tq;
+      const bool valid = i < hi;
+      const uint2 rw = strip[valid ? (int)(i - base) : (int)(lo - base)];
+      const uint32_t r = rw.x;
+      const uint32_t row_off = __umul24(rw.y, row_bytes);  // both below 2^24; product below 2^32
+
+      const char* rowp = phi_bytes + (size_t)(row_off + lane_off);  // constant offsets fold into the loads
+      float4 ph[NS16];
+#pragma unroll
+      for (int c = 0; c < NS16 - 1; ++c) ph[c] = *reinterpret_cast<const float4*>(rowp + 64 * c);
+      ph[NS16 - 1] = *reinterpret_cast<const float4*>(phi_bytes + (row_off + last_off));
+
+      // pass 1: running stripe totals
+      float cum[NS16];
+      float run = 0.f;
+#pragma unroll
+      for (int c = 0; c < NS16; ++c) {
+        float s = th[c].x * ph[c].x;
+        s = fmaf(th[c].y, ph[c].y, s);
+        s = fmaf(th[c].z, ph[c].z, s);
+        s = fmaf(th[c].w, ph[c].w, s);
+        s += dpp_f32<kQpSwap1>(s);
+        s += dpp_f32<kQpSwap2>(s);
+        run += s;
+        cum[c] = run;
+      }
+      const float S = run;
+      const float t = u24(r) * S;
+
+      // crossing stripe and the total before it
+      int cstar = 0;
+      float cprev = 0.f;
+#pragma unroll
+      for (int c = 0; c < NS16; ++c) {
+        const bool below = cum[c] <= t;
+        cstar += below ? 1 : 0;
+        cprev = below ? cum[c] : cprev;
+      }
+
+      // pass 2: the 16 topics of stripe c*
+      const int cs = min(cstar, NS16 - 1);
+      const uint32_t off2 = min(64u * (uint32_t)cs + lane_off, row_bytes - 16u);
+      const float4 p2 = *reinterpret_cast<const float4*>(phi_bytes + (row_off + off2));
+      const float4 t2 = *reinterpret_cast<const float4*>(theta_s + 16 * cs + 4 * q);
+      const float l0 = t2.x * p2.x;
+      const float l1 = fmaf(t2.y, p2.y, l0);
+      const float l2 = fmaf(t2.z, p2.z, l1);
+      const float l3 = fmaf(t2.w, p2.w, l2);
+      const float b0 = dpp_mov_f32<kQpBcast0>(l3);
+      const float b01 = b0 + dpp_mov_f32<kQpBcast1>(l3);
+      const float b012 = b01 + dpp_mov_f32<kQpBcast2>(l3);
+      const float excl = q == 0 ? 0.f : q == 1 ? b0 : q == 2 ? b01 : b012;
+      const float tt = fmaxf(t - (cprev + excl), 0.f);
+      const int e = (l0 <= tt) + (l1 <= tt) + (l2 <= tt);
+      int cand = l3 > tt ? 4 * q + e : kNoTopic;
+      cand = min(cand, dpp_i32_keep<kQpSwap1>(cand));
+      cand = min(cand, dpp_i32_keep<kQpSwap2>(cand));
+      int k = 16 * cs + cand;
+
+      const bool ok = S > 0.f && S <= FLT_MAX;  // false for 0, inf and NaN
+      const bool found = cstar < NS16 && cand != kNoTopic;
+      if (__builtin_expect(__any(valid && !(ok && found)), 0)) {
+        if (!ok) {
+          // zero or non-finite mass: z = floor(u K)
+          k = u24_times(r, K);
+          if (valid && q == 0) atomicAdd(n_degenerate, 1ULL);
+        } else if (!found) {
+          // rounding put t at or past the running sum that should exceed it: the
+          // last topic of positive mass in the crossing stripe (or overall)
+          const int limit = cstar < NS16 ? 16 * (cs + 1) : 16 * NS16;
+          int last = -1;
+          for (int c = 0; c < NS16; ++c) {
+            const uint32_t o = min(64u * (uint32_t)c + lane_off, row_bytes - 16u);
+            const float4 pp = *reinterpret_cast<const float4*>(phi_bytes + (row_off + o));
+            const float4 tp = *reinterpret_cast<const float4*>(theta_s + 16 * c + 4 * q);
+            const int kk = 16 * c + 4 * q;
+            if (kk < limit) {
+              if (tp.x * pp.x > 0.f) last = kk;
+              if (tp.y * pp.y > 0.f) last = kk + 1;
+              if (tp.z * pp.z > 0.f) last = kk + 2;
+              if (tp.w * pp.w > 0.f) last = kk + 3;
+            }
+          }
+          last = max(last, dpp_i32_keep<kQpSwap1>(last));
+          last = max(last, dpp_i32_keep<kQpSwap2>(last));
+          k = last;
+        }
+      }
+      // garbage parameters (negative or NaN entries) must not yield an index outside the tables
+      if (valid && q == 0) z[i] = min(max(k, 0), K - 1);
     }
   }
 }
@@ -632,22 +795,33 @@ int launch_sample_z(augur_lda* h, uint32_t sweep) {
   const int D = h->cfg.D;
   if (D == 0 || h->N == 0) return AUGUR_OK;
   const dim3 grid((D + 3) / 4), block(256);
-#define AUGUR_Z_CASE(NSV)                                                                      \
-  case NSV:                                                                                    \
-    hipLaunchKernelGGL(lda_sample_z_kernel<NSV>, grid, block, 0, h->stream, h->w, h->doc_off,  \
-                       h->theta, h->phi, h->z, D, h->cfg.K, h->ldk, h->cfg.seed, sweep,        \
-                       h->counters);                                                           \
-    break;
-  switch (h->ns) {
-    AUGUR_Z_CASE(1) AUGUR_Z_CASE(2) AUGUR_Z_CASE(3) AUGUR_Z_CASE(4) AUGUR_Z_CASE(5)
-    AUGUR_Z_CASE(6) AUGUR_Z_CASE(7) AUGUR_Z_CASE(8) AUGUR_Z_CASE(9) AUGUR_Z_CASE(10)
-    AUGUR_Z_CASE(11) AUGUR_Z_CASE(12) AUGUR_Z_CASE(13) AUGUR_Z_CASE(14) AUGUR_Z_CASE(15)
-    AUGUR_Z_CASE(16)
-    default:
-      set_error("K = %d is above the supported maximum of 1024 topics", h->cfg.K);
-      return AUGUR_ERR_UNIMPLEMENTED;
+#define AUGUR_Z_ARGS                                                                          \
+  grid, block, 0, h->stream, h->w, h->doc_off, h->theta, h->phi, h->z, D, h->cfg.K, h->ldk,   \
+      h->cfg.seed, sweep, h->counters
+#define AUGUR_ZQ_CASE(N16) \
+  case N16: hipLaunchKernelGGL(lda_sample_z_quad_kernel<N16>, AUGUR_Z_ARGS); break;
+#define AUGUR_Z_CASE(NSV) \
+  case NSV: hipLaunchKernelGGL(lda_sample_z_kernel<NSV>, AUGUR_Z_ARGS); break;
+  if (h->ldk <= 256) {
+    switch ((h->ldk + 15) / 16) {
+      AUGUR_ZQ_CASE(1) AUGUR_ZQ_CASE(2) AUGUR_ZQ_CASE(3) AUGUR_ZQ_CASE(4) AUGUR_ZQ_CASE(5)
+      AUGUR_ZQ_CASE(6) AUGUR_ZQ_CASE(7) AUGUR_ZQ_CASE(8) AUGUR_ZQ_CASE(9) AUGUR_ZQ_CASE(10)
+      AUGUR_ZQ_CASE(11) AUGUR_ZQ_CASE(12) AUGUR_ZQ_CASE(13) AUGUR_ZQ_CASE(14) AUGUR_ZQ_CASE(15)
+      AUGUR_ZQ_CASE(16)
+    }
+  } else {
+    switch (h->ns) {
+      AUGUR_Z_CASE(5) AUGUR_Z_CASE(6) AUGUR_Z_CASE(7) AUGUR_Z_CASE(8) AUGUR_Z_CASE(9)
+      AUGUR_Z_CASE(10) AUGUR_Z_CASE(11) AUGUR_Z_CASE(12) AUGUR_Z_CASE(13) AUGUR_Z_CASE(14)
+      AUGUR_Z_CASE(15) AUGUR_Z_CASE(16)
+      default:
+        set_error("K = %d is above the supported maximum of 1024 topics", h->cfg.K);
+        return AUGUR_ERR_UNIMPLEMENTED;
+    }
   }
 #undef AUGUR_Z_CASE
+#undef AUGUR_ZQ_CASE
+#undef AUGUR_Z_ARGS
   AUGUR_HIP_TRY(hipGetLastError());
   return AUGUR_OK;
 }
@@ -886,7 +1060,9 @@ int augur_lda_create(const augur_lda_config* cfg, const int32_t* doc_len, const 
       if (w[i] < 0 || w[i] >= V)
         AUGUR_CREATE_FAIL("w[%lld] = %d is outside [0, %d)", (long long)i, w[i], V);
 
-  AUGUR_CREATE_TRY(hipMalloc(&h->w, sizeof(int32_t) * n_alloc));
+  // 256 spare entries after the last token: the sampler reads word ids four at a time
+  AUGUR_CREATE_TRY(hipMalloc(&h->w, sizeof(int32_t) * (n_alloc + 256)));
+  AUGUR_CREATE_TRY(hipMemsetAsync(h->w, 0, sizeof(int32_t) * (n_alloc + 256), h->stream));
   AUGUR_CREATE_TRY(hipMalloc(&h->z, sizeof(int32_t) * n_alloc));
   if (h->N > 0)
     AUGUR_CREATE_TRY(hipMemcpyAsync(h->w, w, sizeof(int32_t) * (size_t)h->N,
