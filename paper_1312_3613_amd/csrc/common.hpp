@@ -112,15 +112,24 @@ constexpr int kGammaAttemptCap = 64;
 // can let every lane retry on its own variable instead of waiting for the
 // slowest lane of the wave.
 struct GammaShape {
-  double a, d, c, ln_d;
+  double d, c, ln_d, inv_a;  // a < 1 exactly when inv_a > 1
 };
 __device__ __forceinline__ GammaShape gamma_shape(double a) {
   GammaShape g;
-  g.a = a;
   g.d = (a < 1.0 ? a + 1.0 : a) - 1.0 / 3.0;
   g.c = 1.0 / sqrt(9.0 * g.d);
   g.ln_d = log(g.d);
+  g.inv_a = 1.0 / a;
   return g;
+}
+// Shapes a0 + n for small integer counts n are read from a table built once
+// per handle (the per-variable constants cost a square root, a division and a
+// logarithm otherwise); larger counts are computed on the spot.
+constexpr int kShapeTable = 1024;
+__device__ __forceinline__ GammaShape gamma_shape_count(const GammaShape* __restrict__ table,
+                                                        double a0, int n) {
+  if (n < kShapeTable) return table[n];
+  return gamma_shape(a0 + (double)n);
 }
 // One attempt; on acceptance writes ln(draw) and returns true.
 __device__ __forceinline__ bool gamma_attempt(const GammaShape& g, const U4& b, double& lg) {
@@ -134,7 +143,7 @@ __device__ __forceinline__ bool gamma_attempt(const GammaShape& g, const U4& b, 
   if (!accept) accept = log(U) < 0.5 * x2 + g.d * (1.0 - v + lv);
   accept = accept && t > 0.0;
   lg = g.ln_d + lv;
-  if (g.a < 1.0) lg += log(u32d(b.w)) / g.a;
+  if (g.inv_a > 1.0) lg += log(u32d(b.w)) * g.inv_a;
   return accept;
 }
 // Loop form: attempts until accepted.  `capped` is raised if the cap is reached.

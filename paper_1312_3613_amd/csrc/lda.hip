@@ -445,16 +445,29 @@ __global__ __launch_bounds__(256) void lda_count_words_kernel(
 __global__ __launch_bounds__(256) void lda_count_words_merge_kernel(
     const int32_t* __restrict__ slice_base, const int32_t* __restrict__ part,
     int32_t* __restrict__ n_wk, int V, int ldk) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int v = blockIdx.x * 4 + wave;
-  if (v >= V) return;
+  // one workgroup per word; words with a single slice were stored directly.
+  // Wave g adds slices g, g + 4, ... (four rows in flight per lane); the four
+  // waves' sums meet in LDS.
+  extern __shared__ int32_t acc[];  // [4][ldk]
+  const int v = blockIdx.x;
   const int s0 = slice_base[v], s1 = slice_base[v + 1];
   if (s1 - s0 == 1) return;
+  const int lane = threadIdx.x & 63, g = threadIdx.x >> 6;
   for (int k = lane; k < ldk; k += 64) {
-    int32_t c = 0;
-    for (int s = s0; s < s1; ++s) c += part[(size_t)s * ldk + k];
-    n_wk[(size_t)v * ldk + k] = c;
+    int32_t c0 = 0, c1 = 0, c2 = 0, c3 = 0;
+    int s = s0 + g;
+    for (; s + 12 < s1; s += 16) {
+      c0 += part[(size_t)s * ldk + k];
+      c1 += part[(size_t)(s + 4) * ldk + k];
+      c2 += part[(size_t)(s + 8) * ldk + k];
+      c3 += part[(size_t)(s + 12) * ldk + k];
+    }
+    for (; s < s1; s += 4) c0 += part[(size_t)s * ldk + k];
+    acc[g * ldk + k] = (c0 + c1) + (c2 + c3);
   }
+  __syncthreads();
+  for (int k = threadIdx.x; k < ldk; k += 256)
+    n_wk[(size_t)v * ldk + k] = (acc[k] + acc[ldk + k]) + (acc[2 * ldk + k] + acc[3 * ldk + k]);
 }
 
 // ---- one-time structure of the corpus (create) ----
@@ -500,7 +513,8 @@ __global__ __launch_bounds__(256) void slice_counts_kernel(const int32_t* __rest
 // wave's LDS strip; then each row is normalised by the whole wave.
 __global__ __launch_bounds__(256) void lda_resample_theta_kernel(
     const int32_t* __restrict__ n_dk, float* __restrict__ theta, int D, int K, int ldk, int rows,
-    double alpha, uint64_t seed, uint32_t sweep, unsigned long long* __restrict__ n_capped) {
+    double alpha, const GammaShape* __restrict__ shapes, uint64_t seed, uint32_t sweep,
+    unsigned long long* __restrict__ n_capped) {
   extern __shared__ double lg_all[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int d0 = (blockIdx.x * 4 + wave) * rows;
@@ -513,7 +527,7 @@ __global__ __launch_bounds__(256) void lda_resample_theta_kernel(
   while (k >= K) { k -= K; ++r; }
   uint32_t attempt = 0;
   bool capped = false;
-  GammaShape g = gamma_shape(alpha + (double)(e < total ? n_dk[(size_t)(d0 + r) * ldk + k] : 0));
+  GammaShape g = gamma_shape_count(shapes, alpha, e < total ? n_dk[(size_t)(d0 + r) * ldk + k] : 0);
   while (__any(e < total)) {
     if (e < total) {
       const uint64_t index = (uint64_t)(d0 + r) * (uint64_t)K + (uint64_t)k;
@@ -530,22 +544,26 @@ __global__ __launch_bounds__(256) void lda_resample_theta_kernel(
         k += 64;
         while (k >= K) { k -= K; ++r; }
         attempt = 0;
-        if (e < total) g = gamma_shape(alpha + (double)n_dk[(size_t)(d0 + r) * ldk + k]);
+        if (e < total) g = gamma_shape_count(shapes, alpha, n_dk[(size_t)(d0 + r) * ldk + k]);
       }
     }
   }
   wave_lds_fence();
   for (int rr = 0; rr < nrows; ++rr) {
-    const double* row = lg + (size_t)rr * K;
+    double* row = lg + (size_t)rr * K;
     double m = -INFINITY;
     for (int kk = lane; kk < K; kk += 64) m = row[kk] > m ? row[kk] : m;
     m = wave_allreduce_max(m);
     double sum = 0.0;
-    for (int kk = lane; kk < K; kk += 64) sum += exp(row[kk] - m);
+    for (int kk = lane; kk < K; kk += 64) {  // each lane revisits only its own entries
+      const double ex = exp(row[kk] - m);
+      row[kk] = ex;
+      sum += ex;
+    }
     sum = wave_allreduce_sum(sum);
-    const double L = m + log(sum);
+    const double inv = 1.0 / sum;
     for (int kk = lane; kk < K; kk += 64) {
-      double p = exp(row[kk] - L);
+      double p = row[kk] * inv;
       p = p < (double)FLT_MIN ? (double)FLT_MIN : p;
       theta[(size_t)(d0 + rr) * ldk + kk] = (float)p;
     }
@@ -562,8 +580,8 @@ __global__ __launch_bounds__(256) void lda_resample_theta_kernel(
 // column of its block of rows and retries on its own variable (see theta).
 __global__ __launch_bounds__(256) void lda_phi_draw_kernel(
     const int32_t* __restrict__ n_wk, double* __restrict__ lg, double2* __restrict__ partial, int V,
-    int K, int ldk, double beta, uint64_t seed, uint32_t sweep,
-    unsigned long long* __restrict__ n_capped) {
+    int K, int ldk, double beta, const GammaShape* __restrict__ shapes, uint64_t seed,
+    uint32_t sweep, unsigned long long* __restrict__ n_capped) {
   const int v0 = blockIdx.x * kPhiRowsPerBlock;
   const int v1 = min(V, v0 + kPhiRowsPerBlock);
   bool capped = false;
@@ -572,7 +590,7 @@ __global__ __launch_bounds__(256) void lda_phi_draw_kernel(
     int v = k < K ? v0 : v1;
     double m = -INFINITY, s = 0.0;
     uint32_t attempt = 0;
-    GammaShape g = gamma_shape(beta + (double)(v < v1 ? n_wk[(size_t)v * ldk + k] : 0));
+    GammaShape g = gamma_shape_count(shapes, beta, v < v1 ? n_wk[(size_t)v * ldk + k] : 0);
     while (__any(v < v1)) {
       if (v < v1) {
         const size_t e = (size_t)v * ldk + k;
@@ -595,7 +613,7 @@ __global__ __launch_bounds__(256) void lda_phi_draw_kernel(
           }
           ++v;
           attempt = 0;
-          if (v < v1) g = gamma_shape(beta + (double)n_wk[(size_t)v * ldk + k]);
+          if (v < v1) g = gamma_shape_count(shapes, beta, n_wk[(size_t)v * ldk + k]);
         }
       }
     }
@@ -708,6 +726,12 @@ __global__ __launch_bounds__(256) void sum_log_kernel(const float* __restrict__ 
   block_partial_sum(s, part, smem);
 }
 
+// Per-handle tables of Gamma shape constants for a0 + n, n = 0 .. kShapeTable - 1.
+__global__ __launch_bounds__(256) void shape_table_kernel(GammaShape* __restrict__ table, double a0) {
+  const int n = blockIdx.x * blockDim.x + threadIdx.x;
+  if (n < kShapeTable) table[n] = gamma_shape(a0 + (double)n);
+}
+
 // --------------------------------------------------------------- validation
 __global__ __launch_bounds__(256) void check_range_kernel(const int32_t* __restrict__ a, int64_t n,
                                                            int32_t lo, int32_t hi,
@@ -772,6 +796,7 @@ struct augur_lda {
   double* lg = nullptr;          // [V][ldk] ln Gamma draws of the phi step
   double2* col_partial = nullptr;  // [phi row blocks][K]
   double* col_logZ = nullptr;    // [K]
+  GammaShape *shapes_alpha = nullptr, *shapes_beta = nullptr;  // [kShapeTable] each
   double* red = nullptr;         // [4][kRedBlocks] reduction partials
   unsigned long long* counters = nullptr;  // [0] degenerate tokens [1] capped draws [2] bad input
   int phi_blocks = 0;
@@ -789,6 +814,7 @@ void free_all(augur_lda* h) {
   (void)hipFree(h->col_partial); (void)hipFree(h->col_logZ); (void)hipFree(h->red);
   (void)hipFree(h->counters); (void)hipFree(h->perm); (void)hipFree(h->word_off);
   (void)hipFree(h->slice_base); (void)hipFree(h->slice_part);
+  (void)hipFree(h->shapes_alpha); (void)hipFree(h->shapes_beta);
 }
 
 int launch_sample_z(augur_lda* h, uint32_t sweep) {
@@ -834,8 +860,9 @@ int launch_count(augur_lda* h) {
   hipLaunchKernelGGL(lda_count_words_kernel, dim3((h->n_slices + 3) / 4), dim3(256), shm, h->stream,
                      h->z, h->perm, h->word_off, h->slice_base, h->n_wk, h->slice_part, V, h->ldk,
                      h->n_slices);
-  hipLaunchKernelGGL(lda_count_words_merge_kernel, dim3((V + 3) / 4), dim3(256), 0, h->stream,
-                     h->slice_base, h->slice_part, h->n_wk, V, h->ldk);
+  hipLaunchKernelGGL(lda_count_words_merge_kernel, dim3(V), dim3(256),
+                     sizeof(int32_t) * 4 * (size_t)h->ldk, h->stream, h->slice_base, h->slice_part,
+                     h->n_wk, V, h->ldk);
   AUGUR_HIP_TRY(hipGetLastError());
   return AUGUR_OK;
 }
@@ -911,7 +938,7 @@ int launch_theta(augur_lda* h, uint32_t sweep) {
   const int waves = (D + rows - 1) / rows;
   hipLaunchKernelGGL(lda_resample_theta_kernel, dim3((waves + 3) / 4), dim3(256),
                      sizeof(double) * 4 * (size_t)rows * K, h->stream, h->n_dk, h->theta, D, K,
-                     h->ldk, rows, h->alpha, h->cfg.seed, sweep, h->counters + 1);
+                     h->ldk, rows, h->alpha, h->shapes_alpha, h->cfg.seed, sweep, h->counters + 1);
   AUGUR_HIP_TRY(hipGetLastError());
   return AUGUR_OK;
 }
@@ -920,7 +947,7 @@ int launch_phi(augur_lda* h, uint32_t sweep) {
   const int V = h->cfg.V, K = h->cfg.K;
   const int threads = (int)std::min<int64_t>(256, round_up(K, 64));
   hipLaunchKernelGGL(lda_phi_draw_kernel, dim3(h->phi_blocks), dim3(threads), 0, h->stream, h->n_wk,
-                     h->lg, h->col_partial, V, K, h->ldk, h->beta, h->cfg.seed, sweep,
+                     h->lg, h->col_partial, V, K, h->ldk, h->beta, h->shapes_beta, h->cfg.seed, sweep,
                      h->counters + 1);
   hipLaunchKernelGGL(lda_phi_norm_kernel, dim3(K), dim3(256), 0, h->stream, h->col_partial,
                      h->col_logZ, h->phi_blocks, K);
@@ -1087,6 +1114,13 @@ int augur_lda_create(const augur_lda_config* cfg, const int32_t* doc_len, const 
   AUGUR_CREATE_TRY(hipMalloc(&h->col_partial, sizeof(double2) * (size_t)h->phi_blocks * K));
   AUGUR_CREATE_TRY(hipMalloc(&h->col_logZ, sizeof(double) * (size_t)K));
   AUGUR_CREATE_TRY(hipMalloc(&h->red, sizeof(double) * 4 * kRedBlocks));
+  AUGUR_CREATE_TRY(hipMalloc(&h->shapes_alpha, sizeof(GammaShape) * kShapeTable));
+  AUGUR_CREATE_TRY(hipMalloc(&h->shapes_beta, sizeof(GammaShape) * kShapeTable));
+  hipLaunchKernelGGL(shape_table_kernel, dim3(kShapeTable / 256), dim3(256), 0, h->stream,
+                     h->shapes_alpha, h->alpha);
+  hipLaunchKernelGGL(shape_table_kernel, dim3(kShapeTable / 256), dim3(256), 0, h->stream,
+                     h->shapes_beta, h->beta);
+  AUGUR_CREATE_TRY(hipGetLastError());
   AUGUR_CREATE_TRY(hipMemsetAsync(h->theta, 0, sizeof(float) * dk, h->stream));
   AUGUR_CREATE_TRY(hipMemsetAsync(h->phi, 0, sizeof(float) * vk, h->stream));
   AUGUR_CREATE_TRY(hipMemsetAsync(h->n_dk, 0, sizeof(int32_t) * dk, h->stream));
