@@ -19,9 +19,11 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 
-# HBM bytes per sample_z launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see
-# profiles/), scaled by the copy-kernel factor; None until measured for that workload.
-MEASURED_TRAFFIC_BYTES = {}
+# HBM bytes per sample_z launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by
+# the factors a plain 1 GiB copy shows for the same counters (reads x 2.0, writes x 1.0); the
+# runs and figures are in profiles/lda_large_kernel_trace_and_hbm_traffic.md.  None for workloads
+# that have not been measured.
+MEASURED_TRAFFIC_BYTES = {"large": (6_891_261 * 2.0 + 323_801 * 1.0) * 1024}
 
 
 def sample_z_algorithmic_bytes(N, D, K):
@@ -61,6 +63,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="large", choices=["tiny", "medium", "large", "widek"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe-mib", type=int, default=0,
+                    help="also run one plain device copy of this many MiB (a reference of known "
+                         "size for scaling rocprofv3's FETCH_SIZE/WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)",
@@ -87,6 +92,14 @@ def main():
     h = B.LDA(D, V, K, cfg["alpha"], cfg["beta"], cfg["seed"], doc_len_d, w_d, stream=stream,
               device_ptrs=True)
     t_create = time.perf_counter() - t0
+
+    if args.copy_probe_mib > 0:
+        src = torch.empty(args.copy_probe_mib * (1 << 20) // 4, dtype=torch.float32, device="cuda")
+        src.fill_(1.0)
+        dst = torch.empty_like(src)
+        dst.copy_(src)          # the probe: reads and writes copy_probe_mib MiB
+        torch.cuda.synchronize()
+        del src, dst
 
     h.sweep(args.warmup)
     h.sync()

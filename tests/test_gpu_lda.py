@@ -246,3 +246,67 @@ def test_medium_config_full_parity(B):
     assert sw == 5 and np.abs(th.astype(np.float64).sum(1) - 1).max() < 1e-5
     assert np.abs(ph.astype(np.float64).sum(0) - 1).max() < 1e-4 and th.min() > 0 and ph.min() > 0
     g.close()
+
+
+def test_large_config_sampled_parity(B):
+    """BASELINE's K=200 configuration at full size (about 75M tokens), in the launch configuration
+    bench.py times.  The oracle checks z on ranges of documents it can redo one by one, the count
+    tables in full, theta on sampled ranges and phi in full."""
+    cfg = synth.LDA_CONFIGS["large"]
+    c = synth.lda_corpus(**cfg)
+    D, V, K, N = cfg["D"], cfg["V"], cfg["K"], c["N"]
+    alpha, beta, seed = float(np.float32(cfg["alpha"])), float(np.float32(cfg["beta"])), cfg["seed"]
+    g = B.LDA(D, V, K, cfg["alpha"], cfg["beta"], seed, c["doc_len"], c["w"])
+    off = O.doc_offsets(c["doc_len"])
+    g.sweep(2)                                   # a state two sweeps in, as in the benchmark
+    z0, theta, phi, sw = g.get_state()
+    assert sw == 2
+    g.step_sample_z()
+    z1 = g.get_state(theta=False, phi=False)[0]
+    assert z1.min() >= 0 and z1.max() < K
+    checked = 0
+    for d0 in (0, 123_456, D - 1500):
+        d1 = d0 + 1500
+        sub_off = off[d0:d1 + 1]
+        zo = z1.copy()
+        # the oracle writes its draws for documents d0..d1-1 into zo at their global positions
+        lib = O.lib()
+        import ctypes as Ct
+        lib.orc_lda_sample_z(Ct.c_int32(d1 - d0), Ct.c_int32(K), sub_off.ctypes.data_as(Ct.POINTER(Ct.c_int64)),
+                             c["w"].ctypes.data_as(Ct.POINTER(Ct.c_int32)),
+                             theta[d0:d1].ctypes.data_as(Ct.POINTER(Ct.c_float)),
+                             phi.ctypes.data_as(Ct.POINTER(Ct.c_float)), Ct.c_uint64(seed), Ct.c_uint32(3),
+                             zo.ctypes.data_as(Ct.POINTER(Ct.c_int32)))
+        lo, hi = int(off[d0]), int(off[d1])
+        sub = np.arange(lo, hi)
+        mism = sub[z1[lo:hi] != zo[lo:hi]]
+        assert mism.size <= (1 - P.Z_AGREE) * (hi - lo)
+        doc_of = np.searchsorted(off, mism, side="right") - 1
+        for i, d in zip(mism, doc_of):
+            cdf, t = O.lda_token_cdf(theta[d], phi[c["w"][i]], seed, int(i), 3)
+            P._assert_boundary(cdf, t, int(z1[i]), int(zo[i]), f"token {i}",
+                               float(theta[d, z1[i]]) * float(phi[c["w"][i], z1[i]]))
+        checked += hi - lo
+    print("large: z checked on", checked, "tokens")
+    # counts: the whole tables against the oracle's nested loops on the GPU's own z
+    g.step_count()
+    n_dk, n_wk = g.get_counts()
+    o_dk, o_wk = O.lda_count(off, c["w"], z1, D, V, K)
+    assert np.array_equal(n_dk, o_dk) and np.array_equal(n_wk, o_wk)
+    del o_dk, o_wk
+    # theta on sampled document ranges, phi in full
+    g.step_resample_theta()
+    g.step_resample_phi()
+    _, th1, ph1, _ = g.get_state(z=False)
+    for d0 in (0, 200_000, D - 2000):
+        want = np.zeros((2000, K), dtype=np.float32)
+        nd = np.ascontiguousarray(n_dk[d0:d0 + 2000])
+        lg_first = d0 * K                         # variable index of entry (d, k) is d*K + k
+        lg = O.gamma_log_draws((alpha + nd).ravel(), seed, first=lg_first, sweep=3,
+                               stream=O.STREAM_THETA).reshape(2000, K)
+        from scipy import special
+        want = np.exp(lg - special.logsumexp(lg, axis=1, keepdims=True))
+        want = np.maximum(want, P.FLT_MIN)
+        P.assert_real_close(th1[d0:d0 + 2000], want.astype(np.float32), "theta rows")
+    P.assert_real_close(ph1, O.lda_resample_phi(n_wk, beta, seed, 3), "phi")
+    g.close()
