@@ -23,7 +23,7 @@ using namespace augur;
 namespace {
 
 constexpr int kRedBlocks = 1024;       // partial sums of the log-likelihood reductions
-constexpr int kPhiRowsPerBlock = 32;   // rows of the Gamma matrix handled by one block
+constexpr int kPhiRowsMax = 32;  // most rows of the Gamma matrix handled by one block
 
 // ------------------------------------------------------------------ DPP rows
 // A "row" is 16 consecutive lanes; DPP moves data inside rows at VALU speed.
@@ -234,7 +234,8 @@ constexpr int kQpBcast0 = 0x00, kQpBcast1 = 0x55, kQpBcast2 = 0xAA;
 constexpr int kNoTopic = 0x7FFFFFFF;
 
 template <int NS16>
-__global__ __launch_bounds__(256) void lda_sample_z_quad_kernel(
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NS16 > 8 ? 4 : 1)))
+void lda_sample_z_quad_kernel(
     const int32_t* __restrict__ w, const int64_t* __restrict__ doc_off,
     const float* __restrict__ theta, const float* __restrict__ phi, int32_t* __restrict__ z, int D,
     int K, int ldk, uint64_t seed, uint32_t sweep, unsigned long long* __restrict__ n_degenerate) {
@@ -248,15 +249,21 @@ __global__ __launch_bounds__(256) void lda_sample_z_quad_kernel(
   uint2* strip = strip_all[wave];
   float* theta_s = theta_all[wave];
 
-  // theta_d: registers for pass 1 (the quads all hold the same 16 NS16 values),
-  // LDS for the dynamically indexed read of pass 2
-  float4 th[NS16];
+  // theta_d: LDS copy for the dynamically indexed read of pass 2.  For pass 1 it
+  // sits in registers when the row is short; for long rows pass 1 reads it from
+  // LDS too (all quads read the same 16 bytes per lane: a broadcast), which keeps
+  // the kernel at 128 registers: four waves per SIMD instead of three, and the
+  // number of phi-row loads in flight is what bounds this kernel (measured on
+  // K=200: 4.13 ms with theta in registers, 3.12 ms this way).
+  constexpr bool kThetaRegs = NS16 <= 8;
+  float4 th[kThetaRegs ? NS16 : 1];
 #pragma unroll
   for (int c = 0; c < NS16; ++c) {
     const int col = 16 * c + 4 * q;
-    th[c] = col < ldk ? *reinterpret_cast<const float4*>(theta + (size_t)d * ldk + col)
-                      : make_float4(0.f, 0.f, 0.f, 0.f);
-    if (tq == 0) *reinterpret_cast<float4*>(theta_s + col) = th[c];
+    const float4 v = col < ldk ? *reinterpret_cast<const float4*>(theta + (size_t)d * ldk + col)
+                               : make_float4(0.f, 0.f, 0.f, 0.f);
+    if (kThetaRegs) th[c] = v;
+    if (tq == 0) *reinterpret_cast<float4*>(theta_s + col) = v;
   }
   const uint32_t row_bytes = 4u * (uint32_t)ldk;
   const uint32_t lane_off = 16u * (uint32_t)q;
@@ -278,35 +285,48 @@ __global__ __launch_bounds__(256) void lda_sample_z_quad_kernel(
     }
     const int64_t lo = a > base ? a : base;
     const int64_t hi = b < base + 256 ? b : base + 256;
-    for (int64_t i0 = lo; i0 < hi; i0 += 16) {
-      const int64_t i = i0 + tq;
-      const bool valid = i < hi;
-      const uint2 rw = strip[valid ? (int)(i - base) : (int)(lo - base)];
-      const uint32_t r = rw.x;
-      const uint32_t row_off = __umul24(rw.y, row_bytes);  // both below 2^24; product below 2^32
 
-      const char* rowp = phi_bytes + (size_t)(row_off + lane_off);  // constant offsets fold into the loads
+    // One token per quad.  (A two-register-set software pipeline of this loop
+    // was tried: it costs a wave of occupancy and ran slower.)
+    struct Tok {
       float4 ph[NS16];
+      uint32_t r, row_off;
+      int64_t i;
+      bool valid;
+    };
+    auto fetch = [&](Tok& T, int64_t i0) {
+      T.i = i0 + tq;
+      T.valid = T.i < hi;
+      const uint2 rw = strip[T.valid ? (int)(T.i - base) : (int)(lo - base)];
+      T.r = rw.x;
+      T.row_off = __umul24(rw.y, row_bytes);  // both below 2^24; product below 2^32
+      const char* rowp = phi_bytes + (size_t)(T.row_off + lane_off);  // constant offsets fold into the loads
 #pragma unroll
-      for (int c = 0; c < NS16 - 1; ++c) ph[c] = *reinterpret_cast<const float4*>(rowp + 64 * c);
-      ph[NS16 - 1] = *reinterpret_cast<const float4*>(phi_bytes + (row_off + last_off));
-
+      for (int c = 0; c < NS16 - 1; ++c) T.ph[c] = *reinterpret_cast<const float4*>(rowp + 64 * c);
+      T.ph[NS16 - 1] = *reinterpret_cast<const float4*>(phi_bytes + (T.row_off + last_off));
+    };
+    auto draw = [&](const Tok& T) {
       // pass 1: running stripe totals
+      int theta_off = 4 * q;
+      if (!kThetaRegs) asm volatile("" : "+v"(theta_off));  // keep the LDS reads inside the loop
+      const float* theta_q = theta_s + theta_off;
       float cum[NS16];
       float run = 0.f;
 #pragma unroll
       for (int c = 0; c < NS16; ++c) {
-        float s = th[c].x * ph[c].x;
-        s = fmaf(th[c].y, ph[c].y, s);
-        s = fmaf(th[c].z, ph[c].z, s);
-        s = fmaf(th[c].w, ph[c].w, s);
+        const float4 tc = kThetaRegs ? th[kThetaRegs ? c : 0]
+                                     : *reinterpret_cast<const float4*>(theta_q + 16 * c);
+        float s = tc.x * T.ph[c].x;
+        s = fmaf(tc.y, T.ph[c].y, s);
+        s = fmaf(tc.z, T.ph[c].z, s);
+        s = fmaf(tc.w, T.ph[c].w, s);
         s += dpp_f32<kQpSwap1>(s);
         s += dpp_f32<kQpSwap2>(s);
         run += s;
         cum[c] = run;
       }
       const float S = run;
-      const float t = u24(r) * S;
+      const float t = u24(T.r) * S;
 
       // crossing stripe and the total before it
       int cstar = 0;
@@ -321,7 +341,7 @@ __global__ __launch_bounds__(256) void lda_sample_z_quad_kernel(
       // pass 2: the 16 topics of stripe c*
       const int cs = min(cstar, NS16 - 1);
       const uint32_t off2 = min(64u * (uint32_t)cs + lane_off, row_bytes - 16u);
-      const float4 p2 = *reinterpret_cast<const float4*>(phi_bytes + (row_off + off2));
+      const float4 p2 = *reinterpret_cast<const float4*>(phi_bytes + (T.row_off + off2));
       const float4 t2 = *reinterpret_cast<const float4*>(theta_s + 16 * cs + 4 * q);
       const float l0 = t2.x * p2.x;
       const float l1 = fmaf(t2.y, p2.y, l0);
@@ -340,11 +360,11 @@ __global__ __launch_bounds__(256) void lda_sample_z_quad_kernel(
 
       const bool ok = S > 0.f && S <= FLT_MAX;  // false for 0, inf and NaN
       const bool found = cstar < NS16 && cand != kNoTopic;
-      if (__builtin_expect(__any(valid && !(ok && found)), 0)) {
+      if (__builtin_expect(__any(T.valid && !(ok && found)), 0)) {
         if (!ok) {
           // zero or non-finite mass: z = floor(u K)
-          k = u24_times(r, K);
-          if (valid && q == 0) atomicAdd(n_degenerate, 1ULL);
+          k = u24_times(T.r, K);
+          if (T.valid && q == 0) atomicAdd(n_degenerate, 1ULL);
         } else if (!found) {
           // rounding put t at or past the running sum that should exceed it: the
           // last topic of positive mass in the crossing stripe (or overall)
@@ -352,7 +372,7 @@ __global__ __launch_bounds__(256) void lda_sample_z_quad_kernel(
           int last = -1;
           for (int c = 0; c < NS16; ++c) {
             const uint32_t o = min(64u * (uint32_t)c + lane_off, row_bytes - 16u);
-            const float4 pp = *reinterpret_cast<const float4*>(phi_bytes + (row_off + o));
+            const float4 pp = *reinterpret_cast<const float4*>(phi_bytes + (T.row_off + o));
             const float4 tp = *reinterpret_cast<const float4*>(theta_s + 16 * c + 4 * q);
             const int kk = 16 * c + 4 * q;
             if (kk < limit) {
@@ -368,7 +388,13 @@ __global__ __launch_bounds__(256) void lda_sample_z_quad_kernel(
         }
       }
       // garbage parameters (negative or NaN entries) must not yield an index outside the tables
-      if (valid && q == 0) z[i] = min(max(k, 0), K - 1);
+      if (T.valid && q == 0) z[T.i] = min(max(k, 0), K - 1);
+    };
+
+    for (int64_t i0 = lo; i0 < hi; i0 += 16) {
+      Tok A;
+      fetch(A, i0);
+      draw(A);
     }
   }
 }
@@ -580,10 +606,10 @@ __global__ __launch_bounds__(256) void lda_resample_theta_kernel(
 // column of its block of rows and retries on its own variable (see theta).
 __global__ __launch_bounds__(256) void lda_phi_draw_kernel(
     const int32_t* __restrict__ n_wk, double* __restrict__ lg, double2* __restrict__ partial, int V,
-    int K, int ldk, double beta, const GammaShape* __restrict__ shapes, uint64_t seed,
-    uint32_t sweep, unsigned long long* __restrict__ n_capped) {
-  const int v0 = blockIdx.x * kPhiRowsPerBlock;
-  const int v1 = min(V, v0 + kPhiRowsPerBlock);
+    int K, int ldk, int rows_per_block, double beta, const GammaShape* __restrict__ shapes,
+    uint64_t seed, uint32_t sweep, unsigned long long* __restrict__ n_capped) {
+  const int v0 = blockIdx.x * rows_per_block;
+  const int v1 = min(V, v0 + rows_per_block);
   bool capped = false;
   for (int k0 = 0; k0 < K; k0 += blockDim.x) {
     const int k = k0 + threadIdx.x;
@@ -799,7 +825,7 @@ struct augur_lda {
   GammaShape *shapes_alpha = nullptr, *shapes_beta = nullptr;  // [kShapeTable] each
   double* red = nullptr;         // [4][kRedBlocks] reduction partials
   unsigned long long* counters = nullptr;  // [0] degenerate tokens [1] capped draws [2] bad input
-  int phi_blocks = 0;
+  int phi_blocks = 0, phi_rows = 0;
   int64_t sweep = 0;
   unsigned long long degenerate_reported = 0;
 };
@@ -947,7 +973,7 @@ int launch_phi(augur_lda* h, uint32_t sweep) {
   const int V = h->cfg.V, K = h->cfg.K;
   const int threads = (int)std::min<int64_t>(256, round_up(K, 64));
   hipLaunchKernelGGL(lda_phi_draw_kernel, dim3(h->phi_blocks), dim3(threads), 0, h->stream, h->n_wk,
-                     h->lg, h->col_partial, V, K, h->ldk, h->beta, h->shapes_beta, h->cfg.seed, sweep,
+                     h->lg, h->col_partial, V, K, h->ldk, h->phi_rows, h->beta, h->shapes_beta, h->cfg.seed, sweep,
                      h->counters + 1);
   hipLaunchKernelGGL(lda_phi_norm_kernel, dim3(K), dim3(256), 0, h->stream, h->col_partial,
                      h->col_logZ, h->phi_blocks, K);
@@ -1030,7 +1056,13 @@ int augur_lda_create(const augur_lda_config* cfg, const int32_t* doc_len, const 
   h->beta = (double)cfg->beta;
   h->ldk = (int)round_up(K, 4);
   h->ns = (h->ldk + 63) / 64;
-  h->phi_blocks = (V + kPhiRowsPerBlock - 1) / kPhiRowsPerBlock;
+  {
+    // enough column-waves to fill the chip several times over, at most kPhiRowsMax rows each
+    const int waves_per_block = (int)std::min<int64_t>(4, round_up(K, 64) / 64);
+    const int want_blocks = (16384 + waves_per_block - 1) / waves_per_block;
+    h->phi_rows = std::max(4, std::min(kPhiRowsMax, V / want_blocks));
+    h->phi_blocks = (V + h->phi_rows - 1) / h->phi_rows;
+  }
 
 #define AUGUR_CREATE_TRY(expr)                                                              \
   do {                                                                                      \
