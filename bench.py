@@ -63,6 +63,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="large", choices=["tiny", "medium", "large", "widek"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-overlap", action="store_true",
+                    help="build the word-count table on the main stream instead of beside the theta step")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB (a reference of known "
                          "size for scaling rocprofv3's FETCH_SIZE/WRITE_SIZE counters)")
@@ -92,6 +94,8 @@ def main():
     h = B.LDA(D, V, K, cfg["alpha"], cfg["beta"], cfg["seed"], doc_len_d, w_d, stream=stream,
               device_ptrs=True)
     t_create = time.perf_counter() - t0
+    if args.no_overlap:
+        h.set_overlap(False)
 
     if args.copy_probe_mib > 0:
         src = torch.empty(args.copy_probe_mib * (1 << 20) // 4, dtype=torch.float32, device="cuda")
@@ -138,6 +142,7 @@ def main():
                      "traffic": traffic, "algorithmic_bytes_per_launch": bytes_z,
                      "avg_launch_ms": t_z * 1e3},
         "kernel_ms_per_sweep": {k: v / steps for k, v in ms.items()},
+        "overlap_word_counts_with_theta": not args.no_overlap,
         "log_marginal_per_token": lm / max(N, 1),
         "degenerate_tokens": degenerate,
         "setup_s": {"generate_corpus": t_gen, "create": t_create},

@@ -76,11 +76,20 @@ void augur_lda_destroy(augur_lda* h); /* NULL is a no-op */
  * n_dk[d]); phi_k ~ Dirichlet(beta + n_wk[.][k]).  Asynchronous. */
 int augur_lda_sweep(augur_lda* h, int32_t n_sweeps);
 
-/* Same as sweep, but brackets each step with events on the handle's stream and
- * returns the summed device time of each step over the n_sweeps, in ms:
- * ms[0] sample_z, ms[1] count_accumulate, ms[2] resample theta, ms[3] resample
- * phi, ms[4] whole sweep (first event to last).  Events are recorded without host waits;
- * the call synchronises once at the end.  n_sweeps <= 4096. */
+/* After the z step the word table n_wk and the pair (document table n_dk, theta
+ * step) do not depend on each other.  With overlap on (the default) the word
+ * table is built on a second stream of the library's own (default priority)
+ * beside the other two; the phi step waits for both.  Results are identical
+ * either way.  Not to be changed while a sweep is in flight. */
+int augur_lda_set_overlap(augur_lda* h, int32_t on);
+
+/* Same as sweep, but records events on the handle's stream around the steps and
+ * returns the summed device time over the n_sweeps, in ms: ms[0] sample_z;
+ * ms[1] count_accumulate (with overlap on: the document table only, the word
+ * table runs beside ms[1] and ms[2]); ms[2] resample theta; ms[3] resample phi
+ * (with overlap on: including the wait for the word table); ms[4] whole sweep
+ * (first event to last).  Events are recorded without host waits; the call
+ * synchronises once at the end.  n_sweeps <= 4096. */
 #define AUGUR_LDA_NSTEPS 5
 int augur_lda_sweep_profile(augur_lda* h, int32_t n_sweeps, double* ms);
 

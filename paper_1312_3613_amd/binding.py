@@ -62,6 +62,7 @@ def lib():
         L.augur_lda_destroy.restype = None
         L.augur_lda_sweep.argtypes = [vp, C.c_int32]
         L.augur_lda_sweep_profile.argtypes = [vp, C.c_int32, C.POINTER(C.c_double)]
+        L.augur_lda_set_overlap.argtypes = [vp, C.c_int32]
         for name in ("step_sample_z", "step_count", "step_resample_theta", "step_resample_phi",
                      "step_finish", "sync"):
             getattr(L, "augur_lda_" + name).argtypes = [vp]
@@ -177,6 +178,9 @@ class LDA:
 
     def sweep(self, n=1):
         _check(lib().augur_lda_sweep(self._h, int(n)))
+
+    def set_overlap(self, on):
+        _check(lib().augur_lda_set_overlap(self._h, 1 if on else 0))
 
     def sweep_profile(self, n=1):
         ms = (C.c_double * LDA_NSTEPS)()

@@ -813,6 +813,9 @@ struct augur_lda {
   int ldk = 0;
   int ns = 0;  // stripes of 64 topics per token row
   hipStream_t stream = nullptr;
+  hipStream_t side = nullptr;  // second stream: word counts beside the theta step
+  hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+  bool overlap = true;
   double alpha = 0, beta = 0;
   int32_t *w = nullptr, *z = nullptr, *n_dk = nullptr, *n_wk = nullptr;
   int64_t* doc_off = nullptr;
@@ -841,6 +844,9 @@ void free_all(augur_lda* h) {
   (void)hipFree(h->counters); (void)hipFree(h->perm); (void)hipFree(h->word_off);
   (void)hipFree(h->slice_base); (void)hipFree(h->slice_part);
   (void)hipFree(h->shapes_alpha); (void)hipFree(h->shapes_beta);
+  if (h->side) (void)hipStreamDestroy(h->side);
+  if (h->ev_fork) (void)hipEventDestroy(h->ev_fork);
+  if (h->ev_join) (void)hipEventDestroy(h->ev_join);
 }
 
 int launch_sample_z(augur_lda* h, uint32_t sweep) {
@@ -878,19 +884,30 @@ int launch_sample_z(augur_lda* h, uint32_t sweep) {
   return AUGUR_OK;
 }
 
-int launch_count(augur_lda* h) {
-  const int D = h->cfg.D, V = h->cfg.V;
-  const size_t shm = sizeof(int32_t) * 4 * (size_t)h->ldk;
-  hipLaunchKernelGGL(lda_count_docs_kernel, dim3((D + 3) / 4), dim3(256), shm, h->stream, h->z,
-                     h->doc_off, h->n_dk, D, h->ldk);
-  hipLaunchKernelGGL(lda_count_words_kernel, dim3((h->n_slices + 3) / 4), dim3(256), shm, h->stream,
-                     h->z, h->perm, h->word_off, h->slice_base, h->n_wk, h->slice_part, V, h->ldk,
-                     h->n_slices);
-  hipLaunchKernelGGL(lda_count_words_merge_kernel, dim3(V), dim3(256),
-                     sizeof(int32_t) * 4 * (size_t)h->ldk, h->stream, h->slice_base, h->slice_part,
-                     h->n_wk, V, h->ldk);
+int launch_count_docs(augur_lda* h, hipStream_t stream) {
+  const int D = h->cfg.D;
+  hipLaunchKernelGGL(lda_count_docs_kernel, dim3((D + 3) / 4), dim3(256),
+                     sizeof(int32_t) * 4 * (size_t)h->ldk, stream, h->z, h->doc_off, h->n_dk, D,
+                     h->ldk);
   AUGUR_HIP_TRY(hipGetLastError());
   return AUGUR_OK;
+}
+
+int launch_count_words(augur_lda* h, hipStream_t stream) {
+  const int V = h->cfg.V;
+  const size_t shm = sizeof(int32_t) * 4 * (size_t)h->ldk;
+  hipLaunchKernelGGL(lda_count_words_kernel, dim3((h->n_slices + 3) / 4), dim3(256), shm, stream,
+                     h->z, h->perm, h->word_off, h->slice_base, h->n_wk, h->slice_part, V, h->ldk,
+                     h->n_slices);
+  hipLaunchKernelGGL(lda_count_words_merge_kernel, dim3(V), dim3(256), shm, stream, h->slice_base,
+                     h->slice_part, h->n_wk, V, h->ldk);
+  AUGUR_HIP_TRY(hipGetLastError());
+  return AUGUR_OK;
+}
+
+int launch_count(augur_lda* h) {
+  const int rc = launch_count_docs(h, h->stream);
+  return rc != AUGUR_OK ? rc : launch_count_words(h, h->stream);
 }
 
 // Sort the tokens by word once and cut each word's run into slices.
@@ -1082,6 +1099,9 @@ int augur_lda_create(const augur_lda_config* cfg, const int32_t* doc_len, const 
     return AUGUR_ERR_INVALID_ARG; \
   } while (0)
 
+  AUGUR_CREATE_TRY(hipStreamCreateWithFlags(&h->side, hipStreamNonBlocking));  // default priority
+  AUGUR_CREATE_TRY(hipEventCreateWithFlags(&h->ev_fork, hipEventDisableTiming));
+  AUGUR_CREATE_TRY(hipEventCreateWithFlags(&h->ev_join, hipEventDisableTiming));
   AUGUR_CREATE_TRY(hipMalloc(&h->counters, 4 * sizeof(unsigned long long)));
   AUGUR_CREATE_TRY(hipMemsetAsync(h->counters, 0, 4 * sizeof(unsigned long long), h->stream));
   AUGUR_CREATE_TRY(hipMalloc(&h->doc_off, sizeof(int64_t) * ((size_t)D + 1)));
@@ -1222,17 +1242,52 @@ int augur_lda_step_finish(augur_lda* h) {
   return AUGUR_OK;
 }
 
+// One sweep with index t.  After the z step the two count tables are independent:
+// the document table feeds the theta step, the word table the phi step.  With
+// overlap on, the word table (bound by 4-byte gathers) is built on a second
+// stream beside the document table and the theta step (bound by fp64 arithmetic);
+// the phi step waits for both.  ev, if given, receives five events on the main
+// stream: before z, after z, after the document counts, after theta, after phi.
+static int run_sweep(augur_lda* h, uint32_t t, hipEvent_t* ev) {
+#define AUGUR_MARK(i)                                            \
+  if (ev) AUGUR_HIP_TRY(hipEventRecord(ev[i], h->stream))
+  AUGUR_MARK(0);
+  AUGUR_TRY(launch_sample_z(h, t));
+  AUGUR_MARK(1);
+  if (h->overlap) {
+    // the short document-table kernel first, so that the theta step and the
+    // word-table kernel reach the dispatcher together
+    AUGUR_TRY(launch_count_docs(h, h->stream));
+    AUGUR_HIP_TRY(hipEventRecord(h->ev_fork, h->stream));
+    AUGUR_HIP_TRY(hipStreamWaitEvent(h->side, h->ev_fork, 0));
+  } else {
+    AUGUR_TRY(launch_count(h));
+  }
+  AUGUR_MARK(2);
+  AUGUR_TRY(launch_theta(h, t));
+  if (h->overlap) {
+    AUGUR_TRY(launch_count_words(h, h->side));
+    AUGUR_HIP_TRY(hipEventRecord(h->ev_join, h->side));
+  }
+  AUGUR_MARK(3);
+  if (h->overlap) AUGUR_HIP_TRY(hipStreamWaitEvent(h->stream, h->ev_join, 0));
+  AUGUR_TRY(launch_phi(h, t));
+  AUGUR_MARK(4);
+#undef AUGUR_MARK
+  h->sweep += 1;
+  return AUGUR_OK;
+}
+
 int augur_lda_sweep(augur_lda* h, int32_t n_sweeps) {
   AUGUR_CHECK_HANDLE(h);
   AUGUR_REQUIRE(n_sweeps >= 0, "n_sweeps = %d is negative", n_sweeps);
-  for (int32_t s = 0; s < n_sweeps; ++s) {
-    const uint32_t t = (uint32_t)(h->sweep + 1);
-    AUGUR_TRY(launch_sample_z(h, t));
-    AUGUR_TRY(launch_count(h));
-    AUGUR_TRY(launch_theta(h, t));
-    AUGUR_TRY(launch_phi(h, t));
-    h->sweep += 1;
-  }
+  for (int32_t s = 0; s < n_sweeps; ++s) AUGUR_TRY(run_sweep(h, (uint32_t)(h->sweep + 1), nullptr));
+  return AUGUR_OK;
+}
+
+int augur_lda_set_overlap(augur_lda* h, int32_t on) {
+  AUGUR_REQUIRE(h != nullptr, "handle is NULL");
+  h->overlap = on != 0;
   return AUGUR_OK;
 }
 
@@ -1255,19 +1310,8 @@ int augur_lda_sweep_profile(augur_lda* h, int32_t n_sweeps, double* ms) {
     if (fail_hip(hipEventCreate(&e), "hipEventCreate")) break;
   int done = 0;
   for (int32_t s = 0; s < n_sweeps && rc == AUGUR_OK; ++s) {
-    const uint32_t t = (uint32_t)(h->sweep + 1);
-    hipEvent_t* e = &ev[(size_t)s * 5];
-    if (fail_hip(hipEventRecord(e[0], h->stream), "hipEventRecord")) break;
-    if ((rc = launch_sample_z(h, t)) != AUGUR_OK) break;
-    if (fail_hip(hipEventRecord(e[1], h->stream), "hipEventRecord")) break;
-    if ((rc = launch_count(h)) != AUGUR_OK) break;
-    if (fail_hip(hipEventRecord(e[2], h->stream), "hipEventRecord")) break;
-    if ((rc = launch_theta(h, t)) != AUGUR_OK) break;
-    if (fail_hip(hipEventRecord(e[3], h->stream), "hipEventRecord")) break;
-    if ((rc = launch_phi(h, t)) != AUGUR_OK) break;
-    if (fail_hip(hipEventRecord(e[4], h->stream), "hipEventRecord")) break;
-    h->sweep += 1;
-    ++done;
+    rc = run_sweep(h, (uint32_t)(h->sweep + 1), &ev[(size_t)s * 5]);
+    if (rc == AUGUR_OK) ++done;
   }
   fail_hip(hipStreamSynchronize(h->stream), "hipStreamSynchronize");
   for (int s = 0; s < done && rc == AUGUR_OK; ++s) {

@@ -188,6 +188,19 @@ def test_resume_is_bit_exact_and_deterministic(B):
         h.close()
 
 
+def test_overlapped_and_serial_schedules_agree(B):
+    cfg = dict(synth.LDA_CONFIGS["tiny"], D=300, V=800, K=40, mean_len=120)
+    c = synth.lda_corpus(**cfg)
+    args = (cfg["D"], cfg["V"], cfg["K"], cfg["alpha"], cfg["beta"], 31, c["doc_len"], c["w"])
+    a, b = B.LDA(*args), B.LDA(*args)
+    b.set_overlap(False)
+    for n in (1, 3, 2):
+        a.sweep(n); b.sweep_profile(n)
+        for x, y in zip(a.get_state() + a.get_counts(), b.get_state() + b.get_counts()):
+            assert np.array_equal(x, y)
+    a.close(); b.close()
+
+
 def test_device_pointer_mode_and_stream(B):
     import torch
     cfg = dict(synth.LDA_CONFIGS["tiny"], D=50, V=120, K=10)
