@@ -233,14 +233,20 @@ constexpr int kQpSwap2 = 0x4E;   // quad_perm [2,3,0,1]
 constexpr int kQpBcast0 = 0x00, kQpBcast1 = 0x55, kQpBcast2 = 0xAA;
 constexpr int kNoTopic = 0x7FFFFFFF;
 
-template <int NS16>
+//
+// With kCountDocs the wave also builds its document's row of n_dk in LDS while it
+// draws and stores it at the end (the document half of the counting phase, for
+// free: the wave already owns the document).
+template <int NS16, bool kCountDocs>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NS16 > 8 ? 4 : 1)))
 void lda_sample_z_quad_kernel(
     const int32_t* __restrict__ w, const int64_t* __restrict__ doc_off,
-    const float* __restrict__ theta, const float* __restrict__ phi, int32_t* __restrict__ z, int D,
-    int K, int ldk, uint64_t seed, uint32_t sweep, unsigned long long* __restrict__ n_degenerate) {
+    const float* __restrict__ theta, const float* __restrict__ phi, int32_t* __restrict__ z,
+    int32_t* __restrict__ n_dk, int D, int K, int ldk, uint64_t seed, uint32_t sweep,
+    unsigned long long* __restrict__ n_degenerate) {
   __shared__ uint2 strip_all[4][256];            // {Philox word, word id} per token of the chunk
   __shared__ __align__(16) float theta_all[4][16 * NS16];
+  __shared__ int32_t hist_all[kCountDocs ? 4 : 1][kCountDocs ? 16 * NS16 : 1];
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   const int d = blockIdx.x * 4 + wave;
@@ -248,6 +254,9 @@ void lda_sample_z_quad_kernel(
   const int tq = lane >> 2, q = lane & 3;  // token slot of this quad, lane within the quad
   uint2* strip = strip_all[wave];
   float* theta_s = theta_all[wave];
+  int32_t* hist = hist_all[kCountDocs ? wave : 0];
+  if (kCountDocs)
+    for (int k = lane; k < 16 * NS16; k += 64) hist[k] = 0;
 
   // theta_d: LDS copy for the dynamically indexed read of pass 2.  For pass 1 it
   // sits in registers when the row is short; for long rows pass 1 reads it from
@@ -388,7 +397,11 @@ void lda_sample_z_quad_kernel(
         }
       }
       // garbage parameters (negative or NaN entries) must not yield an index outside the tables
-      if (T.valid && q == 0) z[T.i] = min(max(k, 0), K - 1);
+      k = min(max(k, 0), K - 1);
+      if (T.valid && q == 0) {
+        z[T.i] = k;
+        if (kCountDocs) atomicAdd(&hist[k], 1);
+      }
     };
 
     for (int64_t i0 = lo; i0 < hi; i0 += 16) {
@@ -396,6 +409,10 @@ void lda_sample_z_quad_kernel(
       fetch(A, i0);
       draw(A);
     }
+  }
+  if (kCountDocs) {
+    wave_lds_fence();
+    for (int k = lane; k < ldk; k += 64) n_dk[(size_t)d * ldk + k] = hist[k];
   }
 }
 
@@ -849,15 +866,25 @@ void free_all(augur_lda* h) {
   if (h->ev_join) (void)hipEventDestroy(h->ev_join);
 }
 
-int launch_sample_z(augur_lda* h, uint32_t sweep) {
+// fused: the kernel also writes the document table n_dk (K <= 256 only); returns
+// whether it did through *did_count.
+int launch_sample_z(augur_lda* h, uint32_t sweep, bool fuse_doc_counts = false,
+                    bool* did_count = nullptr) {
   const int D = h->cfg.D;
+  if (did_count) *did_count = false;
   if (D == 0 || h->N == 0) return AUGUR_OK;
   const dim3 grid((D + 3) / 4), block(256);
+#define AUGUR_ZQ_ARGS                                                                          \
+  grid, block, 0, h->stream, h->w, h->doc_off, h->theta, h->phi, h->z, h->n_dk, D, h->cfg.K,    \
+      h->ldk, h->cfg.seed, sweep, h->counters
 #define AUGUR_Z_ARGS                                                                          \
   grid, block, 0, h->stream, h->w, h->doc_off, h->theta, h->phi, h->z, D, h->cfg.K, h->ldk,   \
       h->cfg.seed, sweep, h->counters
-#define AUGUR_ZQ_CASE(N16) \
-  case N16: hipLaunchKernelGGL(lda_sample_z_quad_kernel<N16>, AUGUR_Z_ARGS); break;
+#define AUGUR_ZQ_CASE(N16)                                                                   \
+  case N16:                                                                                  \
+    if (fuse_doc_counts) hipLaunchKernelGGL((lda_sample_z_quad_kernel<N16, true>), AUGUR_ZQ_ARGS);  \
+    else hipLaunchKernelGGL((lda_sample_z_quad_kernel<N16, false>), AUGUR_ZQ_ARGS);          \
+    break;
 #define AUGUR_Z_CASE(NSV) \
   case NSV: hipLaunchKernelGGL(lda_sample_z_kernel<NSV>, AUGUR_Z_ARGS); break;
   if (h->ldk <= 256) {
@@ -867,6 +894,7 @@ int launch_sample_z(augur_lda* h, uint32_t sweep) {
       AUGUR_ZQ_CASE(11) AUGUR_ZQ_CASE(12) AUGUR_ZQ_CASE(13) AUGUR_ZQ_CASE(14) AUGUR_ZQ_CASE(15)
       AUGUR_ZQ_CASE(16)
     }
+    if (did_count) *did_count = fuse_doc_counts;
   } else {
     switch (h->ns) {
       AUGUR_Z_CASE(5) AUGUR_Z_CASE(6) AUGUR_Z_CASE(7) AUGUR_Z_CASE(8) AUGUR_Z_CASE(9)
@@ -880,6 +908,7 @@ int launch_sample_z(augur_lda* h, uint32_t sweep) {
 #undef AUGUR_Z_CASE
 #undef AUGUR_ZQ_CASE
 #undef AUGUR_Z_ARGS
+#undef AUGUR_ZQ_ARGS
   AUGUR_HIP_TRY(hipGetLastError());
   return AUGUR_OK;
 }
@@ -1252,16 +1281,19 @@ static int run_sweep(augur_lda* h, uint32_t t, hipEvent_t* ev) {
 #define AUGUR_MARK(i)                                            \
   if (ev) AUGUR_HIP_TRY(hipEventRecord(ev[i], h->stream))
   AUGUR_MARK(0);
-  AUGUR_TRY(launch_sample_z(h, t));
+  bool have_doc_counts = false;
+  AUGUR_TRY(launch_sample_z(h, t, true, &have_doc_counts));
   AUGUR_MARK(1);
   if (h->overlap) {
-    // the short document-table kernel first, so that the theta step and the
-    // word-table kernel reach the dispatcher together
-    AUGUR_TRY(launch_count_docs(h, h->stream));
+    // the short document-table kernel (if the z kernel did not build the table
+    // itself) first, so that the theta step and the word-table kernel reach the
+    // dispatcher together
+    if (!have_doc_counts) AUGUR_TRY(launch_count_docs(h, h->stream));
     AUGUR_HIP_TRY(hipEventRecord(h->ev_fork, h->stream));
     AUGUR_HIP_TRY(hipStreamWaitEvent(h->side, h->ev_fork, 0));
   } else {
-    AUGUR_TRY(launch_count(h));
+    if (!have_doc_counts) AUGUR_TRY(launch_count_docs(h, h->stream));
+    AUGUR_TRY(launch_count_words(h, h->stream));
   }
   AUGUR_MARK(2);
   AUGUR_TRY(launch_theta(h, t));
