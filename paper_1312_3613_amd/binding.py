@@ -174,7 +174,11 @@ class LDA:
             lib().augur_lda_destroy(self._h)
             self._h = None
 
-    __del__ = close
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:  # interpreter shutdown: the module globals may be gone
+            pass
 
     def sweep(self, n=1):
         _check(lib().augur_lda_sweep(self._h, int(n)))
@@ -262,7 +266,11 @@ class GMM:
             lib().augur_gmm_destroy(self._h)
             self._h = None
 
-    __del__ = close
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:  # interpreter shutdown: the module globals may be gone
+            pass
 
     def sweep(self, n=1):
         _check(lib().augur_gmm_sweep(self._h, int(n)))

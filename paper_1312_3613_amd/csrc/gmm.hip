@@ -44,9 +44,12 @@ __device__ __forceinline__ double gmm_logw(const float* __restrict__ xi, const d
 
 // Gibbs step for z: p(k) proportional to pi_k N(x_i; mu_k, sigma^2 I), drawn by
 // inverse CDF over the weights exp(l_k - max l), running sum in index order.
-// One thread per point; three passes over the K components (max, total, search)
-// so that no per-thread array is needed.  Thread t of a group of four computes
-// the Philox block shared by points 4b..4b+3 redundantly (cheap at this size).
+// One thread per point.  With kCache the K log-weights (then weights) of a
+// thread wait in its own LDS column between the three passes (max, total,
+// search); without it (K too large for LDS) they are recomputed.  Thread t of a
+// group of four computes the Philox block shared by points 4b..4b+3
+// redundantly (cheap at this size).
+template <bool kCache>
 __global__ __launch_bounds__(256) void gmm_sample_z_kernel(
     const float* __restrict__ x, const float* __restrict__ pi, const float* __restrict__ mu,
     int32_t* __restrict__ z, int64_t N, int dim, int K, double sigma, uint64_t seed, uint32_t sweep,
@@ -54,6 +57,7 @@ __global__ __launch_bounds__(256) void gmm_sample_z_kernel(
   extern __shared__ double sh[];
   double* mu_s = sh;              // [K][dim]
   double* lpi_s = sh + K * dim;   // [K]
+  double* col = lpi_s + K + threadIdx.x;  // [K][256]: this thread's column (kCache only)
   for (int e = threadIdx.x; e < K * dim; e += blockDim.x) mu_s[e] = (double)mu[e];
   for (int k = threadIdx.x; k < K; k += blockDim.x) lpi_s[k] = log((double)pi[k]);
   __syncthreads();
@@ -64,10 +68,15 @@ __global__ __launch_bounds__(256) void gmm_sample_z_kernel(
   double m = -INFINITY;
   for (int k = 0; k < K; ++k) {
     const double l = gmm_logw(xi, mu_s, lpi_s, k, dim, inv2s2);
+    if (kCache) col[k * 256] = l;
     m = l > m ? l : m;
   }
   double S = 0.0;
-  for (int k = 0; k < K; ++k) S += exp(gmm_logw(xi, mu_s, lpi_s, k, dim, inv2s2) - m);
+  for (int k = 0; k < K; ++k) {
+    const double p = exp((kCache ? col[k * 256] : gmm_logw(xi, mu_s, lpi_s, k, dim, inv2s2)) - m);
+    if (kCache) col[k * 256] = p;
+    S += p;
+  }
   const U4 blk = random_block(seed, (uint64_t)(i >> 2), sweep, kStreamZ, 0);
   const uint32_t r = word_of(blk, (uint32_t)(i & 3));
   int zi;
@@ -80,7 +89,7 @@ __global__ __launch_bounds__(256) void gmm_sample_z_kernel(
     int last = 0;
     zi = -1;
     for (int k = 0; k < K; ++k) {
-      const double p = exp(gmm_logw(xi, mu_s, lpi_s, k, dim, inv2s2) - m);
+      const double p = kCache ? col[k * 256] : exp(gmm_logw(xi, mu_s, lpi_s, k, dim, inv2s2) - m);
       const double Cn = C + p;
       if (Cn > C) last = k;
       C = Cn;
@@ -93,8 +102,9 @@ __global__ __launch_bounds__(256) void gmm_sample_z_kernel(
 
 // Sufficient statistics, deterministic: a block stages a chunk of points in
 // LDS; thread (k, j) walks the chunk in index order and adds x_i[j] when
-// z_i = k, thread k also counts.  Per-block partials are merged in block order
-// by the second kernel.
+// z_i = k (0.0 otherwise, which leaves the sum unchanged), thread k also
+// counts.  Per-block partials are then added in block order, one workgroup per
+// (k, j) pair with a fixed reduction tree.
 __global__ __launch_bounds__(256) void gmm_stats_partial_kernel(
     const float* __restrict__ x, const int32_t* __restrict__ z, int64_t N, int dim, int K,
     double* __restrict__ part_s, int32_t* __restrict__ part_n) {
@@ -110,11 +120,12 @@ __global__ __launch_bounds__(256) void gmm_stats_partial_kernel(
     const int k = pair / dim, j = pair - k * dim;
     double s = 0.0;
     int32_t c = 0;
-    for (int e = 0; e < n; ++e)
-      if (zs[e] == k) {
-        s += (double)xs[e * dim + j];
-        ++c;
-      }
+#pragma unroll 8
+    for (int e = 0; e < n; ++e) {
+      const bool mine = zs[e] == k;
+      s += mine ? (double)xs[e * dim + j] : 0.0;
+      c += mine ? 1 : 0;
+    }
     part_s[(size_t)blockIdx.x * K * dim + pair] = s;
     if (j == 0) part_n[(size_t)blockIdx.x * K + k] = c;
   }
@@ -125,16 +136,30 @@ __global__ __launch_bounds__(256) void gmm_stats_merge_kernel(const double* __re
                                                                int nblk, int dim, int K,
                                                                double* __restrict__ s_k,
                                                                int32_t* __restrict__ n_k) {
-  const int pair = blockIdx.x * blockDim.x + threadIdx.x;
-  if (pair >= K * dim) return;
-  double s = 0.0;
-  for (int b = 0; b < nblk; ++b) s += part_s[(size_t)b * K * dim + pair];
-  s_k[pair] = s;
+  __shared__ double ss[256];
+  __shared__ int32_t sn[256];
+  const int pair = blockIdx.x;  // one workgroup per (k, j)
   const int k = pair / dim;
-  if (pair - k * dim == 0) {
-    int32_t c = 0;
-    for (int b = 0; b < nblk; ++b) c += part_n[(size_t)b * K + k];
-    n_k[k] = c;
+  const bool count = pair - k * dim == 0;
+  double s = 0.0;
+  int32_t c = 0;
+  for (int b = threadIdx.x; b < nblk; b += 256) {
+    s += part_s[(size_t)b * K * dim + pair];
+    if (count) c += part_n[(size_t)b * K + k];
+  }
+  ss[threadIdx.x] = s;
+  sn[threadIdx.x] = c;
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) {
+    if ((int)threadIdx.x < o) {
+      ss[threadIdx.x] += ss[threadIdx.x + o];
+      sn[threadIdx.x] += sn[threadIdx.x + o];
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    s_k[pair] = ss[0];
+    if (count) n_k[k] = sn[0];
   }
 }
 
@@ -228,9 +253,16 @@ void free_all(augur_gmm* h) {
 int launch_z(augur_gmm* h, uint32_t sweep) {
   const int K = h->cfg.K, dim = h->cfg.dim;
   const int64_t N = h->cfg.N;
-  hipLaunchKernelGGL(gmm_sample_z_kernel, dim3((unsigned)((N + 255) / 256)), dim3(256),
-                     sizeof(double) * ((size_t)K * dim + K), h->stream, h->x, h->pi, h->mu, h->z, N,
-                     dim, K, h->sigma, h->cfg.seed, sweep, h->counters);
+  const size_t base_lds = sizeof(double) * ((size_t)K * dim + K);
+  const size_t cache_lds = base_lds + sizeof(double) * 256 * (size_t)K;
+  if (cache_lds <= 48 * 1024)
+    hipLaunchKernelGGL(gmm_sample_z_kernel<true>, dim3((unsigned)((N + 255) / 256)), dim3(256),
+                       cache_lds, h->stream, h->x, h->pi, h->mu, h->z, N, dim, K, h->sigma,
+                       h->cfg.seed, sweep, h->counters);
+  else
+    hipLaunchKernelGGL(gmm_sample_z_kernel<false>, dim3((unsigned)((N + 255) / 256)), dim3(256),
+                       base_lds, h->stream, h->x, h->pi, h->mu, h->z, N, dim, K, h->sigma,
+                       h->cfg.seed, sweep, h->counters);
   AUGUR_HIP_TRY(hipGetLastError());
   return AUGUR_OK;
 }
@@ -240,7 +272,7 @@ int launch_stats(augur_gmm* h) {
   const size_t shm = sizeof(float) * (size_t)kStatChunk * dim + sizeof(int32_t) * kStatChunk;
   hipLaunchKernelGGL(gmm_stats_partial_kernel, dim3(h->stat_blocks), dim3(256), shm, h->stream, h->x,
                      h->z, h->cfg.N, dim, K, h->part_s, h->part_n);
-  hipLaunchKernelGGL(gmm_stats_merge_kernel, dim3((K * dim + 255) / 256), dim3(256), 0, h->stream,
+  hipLaunchKernelGGL(gmm_stats_merge_kernel, dim3(K * dim), dim3(256), 0, h->stream,
                      h->part_s, h->part_n, h->stat_blocks, dim, K, h->s_k, h->n_k);
   AUGUR_HIP_TRY(hipGetLastError());
   return AUGUR_OK;

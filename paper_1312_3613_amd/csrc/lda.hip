@@ -719,36 +719,49 @@ __global__ __launch_bounds__(256) void lda_phi_write_kernel(const double* __rest
 // Per-token terms of the log joint (Sect. 4.1: log space, terms evaluated in
 // parallel and summed): ln theta[d][z_i] + ln phi[w_i][z_i], and
 // ln sum_k theta[d][k] phi[w_i][k] for the marginal.  One wave per document
-// slot, a 16-lane row per token, fp64 accumulation.
+// slot with theta_d in LDS, a quad per token (64 contiguous bytes of the phi row
+// per load, as in the sampler), fp64 products and sums.
 __global__ __launch_bounds__(256) void lda_loglik_tokens_kernel(
     const int32_t* __restrict__ w, const int32_t* __restrict__ z,
     const int64_t* __restrict__ doc_off, const float* __restrict__ theta,
     const float* __restrict__ phi, int D, int ldk, double* __restrict__ part_lik,
     double* __restrict__ part_marg) {
+  extern __shared__ float theta_lds[];  // [4][ldk16], ldk16 = ldk rounded up to 16
   __shared__ double smem[8];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int row = lane >> 4, j = lane & 15;
+  const int tq = lane >> 2, q = lane & 3;
+  const int ldk16 = (ldk + 15) & ~15;
+  float* th = theta_lds + (size_t)wave * ldk16;
+  const int stripes = ldk16 / 16;
+  const uint32_t row_bytes = 4u * (uint32_t)ldk;
+  const char* phi_bytes = reinterpret_cast<const char*>(phi);
   double lik = 0.0, marg = 0.0;
   for (int d = blockIdx.x * 4 + wave; d < D; d += gridDim.x * 4) {
-    const float* th = theta + (size_t)d * ldk;
+    wave_lds_fence();
+    for (int k = lane; k < ldk16; k += 64) th[k] = k < ldk ? theta[(size_t)d * ldk + k] : 0.f;
+    wave_lds_fence();
     const int64_t a = doc_off[d], b = doc_off[d + 1];
-    for (int64_t i0 = a; i0 < b; i0 += 4) {
-      const int64_t i = i0 + row;
+    for (int64_t i0 = a; i0 < b; i0 += 16) {
+      const int64_t i = i0 + tq;
       const bool valid = i < b;
-      const float* ph = phi + (size_t)(valid ? w[i] : 0) * ldk;
+      const uint32_t row_off = (uint32_t)(valid ? w[i] : 0) * row_bytes;
       double s = 0.0;
-      for (int col = 4 * j; col < ldk; col += 64) {
-        const float4 x = *reinterpret_cast<const float4*>(th + col);
-        const float4 y = *reinterpret_cast<const float4*>(ph + col);
-        s += (double)x.x * (double)y.x + (double)x.y * (double)y.y + (double)x.z * (double)y.z +
-             (double)x.w * (double)y.w;
+      for (int c = 0; c < stripes; ++c) {
+        const uint32_t off = min(64u * (uint32_t)c + 16u * (uint32_t)q, row_bytes - 16u);
+        const float4 y = *reinterpret_cast<const float4*>(phi_bytes + (row_off + off));
+        const float4 x = *reinterpret_cast<const float4*>(th + 16 * c + 4 * q);  // 0 past the row
+        s = fma((double)x.x, (double)y.x, s);
+        s = fma((double)x.y, (double)y.y, s);
+        s = fma((double)x.z, (double)y.z, s);
+        s = fma((double)x.w, (double)y.w, s);
       }
-#pragma unroll
-      for (int o = 8; o > 0; o >>= 1) s += __shfl_xor(s, o, 16);
-      if (valid && j == 0) {
+      s += __shfl_xor(s, 1, 64);
+      s += __shfl_xor(s, 2, 64);
+      if (valid && q == 0) {
         const int zi = z[i];
         marg += log(s);
-        lik += log((double)th[zi]) + log((double)ph[zi]);
+        lik += log((double)th[zi]) +
+               log((double)*reinterpret_cast<const float*>(phi_bytes + (row_off + 4u * (uint32_t)zi)));
       }
     }
   }
@@ -1369,7 +1382,8 @@ int augur_lda_loglik(augur_lda* h, double* log_joint, double* log_marginal_w) {
   double* p_marg = h->red + kRedBlocks;
   double* p_th = h->red + 2 * kRedBlocks;
   double* p_ph = h->red + 3 * kRedBlocks;
-  hipLaunchKernelGGL(lda_loglik_tokens_kernel, dim3(kRedBlocks), dim3(256), 0, h->stream, h->w, h->z,
+  hipLaunchKernelGGL(lda_loglik_tokens_kernel, dim3(kRedBlocks), dim3(256),
+                     sizeof(float) * 4 * (size_t)((h->ldk + 15) & ~15), h->stream, h->w, h->z,
                      h->doc_off, h->theta, h->phi, D, h->ldk, p_lik, p_marg);
   hipLaunchKernelGGL(sum_log_kernel, dim3(kRedBlocks), dim3(256), 0, h->stream, h->theta,
                      (int64_t)D, K, h->ldk, p_th);
