@@ -60,6 +60,52 @@ __device__ __forceinline__ int row_allreduce_max(int x) {
   return x;
 }
 
+// ------------------------------------------------------- document segments
+// The sampler gives one wave a whole document.  Documents longer than
+// kSegTokens positions are cut into segments of that length (counted from the
+// document's first 4-aligned position, so segments are whole Philox strips), one
+// wave each, so that a few very long documents do not serialise the launch.
+// seg_base[d] = id of document d's first segment; NULL when every document is a
+// single segment (then segment id = document id).
+constexpr int kSegTokens = 1024;
+struct Segment {
+  int d;                // document
+  int64_t a, b;         // the document's tokens
+  int64_t first, end;   // this segment: chunk bases first, first + 256, ... below end
+};
+__device__ __forceinline__ Segment segment_of(const int64_t* __restrict__ doc_off,
+                                              const int32_t* __restrict__ seg_base, int D, int s) {
+  Segment g;
+  if (seg_base == nullptr) {
+    g.d = s;
+    g.a = doc_off[s];
+    g.b = doc_off[s + 1];
+    g.first = g.a & ~(int64_t)3;
+    g.end = g.b;
+    return g;
+  }
+  int lo = 0, hi = D;  // largest d with seg_base[d] <= s
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (seg_base[mid] <= s) lo = mid; else hi = mid;
+  }
+  g.d = lo;
+  g.a = doc_off[lo];
+  g.b = doc_off[lo + 1];
+  g.first = (g.a & ~(int64_t)3) + (int64_t)(s - seg_base[lo]) * kSegTokens;
+  g.end = g.b < g.first + kSegTokens ? g.b : g.first + kSegTokens;
+  return g;
+}
+__global__ __launch_bounds__(256) void segment_counts_kernel(const int64_t* __restrict__ doc_off,
+                                                              int D, int32_t* __restrict__ ns) {
+  const int d = blockIdx.x * blockDim.x + threadIdx.x;
+  if (d > D) return;
+  if (d == D) { ns[d] = 0; return; }
+  const int64_t a = doc_off[d], b = doc_off[d + 1];
+  const int64_t span = b - (a & ~(int64_t)3);
+  ns[d] = (int32_t)(span <= kSegTokens ? 1 : (span + kSegTokens - 1) / kSegTokens);
+}
+
 // ------------------------------------------------------------------- init z
 // z_i = floor(K r / 2^32), r = word (i & 3) of block i >> 2 of the init stream.
 __global__ __launch_bounds__(256) void lda_init_z_kernel(int32_t* __restrict__ z, int64_t N, int K,
@@ -96,13 +142,16 @@ __global__ __launch_bounds__(256) void lda_init_z_kernel(int32_t* __restrict__ z
 template <int NS>
 __global__ __launch_bounds__(256) void lda_sample_z_kernel(
     const int32_t* __restrict__ w, const int64_t* __restrict__ doc_off,
-    const float* __restrict__ theta, const float* __restrict__ phi, int32_t* __restrict__ z, int D,
-    int K, int ldk, uint64_t seed, uint32_t sweep, unsigned long long* __restrict__ n_degenerate) {
+    const int32_t* __restrict__ seg_base, int n_segs, const float* __restrict__ theta,
+    const float* __restrict__ phi, int32_t* __restrict__ z, int D, int K, int ldk, uint64_t seed,
+    uint32_t sweep, unsigned long long* __restrict__ n_degenerate) {
   __shared__ uint32_t rnd[4][256];
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
-  const int d = blockIdx.x * 4 + wave;
-  if (d >= D) return;
+  const int seg = blockIdx.x * 4 + wave;
+  if (seg >= n_segs) return;
+  const Segment sg = segment_of(doc_off, seg_base, D, seg);
+  const int d = sg.d;
   const int row = lane >> 4, j = lane & 15;
 
   // theta_d in registers; chunks past the last topic hold 0.  Every lane's byte
@@ -121,8 +170,8 @@ __global__ __launch_bounds__(256) void lda_sample_z_kernel(
   const char* phi_bytes = reinterpret_cast<const char*>(phi);
   const uint32_t row_bytes = 4u * (uint32_t)ldk;
 
-  const int64_t a = doc_off[d], b = doc_off[d + 1];
-  for (int64_t base = a & ~(int64_t)3; base < b; base += 256) {
+  const int64_t a = sg.a, b = sg.end;
+  for (int64_t base = sg.first; base < b; base += 256) {
     {
       const U4 r = random_block(seed, (uint64_t)(base >> 2) + (uint64_t)lane, sweep, kStreamZ, 0);
       wave_lds_fence();  // earlier reads of the strip are done
@@ -241,16 +290,18 @@ template <int NS16, bool kCountDocs>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NS16 > 8 ? 4 : 1)))
 void lda_sample_z_quad_kernel(
     const int32_t* __restrict__ w, const int64_t* __restrict__ doc_off,
-    const float* __restrict__ theta, const float* __restrict__ phi, int32_t* __restrict__ z,
-    int32_t* __restrict__ n_dk, int D, int K, int ldk, uint64_t seed, uint32_t sweep,
-    unsigned long long* __restrict__ n_degenerate) {
+    const int32_t* __restrict__ seg_base, int n_segs, const float* __restrict__ theta,
+    const float* __restrict__ phi, int32_t* __restrict__ z, int32_t* __restrict__ n_dk, int D, int K,
+    int ldk, uint64_t seed, uint32_t sweep, unsigned long long* __restrict__ n_degenerate) {
   __shared__ uint2 strip_all[4][256];            // {Philox word, word id} per token of the chunk
   __shared__ __align__(16) float theta_all[4][16 * NS16];
   __shared__ int32_t hist_all[kCountDocs ? 4 : 1][kCountDocs ? 16 * NS16 : 1];
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
-  const int d = blockIdx.x * 4 + wave;
-  if (d >= D) return;
+  const int seg = blockIdx.x * 4 + wave;
+  if (seg >= n_segs) return;
+  const Segment sg = segment_of(doc_off, seg_base, D, seg);
+  const int d = sg.d;
   const int tq = lane >> 2, q = lane & 3;  // token slot of this quad, lane within the quad
   uint2* strip = strip_all[wave];
   float* theta_s = theta_all[wave];
@@ -279,8 +330,8 @@ void lda_sample_z_quad_kernel(
   const uint32_t last_off = min(64u * (NS16 - 1) + lane_off, row_bytes - 16u);
   const char* phi_bytes = reinterpret_cast<const char*>(phi);
 
-  const int64_t a = doc_off[d], b = doc_off[d + 1];
-  for (int64_t base = a & ~(int64_t)3; base < b; base += 256) {
+  const int64_t a = sg.a, b = sg.end;
+  for (int64_t base = sg.first; base < b; base += 256) {
     {
       // tokens base + 4 lane .. + 3: one Philox block and four word ids (w is
       // padded by 256 entries, so the vector load never leaves the allocation)
@@ -851,6 +902,8 @@ struct augur_lda {
   int64_t* doc_off = nullptr;
   int32_t *perm = nullptr, *word_off = nullptr, *slice_base = nullptr, *slice_part = nullptr;
   int n_slices = 0;
+  int32_t* seg_base = nullptr;  // NULL: every document is one segment
+  int n_segs = 0;
   float *theta = nullptr, *phi = nullptr;
   double* lg = nullptr;          // [V][ldk] ln Gamma draws of the phi step
   double2* col_partial = nullptr;  // [phi row blocks][K]
@@ -873,7 +926,7 @@ void free_all(augur_lda* h) {
   (void)hipFree(h->col_partial); (void)hipFree(h->col_logZ); (void)hipFree(h->red);
   (void)hipFree(h->counters); (void)hipFree(h->perm); (void)hipFree(h->word_off);
   (void)hipFree(h->slice_base); (void)hipFree(h->slice_part);
-  (void)hipFree(h->shapes_alpha); (void)hipFree(h->shapes_beta);
+  (void)hipFree(h->shapes_alpha); (void)hipFree(h->shapes_beta); (void)hipFree(h->seg_base);
   if (h->side) (void)hipStreamDestroy(h->side);
   if (h->ev_fork) (void)hipEventDestroy(h->ev_fork);
   if (h->ev_join) (void)hipEventDestroy(h->ev_join);
@@ -886,13 +939,15 @@ int launch_sample_z(augur_lda* h, uint32_t sweep, bool fuse_doc_counts = false,
   const int D = h->cfg.D;
   if (did_count) *did_count = false;
   if (D == 0 || h->N == 0) return AUGUR_OK;
-  const dim3 grid((D + 3) / 4), block(256);
+  const dim3 grid((h->n_segs + 3) / 4), block(256);
+  // a document cut into segments has no single wave that sees all of its tokens
+  if (h->seg_base != nullptr) fuse_doc_counts = false;
 #define AUGUR_ZQ_ARGS                                                                          \
-  grid, block, 0, h->stream, h->w, h->doc_off, h->theta, h->phi, h->z, h->n_dk, D, h->cfg.K,    \
-      h->ldk, h->cfg.seed, sweep, h->counters
+  grid, block, 0, h->stream, h->w, h->doc_off, h->seg_base, h->n_segs, h->theta, h->phi, h->z,  \
+      h->n_dk, D, h->cfg.K, h->ldk, h->cfg.seed, sweep, h->counters
 #define AUGUR_Z_ARGS                                                                          \
-  grid, block, 0, h->stream, h->w, h->doc_off, h->theta, h->phi, h->z, D, h->cfg.K, h->ldk,   \
-      h->cfg.seed, sweep, h->counters
+  grid, block, 0, h->stream, h->w, h->doc_off, h->seg_base, h->n_segs, h->theta, h->phi, h->z, \
+      D, h->cfg.K, h->ldk, h->cfg.seed, sweep, h->counters
 #define AUGUR_ZQ_CASE(N16)                                                                   \
   case N16:                                                                                  \
     if (fuse_doc_counts) hipLaunchKernelGGL((lda_sample_z_quad_kernel<N16, true>), AUGUR_ZQ_ARGS);  \
@@ -1225,6 +1280,34 @@ int augur_lda_create(const augur_lda_config* cfg, const int32_t* doc_len, const 
       free_all(h);
       delete h;
       return rc_w;
+    }
+  }
+
+  {
+    // segments of long documents
+    int32_t* ns = nullptr;
+    void* temp = nullptr;
+    size_t temp_bytes = 0;
+    AUGUR_CREATE_TRY(hipMalloc(&ns, sizeof(int32_t) * ((size_t)D + 1)));
+    hipError_t e = hipMalloc(&h->seg_base, sizeof(int32_t) * ((size_t)D + 1));
+    hipLaunchKernelGGL(segment_counts_kernel, dim3((D + 256) / 256), dim3(256), 0, h->stream,
+                       h->doc_off, D, ns);
+    if (e == hipSuccess)
+      e = hipcub::DeviceScan::ExclusiveSum(nullptr, temp_bytes, ns, h->seg_base, D + 1, h->stream);
+    if (e == hipSuccess) e = hipMalloc(&temp, std::max<size_t>(temp_bytes, 16));
+    if (e == hipSuccess)
+      e = hipcub::DeviceScan::ExclusiveSum(temp, temp_bytes, ns, h->seg_base, D + 1, h->stream);
+    int32_t total = 0;
+    if (e == hipSuccess)
+      e = hipMemcpyAsync(&total, h->seg_base + D, sizeof(int32_t), hipMemcpyDeviceToHost, h->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(h->stream);
+    (void)hipFree(ns);
+    (void)hipFree(temp);
+    AUGUR_CREATE_TRY(e);
+    h->n_segs = total;
+    if (total == D) {  // the common case: no table needed
+      (void)hipFree(h->seg_base);
+      h->seg_base = nullptr;
     }
   }
 

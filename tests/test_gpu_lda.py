@@ -188,6 +188,27 @@ def test_resume_is_bit_exact_and_deterministic(B):
         h.close()
 
 
+@pytest.mark.parametrize("K", [20, 300])
+def test_long_documents_are_cut_into_segments(B, K):
+    # documents beyond 1024 positions are walked by several waves; results must not change
+    lens = [5000, 3, 1025, 1021, 0, 2500, 1024, 1020, 7]
+    D, V = len(lens), 400
+    lens, w = ragged_corpus(D, V, K, seed=K + 1, lens=lens)
+    g, o = make_pair(B, D, V, K, 0.1, 0.01, 500 + K, lens, w)
+    for _ in range(2):
+        lockstep_sweep(g, o, check_loglik=True)
+    # the sweep entry point (fused / overlapped schedule) against the step-wise one
+    g2 = B.LDA(D, V, K, 0.1, 0.01, 500 + K, lens, w)
+    g2.sweep(3)
+    g3 = B.LDA(D, V, K, 0.1, 0.01, 500 + K, lens, w)
+    for _ in range(3):
+        g3.step_sample_z(); g3.step_count(); g3.step_resample_theta(); g3.step_resample_phi(); g3.step_finish()
+    for x, y in zip(g2.get_state() + g2.get_counts(), g3.get_state() + g3.get_counts()):
+        assert np.array_equal(x, y)
+    for h in (g, g2, g3):
+        h.close()
+
+
 def test_overlapped_and_serial_schedules_agree(B):
     cfg = dict(synth.LDA_CONFIGS["tiny"], D=300, V=800, K=40, mean_len=120)
     c = synth.lda_corpus(**cfg)
