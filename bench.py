@@ -62,7 +62,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="large", choices=["tiny", "medium", "large", "widek"])
+    ap.add_argument("--workload", default="large", choices=["tiny", "medium", "large", "widek", "paper_shape"])
+    ap.add_argument("--topics", type=int, default=None,
+                    help="infer with this many topics instead of the number the corpus was drawn with")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-overlap", action="store_true",
                     help="build the word-count table on the main stream instead of beside the theta step")
@@ -84,6 +86,8 @@ def main():
     t0 = time.perf_counter()
     corpus = synth.lda_corpus(**cfg)
     t_gen = time.perf_counter() - t0
+    if args.topics is not None:
+        cfg = dict(cfg, K=args.topics)
     N, D, V, K = corpus["N"], cfg["D"], cfg["V"], cfg["K"]
 
     torch.cuda.set_device(0)

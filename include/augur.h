@@ -76,6 +76,16 @@ void augur_lda_destroy(augur_lda* h); /* NULL is a no-op */
  * n_dk[d]); phi_k ~ Dirichlet(beta + n_wk[.][k]).  Asynchronous. */
 int augur_lda_sweep(augur_lda* h, int32_t n_sweeps);
 
+/* Extra observed variables, as in the paper's second call of Fig. 3,
+ * map(Set("phi"), ...): with AUGUR_OBSERVE_PHI the handle's phi (put there with
+ * set_state, e.g. the phi learnt on a training corpus) is data; sweep then draws
+ * z, counts n_dk and redraws theta only, and leaves phi and n_wk untouched.
+ * loglik's log_marginal_w of such a handle over held-out documents is the log
+ * predictive probability sum_i ln sum_k theta_d[k] phi[w_i][k].  mask = 0 turns
+ * it off.  The step_x calls are not affected. */
+#define AUGUR_OBSERVE_PHI 1u
+int augur_lda_set_observed(augur_lda* h, uint32_t mask);
+
 /* After the z step the word table n_wk and the pair (document table n_dk, theta
  * step) do not depend on each other.  With overlap on (the default) the word
  * table is built on a second stream of the library's own (default priority)

@@ -349,6 +349,18 @@ int64_t orc_lda_sweep(int32_t D, int32_t V, int32_t K, double alpha, double beta
   return deg;
 }
 
+// The same sweep with phi observed (Fig. 3, second call: the variable set
+// {"phi"} is added to the observed ones): only z and theta are inferred.
+int64_t orc_lda_sweep_phi_observed(int32_t D, int32_t V, int32_t K, double alpha,
+                                   const int64_t* doc_off, const int32_t* w, uint64_t seed,
+                                   uint32_t sweep, int32_t* z, float* theta, const float* phi,
+                                   int32_t* n_dk, int32_t* n_wk_scratch) {
+  const int64_t deg = orc_lda_sample_z(D, K, doc_off, w, theta, phi, seed, sweep, z);
+  orc_lda_count(D, V, K, doc_off, w, z, n_dk, n_wk_scratch);
+  orc_lda_resample_theta(D, K, alpha, n_dk, seed, sweep, theta);
+  return deg;
+}
+
 // Default initial state: z from the init stream, counts, then theta and phi
 // drawn from their conditionals with sweep index 0.
 void orc_lda_init(int32_t D, int32_t V, int32_t K, double alpha, double beta,

@@ -33,6 +33,7 @@ def lib():
         L.orc_gamma_log_draws.restype = C.c_int
         L.orc_lda_sample_z.restype = C.c_int64
         L.orc_lda_sweep.restype = C.c_int64
+        L.orc_lda_sweep_phi_observed.restype = C.c_int64
         L.orc_gmm_sample_z.restype = C.c_int64
         L.orc_gmm_sweep.restype = C.c_int64
         L.orc_gmm_loglik.restype = C.c_double
@@ -202,6 +203,7 @@ class OracleLDA:
         self.n_wk = np.zeros((self.V, self.K), dtype=np.int32)
         self.sweep_index = 0
         self.degenerate = 0
+        self.phi_observed = False
         lib().orc_lda_init(C.c_int32(self.D), C.c_int32(self.V), C.c_int32(self.K),
                            C.c_double(self.alpha), C.c_double(self.beta),
                            _p(self.doc_off, C.c_int64), _p(self.w, C.c_int32),
@@ -209,9 +211,21 @@ class OracleLDA:
                            _p(self.theta, C.c_float), _p(self.phi, C.c_float),
                            _p(self.n_dk, C.c_int32), _p(self.n_wk, C.c_int32))
 
+    def set_observed(self, phi=False):
+        self.phi_observed = bool(phi)
+
     def sweep(self, n=1):
         for _ in range(n):
             t = self.sweep_index + 1
+            if self.phi_observed:
+                scratch = np.zeros_like(self.n_wk)
+                self.degenerate += lib().orc_lda_sweep_phi_observed(
+                    C.c_int32(self.D), C.c_int32(self.V), C.c_int32(self.K), C.c_double(self.alpha),
+                    _p(self.doc_off, C.c_int64), _p(self.w, C.c_int32), C.c_uint64(self.seed),
+                    C.c_uint32(t), _p(self.z, C.c_int32), _p(self.theta, C.c_float),
+                    _p(self.phi, C.c_float), _p(self.n_dk, C.c_int32), _p(scratch, C.c_int32))
+                self.sweep_index = t
+                continue
             self.degenerate += lib().orc_lda_sweep(
                 C.c_int32(self.D), C.c_int32(self.V), C.c_int32(self.K), C.c_double(self.alpha),
                 C.c_double(self.beta), _p(self.doc_off, C.c_int64), _p(self.w, C.c_int32),

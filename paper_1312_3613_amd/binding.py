@@ -63,6 +63,7 @@ def lib():
         L.augur_lda_sweep.argtypes = [vp, C.c_int32]
         L.augur_lda_sweep_profile.argtypes = [vp, C.c_int32, C.POINTER(C.c_double)]
         L.augur_lda_set_overlap.argtypes = [vp, C.c_int32]
+        L.augur_lda_set_observed.argtypes = [vp, C.c_uint32]
         for name in ("step_sample_z", "step_count", "step_resample_theta", "step_resample_phi",
                      "step_finish", "sync"):
             getattr(L, "augur_lda_" + name).argtypes = [vp]
@@ -182,6 +183,9 @@ class LDA:
 
     def sweep(self, n=1):
         _check(lib().augur_lda_sweep(self._h, int(n)))
+
+    def set_observed(self, phi=False):
+        _check(lib().augur_lda_set_observed(self._h, 1 if phi else 0))
 
     def set_overlap(self, on):
         _check(lib().augur_lda_set_overlap(self._h, 1 if on else 0))

@@ -897,6 +897,7 @@ struct augur_lda {
   hipStream_t side = nullptr;  // second stream: word counts beside the theta step
   hipEvent_t ev_fork = nullptr, ev_join = nullptr;
   bool overlap = true;
+  bool phi_observed = false;  // phi is data: sweeps leave it (and the word table) alone
   double alpha = 0, beta = 0;
   int32_t *w = nullptr, *z = nullptr, *n_dk = nullptr, *n_wk = nullptr;
   int64_t* doc_off = nullptr;
@@ -1380,6 +1381,17 @@ static int run_sweep(augur_lda* h, uint32_t t, hipEvent_t* ev) {
   bool have_doc_counts = false;
   AUGUR_TRY(launch_sample_z(h, t, true, &have_doc_counts));
   AUGUR_MARK(1);
+  if (h->phi_observed) {
+    // phi held fixed (the paper's map(Set("phi"), ...) use on held-out documents):
+    // only z and theta are inferred, so neither the word table nor phi is touched
+    if (!have_doc_counts) AUGUR_TRY(launch_count_docs(h, h->stream));
+    AUGUR_MARK(2);
+    AUGUR_TRY(launch_theta(h, t));
+    AUGUR_MARK(3);
+    AUGUR_MARK(4);
+    h->sweep += 1;
+    return AUGUR_OK;
+  }
   if (h->overlap) {
     // the short document-table kernel (if the z kernel did not build the table
     // itself) first, so that the theta step and the word-table kernel reach the
@@ -1410,6 +1422,13 @@ int augur_lda_sweep(augur_lda* h, int32_t n_sweeps) {
   AUGUR_CHECK_HANDLE(h);
   AUGUR_REQUIRE(n_sweeps >= 0, "n_sweeps = %d is negative", n_sweeps);
   for (int32_t s = 0; s < n_sweeps; ++s) AUGUR_TRY(run_sweep(h, (uint32_t)(h->sweep + 1), nullptr));
+  return AUGUR_OK;
+}
+
+int augur_lda_set_observed(augur_lda* h, uint32_t mask) {
+  AUGUR_REQUIRE(h != nullptr, "handle is NULL");
+  AUGUR_REQUIRE((mask & ~AUGUR_OBSERVE_PHI) == 0, "unknown observed-variable bits 0x%x", mask);
+  h->phi_observed = (mask & AUGUR_OBSERVE_PHI) != 0;
   return AUGUR_OK;
 }
 

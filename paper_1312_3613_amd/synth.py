@@ -19,6 +19,11 @@ LDA_CONFIGS = {
                   sweeps=20, seed=20131215),
     "widek": dict(D=50_000, V=100_000, K=1000, mean_len=200, alpha=0.01, beta=0.01, zipf=1.1,
                   sweeps=10, seed=20131216),
+    # the shape of the paper's own corpus (Sect. "Experimental study": 47,556 training documents,
+    # 37,276 words, about 3.2M tokens), generated with 100 topics; used for the run over the
+    # number of topics (the paper's figure of run time against K)
+    "paper_shape": dict(D=47_556, V=37_276, K=100, mean_len=68, alpha=0.1, beta=0.01, zipf=1.1,
+                        sweeps=50, seed=20131217),
 }
 
 GMM_CONFIG = dict(N=1_000_000, dim=8, K=16, alpha=1.0, prior_sd=10.0, sigma=1.0, sweeps=50,

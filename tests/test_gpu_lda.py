@@ -209,6 +209,42 @@ def test_long_documents_are_cut_into_segments(B, K):
         h.close()
 
 
+def test_fold_in_with_phi_observed(B):
+    # learn phi on a training corpus, then infer z and theta on held-out documents with phi as data
+    cfg = dict(synth.LDA_CONFIGS["tiny"], D=240, V=300, K=12, mean_len=60)
+    c = synth.lda_corpus(**cfg)
+    n_train = 200
+    ntok = int(c["doc_len"][:n_train].sum())
+    a, b, seed = cfg["alpha"], cfg["beta"], 77
+    train = B.LDA(n_train, cfg["V"], cfg["K"], a, b, seed, c["doc_len"][:n_train], c["w"][:ntok])
+    train.sweep(30)
+    phi = train.get_state(z=False, theta=False)[2]
+    test_args = (cfg["D"] - n_train, cfg["V"], cfg["K"], a, b, seed + 1, c["doc_len"][n_train:], c["w"][ntok:])
+    g, o = B.LDA(*test_args), O.OracleLDA(*test_args)
+    for h in (g, o):
+        h.set_state(phi=phi)
+        h.set_observed(phi=True)
+    lm0 = g.loglik()[1]
+    n_wk_before = g.get_counts()[1]
+    for _ in range(5):
+        theta0 = o.theta.copy()
+        g.set_state(z=o.z, theta=o.theta, sweep=o.sweep_index)
+        g.sweep(1); o.sweep(1)
+        z, th, ph, sw = g.get_state()
+        assert np.array_equal(ph, phi) and sw == o.sweep_index
+        nm = P.assert_z_lda(z, o.z, o.doc_off, o.w, theta0, phi, o.seed, o.sweep_index)
+        if nm == 0:
+            assert np.array_equal(g.get_counts()[0], o.n_dk)
+            P.assert_real_close(th, o.theta, "theta")
+    g.set_state(z=o.z, theta=o.theta)
+    lj, lm = g.loglik()
+    olj, olm = o.loglik()
+    assert abs(lm - olm) <= P.REAL_RTOL * abs(olm) and abs(lj - olj) <= P.REAL_RTOL * abs(olj)
+    assert lm > lm0                                         # the held-out fit improves from the random start
+    g.set_observed(phi=False)
+    train.close(); g.close()
+
+
 def test_overlapped_and_serial_schedules_agree(B):
     cfg = dict(synth.LDA_CONFIGS["tiny"], D=300, V=800, K=40, mean_len=120)
     c = synth.lda_corpus(**cfg)

@@ -273,3 +273,30 @@ def test_flat_phi_reduces_z_to_draws_from_theta():
     z, _ = O.lda_sample_z(O.doc_offsets([n]), w, theta, phi, seed=12, sweep=1)
     p = theta[0].astype(np.float64)
     assert stats.chisquare(np.bincount(z, minlength=K), p / p.sum() * n).pvalue > 1e-4
+
+
+def test_phi_observed_sweep_targets_theta_posterior_given_phi():
+    # Fig. 3's second call (phi added to the observed set): with phi fixed the chain over (z, theta)
+    # has theta-marginal p(theta | w, phi) ~ Beta-prior x prod_i (theta phi[w_i][0] + (1-theta) phi[w_i][1]),
+    # integrated numerically here for one document and K = 2.
+    from scipy import integrate
+    V, K, alpha = 3, 2, 0.7
+    phi = np.array([[0.6, 0.1], [0.3, 0.2], [0.1, 0.7]], dtype=np.float32)
+    w = np.array([0, 0, 2, 1, 2, 2, 0], dtype=np.int32)
+    ph = phi.astype(np.float64)
+
+    def dens(t):
+        return t ** (alpha - 1) * (1 - t) ** (alpha - 1) * np.prod(t * ph[w, 0] + (1 - t) * ph[w, 1])
+    Z = integrate.quad(dens, 0, 1)[0]
+    m1 = integrate.quad(lambda t: t * dens(t), 0, 1)[0] / Z
+    m2 = integrate.quad(lambda t: t * t * dens(t), 0, 1)[0] / Z
+    m = O.OracleLDA(1, V, K, alpha, 0.5, seed=9, doc_len=[w.size], w=w)
+    m.set_state(phi=phi)
+    m.set_observed(phi=True)
+    T = 60_000
+    g = np.empty((T, 2))
+    for t in range(T):
+        m.sweep(1)
+        g[t] = [m.theta[0, 0], m.theta[0, 0] ** 2]
+    assert np.array_equal(m.phi, phi)                       # phi is data: untouched
+    _batch_check(g, np.array([m1, m2]))
