@@ -71,7 +71,7 @@ void philox4x32_10(const uint32_t ctr_in[4], const uint32_t key_in[2], uint32_t 
 
 enum Stream : uint32_t {
   STREAM_INIT_Z = 0, STREAM_Z = 1, STREAM_THETA = 2, STREAM_PHI = 3,
-  STREAM_GMM_PI = 4, STREAM_GMM_MU = 5
+  STREAM_GMM_PI = 4, STREAM_GMM_MU = 5, STREAM_GMM_VAR = 6
 };
 
 // The block of four 32-bit words belonging to (seed, variable index, sweep,
@@ -198,6 +198,29 @@ void gmm_point_cdf(const float* x, const float* pi, const float* mu, int K, int 
       q += df * df;
     }
     l[k] = std::log((double)pi[k]) - q / (2.0 * sigma * sigma);
+    if (l[k] > m) m = l[k];
+  }
+  double C = 0.0;
+  for (int k = 0; k < K; ++k) {
+    C += std::exp(l[k] - m);
+    cdf[k] = C;
+  }
+}
+
+// Mixture conditional with a variance per component:
+// ln pi_k - (dim/2) ln var_k - |x - mu_k|^2 / (2 var_k).
+void gmmuv_point_cdf(const float* x, const float* pi, const float* mu, const float* var, int K,
+                     int dim, double* cdf) {
+  std::vector<double> l(K);
+  double m = -INFINITY;
+  for (int k = 0; k < K; ++k) {
+    double q = 0.0;
+    for (int j = 0; j < dim; ++j) {
+      const double df = (double)x[j] - (double)mu[(int64_t)k * dim + j];
+      q += df * df;
+    }
+    const double v = (double)var[k];
+    l[k] = std::log((double)pi[k]) - 0.5 * (double)dim * std::log(v) - q / (2.0 * v);
     if (l[k] > m) m = l[k];
   }
   double C = 0.0;
@@ -499,6 +522,129 @@ double orc_gmm_loglik(int64_t N, int32_t dim, int32_t K, double alpha, double pr
     }
     lj += std::log((double)pi[k]) - 0.5 * (double)dim * LN_2PI - (double)dim * std::log(sigma) -
           q / (2.0 * sigma * sigma);
+  }
+  return lj;
+}
+
+// ------------------------- Gaussian mixture with unknown component variances
+// The supplementary Gaussian mixture as printed: a variance per component with an
+// inverse-Gamma prior, var_k ~ InverseGamma(a0, b0) (the listing's
+// InverseGamma(1,1)); here for points in R^dim with covariance var_k I.
+// Conditionals (all conjugate): z as above with var_k; pi ~ Dirichlet(alpha + n);
+// mu_kj ~ N((s_kj / var_k) / lambda_k, 1 / lambda_k), lambda_k = 1/prior_sd^2 +
+// n_k / var_k; var_k ~ InverseGamma(a0 + n_k dim / 2, b0 + SS_k / 2) with
+// SS_k = sum over points of component k of |x_i - mu_k|^2 (the new mu).
+// An inverse-Gamma draw is rate / Gamma(shape) (variance stream, index k).
+int64_t orc_gmmuv_sample_z(int64_t N, int32_t dim, int32_t K, const float* x, const float* pi,
+                           const float* mu, const float* var, uint64_t seed, uint32_t sweep,
+                           int32_t* z) {
+  std::vector<double> cdf(K);
+  int64_t degenerate = 0;
+  for (int64_t i = 0; i < N; ++i) {
+    gmmuv_point_cdf(x + i * dim, pi, mu, var, K, dim, cdf.data());
+    const double S = cdf[K - 1];
+    const double u = datum_uniform(seed, (uint64_t)i, sweep, STREAM_Z);
+    if (!(S > 0.0) || !std::isfinite(S)) {
+      z[i] = (int32_t)(u * (double)K);
+      ++degenerate;
+    } else {
+      z[i] = inverse_cdf(cdf.data(), K, u * S);
+    }
+  }
+  return degenerate;
+}
+
+void orc_gmmuv_point_cdf(int32_t dim, int32_t K, const float* x_i, const float* pi,
+                         const float* mu, const float* var, uint64_t seed, uint64_t point,
+                         uint32_t sweep, double* cdf, double* t) {
+  gmmuv_point_cdf(x_i, pi, mu, var, K, dim, cdf);
+  *t = datum_uniform(seed, point, sweep, STREAM_Z) * cdf[K - 1];
+}
+
+int orc_gmmuv_resample(int64_t N, int32_t dim, int32_t K, double alpha, double prior_sd, double a0,
+                       double b0, const float* x, const int32_t* z, const int32_t* n_k,
+                       const double* s_k, uint64_t seed, uint32_t sweep, float* pi, float* mu,
+                       float* var) {
+  std::vector<double> lg(K);
+  int capped = 0;
+  for (int32_t k = 0; k < K; ++k)
+    lg[k] = gamma_log_draw(alpha + (double)n_k[k], seed, (uint64_t)k, sweep, STREAM_GMM_PI,
+                           nullptr, &capped);
+  normalise_log_draws(lg.data(), K, 1, pi);
+  for (int32_t k = 0; k < K; ++k) {
+    const double v = (double)var[k];
+    const double lambda = 1.0 / (prior_sd * prior_sd) + (double)n_k[k] / v;
+    for (int32_t j = 0; j < dim; ++j) {
+      const int64_t e = (int64_t)k * dim + j;
+      uint32_t r[4];
+      random_block(seed, (uint64_t)e, sweep, STREAM_GMM_MU, 0, r);
+      mu[e] = (float)((s_k[e] / v) / lambda + normal_from(r) / std::sqrt(lambda));
+    }
+  }
+  std::vector<double> ss(K, 0.0);
+  for (int64_t i = 0; i < N; ++i) {
+    const int32_t k = z[i];
+    for (int32_t j = 0; j < dim; ++j) {
+      const double df = (double)x[i * dim + j] - (double)mu[(int64_t)k * dim + j];
+      ss[k] += df * df;
+    }
+  }
+  for (int32_t k = 0; k < K; ++k) {
+    const double shape = a0 + 0.5 * (double)n_k[k] * (double)dim;
+    const double rate = b0 + 0.5 * ss[k];
+    const double lgam = gamma_log_draw(shape, seed, (uint64_t)k, sweep, STREAM_GMM_VAR, nullptr,
+                                       &capped);
+    double v = std::exp(std::log(rate) - lgam);
+    if (v < (double)FLT_MIN) v = (double)FLT_MIN;
+    var[k] = (float)v;
+  }
+  return capped;
+}
+
+int64_t orc_gmmuv_sweep(int64_t N, int32_t dim, int32_t K, double alpha, double prior_sd, double a0,
+                        double b0, const float* x, uint64_t seed, uint32_t sweep, int32_t* z,
+                        float* pi, float* mu, float* var, int32_t* n_k, double* s_k) {
+  const int64_t deg = orc_gmmuv_sample_z(N, dim, K, x, pi, mu, var, seed, sweep, z);
+  orc_gmm_stats(N, dim, K, x, z, n_k, s_k);
+  orc_gmmuv_resample(N, dim, K, alpha, prior_sd, a0, b0, x, z, n_k, s_k, seed, sweep, pi, mu, var);
+  return deg;
+}
+
+// Initial state: z from the init stream, var_k = b0 / a0, then pi, mu and var
+// from their conditionals with sweep index 0.
+void orc_gmmuv_init(int64_t N, int32_t dim, int32_t K, double alpha, double prior_sd, double a0,
+                    double b0, const float* x, uint64_t seed, int32_t* z, float* pi, float* mu,
+                    float* var, int32_t* n_k, double* s_k) {
+  orc_gmm_init_z(N, K, seed, z);
+  for (int32_t k = 0; k < K; ++k) var[k] = (float)(b0 / a0);
+  orc_gmm_stats(N, dim, K, x, z, n_k, s_k);
+  orc_gmmuv_resample(N, dim, K, alpha, prior_sd, a0, b0, x, z, n_k, s_k, seed, 0, pi, mu, var);
+}
+
+// ln p(pi, mu, var, z, x): Dirichlet, Normal and inverse-Gamma priors plus the
+// per-point terms ln pi_z + ln N(x_i; mu_z, var_z I).
+double orc_gmmuv_loglik(int64_t N, int32_t dim, int32_t K, double alpha, double prior_sd, double a0,
+                        double b0, const float* x, const int32_t* z, const float* pi,
+                        const float* mu, const float* var) {
+  const double LN_2PI = 1.8378770664093454835606594728112;
+  double lj = log_dirichlet_sym(pi, K, 1, alpha);
+  for (int64_t e = 0; e < (int64_t)K * dim; ++e) {
+    const double m = (double)mu[e];
+    lj += -0.5 * LN_2PI - std::log(prior_sd) - m * m / (2.0 * prior_sd * prior_sd);
+  }
+  for (int32_t k = 0; k < K; ++k) {
+    const double v = (double)var[k];
+    lj += a0 * std::log(b0) - std::lgamma(a0) - (a0 + 1.0) * std::log(v) - b0 / v;
+  }
+  for (int64_t i = 0; i < N; ++i) {
+    const int32_t k = z[i];
+    const double v = (double)var[k];
+    double q = 0.0;
+    for (int32_t j = 0; j < dim; ++j) {
+      const double df = (double)x[i * dim + j] - (double)mu[(int64_t)k * dim + j];
+      q += df * df;
+    }
+    lj += std::log((double)pi[k]) - 0.5 * (double)dim * (LN_2PI + std::log(v)) - q / (2.0 * v);
   }
   return lj;
 }

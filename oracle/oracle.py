@@ -12,7 +12,8 @@ from . import build as _build
 
 _LIB = None
 
-STREAM_INIT_Z, STREAM_Z, STREAM_THETA, STREAM_PHI, STREAM_GMM_PI, STREAM_GMM_MU = range(6)
+(STREAM_INIT_Z, STREAM_Z, STREAM_THETA, STREAM_PHI, STREAM_GMM_PI, STREAM_GMM_MU,
+ STREAM_GMM_VAR) = range(7)
 
 
 def _p(a, ct):
@@ -40,6 +41,10 @@ def lib():
         L.orc_lda_resample_theta.restype = C.c_int
         L.orc_lda_resample_phi.restype = C.c_int
         L.orc_gmm_resample.restype = C.c_int
+        L.orc_gmmuv_sample_z.restype = C.c_int64
+        L.orc_gmmuv_sweep.restype = C.c_int64
+        L.orc_gmmuv_resample.restype = C.c_int
+        L.orc_gmmuv_loglik.restype = C.c_double
         _LIB = L
     return _LIB
 
@@ -394,3 +399,105 @@ class OracleGMM:
 
     def get_stats(self):
         return self.n_k.copy(), self.s_k.copy()
+
+
+# ------------------------------------------- GMM with unknown component variances
+def gmmuv_sample_z(x, pi, mu, var, seed, sweep):
+    x, pi, mu, var = _f32(x), _f32(pi), _f32(mu), _f32(var)
+    N, dim = x.shape
+    z = np.zeros(N, dtype=np.int32)
+    deg = lib().orc_gmmuv_sample_z(C.c_int64(N), C.c_int32(dim), C.c_int32(pi.size), _p(x, C.c_float),
+                                   _p(pi, C.c_float), _p(mu, C.c_float), _p(var, C.c_float),
+                                   C.c_uint64(seed), C.c_uint32(sweep), _p(z, C.c_int32))
+    return z, deg
+
+
+def gmmuv_point_cdf(x_i, pi, mu, var, seed, point, sweep):
+    x_i, pi, mu, var = _f32(x_i), _f32(pi), _f32(mu), _f32(var)
+    cdf = np.zeros(pi.size, dtype=np.float64)
+    t = C.c_double(0.0)
+    lib().orc_gmmuv_point_cdf(C.c_int32(x_i.size), C.c_int32(pi.size), _p(x_i, C.c_float),
+                              _p(pi, C.c_float), _p(mu, C.c_float), _p(var, C.c_float),
+                              C.c_uint64(seed), C.c_uint64(point), C.c_uint32(sweep),
+                              _p(cdf, C.c_double), C.byref(t))
+    return cdf, t.value
+
+
+def gmmuv_resample(x, z, n_k, s_k, var, alpha, prior_sd, a0, b0, seed, sweep):
+    x, z, n_k, s_k = _f32(x), _i32(z), _i32(n_k), _f64(s_k)
+    var = _f32(var).copy()
+    N, dim = x.shape
+    K = n_k.size
+    pi = np.zeros(K, dtype=np.float32)
+    mu = np.zeros((K, dim), dtype=np.float32)
+    lib().orc_gmmuv_resample(C.c_int64(N), C.c_int32(dim), C.c_int32(K), C.c_double(alpha),
+                             C.c_double(prior_sd), C.c_double(a0), C.c_double(b0), _p(x, C.c_float),
+                             _p(z, C.c_int32), _p(n_k, C.c_int32), _p(s_k, C.c_double),
+                             C.c_uint64(seed), C.c_uint32(sweep), _p(pi, C.c_float), _p(mu, C.c_float),
+                             _p(var, C.c_float))
+    return pi, mu, var
+
+
+def gmmuv_loglik(x, z, pi, mu, var, alpha, prior_sd, a0, b0):
+    x, z, pi, mu, var = _f32(x), _i32(z), _f32(pi), _f32(mu), _f32(var)
+    N, dim = x.shape
+    return lib().orc_gmmuv_loglik(C.c_int64(N), C.c_int32(dim), C.c_int32(pi.size), C.c_double(alpha),
+                                  C.c_double(prior_sd), C.c_double(a0), C.c_double(b0),
+                                  _p(x, C.c_float), _p(z, C.c_int32), _p(pi, C.c_float),
+                                  _p(mu, C.c_float), _p(var, C.c_float))
+
+
+class OracleGMMUV(OracleGMM):
+    """Mixture with var_k ~ InverseGamma(a0, b0) per component."""
+
+    def __init__(self, K, alpha, prior_sd, a0, b0, seed, x):
+        self.x = _f32(x).copy()
+        self.N, self.dim = self.x.shape
+        self.K = int(K)
+        self.alpha, self.prior_sd = float(np.float32(alpha)), float(np.float32(prior_sd))
+        self.a0, self.b0 = float(np.float32(a0)), float(np.float32(b0))
+        self.sigma = None
+        self.seed = int(seed)
+        self.z = np.zeros(self.N, dtype=np.int32)
+        self.pi = np.zeros(self.K, dtype=np.float32)
+        self.mu = np.zeros((self.K, self.dim), dtype=np.float32)
+        self.var = np.zeros(self.K, dtype=np.float32)
+        self.n_k = np.zeros(self.K, dtype=np.int32)
+        self.s_k = np.zeros((self.K, self.dim), dtype=np.float64)
+        self.sweep_index = 0
+        self.degenerate = 0
+        lib().orc_gmmuv_init(C.c_int64(self.N), C.c_int32(self.dim), C.c_int32(self.K),
+                             C.c_double(self.alpha), C.c_double(self.prior_sd), C.c_double(self.a0),
+                             C.c_double(self.b0), _p(self.x, C.c_float), C.c_uint64(self.seed),
+                             _p(self.z, C.c_int32), _p(self.pi, C.c_float), _p(self.mu, C.c_float),
+                             _p(self.var, C.c_float), _p(self.n_k, C.c_int32), _p(self.s_k, C.c_double))
+
+    def sweep(self, n=1):
+        for _ in range(n):
+            t = self.sweep_index + 1
+            self.degenerate += lib().orc_gmmuv_sweep(
+                C.c_int64(self.N), C.c_int32(self.dim), C.c_int32(self.K), C.c_double(self.alpha),
+                C.c_double(self.prior_sd), C.c_double(self.a0), C.c_double(self.b0),
+                _p(self.x, C.c_float), C.c_uint64(self.seed), C.c_uint32(t), _p(self.z, C.c_int32),
+                _p(self.pi, C.c_float), _p(self.mu, C.c_float), _p(self.var, C.c_float),
+                _p(self.n_k, C.c_int32), _p(self.s_k, C.c_double))
+            self.sweep_index = t
+
+    def step_sample_z(self):
+        self.z, deg = gmmuv_sample_z(self.x, self.pi, self.mu, self.var, self.seed, self.sweep_index + 1)
+        self.degenerate += deg
+
+    def step_resample(self):
+        self.pi, self.mu, self.var = gmmuv_resample(self.x, self.z, self.n_k, self.s_k, self.var,
+                                                    self.alpha, self.prior_sd, self.a0, self.b0,
+                                                    self.seed, self.sweep_index + 1)
+
+    def loglik(self):
+        return gmmuv_loglik(self.x, self.z, self.pi, self.mu, self.var, self.alpha, self.prior_sd,
+                            self.a0, self.b0)
+
+    def get_state(self):
+        return self.z.copy(), self.pi.copy(), self.mu.copy(), self.sweep_index
+
+    def set_var(self, var):
+        self.var = _f32(var).copy()

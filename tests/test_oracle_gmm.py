@@ -143,3 +143,88 @@ def test_gmm_determinism_and_steps():
     r.sweep(3)
     for x, y in zip(a.get_state(), r.get_state()):
         assert np.array_equal(x, y)
+
+
+# ---------------------------------------------- unknown component variances (the listing's model)
+def test_uv_conditional_matches_library_densities():
+    x, pi, mu = _toy(seed=3)
+    var = np.array([0.5, 2.0, 1.0, 4.0], dtype=np.float32)
+    for i in range(x.shape[0]):
+        cdf, t = O.gmmuv_point_cdf(x[i], pi, mu, var, seed=3, point=i, sweep=2)
+        p = np.diff(np.concatenate([[0.0], cdf])) / cdf[-1]
+        logw = np.log(pi.astype(np.float64)) + np.array(
+            [stats.multivariate_normal.logpdf(x[i].astype(np.float64), mu[k].astype(np.float64),
+                                              float(var[k]) * np.eye(x.shape[1])) for k in range(pi.size)])
+        # p comes from differences of a running sum of magnitude 1: absolute rounding of 1e-16
+        assert np.allclose(p, np.exp(logw - special.logsumexp(logw)), rtol=1e-10, atol=1e-14)
+    z, _ = O.gmmuv_sample_z(x, pi, mu, var, seed=3, sweep=2)
+    for i in range(x.shape[0]):
+        cdf, t = O.gmmuv_point_cdf(x[i], pi, mu, var, seed=3, point=i, sweep=2)
+        assert z[i] == int((cdf <= t).sum())
+
+
+def test_uv_variance_is_inverse_gamma_posterior_and_mean_uses_variance():
+    rng = np.random.default_rng(4)
+    N, dim, a0, b0, prior_sd = 40, 2, 1.0, 1.0, 3.0
+    x = rng.normal(2.0, 1.5, size=(N, dim)).astype(np.float32)
+    z = np.zeros(N, dtype=np.int32)
+    n_k, s_k = O.gmm_stats(x, z, 1)
+    var0 = np.array([2.5], dtype=np.float32)
+    T = 20_000
+    mus, vars_ = np.empty((T, dim)), np.empty(T)
+    for s in range(T):
+        _, mu, var = O.gmmuv_resample(x, z, n_k, s_k, var0, 1.0, prior_sd, a0, b0, seed=8, sweep=s)
+        mus[s], vars_[s] = mu[0], var[0]
+    lam = 1 / prior_sd ** 2 + N / 2.5
+    mean = (s_k[0] / 2.5) / lam
+    for j in range(dim):
+        assert stats.kstest(mus[:, j], "norm", args=(mean[j], lam ** -0.5)).pvalue > 1e-4
+    # var | mu ~ InvGamma(a0 + N dim / 2, b0 + SS(mu)/2): check through the pivot
+    # (b0 + SS/2) / var ~ Gamma(shape), whatever mu was drawn
+    ss = ((x.astype(np.float64)[None, :, :] - mus[:, None, :].astype(np.float32).astype(np.float64)) ** 2).sum(axis=(1, 2))
+    pivot = (b0 + 0.5 * ss) / vars_
+    assert stats.kstest(pivot, "gamma", args=(a0 + 0.5 * N * dim,)).pvalue > 1e-4
+    # an empty component draws its variance from the prior InvGamma(a0, b0)
+    e_n, e_s = np.array([0], dtype=np.int32), np.zeros((1, dim))
+    v0 = np.array([O.gmmuv_resample(x[:0].reshape(0, dim), z[:0], e_n, e_s, var0, 1.0, prior_sd, 3.0, 2.0,
+                                    seed=9, sweep=s)[2][0] for s in range(T)], dtype=np.float64)
+    assert stats.kstest(v0, "invgamma", args=(3.0, 0, 2.0)).pvalue > 1e-4
+
+
+def test_uv_log_joint_against_library_densities():
+    d = synth.gmm_points(N=200, dim=3, K=3, seed=6)
+    m = O.OracleGMMUV(3, 1.5, 10.0, 2.0, 3.0, seed=2, x=d["x"])
+    m.sweep(3)
+    pi, mu, var, x = (m.pi.astype(np.float64), m.mu.astype(np.float64), m.var.astype(np.float64),
+                      m.x.astype(np.float64))
+    want = stats.dirichlet.logpdf(pi / pi.sum(), np.full(3, 1.5))
+    want += stats.norm.logpdf(mu, 0.0, 10.0).sum()
+    want += stats.invgamma.logpdf(var, 2.0, scale=3.0).sum()
+    want += np.log(pi[m.z]).sum() + stats.norm.logpdf(x, mu[m.z], np.sqrt(var[m.z])[:, None]).sum()
+    assert abs(m.loglik() - want) < 1e-9 * abs(want)
+
+
+def test_uv_recovers_means_and_variances():
+    rng = np.random.default_rng(1)
+    K, dim, N = 3, 2, 12_000
+    mu_t = np.array([[-6.0, 0.0], [0.0, 5.0], [7.0, -3.0]])
+    var_t = np.array([0.5, 2.0, 4.0])
+    z_t = rng.integers(0, K, size=N)
+    x = (mu_t[z_t] + np.sqrt(var_t[z_t])[:, None] * rng.standard_normal((N, dim))).astype(np.float32)
+    m = O.OracleGMMUV(K, 1.0, 10.0, 1.0, 1.0, seed=5, x=x)
+    z0 = z_t.copy().astype(np.int32)
+    flip = rng.random(N) < 0.2
+    z0[flip] = rng.integers(0, K, size=int(flip.sum()))
+    m.set_state(z=z0)
+    m.step_resample(); m.step_finish()
+    m.sweep(30)
+    assert np.abs(m.mu - mu_t).max() < 0.1
+    assert np.abs(m.var / var_t - 1).max() < 0.1
+    assert (m.z == z_t).mean() > 0.97 and m.degenerate == 0
+    # determinism and the step-wise calls
+    a = O.OracleGMMUV(K, 1.0, 10.0, 1.0, 1.0, seed=5, x=x)
+    b = O.OracleGMMUV(K, 1.0, 10.0, 1.0, 1.0, seed=5, x=x)
+    a.sweep(3)
+    for _ in range(3):
+        b.step_sample_z(); b.step_stats(); b.step_resample(); b.step_finish()
+    assert np.array_equal(a.z, b.z) and np.array_equal(a.mu, b.mu) and np.array_equal(a.var, b.var)
