@@ -130,14 +130,21 @@ int augur_lda_sync(augur_lda* h);
 
 /* ------------------------------------------------ Gaussian mixture (supplement)
  * pi ~ Dirichlet(alpha 1_K), mu_k ~ N(0, prior_sd^2 I), z_i ~ Categorical(pi),
- * x_i ~ N(mu_{z_i}, sigma^2 I); x observed.  Layout: x float[N][dim],
- * z int32[N], pi float[K], mu float[K][dim], n_k int32[K], s_k double[K][dim]. */
+ * x_i ~ N(mu_{z_i}, v_{z_i} I); x observed.  Known variance (var_shape = 0):
+ * v_k = sigma^2 for every k.  Unknown variances (var_shape > 0, the model of
+ * the supplement's Gaussian-mixture listing, whose per-component scale is read
+ * as a variance): var_k ~ InverseGamma(var_shape, var_scale), v_k = var_k, and
+ * sigma is ignored.  Layout: x float[N][dim], z int32[N], pi float[K],
+ * mu float[K][dim], var float[K], n_k int32[K], s_k double[K][dim]. */
 typedef struct augur_gmm augur_gmm;
 
 typedef struct {
   int64_t N;
   int32_t dim, K;
-  float alpha, prior_sd, sigma; /* all > 0, finite */
+  float alpha, prior_sd; /* > 0, finite */
+  float sigma;           /* known variance: > 0, finite */
+  float var_shape;       /* 0: known variance; > 0: inverse-Gamma shape a0 */
+  float var_scale;       /* inverse-Gamma scale b0 (> 0 when var_shape > 0) */
   uint64_t seed;
   int32_t device;
   void* stream;
@@ -146,9 +153,13 @@ typedef struct {
 
 int augur_gmm_create(const augur_gmm_config* cfg, const float* x, augur_gmm** out);
 void augur_gmm_destroy(augur_gmm* h);
-/* One sweep: z_i from p(k) ~ pi_k exp(-|x_i - mu_k|^2 / (2 sigma^2)); n_k and
- * s_k = sum of x_i with z_i = k; pi ~ Dirichlet(alpha + n); mu_kj ~ Normal with
- * precision 1/prior_sd^2 + n_k/sigma^2 and mean (s_kj/sigma^2)/precision. */
+/* One sweep: z_i from p(k) ~ pi_k v_k^(-dim/2) exp(-|x_i - mu_k|^2 / (2 v_k));
+ * n_k and s_k = sum of x_i with z_i = k; pi ~ Dirichlet(alpha + n); mu_kj ~
+ * Normal with precision 1/prior_sd^2 + n_k/v_k and mean (s_kj/v_k)/precision;
+ * with unknown variances then var_k ~ InverseGamma(var_shape + n_k dim / 2,
+ * var_scale + SS_k / 2), SS_k = sum over z_i = k of |x_i - mu_k|^2 at the new
+ * mean.  The initial state (sweep index 0) has var_k = var_scale / var_shape
+ * before its first draw. */
 int augur_gmm_sweep(augur_gmm* h, int32_t n_sweeps);
 int augur_gmm_step_sample_z(augur_gmm* h);
 int augur_gmm_step_stats(augur_gmm* h);
@@ -158,6 +169,10 @@ int augur_gmm_loglik(augur_gmm* h, double* log_joint);
 int augur_gmm_get_state(augur_gmm* h, int32_t* z, float* pi, float* mu, int64_t* sweep);
 int augur_gmm_set_state(augur_gmm* h, const int32_t* z, const float* pi, const float* mu,
                         int64_t sweep);
+/* Unknown variances only (AUGUR_ERR_INVALID_ARG otherwise): var float[K], host or
+ * device as the handle's flags say; set_var requires positive finite values. */
+int augur_gmm_get_var(augur_gmm* h, float* var);
+int augur_gmm_set_var(augur_gmm* h, const float* var);
 int augur_gmm_get_stats(augur_gmm* h, int32_t* n_k, double* s_k);
 int augur_gmm_get_degenerate(augur_gmm* h, int64_t* count);
 int augur_gmm_sync(augur_gmm* h);

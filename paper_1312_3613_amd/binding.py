@@ -33,7 +33,8 @@ class LdaConfig(C.Structure):
 
 class GmmConfig(C.Structure):
     _fields_ = [("N", C.c_int64), ("dim", C.c_int32), ("K", C.c_int32), ("alpha", C.c_float),
-                ("prior_sd", C.c_float), ("sigma", C.c_float), ("seed", C.c_uint64),
+                ("prior_sd", C.c_float), ("sigma", C.c_float), ("var_shape", C.c_float),
+                ("var_scale", C.c_float), ("seed", C.c_uint64),
                 ("device", C.c_int32), ("stream", C.c_void_p), ("flags", C.c_uint32)]
 
 
@@ -82,6 +83,8 @@ def lib():
         L.augur_gmm_get_state.argtypes = [vp, vp, vp, vp, C.POINTER(C.c_int64)]
         L.augur_gmm_set_state.argtypes = [vp, vp, vp, vp, C.c_int64]
         L.augur_gmm_get_stats.argtypes = [vp, vp, vp]
+        L.augur_gmm_get_var.argtypes = [vp, vp]
+        L.augur_gmm_set_var.argtypes = [vp, vp]
         L.augur_gmm_get_degenerate.argtypes = [vp, C.POINTER(C.c_int64)]
         _LIB = L
     return _LIB
@@ -251,7 +254,7 @@ class GMM:
     """augur_gmm_* handle."""
 
     def __init__(self, K, alpha, prior_sd, sigma, seed, x, device=0, stream=None,
-                 device_ptrs=False):
+                 device_ptrs=False, var_shape=0.0, var_scale=0.0):
         self._h = None
         self._arr = _Arrays(device_ptrs, device)
         xa = self._arr.input(x, "f32")
@@ -259,7 +262,8 @@ class GMM:
             raise ValueError("x must be [N][dim]")
         self.N, self.dim, self.K = int(xa.shape[0]), int(xa.shape[1]), int(K)
         cfg = GmmConfig(self.N, self.dim, self.K, float(alpha), float(prior_sd), float(sigma),
-                        int(seed), int(device), _stream_handle(stream),
+                        float(var_shape), float(var_scale), int(seed), int(device),
+                        _stream_handle(stream),
                         PTRS_DEVICE if device_ptrs else 0)
         h = C.c_void_p()
         _check(lib().augur_gmm_create(C.byref(cfg), _ptr(xa), C.byref(h)))
@@ -314,6 +318,14 @@ class GMM:
         ma = self._arr.input(mu, "f32", self.K * self.dim)
         _check(lib().augur_gmm_set_state(self._h, _ptr(za), _ptr(pa), _ptr(ma),
                                          -1 if sweep is None else int(sweep)))
+
+    def get_var(self):
+        var = self._arr.empty((self.K,), "f32")
+        _check(lib().augur_gmm_get_var(self._h, _ptr(var)))
+        return var
+
+    def set_var(self, var):
+        _check(lib().augur_gmm_set_var(self._h, _ptr(self._arr.input(var, "f32", self.K))))
 
     def get_stats(self):
         n_k = self._arr.empty((self.K,), "i32")

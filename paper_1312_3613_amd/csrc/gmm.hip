@@ -1,11 +1,14 @@
-// Gaussian mixture with known covariance sigma^2 I (the supplementary Gaussian
-// mixture model of arXiv 1312.3613 with the variance fixed): Gibbs sweep over
-// z, the weights pi (Dirichlet-categorical conjugacy) and the means mu
-// (Normal-Normal conjugacy), as HIP kernels behind the augur_gmm_* C ABI.
+// Gaussian mixture (the supplementary Gaussian mixture model of arXiv
+// 1312.3613): Gibbs sweep over z, the weights pi (Dirichlet-categorical
+// conjugacy), the means mu (Normal-Normal conjugacy) and, when the variances
+// are unknown, var_k (inverse-Gamma-Normal conjugacy, covariance var_k I), as
+// HIP kernels behind the augur_gmm_* C ABI.  With the variance known every
+// component has covariance sigma^2 I.
 //
 // Device layout: x float[N][dim], z int32[N], pi float[K], mu float[K][dim],
-// n_k int32[K], s_k double[K][dim].  The z conditional is evaluated in fp64 from
-// the fp32 state (N * K * dim fused multiply-adds per sweep is small).
+// var float[K], n_k int32[K], s_k double[K][dim], q_k double[K] (sum of |x_i|^2,
+// unknown variances only).  The z conditional is evaluated in fp64 from the
+// fp32 state (N * K * dim fused multiply-adds per sweep is small).
 #include "common.hpp"
 
 #include <algorithm>
@@ -17,7 +20,8 @@ using namespace augur;
 namespace {
 
 constexpr int kRedBlocks = 512;
-constexpr int kStatChunk = 1024;  // points per block of the statistics kernel
+constexpr int kStatChunk = 1024;    // points per block of the statistics kernel, fp32 staging
+constexpr int kStatChunkSq = 512;   // with the sum of squares (fp64 staging)
 
 __global__ __launch_bounds__(256) void gmm_init_z_kernel(int32_t* __restrict__ z, int64_t N, int K,
                                                           uint64_t seed) {
@@ -31,18 +35,22 @@ __global__ __launch_bounds__(256) void gmm_init_z_kernel(int32_t* __restrict__ z
   }
 }
 
-// ln pi_k - |x - mu_k|^2 / (2 sigma^2) for one point; mu and ln pi in LDS.
+// ln pi_k - (dim/2) ln v_k - |x - mu_k|^2 / (2 v_k) for one point; mu, the
+// constant part lw_k and 1/(2 v_k) in LDS.  With the variance known the
+// (dim/2) ln v term is the same for every k and left out.
 __device__ __forceinline__ double gmm_logw(const float* __restrict__ xi, const double* mu_s,
-                                           const double* lpi_s, int k, int dim, double inv2s2) {
+                                           const double* lw_s, const double* inv2v_s, int k,
+                                           int dim) {
   double q = 0.0;
   for (int j = 0; j < dim; ++j) {
     const double df = (double)xi[j] - mu_s[k * dim + j];
     q += df * df;
   }
-  return lpi_s[k] - q * inv2s2;
+  return lw_s[k] - q * inv2v_s[k];
 }
 
-// Gibbs step for z: p(k) proportional to pi_k N(x_i; mu_k, sigma^2 I), drawn by
+// Gibbs step for z: p(k) proportional to pi_k N(x_i; mu_k, v_k I), v_k = var[k]
+// or sigma^2 for every k when var is NULL, drawn by
 // inverse CDF over the weights exp(l_k - max l), running sum in index order.
 // One thread per point.  With kCache the K log-weights (then weights) of a
 // thread wait in its own LDS column between the three passes (max, total,
@@ -52,28 +60,38 @@ __device__ __forceinline__ double gmm_logw(const float* __restrict__ xi, const d
 template <bool kCache>
 __global__ __launch_bounds__(256) void gmm_sample_z_kernel(
     const float* __restrict__ x, const float* __restrict__ pi, const float* __restrict__ mu,
-    int32_t* __restrict__ z, int64_t N, int dim, int K, double sigma, uint64_t seed, uint32_t sweep,
-    unsigned long long* __restrict__ n_degenerate) {
+    const float* __restrict__ var, int32_t* __restrict__ z, int64_t N, int dim, int K, double sigma,
+    uint64_t seed, uint32_t sweep, unsigned long long* __restrict__ n_degenerate) {
   extern __shared__ double sh[];
-  double* mu_s = sh;              // [K][dim]
-  double* lpi_s = sh + K * dim;   // [K]
-  double* col = lpi_s + K + threadIdx.x;  // [K][256]: this thread's column (kCache only)
+  double* mu_s = sh;                // [K][dim]
+  double* lw_s = sh + K * dim;      // [K]
+  double* inv2v_s = lw_s + K;       // [K]
+  double* col = inv2v_s + K + threadIdx.x;  // [K][256]: this thread's column (kCache only)
   for (int e = threadIdx.x; e < K * dim; e += blockDim.x) mu_s[e] = (double)mu[e];
-  for (int k = threadIdx.x; k < K; k += blockDim.x) lpi_s[k] = log((double)pi[k]);
+  for (int k = threadIdx.x; k < K; k += blockDim.x) {
+    const double lp = log((double)pi[k]);
+    if (var != nullptr) {
+      const double v = (double)var[k];
+      lw_s[k] = lp - 0.5 * (double)dim * log(v);
+      inv2v_s[k] = 1.0 / (2.0 * v);
+    } else {
+      lw_s[k] = lp;
+      inv2v_s[k] = 1.0 / (2.0 * sigma * sigma);
+    }
+  }
   __syncthreads();
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= N) return;
   const float* xi = x + i * dim;
-  const double inv2s2 = 1.0 / (2.0 * sigma * sigma);
   double m = -INFINITY;
   for (int k = 0; k < K; ++k) {
-    const double l = gmm_logw(xi, mu_s, lpi_s, k, dim, inv2s2);
+    const double l = gmm_logw(xi, mu_s, lw_s, inv2v_s, k, dim);
     if (kCache) col[k * 256] = l;
     m = l > m ? l : m;
   }
   double S = 0.0;
   for (int k = 0; k < K; ++k) {
-    const double p = exp((kCache ? col[k * 256] : gmm_logw(xi, mu_s, lpi_s, k, dim, inv2s2)) - m);
+    const double p = exp((kCache ? col[k * 256] : gmm_logw(xi, mu_s, lw_s, inv2v_s, k, dim)) - m);
     if (kCache) col[k * 256] = p;
     S += p;
   }
@@ -89,7 +107,7 @@ __global__ __launch_bounds__(256) void gmm_sample_z_kernel(
     int last = 0;
     zi = -1;
     for (int k = 0; k < K; ++k) {
-      const double p = kCache ? col[k * 256] : exp(gmm_logw(xi, mu_s, lpi_s, k, dim, inv2s2) - m);
+      const double p = kCache ? col[k * 256] : exp(gmm_logw(xi, mu_s, lw_s, inv2v_s, k, dim) - m);
       const double Cn = C + p;
       if (Cn > C) last = k;
       C = Cn;
@@ -101,50 +119,69 @@ __global__ __launch_bounds__(256) void gmm_sample_z_kernel(
 }
 
 // Sufficient statistics, deterministic: a block stages a chunk of points in
-// LDS; thread (k, j) walks the chunk in index order and adds x_i[j] when
-// z_i = k (0.0 otherwise, which leaves the sum unchanged), thread k also
-// counts.  Per-block partials are then added in block order, one workgroup per
-// (k, j) pair with a fixed reduction tree.
+// LDS, W values a point: its dim coordinates and, with kSumSq, |x_i|^2 (the
+// staged values are then fp64).  Thread (k, j) walks the chunk in index order
+// and adds value j of point i when z_i = k (0.0 otherwise, which leaves the sum
+// unchanged), thread (k, 0) also counts.  Per-block partials are then added in
+// block order, one workgroup per (k, j) pair with a fixed reduction tree.
+template <bool kSumSq>
 __global__ __launch_bounds__(256) void gmm_stats_partial_kernel(
     const float* __restrict__ x, const int32_t* __restrict__ z, int64_t N, int dim, int K,
     double* __restrict__ part_s, int32_t* __restrict__ part_n) {
-  extern __shared__ unsigned char raw[];
-  float* xs = reinterpret_cast<float*>(raw);                               // [chunk][dim]
-  int32_t* zs = reinterpret_cast<int32_t*>(xs + (size_t)kStatChunk * dim);  // [chunk]
-  const int64_t p0 = (int64_t)blockIdx.x * kStatChunk;
-  const int n = (int)std::min<int64_t>(kStatChunk, N - p0);
-  for (int e = threadIdx.x; e < n * dim; e += blockDim.x) xs[e] = x[p0 * dim + e];
+  using T = typename std::conditional<kSumSq, double, float>::type;
+  extern __shared__ __align__(8) unsigned char raw[];
+  constexpr int kChunk = kSumSq ? kStatChunkSq : kStatChunk;
+  const int W = dim + (kSumSq ? 1 : 0);
+  T* xs = reinterpret_cast<T*>(raw);                                  // [chunk][W]
+  int32_t* zs = reinterpret_cast<int32_t*>(xs + (size_t)kChunk * W);  // [chunk]
+  const int64_t p0 = (int64_t)blockIdx.x * kChunk;
+  const int n = (int)std::min<int64_t>(kChunk, N - p0);
+  if (kSumSq) {
+    for (int e = threadIdx.x; e < n; e += blockDim.x) {
+      double q = 0.0;
+      for (int j = 0; j < dim; ++j) {
+        const double v = (double)x[(p0 + e) * dim + j];
+        xs[e * W + j] = (T)v;
+        q += v * v;
+      }
+      xs[e * W + dim] = (T)q;
+    }
+  } else {
+    for (int e = threadIdx.x; e < n * dim; e += blockDim.x) xs[e] = (T)x[p0 * dim + e];
+  }
   for (int e = threadIdx.x; e < n; e += blockDim.x) zs[e] = z[p0 + e];
   __syncthreads();
-  for (int pair = threadIdx.x; pair < K * dim; pair += blockDim.x) {
-    const int k = pair / dim, j = pair - k * dim;
+  for (int pair = threadIdx.x; pair < K * W; pair += blockDim.x) {
+    const int k = pair / W, j = pair - k * W;
     double s = 0.0;
     int32_t c = 0;
 #pragma unroll 8
     for (int e = 0; e < n; ++e) {
       const bool mine = zs[e] == k;
-      s += mine ? (double)xs[e * dim + j] : 0.0;
+      s += mine ? (double)xs[e * W + j] : 0.0;
       c += mine ? 1 : 0;
     }
-    part_s[(size_t)blockIdx.x * K * dim + pair] = s;
+    part_s[(size_t)blockIdx.x * K * W + pair] = s;
     if (j == 0) part_n[(size_t)blockIdx.x * K + k] = c;
   }
 }
 
+// W = dim (+ 1 with the sum of squares, whose totals go to q_k).
 __global__ __launch_bounds__(256) void gmm_stats_merge_kernel(const double* __restrict__ part_s,
                                                                const int32_t* __restrict__ part_n,
-                                                               int nblk, int dim, int K,
+                                                               int nblk, int dim, int W, int K,
                                                                double* __restrict__ s_k,
+                                                               double* __restrict__ q_k,
                                                                int32_t* __restrict__ n_k) {
   __shared__ double ss[256];
   __shared__ int32_t sn[256];
   const int pair = blockIdx.x;  // one workgroup per (k, j)
-  const int k = pair / dim;
-  const bool count = pair - k * dim == 0;
+  const int k = pair / W, j = pair - k * W;
+  const bool count = j == 0;
   double s = 0.0;
   int32_t c = 0;
   for (int b = threadIdx.x; b < nblk; b += 256) {
-    s += part_s[(size_t)b * K * dim + pair];
+    s += part_s[(size_t)b * K * W + pair];
     if (count) c += part_n[(size_t)b * K + k];
   }
   ss[threadIdx.x] = s;
@@ -158,19 +195,27 @@ __global__ __launch_bounds__(256) void gmm_stats_merge_kernel(const double* __re
     __syncthreads();
   }
   if (threadIdx.x == 0) {
-    s_k[pair] = ss[0];
+    if (j < dim) s_k[k * dim + j] = ss[0];
+    else q_k[k] = ss[0];
     if (count) n_k[k] = sn[0];
   }
 }
 
 // pi ~ Dirichlet(alpha + n) from K log-domain Gamma draws normalised in index
-// order; mu_kj ~ N(mean, 1/lambda), lambda = 1/prior_sd^2 + n_k/sigma^2,
-// mean = (s_kj / sigma^2) / lambda.  One block.
+// order; mu_kj ~ N(mean, 1/lambda), lambda = 1/prior_sd^2 + n_k/v_k,
+// mean = (s_kj / v_k) / lambda, v_k the component's current variance (sigma^2
+// when var is NULL).  With unknown variances then
+// var_k ~ InverseGamma(a0 + n_k dim / 2, b0 + SS_k / 2), SS_k the sum of
+// |x_i - mu_k|^2 over the component's points with the NEW (fp32) mean, taken
+// from the sufficient statistics as q_k - 2 mu_k . s_k + n_k |mu_k|^2 in fp64,
+// and drawn as exp(ln rate - ln G), G ~ Gamma(shape).  One block.
 __global__ __launch_bounds__(256) void gmm_resample_kernel(
-    const int32_t* __restrict__ n_k, const double* __restrict__ s_k, float* __restrict__ pi,
-    float* __restrict__ mu, int dim, int K, double alpha, double prior_sd, double sigma,
-    uint64_t seed, uint32_t sweep, unsigned long long* __restrict__ n_capped) {
-  extern __shared__ double lg[];  // [K]
+    const int32_t* __restrict__ n_k, const double* __restrict__ s_k, const double* __restrict__ q_k,
+    float* __restrict__ pi, float* __restrict__ mu, float* __restrict__ var, int dim, int K,
+    double alpha, double prior_sd, double sigma, double a0, double b0, uint64_t seed, uint32_t sweep,
+    unsigned long long* __restrict__ n_capped) {
+  extern __shared__ double lg[];                            // [K]
+  float* mu_new = reinterpret_cast<float*>(lg + K);         // [K][dim]
   bool capped = false;
   for (int k = threadIdx.x; k < K; k += blockDim.x)
     lg[k] = gamma_log_draw(alpha + (double)n_k[k], seed, (uint64_t)k, sweep, kStreamGmmPi, capped);
@@ -186,18 +231,43 @@ __global__ __launch_bounds__(256) void gmm_resample_kernel(
   }
   for (int e = threadIdx.x; e < K * dim; e += blockDim.x) {
     const int k = e / dim;
-    const double lambda = 1.0 / (prior_sd * prior_sd) + (double)n_k[k] / (sigma * sigma);
-    const double mean = (s_k[e] / (sigma * sigma)) / lambda;
+    const double v = var != nullptr ? (double)var[k] : sigma * sigma;
+    const double lambda = 1.0 / (prior_sd * prior_sd) + (double)n_k[k] / v;
+    const double mean = (s_k[e] / v) / lambda;
     const U4 b = random_block(seed, (uint64_t)e, sweep, kStreamGmmMu, 0);
-    mu[e] = (float)(mean + normal_from(b) / sqrt(lambda));
+    const float m = (float)(mean + normal_from(b) / sqrt(lambda));
+    mu[e] = m;
+    mu_new[e] = m;
+  }
+  if (var != nullptr) {
+    __syncthreads();  // every mean above read the old variances; the new means are in LDS
+    for (int k = threadIdx.x; k < K; k += blockDim.x) {
+      const double n = (double)n_k[k];
+      double dot = 0.0, sq = 0.0;
+      for (int j = 0; j < dim; ++j) {
+        const double m = (double)mu_new[k * dim + j];
+        dot += m * s_k[k * dim + j];
+        sq += m * m;
+      }
+      double ss = q_k[k] - 2.0 * dot + n * sq;
+      ss = ss > 0.0 ? ss : 0.0;
+      const double shape = a0 + 0.5 * n * (double)dim;
+      const double rate = b0 + 0.5 * ss;
+      const double lgam = gamma_log_draw(shape, seed, (uint64_t)k, sweep, kStreamGmmVar, capped);
+      double v = exp(log(rate) - lgam);
+      v = v < (double)FLT_MIN ? (double)FLT_MIN : v;
+      var[k] = (float)v;
+    }
   }
   if (capped) atomicAdd(n_capped, 1ULL);
 }
 
-// Per-point terms of the log joint: ln pi_z + ln N(x_i; mu_z, sigma^2 I).
+// Per-point terms of the log joint: ln pi_z + ln N(x_i; mu_z, v_z I), v_k =
+// var[k] or sigma^2 when var is NULL.
 __global__ __launch_bounds__(256) void gmm_loglik_kernel(
     const float* __restrict__ x, const int32_t* __restrict__ z, const float* __restrict__ pi,
-    const float* __restrict__ mu, int64_t N, int dim, double sigma, double* __restrict__ part) {
+    const float* __restrict__ mu, const float* __restrict__ var, int64_t N, int dim, double sigma,
+    double* __restrict__ part) {
   __shared__ double smem[8];
   const double LN_2PI = 1.8378770664093454835606594728112;
   double s = 0.0;
@@ -209,8 +279,13 @@ __global__ __launch_bounds__(256) void gmm_loglik_kernel(
       const double df = (double)x[i * dim + j] - (double)mu[k * dim + j];
       q += df * df;
     }
-    s += log((double)pi[k]) - 0.5 * (double)dim * LN_2PI - (double)dim * log(sigma) -
-         q / (2.0 * sigma * sigma);
+    if (var != nullptr) {
+      const double v = (double)var[k];
+      s += log((double)pi[k]) - 0.5 * (double)dim * (LN_2PI + log(v)) - q / (2.0 * v);
+    } else {
+      s += log((double)pi[k]) - 0.5 * (double)dim * LN_2PI - (double)dim * log(sigma) -
+           q / (2.0 * sigma * sigma);
+    }
   }
   block_partial_sum(s, part, smem);
 }
@@ -230,10 +305,11 @@ __global__ __launch_bounds__(256) void gmm_check_range_kernel(const int32_t* __r
 struct augur_gmm {
   augur_gmm_config cfg{};
   hipStream_t stream = nullptr;
-  double alpha = 0, prior_sd = 0, sigma = 0;
-  float *x = nullptr, *pi = nullptr, *mu = nullptr;
+  double alpha = 0, prior_sd = 0, sigma = 0, a0 = 0, b0 = 0;
+  bool unknown_var = false;
+  float *x = nullptr, *pi = nullptr, *mu = nullptr, *var = nullptr;  // var: unknown variances only
   int32_t *z = nullptr, *n_k = nullptr, *part_n = nullptr;
-  double *s_k = nullptr, *part_s = nullptr, *red = nullptr;
+  double *s_k = nullptr, *q_k = nullptr, *part_s = nullptr, *red = nullptr;
   unsigned long long* counters = nullptr;  // [0] degenerate [1] capped [2] bad input
   int stat_blocks = 0;
   int64_t sweep = 0;
@@ -247,21 +323,21 @@ bool device_ptrs(const augur_gmm* h) { return (h->cfg.flags & AUGUR_PTRS_DEVICE)
 void free_all(augur_gmm* h) {
   (void)hipFree(h->x); (void)hipFree(h->pi); (void)hipFree(h->mu); (void)hipFree(h->z);
   (void)hipFree(h->n_k); (void)hipFree(h->part_n); (void)hipFree(h->s_k); (void)hipFree(h->part_s);
-  (void)hipFree(h->red); (void)hipFree(h->counters);
+  (void)hipFree(h->red); (void)hipFree(h->counters); (void)hipFree(h->var); (void)hipFree(h->q_k);
 }
 
 int launch_z(augur_gmm* h, uint32_t sweep) {
   const int K = h->cfg.K, dim = h->cfg.dim;
   const int64_t N = h->cfg.N;
-  const size_t base_lds = sizeof(double) * ((size_t)K * dim + K);
+  const size_t base_lds = sizeof(double) * ((size_t)K * dim + 2 * (size_t)K);
   const size_t cache_lds = base_lds + sizeof(double) * 256 * (size_t)K;
   if (cache_lds <= 48 * 1024)
     hipLaunchKernelGGL(gmm_sample_z_kernel<true>, dim3((unsigned)((N + 255) / 256)), dim3(256),
-                       cache_lds, h->stream, h->x, h->pi, h->mu, h->z, N, dim, K, h->sigma,
+                       cache_lds, h->stream, h->x, h->pi, h->mu, h->var, h->z, N, dim, K, h->sigma,
                        h->cfg.seed, sweep, h->counters);
   else
     hipLaunchKernelGGL(gmm_sample_z_kernel<false>, dim3((unsigned)((N + 255) / 256)), dim3(256),
-                       base_lds, h->stream, h->x, h->pi, h->mu, h->z, N, dim, K, h->sigma,
+                       base_lds, h->stream, h->x, h->pi, h->mu, h->var, h->z, N, dim, K, h->sigma,
                        h->cfg.seed, sweep, h->counters);
   AUGUR_HIP_TRY(hipGetLastError());
   return AUGUR_OK;
@@ -269,19 +345,27 @@ int launch_z(augur_gmm* h, uint32_t sweep) {
 
 int launch_stats(augur_gmm* h) {
   const int K = h->cfg.K, dim = h->cfg.dim;
-  const size_t shm = sizeof(float) * (size_t)kStatChunk * dim + sizeof(int32_t) * kStatChunk;
-  hipLaunchKernelGGL(gmm_stats_partial_kernel, dim3(h->stat_blocks), dim3(256), shm, h->stream, h->x,
-                     h->z, h->cfg.N, dim, K, h->part_s, h->part_n);
-  hipLaunchKernelGGL(gmm_stats_merge_kernel, dim3(K * dim), dim3(256), 0, h->stream,
-                     h->part_s, h->part_n, h->stat_blocks, dim, K, h->s_k, h->n_k);
+  if (h->unknown_var) {
+    const size_t shm = sizeof(double) * (size_t)kStatChunkSq * (dim + 1) + sizeof(int32_t) * kStatChunkSq;
+    hipLaunchKernelGGL(gmm_stats_partial_kernel<true>, dim3(h->stat_blocks), dim3(256), shm,
+                       h->stream, h->x, h->z, h->cfg.N, dim, K, h->part_s, h->part_n);
+  } else {
+    const size_t shm = sizeof(float) * (size_t)kStatChunk * dim + sizeof(int32_t) * kStatChunk;
+    hipLaunchKernelGGL(gmm_stats_partial_kernel<false>, dim3(h->stat_blocks), dim3(256), shm,
+                       h->stream, h->x, h->z, h->cfg.N, dim, K, h->part_s, h->part_n);
+  }
+  const int W = dim + (h->unknown_var ? 1 : 0);
+  hipLaunchKernelGGL(gmm_stats_merge_kernel, dim3(K * W), dim3(256), 0, h->stream, h->part_s,
+                     h->part_n, h->stat_blocks, dim, W, K, h->s_k, h->q_k, h->n_k);
   AUGUR_HIP_TRY(hipGetLastError());
   return AUGUR_OK;
 }
 
 int launch_resample(augur_gmm* h, uint32_t sweep) {
-  hipLaunchKernelGGL(gmm_resample_kernel, dim3(1), dim3(256), sizeof(double) * (size_t)h->cfg.K,
-                     h->stream, h->n_k, h->s_k, h->pi, h->mu, h->cfg.dim, h->cfg.K, h->alpha,
-                     h->prior_sd, h->sigma, h->cfg.seed, sweep, h->counters + 1);
+  const size_t shm = sizeof(double) * (size_t)h->cfg.K + sizeof(float) * (size_t)h->cfg.K * h->cfg.dim;
+  hipLaunchKernelGGL(gmm_resample_kernel, dim3(1), dim3(256), shm, h->stream, h->n_k, h->s_k, h->q_k,
+                     h->pi, h->mu, h->var, h->cfg.dim, h->cfg.K, h->alpha, h->prior_sd, h->sigma,
+                     h->a0, h->b0, h->cfg.seed, sweep, h->counters + 1);
   AUGUR_HIP_TRY(hipGetLastError());
   return AUGUR_OK;
 }
@@ -318,9 +402,17 @@ int augur_gmm_create(const augur_gmm_config* cfg, const float* x, augur_gmm** ou
   AUGUR_REQUIRE((int64_t)cfg->K * cfg->dim <= 4096 && cfg->dim <= 14,
                 "supported sizes: dim <= 14 and K * dim <= 4096 (got dim %d, K %d)", cfg->dim,
                 cfg->K);
+  const bool unknown_var = cfg->var_shape > 0.f;
   AUGUR_REQUIRE(std::isfinite(cfg->alpha) && cfg->alpha > 0.f && std::isfinite(cfg->prior_sd) &&
-                    cfg->prior_sd > 0.f && std::isfinite(cfg->sigma) && cfg->sigma > 0.f,
-                "alpha, prior_sd and sigma must be positive and finite");
+                    cfg->prior_sd > 0.f,
+                "alpha and prior_sd must be positive and finite");
+  if (unknown_var)
+    AUGUR_REQUIRE(std::isfinite(cfg->var_shape) && std::isfinite(cfg->var_scale) &&
+                      cfg->var_scale > 0.f,
+                  "var_shape and var_scale must be positive and finite for unknown variances");
+  else
+    AUGUR_REQUIRE(cfg->var_shape == 0.f && std::isfinite(cfg->sigma) && cfg->sigma > 0.f,
+                  "known variance: var_shape must be 0 and sigma positive and finite");
   AUGUR_REQUIRE((cfg->flags & ~AUGUR_PTRS_DEVICE) == 0, "unknown flag bits 0x%x", cfg->flags);
   int ndev = 0;
   AUGUR_HIP_TRY(hipGetDeviceCount(&ndev));
@@ -336,9 +428,14 @@ int augur_gmm_create(const augur_gmm_config* cfg, const float* x, augur_gmm** ou
   h->alpha = (double)cfg->alpha;
   h->prior_sd = (double)cfg->prior_sd;
   h->sigma = (double)cfg->sigma;
+  h->unknown_var = unknown_var;
+  h->a0 = (double)cfg->var_shape;
+  h->b0 = (double)cfg->var_scale;
   const int64_t N = cfg->N;
   const int K = cfg->K, dim = cfg->dim;
-  h->stat_blocks = (int)((N + kStatChunk - 1) / kStatChunk);
+  const int chunk = unknown_var ? kStatChunkSq : kStatChunk;
+  const int W = dim + (unknown_var ? 1 : 0);
+  h->stat_blocks = (int)((N + chunk - 1) / chunk);
 
 #define AUGUR_CREATE_TRY(expr)                                                              \
   do {                                                                                      \
@@ -359,7 +456,14 @@ int augur_gmm_create(const augur_gmm_config* cfg, const float* x, augur_gmm** ou
   AUGUR_CREATE_TRY(hipMalloc(&h->mu, sizeof(float) * (size_t)K * dim));
   AUGUR_CREATE_TRY(hipMalloc(&h->n_k, sizeof(int32_t) * (size_t)K));
   AUGUR_CREATE_TRY(hipMalloc(&h->s_k, sizeof(double) * (size_t)K * dim));
-  AUGUR_CREATE_TRY(hipMalloc(&h->part_s, sizeof(double) * (size_t)h->stat_blocks * K * dim));
+  AUGUR_CREATE_TRY(hipMalloc(&h->part_s, sizeof(double) * (size_t)h->stat_blocks * K * W));
+  if (unknown_var) {
+    // start from the prior's scale/shape ratio; the first conditional draw replaces it
+    std::vector<float> v0((size_t)K, (float)(h->b0 / h->a0));
+    AUGUR_CREATE_TRY(hipMalloc(&h->var, sizeof(float) * (size_t)K));
+    AUGUR_CREATE_TRY(hipMalloc(&h->q_k, sizeof(double) * (size_t)K));
+    AUGUR_CREATE_TRY(hipMemcpy(h->var, v0.data(), sizeof(float) * (size_t)K, hipMemcpyHostToDevice));
+  }
   AUGUR_CREATE_TRY(hipMalloc(&h->part_n, sizeof(int32_t) * (size_t)h->stat_blocks * K));
   AUGUR_CREATE_TRY(hipMalloc(&h->red, sizeof(double) * kRedBlocks));
   AUGUR_CREATE_TRY(hipMemcpyAsync(h->x, x, sizeof(float) * (size_t)N * dim,
@@ -429,10 +533,13 @@ int augur_gmm_loglik(augur_gmm* h, double* log_joint) {
   AUGUR_REQUIRE(log_joint != nullptr, "log_joint is NULL");
   const int K = h->cfg.K, dim = h->cfg.dim;
   hipLaunchKernelGGL(gmm_loglik_kernel, dim3(kRedBlocks), dim3(256), 0, h->stream, h->x, h->z, h->pi,
-                     h->mu, h->cfg.N, dim, h->sigma, h->red);
+                     h->mu, h->var, h->cfg.N, dim, h->sigma, h->red);
   AUGUR_HIP_TRY(hipGetLastError());
   std::vector<double> part(kRedBlocks);
-  std::vector<float> pi(K), mu((size_t)K * dim);
+  std::vector<float> pi(K), mu((size_t)K * dim), var(h->unknown_var ? K : 0);
+  if (h->unknown_var)
+    AUGUR_HIP_TRY(hipMemcpyAsync(var.data(), h->var, sizeof(float) * K, hipMemcpyDeviceToHost,
+                                 h->stream));
   AUGUR_HIP_TRY(hipMemcpyAsync(part.data(), h->red, sizeof(double) * kRedBlocks,
                                hipMemcpyDeviceToHost, h->stream));
   AUGUR_HIP_TRY(hipMemcpyAsync(pi.data(), h->pi, sizeof(float) * K, hipMemcpyDeviceToHost,
@@ -440,13 +547,17 @@ int augur_gmm_loglik(augur_gmm* h, double* log_joint) {
   AUGUR_HIP_TRY(hipMemcpyAsync(mu.data(), h->mu, sizeof(float) * mu.size(), hipMemcpyDeviceToHost,
                                h->stream));
   AUGUR_HIP_TRY(hipStreamSynchronize(h->stream));
-  // the K + K*dim prior terms are a handful of scalars: summed on the host
+  // the prior terms are a handful of scalars: summed on the host
   const double LN_2PI = 1.8378770664093454835606594728112;
   double lj = std::lgamma(K * h->alpha) - K * std::lgamma(h->alpha);
   for (int k = 0; k < K; ++k) lj += (h->alpha - 1.0) * std::log((double)pi[k]);
   for (size_t e = 0; e < mu.size(); ++e) {
     const double m = (double)mu[e];
     lj += -0.5 * LN_2PI - std::log(h->prior_sd) - m * m / (2.0 * h->prior_sd * h->prior_sd);
+  }
+  for (size_t k = 0; k < var.size(); ++k) {  // var_k ~ InverseGamma(a0, b0)
+    const double v = (double)var[k];
+    lj += h->a0 * std::log(h->b0) - std::lgamma(h->a0) - (h->a0 + 1.0) * std::log(v) - h->b0 / v;
   }
   for (int i = 0; i < kRedBlocks; ++i) lj += part[i];
   *log_joint = lj;
@@ -500,6 +611,38 @@ int augur_gmm_set_state(augur_gmm* h, const int32_t* z, const float* pi, const f
                                  h->stream));
   AUGUR_HIP_TRY(hipStreamSynchronize(h->stream));
   if (sweep >= 0) h->sweep = sweep;
+  return AUGUR_OK;
+}
+
+int augur_gmm_get_var(augur_gmm* h, float* var) {
+  AUGUR_CHECK_HANDLE(h);
+  AUGUR_REQUIRE(h->unknown_var, "this handle has a known variance (var_shape = 0)");
+  AUGUR_REQUIRE(var != nullptr, "var is NULL");
+  AUGUR_HIP_TRY(hipMemcpyAsync(var, h->var, sizeof(float) * (size_t)h->cfg.K,
+                               device_ptrs(h) ? hipMemcpyDeviceToDevice : hipMemcpyDeviceToHost,
+                               h->stream));
+  AUGUR_HIP_TRY(hipStreamSynchronize(h->stream));
+  return AUGUR_OK;
+}
+
+int augur_gmm_set_var(augur_gmm* h, const float* var) {
+  AUGUR_CHECK_HANDLE(h);
+  AUGUR_REQUIRE(h->unknown_var, "this handle has a known variance (var_shape = 0)");
+  AUGUR_REQUIRE(var != nullptr, "var is NULL");
+  std::vector<float> v((size_t)h->cfg.K);  // K values: checked on the host either way
+  if (device_ptrs(h)) {
+    AUGUR_HIP_TRY(hipMemcpyAsync(v.data(), var, sizeof(float) * v.size(), hipMemcpyDeviceToHost,
+                                 h->stream));
+    AUGUR_HIP_TRY(hipStreamSynchronize(h->stream));
+  } else {
+    std::copy(var, var + v.size(), v.begin());
+  }
+  for (int k = 0; k < h->cfg.K; ++k)
+    AUGUR_REQUIRE(std::isfinite(v[k]) && v[k] > 0.f, "var[%d] = %g is not positive and finite", k,
+                  (double)v[k]);
+  AUGUR_HIP_TRY(hipMemcpyAsync(h->var, v.data(), sizeof(float) * v.size(), hipMemcpyHostToDevice,
+                               h->stream));
+  AUGUR_HIP_TRY(hipStreamSynchronize(h->stream));
   return AUGUR_OK;
 }
 

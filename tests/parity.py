@@ -54,6 +54,18 @@ def assert_z_gmm(z_gpu, z_orc, x, pi, mu, sigma, seed, sweep):
     return mism.size
 
 
+def assert_z_gmmuv(z_gpu, z_orc, x, pi, mu, var, seed, sweep):
+    z_gpu, z_orc = np.asarray(z_gpu), np.asarray(z_orc)
+    N = z_orc.size
+    assert z_gpu.min() >= 0 and z_gpu.max() < pi.size
+    mism = np.nonzero(z_gpu != z_orc)[0]
+    assert mism.size <= (1.0 - Z_AGREE) * N, f"{mism.size} of {N} z differ"
+    for i in mism:
+        cdf, t = O.gmmuv_point_cdf(x[i], pi, mu, var, seed, int(i), sweep)
+        _assert_boundary(cdf, t, int(z_gpu[i]), int(z_orc[i]), f"point {i}")
+    return mism.size
+
+
 def _assert_boundary(cdf, t, zg, zo, what, mass=None):
     lo, hi = min(zg, zo), max(zg, zo)
     between = cdf[lo:hi]                       # boundaries C_lo .. C_{hi-1} separate the answers

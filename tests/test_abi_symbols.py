@@ -40,7 +40,7 @@ def test_argument_errors_without_device():
     assert L.augur_lda_create(C.byref(cfg), None, None, C.byref(h)) == B.ERR_INVALID_ARG
     assert L.augur_lda_create(C.byref(cfg), None, None, None) == B.ERR_INVALID_ARG
     assert h.value is None
-    g = B.GmmConfig(0, 8, 16, 1.0, 10.0, 1.0, 1, 0, None, 0)
+    g = B.GmmConfig(0, 8, 16, 1.0, 10.0, 1.0, 0.0, 0.0, 1, 0, None, 0)
     assert L.augur_gmm_create(C.byref(g), None, C.byref(h)) == B.ERR_INVALID_ARG
     for fn in (L.augur_lda_sync, L.augur_gmm_sync, L.augur_lda_step_finish, L.augur_gmm_step_finish):
         assert fn(None) == B.ERR_INVALID_ARG
