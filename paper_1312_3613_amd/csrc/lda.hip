@@ -96,6 +96,32 @@ __device__ __forceinline__ Segment segment_of(const int64_t* __restrict__ doc_of
   g.end = g.b < g.first + kSegTokens ? g.b : g.first + kSegTokens;
   return g;
 }
+// True when document d is cut into more than one segment: then no single wave
+// sees all of its tokens, and its row of n_dk is zeroed first and every segment
+// adds its own histogram to it (integer adds: the result does not depend on the
+// order).
+__device__ __forceinline__ bool is_split(const int32_t* __restrict__ seg_base, int d) {
+  return seg_base != nullptr && seg_base[d + 1] - seg_base[d] > 1;
+}
+__global__ __launch_bounds__(256) void zero_split_rows_kernel(const int32_t* __restrict__ seg_base,
+                                                               int32_t* __restrict__ n_dk, int D,
+                                                               int ldk) {
+  const int lane = threadIdx.x & 63;
+  const int d = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (d >= D || !is_split(seg_base, d)) return;
+  for (int k = lane; k < ldk; k += 64) n_dk[(size_t)d * ldk + k] = 0;
+}
+// Stores (whole document) or adds (segment of a split document) a wave's LDS
+// histogram into the document's row.
+__device__ __forceinline__ void flush_doc_histogram(const int32_t* hist, int32_t* __restrict__ row,
+                                                    int ldk, bool split, int lane) {
+  if (!split) {
+    for (int k = lane; k < ldk; k += 64) row[k] = hist[k];
+  } else {
+    for (int k = lane; k < ldk; k += 64)
+      if (hist[k] != 0) atomicAdd(&row[k], hist[k]);
+  }
+}
 __global__ __launch_bounds__(256) void segment_counts_kernel(const int64_t* __restrict__ doc_off,
                                                               int D, int32_t* __restrict__ ns) {
   const int d = blockIdx.x * blockDim.x + threadIdx.x;
@@ -285,7 +311,8 @@ constexpr int kNoTopic = 0x7FFFFFFF;
 //
 // With kCountDocs the wave also builds its document's row of n_dk in LDS while it
 // draws and stores it at the end (the document half of the counting phase, for
-// free: the wave already owns the document).
+// free: the wave already owns the document; a segment of a split document adds
+// to the row, which the host zeroes before the launch).
 template <int NS16, bool kCountDocs>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NS16 > 8 ? 4 : 1)))
 void lda_sample_z_quad_kernel(
@@ -463,7 +490,7 @@ void lda_sample_z_quad_kernel(
   }
   if (kCountDocs) {
     wave_lds_fence();
-    for (int k = lane; k < ldk; k += 64) n_dk[(size_t)d * ldk + k] = hist[k];
+    flush_doc_histogram(hist, n_dk + (size_t)d * ldk, ldk, is_split(seg_base, d), lane);
   }
 }
 
@@ -473,21 +500,23 @@ void lda_sample_z_quad_kernel(
 // built from LDS histograms whose owner is fixed by the static structure of the
 // corpus.
 //
-// Documents: one wave per document builds the row in LDS and stores it whole.
+// Documents: one wave per segment (a whole document unless it is split) builds
+// the row in LDS and stores it, or adds it to the zeroed row of a split document.
 __global__ __launch_bounds__(256) void lda_count_docs_kernel(
-    const int32_t* __restrict__ z, const int64_t* __restrict__ doc_off, int32_t* __restrict__ n_dk,
-    int D, int ldk) {
+    const int32_t* __restrict__ z, const int64_t* __restrict__ doc_off,
+    const int32_t* __restrict__ seg_base, int n_segs, int32_t* __restrict__ n_dk, int D, int ldk) {
   extern __shared__ int32_t hist_all[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int d = blockIdx.x * 4 + wave;
-  if (d >= D) return;
+  const int seg = blockIdx.x * 4 + wave;
+  if (seg >= n_segs) return;
+  const Segment sg = segment_of(doc_off, seg_base, D, seg);
   int32_t* hist = hist_all + (size_t)wave * ldk;
   for (int k = lane; k < ldk; k += 64) hist[k] = 0;
   wave_lds_fence();
-  const int64_t a = doc_off[d], b = doc_off[d + 1];
-  for (int64_t i = a + lane; i < b; i += 64) atomicAdd(&hist[z[i]], 1);
+  const int64_t a = sg.first > sg.a ? sg.first : sg.a;
+  for (int64_t i = a + lane; i < sg.end; i += 64) atomicAdd(&hist[z[i]], 1);
   wave_lds_fence();
-  for (int k = lane; k < ldk; k += 64) n_dk[(size_t)d * ldk + k] = hist[k];
+  flush_doc_histogram(hist, n_dk + (size_t)sg.d * ldk, ldk, is_split(seg_base, sg.d), lane);
 }
 
 // Words: tokens were sorted by word once (perm).  A word's run of tokens is cut
@@ -769,14 +798,14 @@ __global__ __launch_bounds__(256) void lda_phi_write_kernel(const double* __rest
 // -------------------------------------------------------------------- loglik
 // Per-token terms of the log joint (Sect. 4.1: log space, terms evaluated in
 // parallel and summed): ln theta[d][z_i] + ln phi[w_i][z_i], and
-// ln sum_k theta[d][k] phi[w_i][k] for the marginal.  One wave per document
-// slot with theta_d in LDS, a quad per token (64 contiguous bytes of the phi row
+// ln sum_k theta[d][k] phi[w_i][k] for the marginal.  One wave per segment
+// slot (a whole document unless it is split) with theta_d in LDS, a quad per token (64 contiguous bytes of the phi row
 // per load, as in the sampler), fp64 products and sums.
 __global__ __launch_bounds__(256) void lda_loglik_tokens_kernel(
     const int32_t* __restrict__ w, const int32_t* __restrict__ z,
-    const int64_t* __restrict__ doc_off, const float* __restrict__ theta,
-    const float* __restrict__ phi, int D, int ldk, double* __restrict__ part_lik,
-    double* __restrict__ part_marg) {
+    const int64_t* __restrict__ doc_off, const int32_t* __restrict__ seg_base, int n_segs,
+    const float* __restrict__ theta, const float* __restrict__ phi, int D, int ldk,
+    double* __restrict__ part_lik, double* __restrict__ part_marg) {
   extern __shared__ float theta_lds[];  // [4][ldk16], ldk16 = ldk rounded up to 16
   __shared__ double smem[8];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -787,11 +816,13 @@ __global__ __launch_bounds__(256) void lda_loglik_tokens_kernel(
   const uint32_t row_bytes = 4u * (uint32_t)ldk;
   const char* phi_bytes = reinterpret_cast<const char*>(phi);
   double lik = 0.0, marg = 0.0;
-  for (int d = blockIdx.x * 4 + wave; d < D; d += gridDim.x * 4) {
+  for (int seg = blockIdx.x * 4 + wave; seg < n_segs; seg += gridDim.x * 4) {
+    const Segment sg = segment_of(doc_off, seg_base, D, seg);
+    const int d = sg.d;
     wave_lds_fence();
     for (int k = lane; k < ldk16; k += 64) th[k] = k < ldk ? theta[(size_t)d * ldk + k] : 0.f;
     wave_lds_fence();
-    const int64_t a = doc_off[d], b = doc_off[d + 1];
+    const int64_t a = sg.first > sg.a ? sg.first : sg.a, b = sg.end;
     for (int64_t i0 = a; i0 < b; i0 += 16) {
       const int64_t i = i0 + tq;
       const bool valid = i < b;
@@ -933,6 +964,15 @@ void free_all(augur_lda* h) {
   if (h->ev_join) (void)hipEventDestroy(h->ev_join);
 }
 
+// Rows of n_dk that several segments add to start from zero.
+int zero_split_rows(augur_lda* h, hipStream_t stream) {
+  if (h->seg_base == nullptr) return AUGUR_OK;
+  hipLaunchKernelGGL(zero_split_rows_kernel, dim3((h->cfg.D + 3) / 4), dim3(256), 0, stream,
+                     h->seg_base, h->n_dk, h->cfg.D, h->ldk);
+  AUGUR_HIP_TRY(hipGetLastError());
+  return AUGUR_OK;
+}
+
 // fused: the kernel also writes the document table n_dk (K <= 256 only); returns
 // whether it did through *did_count.
 int launch_sample_z(augur_lda* h, uint32_t sweep, bool fuse_doc_counts = false,
@@ -941,8 +981,10 @@ int launch_sample_z(augur_lda* h, uint32_t sweep, bool fuse_doc_counts = false,
   if (did_count) *did_count = false;
   if (D == 0 || h->N == 0) return AUGUR_OK;
   const dim3 grid((h->n_segs + 3) / 4), block(256);
-  // a document cut into segments has no single wave that sees all of its tokens
-  if (h->seg_base != nullptr) fuse_doc_counts = false;
+  if (fuse_doc_counts && h->ldk <= 256) {
+    const int rc = zero_split_rows(h, h->stream);
+    if (rc != AUGUR_OK) return rc;
+  }
 #define AUGUR_ZQ_ARGS                                                                          \
   grid, block, 0, h->stream, h->w, h->doc_off, h->seg_base, h->n_segs, h->theta, h->phi, h->z,  \
       h->n_dk, D, h->cfg.K, h->ldk, h->cfg.seed, sweep, h->counters
@@ -984,9 +1026,14 @@ int launch_sample_z(augur_lda* h, uint32_t sweep, bool fuse_doc_counts = false,
 
 int launch_count_docs(augur_lda* h, hipStream_t stream) {
   const int D = h->cfg.D;
-  hipLaunchKernelGGL(lda_count_docs_kernel, dim3((D + 3) / 4), dim3(256),
-                     sizeof(int32_t) * 4 * (size_t)h->ldk, stream, h->z, h->doc_off, h->n_dk, D,
-                     h->ldk);
+  if (D == 0) return AUGUR_OK;
+  {
+    const int rc = zero_split_rows(h, stream);
+    if (rc != AUGUR_OK) return rc;
+  }
+  hipLaunchKernelGGL(lda_count_docs_kernel, dim3((h->n_segs + 3) / 4), dim3(256),
+                     sizeof(int32_t) * 4 * (size_t)h->ldk, stream, h->z, h->doc_off, h->seg_base,
+                     h->n_segs, h->n_dk, D, h->ldk);
   AUGUR_HIP_TRY(hipGetLastError());
   return AUGUR_OK;
 }
@@ -1486,7 +1533,7 @@ int augur_lda_loglik(augur_lda* h, double* log_joint, double* log_marginal_w) {
   double* p_ph = h->red + 3 * kRedBlocks;
   hipLaunchKernelGGL(lda_loglik_tokens_kernel, dim3(kRedBlocks), dim3(256),
                      sizeof(float) * 4 * (size_t)((h->ldk + 15) & ~15), h->stream, h->w, h->z,
-                     h->doc_off, h->theta, h->phi, D, h->ldk, p_lik, p_marg);
+                     h->doc_off, h->seg_base, h->n_segs, h->theta, h->phi, D, h->ldk, p_lik, p_marg);
   hipLaunchKernelGGL(sum_log_kernel, dim3(kRedBlocks), dim3(256), 0, h->stream, h->theta,
                      (int64_t)D, K, h->ldk, p_th);
   hipLaunchKernelGGL(sum_log_kernel, dim3(kRedBlocks), dim3(256), 0, h->stream, h->phi, (int64_t)V,

@@ -122,6 +122,22 @@ def lda_corpus(D, V, K, mean_len, alpha, beta, seed, zipf=None, return_truth=Fal
     return out
 
 
+def categorical_mixture(N, K, V, seed, alpha=0.5, beta=0.5, return_truth=False):
+    """N draws from the categorical mixture of the paper's supplement: weights ~ Dirichlet(beta 1_K),
+    K component distributions over V values ~ Dirichlet(alpha 1_V), z_i ~ Categorical(weights),
+    x_i ~ Categorical(component z_i).  In LDA terms: one document of N tokens."""
+    rng = np.random.default_rng(seed)
+    weights = rng.dirichlet(np.full(K, beta))
+    comp = rng.dirichlet(np.full(V, alpha), size=K)
+    z = rng.choice(K, size=N, p=weights).astype(np.int32)
+    cdf = np.cumsum(comp, axis=1)
+    x = np.minimum((rng.random(N)[:, None] > cdf[z]).sum(axis=1), V - 1).astype(np.int32)
+    out = dict(x=x)
+    if return_truth:
+        out.update(z=z, weights=weights.astype(np.float32), comp=comp.astype(np.float32))
+    return out
+
+
 def gmm_points(N, dim, K, seed, mean_sd=10.0, sigma=1.0, return_truth=False, **_unused):
     """N points in R^dim from K unit-covariance components: means ~ N(0, mean_sd^2 I),
     weights ~ Dirichlet(1), x = mu_z + sigma * N(0, I).  fp32."""

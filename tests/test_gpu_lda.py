@@ -209,6 +209,32 @@ def test_long_documents_are_cut_into_segments(B, K):
         h.close()
 
 
+@pytest.mark.parametrize("K,V,N", [(8, 50, 200_003), (100, 1000, 1_000_000)])
+def test_categorical_mixture_is_one_long_document(B, K, V, N):
+    # the supplement's categorical mixture: one document of N tokens (hundreds of segments),
+    # Dirichlet(0.5) priors on the weights and on the components
+    d = synth.categorical_mixture(N, K, V, seed=K)
+    lens = np.array([N], dtype=np.int32)
+    g, o = make_pair(B, 1, V, K, 0.5, 0.5, 41, lens, d["x"])
+    n_dk, n_wk = g.get_counts()
+    assert np.array_equal(np_(n_dk), o.n_dk) and np.array_equal(np_(n_wk), o.n_wk)
+    for _ in range(2):
+        lockstep_sweep(g, o, check_loglik=True)
+    # the sweep entry point (counts fused into the sampler, overlapped schedule) against the
+    # step-wise calls
+    g2 = B.LDA(1, V, K, 0.5, 0.5, 41, lens, d["x"])
+    g3 = B.LDA(1, V, K, 0.5, 0.5, 41, lens, d["x"])
+    g2.sweep(3)
+    for _ in range(3):
+        g3.step_sample_z(); g3.step_count(); g3.step_resample_theta(); g3.step_resample_phi(); g3.step_finish()
+    for x, y in zip(g2.get_state() + g2.get_counts(), g3.get_state() + g3.get_counts()):
+        assert np.array_equal(x, y)
+    n_dk, n_wk = g2.get_counts()
+    assert np_(n_dk).sum() == N and np.array_equal(np_(n_dk)[0], np_(n_wk).sum(axis=0))
+    for h in (g, g2, g3):
+        h.close()
+
+
 def test_fold_in_with_phi_observed(B):
     # learn phi on a training corpus, then infer z and theta on held-out documents with phi as data
     cfg = dict(synth.LDA_CONFIGS["tiny"], D=240, V=300, K=12, mean_len=60)

@@ -300,3 +300,28 @@ def test_phi_observed_sweep_targets_theta_posterior_given_phi():
         g[t] = [m.theta[0, 0], m.theta[0, 0] ** 2]
     assert np.array_equal(m.phi, phi)                       # phi is data: untouched
     _batch_check(g, np.array([m1, m2]))
+
+
+def test_single_document_is_the_categorical_mixture():
+    # The categorical mixture of the supplement is the LDA program with one document: the shared
+    # weights are the document's theta and the K component distributions the columns of phi.
+    K, V, N = 3, 12, 30_000
+    d = synth.categorical_mixture(N, K, V, seed=5, return_truth=True)
+    o = O.OracleLDA(1, V, K, 0.5, 0.5, 9, np.array([N], dtype=np.int32), d["x"])
+    # the conditional of z_i written out from the mixture's definition
+    for i in (0, 1, 17, N - 1):
+        cdf, t = O.lda_token_cdf(o.theta[0], o.phi[d["x"][i]], o.seed, i, 1)
+        p = o.theta[0].astype(np.float64) * o.phi[d["x"][i]].astype(np.float64)
+        assert np.allclose(np.diff(np.concatenate([[0.0], cdf])), p, rtol=1e-12)
+    # A mixture of categoricals observed through single draws is identifiable only through its
+    # marginal sum_k weights_k comp_k[v]: the chain's average of it must match the empirical
+    # frequencies of x (N is large, so the posterior of the marginal is tight around them).
+    o.sweep(20)
+    marg = np.zeros(V)
+    T = 60
+    for _ in range(T):
+        o.sweep(1)
+        marg += o.phi.astype(np.float64) @ o.theta[0].astype(np.float64)
+    freq = np.bincount(d["x"], minlength=V) / N
+    assert np.abs(marg / T - freq).max() < 0.004
+    assert o.n_dk.sum() == N and np.array_equal(o.n_dk[0], o.n_wk.sum(axis=0))
