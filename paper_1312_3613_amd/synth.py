@@ -130,8 +130,11 @@ def categorical_mixture(N, K, V, seed, alpha=0.5, beta=0.5, return_truth=False):
     weights = rng.dirichlet(np.full(K, beta))
     comp = rng.dirichlet(np.full(V, alpha), size=K)
     z = rng.choice(K, size=N, p=weights).astype(np.int32)
-    cdf = np.cumsum(comp, axis=1)
-    x = np.minimum((rng.random(N)[:, None] > cdf[z]).sum(axis=1), V - 1).astype(np.int32)
+    x = np.empty(N, dtype=np.int32)
+    for k in range(K):
+        mine = np.nonzero(z == k)[0]
+        cdf = np.cumsum(comp[k])
+        x[mine] = np.minimum(np.searchsorted(cdf, rng.random(mine.size) * cdf[-1], side="right"), V - 1)
     out = dict(x=x)
     if return_truth:
         out.update(z=z, weights=weights.astype(np.float32), comp=comp.astype(np.float32))
