@@ -1,5 +1,7 @@
 // Oracle for the uncollapsed Gibbs sweep of Augur (arXiv 1312.3613) on LDA and
-// on a Gaussian mixture with known covariance.
+// on a Gaussian mixture (known covariance, or unknown per-component variances),
+// and for its data-parallel random-walk Metropolis-Hastings sampler on the
+// multivariate regression model.
 //
 // THIS FILE IS TEST INFRASTRUCTURE.  It is a plain, slow, single-threaded CPU
 // program written from the paper's statement of the method so that a reader can
@@ -24,7 +26,13 @@
 //     summed.
 //   * Supplementary Gaussian mixture (Fig. "GMM"), in the variant with known
 //     covariance sigma^2 I, prior N(0, prior_sd^2 I) on the means and a
-//     symmetric Dirichlet(alpha) on the weights.
+//     symmetric Dirichlet(alpha) on the weights; and as printed, with an
+//     inverse-Gamma prior on each component's variance.
+//   * Sect. 4.1 and Fig. "regression": the function f proportional to the
+//     posterior of the regression model is the product of the priors of b, tau
+//     and w_k and of the per-datum terms p(x_n) p(y_n | x_n . w + b, tau),
+//     evaluated in log space; a library random-walk Metropolis-Hastings
+//     sampler (no tuning; supplement, "Multivariate Regression") drives it.
 //
 // Readings where the paper is silent (all listed in the design notes):
 //   * phi is stored [V][K] (row = word), theta [D][K].
@@ -71,7 +79,8 @@ void philox4x32_10(const uint32_t ctr_in[4], const uint32_t key_in[2], uint32_t 
 
 enum Stream : uint32_t {
   STREAM_INIT_Z = 0, STREAM_Z = 1, STREAM_THETA = 2, STREAM_PHI = 3,
-  STREAM_GMM_PI = 4, STREAM_GMM_MU = 5, STREAM_GMM_VAR = 6
+  STREAM_GMM_PI = 4, STREAM_GMM_MU = 5, STREAM_GMM_VAR = 6, STREAM_MH_PROPOSAL = 7,
+  STREAM_MH_ACCEPT = 8
 };
 
 // The block of four 32-bit words belonging to (seed, variable index, sweep,
@@ -647,6 +656,81 @@ double orc_gmmuv_loglik(int64_t N, int32_t dim, int32_t K, double alpha, double 
     lj += std::log((double)pi[k]) - 0.5 * (double)dim * (LN_2PI + std::log(v)) - q / (2.0 * v);
   }
   return lj;
+}
+
+// --------------------------- Metropolis-Hastings on the multivariate regression
+// Model (Fig. "regression"): w_k ~ N(0, prior_sd^2), b ~ N(0, prior_sd^2),
+// tau ~ InverseGamma(a0, b0), x_nk ~ Uniform(l, u), y_n ~ N(x_n . w + b, tau).
+// The second argument of the listing's Gaussian is read as a variance (it is
+// what the inverse-Gamma prior is put on).  Parameters are fp64 and ordered
+// theta = (w_0 .. w_{K-1}, b, tau); the data are fp32.
+//
+// ln f (Sect. 4.1): sum of the log prior terms and of the N per-datum terms
+// ln p(x_n) + ln N(y_n; x_n . w + b, tau), with ln p(x_n) = -K ln(u - l).
+// tau <= 0 has density zero: -infinity.
+double orc_mhreg_logf(int64_t N, int32_t K, const float* x, const float* y, const double* theta,
+                      double prior_sd, double a0, double b0, double l, double u) {
+  const double LN_2PI = 1.8378770664093454835606594728112;
+  const double* w = theta;
+  const double b = theta[K], tau = theta[K + 1];
+  if (!(tau > 0.0)) return -INFINITY;
+  double lf = 0.0;
+  for (int32_t k = 0; k <= K; ++k)  // w_0 .. w_{K-1} and b
+    lf += -0.5 * LN_2PI - std::log(prior_sd) - theta[k] * theta[k] / (2.0 * prior_sd * prior_sd);
+  lf += a0 * std::log(b0) - std::lgamma(a0) - (a0 + 1.0) * std::log(tau) - b0 / tau;
+  for (int64_t n = 0; n < N; ++n) {
+    double mean = b;
+    for (int32_t k = 0; k < K; ++k) mean += w[k] * (double)x[n * K + k];
+    const double r = (double)y[n] - mean;
+    lf += -(double)K * std::log(u - l) - 0.5 * (LN_2PI + std::log(tau)) - r * r / (2.0 * tau);
+  }
+  return lf;
+}
+
+// Proposal of step t (t = 1, 2, ...): every parameter moves at once,
+// theta'_e = theta_e + step * n_e, n_e the standard normal of block (index e,
+// sweep t) of the proposal stream.
+void orc_mhreg_propose(int32_t K, const double* theta, double step, uint64_t seed, uint32_t t,
+                       double* proposal) {
+  for (int32_t e = 0; e < K + 2; ++e) {
+    uint32_t r[4];
+    random_block(seed, (uint64_t)e, t, STREAM_MH_PROPOSAL, 0, r);
+    proposal[e] = theta[e] + step * normal_from(r);
+  }
+}
+
+// Uniform of the acceptance test of step t.
+double orc_mhreg_accept_uniform(uint64_t seed, uint32_t t) {
+  uint32_t r[4];
+  random_block(seed, 0, t, STREAM_MH_ACCEPT, 0, r);
+  return uniform32(r[0]);
+}
+
+// n_steps steps from (theta, *logf), the first with index first_step.  The
+// random walk is symmetric, so a proposal is accepted iff ln u < ln f(theta') -
+// ln f(theta).  trace (may be NULL) receives theta and ln f after every step,
+// K + 3 doubles a row.  Returns the number of accepted proposals.
+int64_t orc_mhreg_run(int64_t N, int32_t K, const float* x, const float* y, double prior_sd,
+                      double a0, double b0, double l, double u, double step, uint64_t seed,
+                      uint32_t first_step, int64_t n_steps, double* theta, double* logf,
+                      double* trace) {
+  std::vector<double> prop(K + 2);
+  int64_t accepted = 0;
+  for (int64_t s = 0; s < n_steps; ++s) {
+    const uint32_t t = first_step + (uint32_t)s;
+    orc_mhreg_propose(K, theta, step, seed, t, prop.data());
+    const double lp = orc_mhreg_logf(N, K, x, y, prop.data(), prior_sd, a0, b0, l, u);
+    if (std::log(orc_mhreg_accept_uniform(seed, t)) < lp - *logf) {
+      for (int32_t e = 0; e < K + 2; ++e) theta[e] = prop[e];
+      *logf = lp;
+      ++accepted;
+    }
+    if (trace) {
+      for (int32_t e = 0; e < K + 2; ++e) trace[s * (K + 3) + e] = theta[e];
+      trace[s * (K + 3) + K + 2] = *logf;
+    }
+  }
+  return accepted;
 }
 
 }  // extern "C"

@@ -13,7 +13,7 @@ from . import build as _build
 _LIB = None
 
 (STREAM_INIT_Z, STREAM_Z, STREAM_THETA, STREAM_PHI, STREAM_GMM_PI, STREAM_GMM_MU,
- STREAM_GMM_VAR) = range(7)
+ STREAM_GMM_VAR, STREAM_MH_PROPOSAL, STREAM_MH_ACCEPT) = range(9)
 
 
 def _p(a, ct):
@@ -45,6 +45,9 @@ def lib():
         L.orc_gmmuv_sweep.restype = C.c_int64
         L.orc_gmmuv_resample.restype = C.c_int
         L.orc_gmmuv_loglik.restype = C.c_double
+        L.orc_mhreg_logf.restype = C.c_double
+        L.orc_mhreg_accept_uniform.restype = C.c_double
+        L.orc_mhreg_run.restype = C.c_int64
         _LIB = L
     return _LIB
 
@@ -501,3 +504,64 @@ class OracleGMMUV(OracleGMM):
 
     def set_var(self, var):
         self.var = _f32(var).copy()
+
+
+# ------------------------------- Metropolis-Hastings on the multivariate regression
+def mhreg_logf(x, y, theta, prior_sd, a0, b0, l, u):
+    x, y, theta = _f32(x), _f32(y), _f64(theta)
+    N, K = x.shape
+    return lib().orc_mhreg_logf(C.c_int64(N), C.c_int32(K), _p(x, C.c_float), _p(y, C.c_float),
+                                _p(theta, C.c_double), C.c_double(prior_sd), C.c_double(a0),
+                                C.c_double(b0), C.c_double(l), C.c_double(u))
+
+
+def mhreg_propose(theta, step, seed, t):
+    theta = _f64(theta)
+    out = np.zeros_like(theta)
+    lib().orc_mhreg_propose(C.c_int32(theta.size - 2), _p(theta, C.c_double), C.c_double(step),
+                            C.c_uint64(seed), C.c_uint32(t), _p(out, C.c_double))
+    return out
+
+
+def mhreg_accept_uniform(seed, t):
+    return lib().orc_mhreg_accept_uniform(C.c_uint64(seed), C.c_uint32(t))
+
+
+class OracleMHRegression:
+    """Random-walk Metropolis-Hastings chain over theta = (w_0..w_{K-1}, b, tau)."""
+
+    def __init__(self, x, y, prior_sd, a0, b0, l, u, step, seed, theta0=None):
+        self.x, self.y = _f32(x).copy(), _f32(y).copy()
+        self.N, self.K = self.x.shape
+        f = lambda v: float(np.float32(v))
+        self.prior_sd, self.a0, self.b0, self.l, self.u = f(prior_sd), f(a0), f(b0), f(l), f(u)
+        self.step = f(step)
+        self.seed = int(seed)
+        if theta0 is None:
+            theta0 = np.concatenate([np.zeros(self.K + 1), [1.0]])
+        self.theta = _f64(theta0).copy()
+        self.logf = self.evaluate(self.theta)
+        self.step_index = 0
+        self.accepted = 0
+
+    def evaluate(self, theta):
+        return mhreg_logf(self.x, self.y, theta, self.prior_sd, self.a0, self.b0, self.l, self.u)
+
+    def run(self, n, trace=False):
+        tr = np.zeros((n, self.K + 3), dtype=np.float64) if trace else None
+        lf = C.c_double(self.logf)
+        self.accepted += lib().orc_mhreg_run(
+            C.c_int64(self.N), C.c_int32(self.K), _p(self.x, C.c_float), _p(self.y, C.c_float),
+            C.c_double(self.prior_sd), C.c_double(self.a0), C.c_double(self.b0), C.c_double(self.l),
+            C.c_double(self.u), C.c_double(self.step), C.c_uint64(self.seed),
+            C.c_uint32(self.step_index + 1), C.c_int64(n), _p(self.theta, C.c_double), C.byref(lf),
+            _p(tr, C.c_double) if trace else None)
+        self.logf = lf.value
+        self.step_index += n
+        return tr
+
+    def set_state(self, theta, step_index=None):
+        self.theta = _f64(theta).copy()
+        self.logf = self.evaluate(self.theta)
+        if step_index is not None:
+            self.step_index = int(step_index)

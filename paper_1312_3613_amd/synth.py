@@ -153,3 +153,19 @@ def gmm_points(N, dim, K, seed, mean_sd=10.0, sigma=1.0, return_truth=False, **_
     if return_truth:
         out.update(z=z, mu=mu.astype(np.float32), pi=pi.astype(np.float32))
     return out
+
+
+def regression_data(N, K, seed, l=-1.0, u=1.0, noise_var=0.25, return_truth=False):
+    """(x, y) from the multivariate regression program: x_nk ~ Uniform(l, u), weights and bias
+    ~ N(0, 1) (tighter than the model's prior so that y stays O(1)), y_n ~ N(x_n . w + b,
+    noise_var).  fp32.  Stands in for the UCI regression tables of the paper's supplement
+    (roughly 300 to 5000 rows, 6 to 11 predictors), which are not available here."""
+    rng = np.random.default_rng(seed)
+    w = rng.standard_normal(K)
+    b = rng.standard_normal()
+    x = rng.uniform(l, u, size=(N, K)).astype(np.float32)
+    y = (x.astype(np.float64) @ w + b + np.sqrt(noise_var) * rng.standard_normal(N)).astype(np.float32)
+    out = dict(x=x, y=y)
+    if return_truth:
+        out.update(w=w, b=b, tau=noise_var)
+    return out
