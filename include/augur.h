@@ -177,6 +177,54 @@ int augur_gmm_get_stats(augur_gmm* h, int32_t* n_k, double* s_k);
 int augur_gmm_get_degenerate(augur_gmm* h, int64_t* count);
 int augur_gmm_sync(augur_gmm* h);
 
+/* ----------------------- Metropolis-Hastings on the multivariate regression model
+ * Sect. 4.1 and Fig. "regression": w_k ~ N(0, prior_sd^2) (k < K),
+ * b ~ N(0, prior_sd^2), tau ~ InverseGamma(tau_shape, tau_scale),
+ * x_nk ~ Uniform(x_lo, x_hi), y_n ~ N(x_n . w + b, tau), tau a variance; x and y
+ * observed.  ln f = ln of the product of these densities: the per-datum terms
+ * are evaluated in parallel and summed (fp64).  The sampler is the random walk
+ * of the supplement's "Multivariate Regression" experiment: step t proposes
+ * theta' = theta + step * n_t (n_t standard normal, all parameters at once) and
+ * accepts iff ln u_t < ln f(theta') - ln f(theta); a proposal with tau' <= 0 has
+ * density zero and is refused.  theta = (w_0 .. w_{K-1}, b, tau): K + 2 doubles.
+ * Layout: x float[N][K], y float[N]; array pointers are host or device as
+ * flags say, scalars always host. */
+typedef struct augur_mhreg augur_mhreg;
+
+typedef struct {
+  int64_t N;          /* 1 .. 2^31-1 */
+  int32_t K;          /* 1 .. 64 predictors */
+  float prior_sd;     /* > 0 */
+  float tau_shape;    /* > 0 */
+  float tau_scale;    /* > 0 */
+  float x_lo, x_hi;   /* x_lo < x_hi; every x must lie in [x_lo, x_hi] */
+  float step;         /* > 0: standard deviation of the random walk */
+  uint64_t seed;
+  int32_t device;
+  void* stream;
+  uint32_t flags;     /* AUGUR_PTRS_DEVICE */
+} augur_mhreg_config;
+
+/* Copies x and y.  theta0 may be NULL (w = 0, b = 0, tau = 1); otherwise finite
+ * with tau > 0.  AUGUR_ERR_INVALID_ARG if a value of x is outside its support or
+ * x or y holds a non-finite value. */
+int augur_mhreg_create(const augur_mhreg_config* cfg, const float* x, const float* y,
+                       const double* theta0, augur_mhreg** out);
+void augur_mhreg_destroy(augur_mhreg* h);
+/* n_steps steps, asynchronous on the handle's stream unless a host trace is
+ * asked for.  trace: NULL, or n_steps rows of K + 3 doubles (theta, then ln f)
+ * after each step. */
+int augur_mhreg_run(augur_mhreg* h, int64_t n_steps, double* trace);
+/* Any output may be NULL.  accepted counts accepted proposals since create. */
+int augur_mhreg_get_state(augur_mhreg* h, double* theta, double* logf, int64_t* step_index,
+                          int64_t* accepted);
+/* theta NULL: left as is (else ln f is re-evaluated); step_index < 0: left as is. */
+int augur_mhreg_set_state(augur_mhreg* h, const double* theta, int64_t step_index);
+/* 0: automatic; 1: all steps of a run in one launch of one workgroup (N <= 65536);
+ * 2: one launch per step over many workgroups.  Same results either way. */
+int augur_mhreg_set_schedule(augur_mhreg* h, int32_t schedule);
+int augur_mhreg_sync(augur_mhreg* h);
+
 #ifdef __cplusplus
 }
 #endif

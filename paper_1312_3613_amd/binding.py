@@ -38,6 +38,13 @@ class GmmConfig(C.Structure):
                 ("device", C.c_int32), ("stream", C.c_void_p), ("flags", C.c_uint32)]
 
 
+class MhRegConfig(C.Structure):
+    _fields_ = [("N", C.c_int64), ("K", C.c_int32), ("prior_sd", C.c_float),
+                ("tau_shape", C.c_float), ("tau_scale", C.c_float), ("x_lo", C.c_float),
+                ("x_hi", C.c_float), ("step", C.c_float), ("seed", C.c_uint64),
+                ("device", C.c_int32), ("stream", C.c_void_p), ("flags", C.c_uint32)]
+
+
 def lib():
     """Load libaugur_hip.so (building it first only if it does not exist)."""
     global _LIB
@@ -86,6 +93,15 @@ def lib():
         L.augur_gmm_get_var.argtypes = [vp, vp]
         L.augur_gmm_set_var.argtypes = [vp, vp]
         L.augur_gmm_get_degenerate.argtypes = [vp, C.POINTER(C.c_int64)]
+        L.augur_mhreg_create.argtypes = [C.POINTER(MhRegConfig), vp, vp, vp, C.POINTER(vp)]
+        L.augur_mhreg_destroy.argtypes = [vp]
+        L.augur_mhreg_destroy.restype = None
+        L.augur_mhreg_run.argtypes = [vp, C.c_int64, vp]
+        L.augur_mhreg_get_state.argtypes = [vp, vp, C.POINTER(C.c_double), C.POINTER(C.c_int64),
+                                            C.POINTER(C.c_int64)]
+        L.augur_mhreg_set_state.argtypes = [vp, vp, C.c_int64]
+        L.augur_mhreg_set_schedule.argtypes = [vp, C.c_int32]
+        L.augur_mhreg_sync.argtypes = [vp]
         _LIB = L
     return _LIB
 
@@ -337,3 +353,57 @@ class GMM:
         c = C.c_int64()
         _check(lib().augur_gmm_get_degenerate(self._h, C.byref(c)))
         return c.value
+
+
+class MHRegression:
+    """augur_mhreg_* handle: random-walk Metropolis-Hastings over theta = (w, b, tau)."""
+
+    def __init__(self, x, y, prior_sd, tau_shape, tau_scale, x_lo, x_hi, step, seed, theta0=None,
+                 device=0, stream=None, device_ptrs=False):
+        self._h = None
+        self._arr = _Arrays(device_ptrs, device)
+        xa = self._arr.input(x, "f32")
+        if xa.ndim != 2:
+            raise ValueError("x must be [N][K]")
+        self.N, self.K = int(xa.shape[0]), int(xa.shape[1])
+        ya = self._arr.input(y, "f32", self.N)
+        ta = self._arr.input(theta0, "f64", self.K + 2)
+        cfg = MhRegConfig(self.N, self.K, float(prior_sd), float(tau_shape), float(tau_scale),
+                          float(x_lo), float(x_hi), float(step), int(seed), int(device),
+                          _stream_handle(stream), PTRS_DEVICE if device_ptrs else 0)
+        h = C.c_void_p()
+        _check(lib().augur_mhreg_create(C.byref(cfg), _ptr(xa), _ptr(ya), _ptr(ta), C.byref(h)))
+        self._h = h
+
+    def close(self):
+        if self._h is not None:
+            lib().augur_mhreg_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:  # interpreter shutdown: the module globals may be gone
+            pass
+
+    def run(self, n, trace=False):
+        tr = self._arr.empty((int(n), self.K + 3), "f64") if trace else None
+        _check(lib().augur_mhreg_run(self._h, int(n), _ptr(tr)))
+        return tr
+
+    def get_state(self):
+        theta = self._arr.empty((self.K + 2,), "f64")
+        lf, si, acc = C.c_double(), C.c_int64(), C.c_int64()
+        _check(lib().augur_mhreg_get_state(self._h, _ptr(theta), C.byref(lf), C.byref(si),
+                                           C.byref(acc)))
+        return theta, lf.value, si.value, acc.value
+
+    def set_state(self, theta=None, step_index=None):
+        ta = self._arr.input(theta, "f64", self.K + 2)
+        _check(lib().augur_mhreg_set_state(self._h, _ptr(ta), -1 if step_index is None else int(step_index)))
+
+    def set_schedule(self, schedule):
+        _check(lib().augur_mhreg_set_schedule(self._h, int(schedule)))
+
+    def sync(self):
+        _check(lib().augur_mhreg_sync(self._h))

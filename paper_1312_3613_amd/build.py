@@ -9,7 +9,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libaugur_hip.so")
-SOURCES = ["api.cpp", "lda.hip", "gmm.hip"]
+SOURCES = ["api.cpp", "lda.hip", "gmm.hip", "mh.hip"]
 HEADERS = ["common.hpp", os.path.join("..", "..", "include", "augur.h")]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")

@@ -52,7 +52,7 @@ struct DeviceGuard {
 // ------------------------------------------------------------ random streams
 enum : uint32_t {
   kStreamInitZ = 0, kStreamZ = 1, kStreamTheta = 2, kStreamPhi = 3, kStreamGmmPi = 4,
-  kStreamGmmMu = 5, kStreamGmmVar = 6
+  kStreamGmmMu = 5, kStreamGmmVar = 6, kStreamMhProposal = 7, kStreamMhAccept = 8
 };
 
 struct U4 { uint32_t x, y, z, w; };
