@@ -8,23 +8,30 @@
 //   w_k ~ N(0, prior_sd^2), b ~ N(0, prior_sd^2), tau ~ InverseGamma(a0, b0),
 //   x_nk ~ Uniform(lo, hi), y_n ~ N(x_n . w + b, tau)      (tau a variance)
 //
-// theta = (w_0 .. w_{K-1}, b, tau) is fp64; x float[N][K] and y float[N] stay
-// in HBM (or LDS, below).  The only data-dependent part of ln f is the sum of
-// squared residuals SSR(w, b); everything else is a handful of scalars.
+// theta = (w_0 .. w_{K-1}, b, tau) is fp64.  The library keeps its own copy of
+// the data, transposed and zero-padded: xt float[K][ld] and y float[ld] (ld = N
+// rounded up to 64), so that a thread reads four consecutive points of every
+// predictor with one 16-byte load, at unit stride across the wave.  The only data-dependent part of ln f is the sum of squared
+// residuals SSR(w, b); everything else is a handful of scalars.
 //
 // SSR has one summation order whatever the launch shape: points are grouped in
-// chunks of 1024; in a chunk, thread j of 256 adds points j, j+256, j+512,
-// j+768 in that order, each wave adds its 64 lanes with an xor butterfly, the
-// four wave sums are added in wave order; the chunk sums are then added the
-// same way (thread j takes chunks j, j+256, ...).
+// chunks of 1024; in a chunk, thread j of 256 adds points 4j, 4j+1, 4j+2,
+// 4j+3 in that order; each wave adds its 64 lanes by wave_sum's fixed tree
+// (pairs, quads, eights and sixteens inside a row of 16 lanes, then the four
+// rows in order); the four wave sums are added in wave order; the chunk sums
+// are then added the same way (thread j takes chunks j, j+256, ...).
 //
 // Two schedules:
 //  * chain kernel (N <= 65536): ONE workgroup of 1024 threads runs all the
-//    requested steps in a single launch; the data sit in LDS (transposed,
-//    conflict-free) when they fit, else they come from L2 every step.  At the
-//    sizes of the paper's regression tables (hundreds to thousands of rows) a
-//    launch per step would cost several times the arithmetic.
-//  * step kernel (any N): one launch per step over min(chunks, 2048) workgroups;
+//    requested steps in a single launch; the data sit in LDS when they fit,
+//    else they come from L2 every step.  The random numbers (they do not
+//    depend on the state) are drawn for a batch of steps at a time by all 1024
+//    threads.  At the sizes of the paper's
+//    regression tables (hundreds to thousands of rows) a launch per step would
+//    cost several times the arithmetic.
+//  * step kernel (any N): one launch per step over min(chunks, 256) workgroups
+//    (one a compute unit: each workgroup pays one device-scope release, a cache
+//    write-back, before its ticket, and that cost grows with their number);
 //    the workgroup that finishes last (a ticket from one device-scope atomic, no
 //    waiting) adds the chunk sums and takes the decision.
 #include "common.hpp"
@@ -40,8 +47,9 @@ namespace {
 constexpr int kChunk = 1024;
 constexpr int kMaxK = 64;
 constexpr int kMaxChainChunks = 64;        // chain kernel: N <= 64 * 1024
-constexpr int kMaxStepBlocks = 2048;
-constexpr size_t kLdsDataBytes = 128 * 1024;  // data cached in LDS up to this size
+constexpr int kMaxStepBlocks = 256;
+constexpr int kStepBatch = 32;            // chunks a workgroup sums between two barriers
+constexpr size_t kLdsDataBytes = 144 * 1024;  // data cached in LDS up to this size (160 KB a CU)
 constexpr double kLn2Pi = 1.8378770664093454835606594728112;
 
 struct MhParams {
@@ -60,55 +68,81 @@ struct MhState {
   unsigned int ticket;
 };
 
-// theta'_e = theta_e + step * n_e: block (index e, step t) of the proposal stream.
-__device__ __forceinline__ double propose_one(const MhParams& p, double theta_e, int e, uint32_t t) {
-  return theta_e + p.step * normal_from(random_block(p.seed, (uint64_t)e, t, kStreamMhProposal, 0));
+// n_e of step t: block (index e, step t) of the proposal stream; theta'_e = theta_e + step n_e.
+__device__ __forceinline__ double proposal_normal(const MhParams& p, int e, uint32_t t) {
+  return normal_from(random_block(p.seed, (uint64_t)e, t, kStreamMhProposal, 0));
+}
+// ln u of the acceptance test of step t.
+__device__ __forceinline__ double accept_log_uniform(const MhParams& p, uint32_t t) {
+  return log(u32d(random_block(p.seed, 0, t, kStreamMhAccept, 0).x));
 }
 
-// Squared residual of point n.  kLds: x is stored [K][ld] and y [ld] in LDS.
-template <bool kLds>
-__device__ __forceinline__ double sq_residual(const float* __restrict__ x, const float* __restrict__ y,
-                                              int64_t n, int K, int64_t ld, const double* th) {
-  double mean = th[K];
-  if (kLds) {
-    for (int k = 0; k < K; ++k) mean += th[k] * (double)x[(int64_t)k * ld + n];
-  } else {
-    for (int k = 0; k < K; ++k) mean += th[k] * (double)x[n * K + k];
-  }
-  const double r = (double)y[n] - mean;
-  return r * r;
+// Sum over the 64 lanes of a wave (all active), the same value in every lane.  Data-parallel
+// primitive moves inside a row of 16 lanes: lane i adds lane i^1, then i^2 (quad permutes),
+// then 7-i of its half row, then 15-i of its row; after each move every lane of the group
+// holds the bit-identical group sum (addition commutes).  The four row sums are then read
+// from lanes 0, 16, 32, 48 and added in that order.
+template <int kCtrl>
+__device__ __forceinline__ double dpp_move(double v) {
+  const long long b = __double_as_longlong(v);
+  const int lo = __builtin_amdgcn_update_dpp(0, (int)b, kCtrl, 0xF, 0xF, false);
+  const int hi = __builtin_amdgcn_update_dpp(0, (int)(b >> 32), kCtrl, 0xF, 0xF, false);
+  return __longlong_as_double(((long long)hi << 32) | (long long)(unsigned int)lo);
+}
+__device__ __forceinline__ double read_lane(double v, int lane) {
+  const long long b = __double_as_longlong(v);
+  const int lo = __builtin_amdgcn_readlane((int)b, lane);
+  const int hi = __builtin_amdgcn_readlane((int)(b >> 32), lane);
+  return __longlong_as_double(((long long)hi << 32) | (long long)(unsigned int)lo);
+}
+__device__ __forceinline__ double wave_sum(double v) {
+  v += dpp_move<0xB1>(v);   // quad_perm [1,0,3,2]
+  v += dpp_move<0x4E>(v);   // quad_perm [2,3,0,1]
+  v += dpp_move<0x141>(v);  // row_half_mirror
+  v += dpp_move<0x140>(v);  // row_mirror
+  return ((read_lane(v, 0) + read_lane(v, 16)) + read_lane(v, 32)) + read_lane(v, 48);
 }
 
 // Sum over one chunk by a group of 256 consecutive threads (four waves); g = index in the
-// group.  Returns the wave's sum in every lane; the caller adds the four waves in order.
-template <bool kLds>
-__device__ __forceinline__ double chunk_wave_sum(const float* __restrict__ x, const float* __restrict__ y,
+// group.  xt is stored [K][ld] and y [ld] (HBM or LDS alike), 16-byte aligned, zero beyond N.
+// Returns the wave's sum in every lane; the caller adds the four waves in order.
+__device__ __forceinline__ double chunk_wave_sum(const float* __restrict__ xt, const float* __restrict__ y,
                                                  int64_t N, int K, int64_t ld, int64_t base,
                                                  const double* th, int g) {
+  const int64_t m = base + 4 * g;
+  const int64_t at = m < ld ? m : base;  // a valid address; the values are dropped below
+  double mean[4];
+  const double b = th[K];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) mean[i] = b;
+#pragma unroll 8
+  for (int k = 0; k < K; ++k) {
+    const float4 v = *reinterpret_cast<const float4*>(xt + (int64_t)k * ld + at);
+    const double w = th[k];
+    mean[0] += w * (double)v.x;
+    mean[1] += w * (double)v.y;
+    mean[2] += w * (double)v.z;
+    mean[3] += w * (double)v.w;
+  }
+  const float4 yv = *reinterpret_cast<const float4*>(y + at);
+  const double r[4] = {(double)yv.x - mean[0], (double)yv.y - mean[1], (double)yv.z - mean[2],
+                       (double)yv.w - mean[3]};
   double s = 0.0;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int64_t n = base + g + 256 * i;
-    if (n < N) s += sq_residual<kLds>(x, y, n, K, ld, th);
-  }
-  return wave_allreduce_sum(s);
+  for (int i = 0; i < 4; ++i) s += m + i < N ? r[i] * r[i] : 0.0;
+  return wave_sum(s);
 }
 
-// ln f at the proposal from its SSR; -inf outside the support of tau.
-__device__ __forceinline__ double logf_from_ssr(const MhParams& p, const double* th, double ssr) {
+// ln f at the proposal from its SSR and ln tau; -inf outside the support of tau.
+__device__ __forceinline__ double logf_from_ssr(const MhParams& p, const double* th, double ln_tau,
+                                                double ssr) {
   const int K = p.K;
   const double tau = th[K + 1];
   if (!(tau > 0.0)) return -INFINITY;
   double sq = 0.0;
   for (int k = 0; k <= K; ++k) sq += th[k] * th[k];
-  const double ln_tau = log(tau);
   return p.ln_prior_const - sq / (2.0 * p.prior_sd * p.prior_sd) - (p.a0 + 1.0) * ln_tau - p.b0 / tau +
          p.ln_x_const - 0.5 * (double)p.N * (kLn2Pi + ln_tau) - ssr / (2.0 * tau);
-}
-
-__device__ __forceinline__ bool accept_test(const MhParams& p, uint32_t t, double lp, double lf) {
-  const double u = u32d(random_block(p.seed, 0, t, kStreamMhAccept, 0).x);
-  return log(u) < lp - lf;
 }
 
 // Adds n chunk sums (LDS or global) in the fixed order; first 256 threads of the block.
@@ -117,7 +151,7 @@ __device__ __forceinline__ double final_sum(const double* part, int n, int tid, 
   double s = 0.0;
   if (tid < 256) {
     for (int c = tid; c < n; c += 256) s += part[c];
-    s = wave_allreduce_sum(s);
+    s = wave_sum(s);
     if ((tid & 63) == 0) smem4[tid >> 6] = s;
   }
   __syncthreads();
@@ -126,123 +160,180 @@ __device__ __forceinline__ double final_sum(const double* part, int n, int tid, 
 
 // ---------------------------------------------------------------- chain kernel
 // One workgroup, all steps.  Thread group q (256 threads) takes chunks q, q+4, ...
+// The last K + 2 threads each own one parameter (in a register).  The normals
+// and ln u of a batch of B = 1024 / (K + 3) steps are drawn by all threads at
+// once into LDS tables.  A step has three phases, with a barrier after each:
+// (1) chunk sums; (2) thread 0 decides; (3) the owners update theta, write the
+// trace row and publish the next proposal (with ln tau', which the otherwise
+// idle owner computes while the next step's chunk sums are under way).
+constexpr int kTableSlots = 1024;
 template <bool kLds>
 __global__ __launch_bounds__(1024) void mhreg_chain_kernel(
-    const float* __restrict__ x, const float* __restrict__ y, MhParams p, MhState* __restrict__ st,
+    const float* __restrict__ xt, const float* __restrict__ y, MhParams p, MhState* __restrict__ st,
     int64_t n_steps, uint32_t first_step, double* __restrict__ trace, int64_t ld) {
-  extern __shared__ __align__(16) float data[];  // kLds: x as [K][ld], then y [ld]
-  __shared__ double th[kMaxK + 2], prop[kMaxK + 2];
+  extern __shared__ __align__(16) float data[];  // kLds: xt [K][ld], then y [ld]
+  __shared__ double prop[kMaxK + 2];
   __shared__ double wsum[16], part[kMaxChainChunks], smem4[4];
-  __shared__ double lf_s;
-  __shared__ unsigned long long acc_s;
+  __shared__ double table[kTableSlots];  // [B][K + 3]: normals of the K + 2 parameters, ln u
+  __shared__ double ln_tau_s;
+  __shared__ int take_s;
   const int tid = threadIdx.x, K = p.K;
   const int q = tid >> 8, g = tid & 255, wave = tid >> 6;
   const int nchunks = (int)((p.N + kChunk - 1) / kChunk);
+  const int e = tid - (1024 - (K + 2));  // parameter owned by this thread, if >= 0
+  const bool owner = e >= 0;
+  const int row = K + 3, B = kTableSlots / row;
+  const int my_step = tid / row, my_item = tid - my_step * row;
+  // draws of steps t0 .. t0 + B - 1
+  auto fill_table = [&](uint32_t t0) {
+    if (my_step < B)
+      table[tid] = my_item < K + 2 ? proposal_normal(p, my_item, t0 + (uint32_t)my_step)
+                                   : accept_log_uniform(p, t0 + (uint32_t)my_step);
+  };
   if (kLds) {
-    for (int64_t e = tid; e < p.N * K; e += 1024) data[(e % K) * ld + e / K] = x[e];
-    for (int64_t n = tid; n < p.N; n += 1024) data[(int64_t)K * ld + n] = y[n];
+    for (int64_t i = tid; i < (int64_t)(K + 1) * ld; i += 1024) data[i] = i < (int64_t)K * ld ? xt[i] : y[i - (int64_t)K * ld];
   }
-  const float* xd = kLds ? data : x;
+  const float* xd = kLds ? data : xt;
   const float* yd = kLds ? data + (int64_t)K * ld : y;
-  if (tid < K + 2) th[tid] = st->theta[tid];
+  fill_table(first_step);
+  __syncthreads();
+  double th_e = 0.0, lf = 0.0;
+  unsigned long long acc = 0;
+  if (owner) {
+    th_e = st->theta[e];
+    const double v = th_e + p.step * table[e];
+    prop[e] = v;
+    if (e == K + 1) ln_tau_s = v > 0.0 ? log(v) : 0.0;
+  }
   if (tid == 0) {
-    lf_s = st->logf;
-    acc_s = st->accepted;
+    lf = st->logf;
+    acc = st->accepted;
   }
   __syncthreads();
   for (int64_t s = 0; s < n_steps; ++s) {
-    const uint32_t t = first_step + (uint32_t)s;
-    if (tid < K + 2) prop[tid] = propose_one(p, th[tid], tid, t);
-    __syncthreads();
+    const int sb = (int)(s % B);  // slot of step s in the table
     const bool in_support = prop[K + 1] > 0.0;
+    // (1) sum of squared residuals at the proposal, valid in thread 0
     double ssr = 0.0;
     if (in_support) {
-      for (int c0 = 0; c0 < nchunks; c0 += 4) {
-        const int c = c0 + q;
-        const double w = c < nchunks
-                             ? chunk_wave_sum<kLds>(xd, yd, p.N, K, ld, (int64_t)c * kChunk, prop, g)
-                             : 0.0;
+      if (nchunks <= 4) {
+        const double w = q < nchunks ? chunk_wave_sum(xd, yd, p.N, K, ld, (int64_t)q * kChunk, prop, g)
+                                     : 0.0;
         if ((tid & 63) == 0) wsum[wave] = w;
         __syncthreads();
-        if (g == 0 && c < nchunks)
-          part[c] = ((wsum[4 * q] + wsum[4 * q + 1]) + wsum[4 * q + 2]) + wsum[4 * q + 3];
-        __syncthreads();
+        if (tid == 0) {
+          // what final_sum gives for up to four chunk sums (absent ones are 0.0): lanes 0..3 of
+          // wave 0 hold them, the quad moves add (c0 + c1) + (c2 + c3), everything else adds 0.0
+          double c[4];
+          for (int i = 0; i < 4; ++i)
+            c[i] = ((wsum[4 * i] + wsum[4 * i + 1]) + wsum[4 * i + 2]) + wsum[4 * i + 3];
+          ssr = (c[0] + c[1]) + (c[2] + c[3]);
+        }
+      } else {
+        for (int c0 = 0; c0 < nchunks; c0 += 4) {
+          const int c = c0 + q;
+          const double w = c < nchunks
+                               ? chunk_wave_sum(xd, yd, p.N, K, ld, (int64_t)c * kChunk, prop, g)
+                               : 0.0;
+          if ((tid & 63) == 0) wsum[wave] = w;
+          __syncthreads();
+          if (g == 0 && c < nchunks)
+            part[c] = ((wsum[4 * q] + wsum[4 * q + 1]) + wsum[4 * q + 2]) + wsum[4 * q + 3];
+          __syncthreads();
+        }
+        ssr = final_sum(part, nchunks, tid, smem4);
       }
-      ssr = final_sum(part, nchunks, tid, smem4);
     }
+    // (2) the decision of step s
     if (tid == 0) {
-      const double lp = in_support ? logf_from_ssr(p, prop, ssr) : -INFINITY;
-      const bool take = accept_test(p, t, lp, lf_s);
+      const double lp = in_support ? logf_from_ssr(p, prop, ln_tau_s, ssr) : -INFINITY;
+      const bool take = table[sb * row + K + 2] < lp - lf;
       if (take) {
-        lf_s = lp;
-        acc_s += 1;
+        lf = lp;
+        acc += 1;
       }
-      wsum[0] = take ? 1.0 : 0.0;
+      take_s = take ? 1 : 0;
     }
     __syncthreads();
-    const bool take = wsum[0] != 0.0;
-    if (tid < K + 2) {
-      if (take) th[tid] = prop[tid];
-      if (trace) trace[s * (K + 3) + tid] = th[tid];
+    if (sb == B - 1) {  // the table is used up: draw the next batch
+      fill_table(first_step + (uint32_t)(s + 1));
+      __syncthreads();
     }
-    if (tid == 0 && trace) trace[s * (K + 3) + K + 2] = lf_s;
+    // (3) new state, trace row, next proposal
+    if (owner) {
+      if (take_s) th_e = prop[e];
+      if (trace) trace[s * (K + 3) + e] = th_e;
+      const double v = th_e + p.step * table[(sb == B - 1 ? 0 : sb + 1) * row + e];
+      prop[e] = v;
+      if (e == K + 1) ln_tau_s = v > 0.0 ? log(v) : 0.0;
+    }
+    if (tid == 0 && trace) trace[s * (K + 3) + K + 2] = lf;
     __syncthreads();
   }
-  if (tid < K + 2) st->theta[tid] = th[tid];
+  if (owner) st->theta[e] = th_e;
   if (tid == 0) {
-    st->logf = lf_s;
-    st->accepted = acc_s;
+    st->logf = lf;
+    st->accepted = acc;
   }
 }
 
 // ----------------------------------------------------------------- step kernel
 // One step.  With decide = false only ln f at st->theta is computed (into st->logf).
-__global__ __launch_bounds__(256) void mhreg_step_kernel(
-    const float* __restrict__ x, const float* __restrict__ y, MhParams p, MhState* __restrict__ st,
-    double* __restrict__ part, uint32_t t, bool decide, double* __restrict__ trace_row) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(6, 8))) void mhreg_step_kernel(
+    const float* __restrict__ xt, const float* __restrict__ y, int64_t ld, MhParams p,
+    MhState* __restrict__ st, double* part, uint32_t t, bool decide,
+    double* __restrict__ trace_row) {
   __shared__ double prop[kMaxK + 2];
-  __shared__ double wsum[4], smem4[4];
+  __shared__ double wsum[kStepBatch][4], smem4[4];
   __shared__ bool last_s;
   const int tid = threadIdx.x, K = p.K;
   const int nchunks = (int)((p.N + kChunk - 1) / kChunk);
-  if (tid < K + 2) prop[tid] = decide ? propose_one(p, st->theta[tid], tid, t) : st->theta[tid];
+  if (tid < K + 2)
+    prop[tid] = decide ? st->theta[tid] + p.step * proposal_normal(p, tid, t) : st->theta[tid];
   __syncthreads();
   const bool in_support = prop[K + 1] > 0.0;
   if (in_support) {
-    for (int c = blockIdx.x; c < nchunks; c += gridDim.x) {
-      const double w = chunk_wave_sum<false>(x, y, p.N, K, 0, (int64_t)c * kChunk, prop, tid);
-      if ((tid & 63) == 0) wsum[tid >> 6] = w;
+    // this workgroup's chunks, kStepBatch at a time; no barrier between the chunks of a batch,
+    // so the waves of a workgroup run ahead of one another and keep loads in flight
+    for (int c0 = blockIdx.x; c0 < nchunks; c0 += kStepBatch * gridDim.x) {
+      int j = 0;
+      for (int c = c0; j < kStepBatch && c < nchunks; ++j, c += gridDim.x) {
+        const double w = chunk_wave_sum(xt, y, p.N, K, ld, (int64_t)c * kChunk, prop, tid);
+        if ((tid & 63) == 0) wsum[j][tid >> 6] = w;
+      }
       __syncthreads();
-      if (tid == 0) part[c] = ((wsum[0] + wsum[1]) + wsum[2]) + wsum[3];
+      if (tid < j)
+        part[c0 + tid * (int)gridDim.x] = ((wsum[tid][0] + wsum[tid][1]) + wsum[tid][2]) + wsum[tid][3];
       __syncthreads();
     }
   }
-  if (tid == 0) {
-    __threadfence();  // this workgroup's chunk sums before its ticket
-    const unsigned int ticket = atomicAdd(&st->ticket, 1u);
-    last_s = ticket == gridDim.x - 1;
-    if (last_s) __threadfence();  // the others' chunk sums after their tickets
+  if (tid < 64) {
+    // the chunk sums above were stored by this wave: release them device-wide (one cache
+    // write-back a workgroup, no invalidate), then take the ticket
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+    if (tid == 0) {
+      const unsigned int ticket = atomicAdd(&st->ticket, 1u);
+      last_s = ticket == gridDim.x - 1;
+    }
   }
   __syncthreads();
   if (!last_s) return;
-  // the workgroup that drew the last ticket: every chunk sum is in memory
-  __shared__ double part_s[256];
+  // The workgroup that drew the last ticket: every other workgroup released its chunk sums
+  // before its ticket.  Acquire (drops stale cache lines; this workgroup only), then ordinary
+  // loads, which unlike atomic ones can all be in flight together.
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
   double s = 0.0;
   if (in_support)
-    for (int c = tid; c < nchunks; c += 256)
-      s += __longlong_as_double((long long)__hip_atomic_load(
-          reinterpret_cast<unsigned long long*>(part) + c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-  part_s[tid] = s;  // thread j holds chunks j, j+256, ... : the fixed order's first level
-  __syncthreads();
-  s = wave_allreduce_sum(part_s[tid]);
+    for (int c = tid; c < nchunks; c += 256) s += part[c];  // chunks j, j+256, ...: first level
+  s = wave_sum(s);
   if ((tid & 63) == 0) smem4[tid >> 6] = s;
   __syncthreads();
   const double ssr = ((smem4[0] + smem4[1]) + smem4[2]) + smem4[3];
   __shared__ bool take_s;
   if (tid == 0) {
-    const double lp = in_support ? logf_from_ssr(p, prop, ssr) : -INFINITY;
+    const double lp = in_support ? logf_from_ssr(p, prop, log(prop[K + 1]), ssr) : -INFINITY;
     if (decide) {
-      take_s = accept_test(p, t, lp, st->logf);
+      take_s = accept_log_uniform(p, t) < lp - st->logf;
       if (take_s) {
         st->logf = lp;
         st->accepted += 1;
@@ -260,6 +351,17 @@ __global__ __launch_bounds__(256) void mhreg_step_kernel(
     if (trace_row) trace_row[tid] = v;
   }
   if (tid == 0 && trace_row) trace_row[K + 2] = st->logf;
+}
+
+// xt[k][n] = x[n][k]; the padding columns n >= N are zero.
+__global__ __launch_bounds__(256) void mhreg_transpose_kernel(const float* __restrict__ x,
+                                                               float* __restrict__ xt, int64_t N,
+                                                               int K, int64_t ld) {
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < (int64_t)K * ld; e += stride) {
+    const int64_t k = e / ld, n = e - k * ld;
+    xt[e] = n < N ? x[n * K + k] : 0.f;
+  }
 }
 
 // Counts values outside [lo, hi] (or not finite) in x and non-finite values in y.
@@ -283,7 +385,8 @@ struct augur_mhreg {
   augur_mhreg_config cfg{};
   hipStream_t stream = nullptr;
   MhParams p{};
-  float *x = nullptr, *y = nullptr;
+  float *xt = nullptr, *y = nullptr;  // xt [K][ld]
+  int64_t ld = 0;
   MhState* st = nullptr;
   double* part = nullptr;
   unsigned long long* bad = nullptr;
@@ -298,7 +401,7 @@ namespace {
 bool device_ptrs(const augur_mhreg* h) { return (h->cfg.flags & AUGUR_PTRS_DEVICE) != 0; }
 
 void free_all(augur_mhreg* h) {
-  (void)hipFree(h->x); (void)hipFree(h->y); (void)hipFree(h->st); (void)hipFree(h->part);
+  (void)hipFree(h->xt); (void)hipFree(h->y); (void)hipFree(h->st); (void)hipFree(h->part);
   (void)hipFree(h->bad);
 }
 
@@ -316,13 +419,13 @@ void free_all(augur_mhreg* h) {
 bool use_chain(const augur_mhreg* h) {
   if (h->schedule == 1) return true;
   if (h->schedule == 2) return false;
-  return h->cfg.N <= 16384;
+  return h->cfg.N <= 4096;
 }
 
 // ln f at the current theta into the state.
 int launch_evaluate(augur_mhreg* h) {
-  hipLaunchKernelGGL(mhreg_step_kernel, dim3(h->step_blocks), dim3(256), 0, h->stream, h->x, h->y,
-                     h->p, h->st, h->part, 0u, false, (double*)nullptr);
+  hipLaunchKernelGGL(mhreg_step_kernel, dim3(h->step_blocks), dim3(256), 0, h->stream, h->xt, h->y,
+                     h->ld, h->p, h->st, h->part, 0u, false, (double*)nullptr);
   AUGUR_HIP_TRY(hipGetLastError());
   return AUGUR_OK;
 }
@@ -331,7 +434,7 @@ int launch_steps(augur_mhreg* h, int64_t n_steps, double* trace_dev) {
   const int K = h->cfg.K;
   const uint32_t first = (uint32_t)(h->step_index + 1);
   if (use_chain(h)) {
-    const int64_t ld = round_up(h->cfg.N, 64);
+    const int64_t ld = h->ld;
     const size_t data_bytes = sizeof(float) * (size_t)ld * (K + 1);
     if (data_bytes <= kLdsDataBytes) {
       if (!h->lds_attr_set) {
@@ -340,17 +443,17 @@ int launch_steps(augur_mhreg* h, int64_t n_steps, double* trace_dev) {
                                           (int)kLdsDataBytes));
         h->lds_attr_set = true;
       }
-      hipLaunchKernelGGL(mhreg_chain_kernel<true>, dim3(1), dim3(1024), data_bytes, h->stream, h->x,
+      hipLaunchKernelGGL(mhreg_chain_kernel<true>, dim3(1), dim3(1024), data_bytes, h->stream, h->xt,
                          h->y, h->p, h->st, n_steps, first, trace_dev, ld);
     } else {
-      hipLaunchKernelGGL(mhreg_chain_kernel<false>, dim3(1), dim3(1024), 0, h->stream, h->x, h->y,
-                         h->p, h->st, n_steps, first, trace_dev, (int64_t)0);
+      hipLaunchKernelGGL(mhreg_chain_kernel<false>, dim3(1), dim3(1024), 0, h->stream, h->xt, h->y,
+                         h->p, h->st, n_steps, first, trace_dev, ld);
     }
     AUGUR_HIP_TRY(hipGetLastError());
   } else {
     for (int64_t s = 0; s < n_steps; ++s) {
-      hipLaunchKernelGGL(mhreg_step_kernel, dim3(h->step_blocks), dim3(256), 0, h->stream, h->x,
-                         h->y, h->p, h->st, h->part, first + (uint32_t)s, true,
+      hipLaunchKernelGGL(mhreg_step_kernel, dim3(h->step_blocks), dim3(256), 0, h->stream, h->xt,
+                         h->y, h->ld, h->p, h->st, h->part, first + (uint32_t)s, true,
                          trace_dev ? trace_dev + s * (K + 3) : (double*)nullptr);
     }
     AUGUR_HIP_TRY(hipGetLastError());
@@ -436,16 +539,40 @@ int augur_mhreg_create(const augur_mhreg_config* cfg, const float* x, const floa
   } while (0)
 
   const hipMemcpyKind in_kind = device_ptrs(h) ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice;
-  AUGUR_CREATE_TRY(hipMalloc(&h->x, sizeof(float) * (size_t)N * K));
-  AUGUR_CREATE_TRY(hipMalloc(&h->y, sizeof(float) * (size_t)N));
+  h->ld = round_up(N, 64);
+  float* x_in = nullptr;  // the caller's layout, on the device; only needed until the transpose
+  if (device_ptrs(h)) {
+    x_in = const_cast<float*>(x);
+  } else {
+    AUGUR_CREATE_TRY(hipMalloc(&x_in, sizeof(float) * (size_t)N * K));
+    hipError_t e_up = hipMemcpyAsync(x_in, x, sizeof(float) * (size_t)N * K, hipMemcpyHostToDevice, h->stream);
+    if (e_up != hipSuccess) {
+      (void)hipFree(x_in);
+      AUGUR_CREATE_TRY(e_up);
+    }
+  }
+  struct StagingGuard {
+    float* p;
+    hipStream_t s;
+    ~StagingGuard() {
+      if (p) {
+        (void)hipStreamSynchronize(s);
+        (void)hipFree(p);
+      }
+    }
+  } staging{device_ptrs(h) ? nullptr : x_in, h->stream};
+  AUGUR_CREATE_TRY(hipMalloc(&h->xt, sizeof(float) * (size_t)h->ld * K));
+  AUGUR_CREATE_TRY(hipMalloc(&h->y, sizeof(float) * (size_t)h->ld));
+  AUGUR_CREATE_TRY(hipMemsetAsync(h->y, 0, sizeof(float) * (size_t)h->ld, h->stream));
   AUGUR_CREATE_TRY(hipMalloc(&h->st, sizeof(MhState)));
   AUGUR_CREATE_TRY(hipMalloc(&h->part, sizeof(double) * (size_t)h->nchunks));
   AUGUR_CREATE_TRY(hipMalloc(&h->bad, sizeof(unsigned long long)));
   AUGUR_CREATE_TRY(hipMemsetAsync(h->st, 0, sizeof(MhState), h->stream));
   AUGUR_CREATE_TRY(hipMemsetAsync(h->bad, 0, sizeof(unsigned long long), h->stream));
-  AUGUR_CREATE_TRY(hipMemcpyAsync(h->x, x, sizeof(float) * (size_t)N * K, in_kind, h->stream));
   AUGUR_CREATE_TRY(hipMemcpyAsync(h->y, y, sizeof(float) * (size_t)N, in_kind, h->stream));
-  hipLaunchKernelGGL(mhreg_check_kernel, dim3(512), dim3(256), 0, h->stream, h->x, h->y, N, K,
+  hipLaunchKernelGGL(mhreg_transpose_kernel, dim3(1024), dim3(256), 0, h->stream, x_in, h->xt, N, K,
+                     h->ld);
+  hipLaunchKernelGGL(mhreg_check_kernel, dim3(512), dim3(256), 0, h->stream, x_in, h->y, N, K,
                      cfg->x_lo, cfg->x_hi, h->bad);
   AUGUR_CREATE_TRY(hipGetLastError());
   unsigned long long bad = 0;
