@@ -86,18 +86,21 @@ int augur_lda_sweep(augur_lda* h, int32_t n_sweeps);
 #define AUGUR_OBSERVE_PHI 1u
 int augur_lda_set_observed(augur_lda* h, uint32_t mask);
 
-/* After the z step the word table n_wk and the pair (document table n_dk, theta
- * step) do not depend on each other.  With overlap on (the default) the word
- * table is built on a second stream of the library's own (default priority)
- * beside the other two; the phi step waits for both.  Results are identical
- * either way.  Not to be changed while a sweep is in flight. */
+/* After the z step the pair (word table n_wk, phi step) and the pair (document
+ * table n_dk, theta step) do not depend on each other (Sect. 4.2: theta and phi
+ * are conditionally independent given z).  With overlap on (the default) the
+ * first pair runs on a second stream of the library's own (default priority)
+ * beside the second; the handle's stream waits for it before the sweep ends.
+ * Results are identical either way.  Not to be changed while a sweep is in
+ * flight. */
 int augur_lda_set_overlap(augur_lda* h, int32_t on);
 
 /* Same as sweep, but records events on the handle's stream around the steps and
  * returns the summed device time over the n_sweeps, in ms: ms[0] sample_z;
- * ms[1] count_accumulate (with overlap on: the document table only, the word
- * table runs beside ms[1] and ms[2]); ms[2] resample theta; ms[3] resample phi
- * (with overlap on: including the wait for the word table); ms[4] whole sweep
+ * ms[1] count_accumulate (with overlap on: the document table only; the word
+ * table and the phi step run beside ms[1] and ms[2]); ms[2] resample theta;
+ * ms[3] resample phi (with overlap on: the wait for the second stream after the
+ * theta step); ms[4] whole sweep
  * (first event to last).  Events are recorded without host waits; the call
  * synchronises once at the end.  n_sweeps <= 4096. */
 #define AUGUR_LDA_NSTEPS 5

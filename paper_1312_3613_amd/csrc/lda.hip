@@ -1131,17 +1131,17 @@ int launch_theta(augur_lda* h, uint32_t sweep) {
   return AUGUR_OK;
 }
 
-int launch_phi(augur_lda* h, uint32_t sweep) {
+int launch_phi(augur_lda* h, uint32_t sweep, hipStream_t stream) {
   const int V = h->cfg.V, K = h->cfg.K;
   const int threads = (int)std::min<int64_t>(256, round_up(K, 64));
-  hipLaunchKernelGGL(lda_phi_draw_kernel, dim3(h->phi_blocks), dim3(threads), 0, h->stream, h->n_wk,
+  hipLaunchKernelGGL(lda_phi_draw_kernel, dim3(h->phi_blocks), dim3(threads), 0, stream, h->n_wk,
                      h->lg, h->col_partial, V, K, h->ldk, h->phi_rows, h->beta, h->shapes_beta, h->cfg.seed, sweep,
                      h->counters + 1);
-  hipLaunchKernelGGL(lda_phi_norm_kernel, dim3(K), dim3(256), 0, h->stream, h->col_partial,
+  hipLaunchKernelGGL(lda_phi_norm_kernel, dim3(K), dim3(256), 0, stream, h->col_partial,
                      h->col_logZ, h->phi_blocks, K);
   const int64_t total = (int64_t)V * h->ldk;
   hipLaunchKernelGGL(lda_phi_write_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0,
-                     h->stream, h->lg, h->col_logZ, h->phi, V, K, h->ldk);
+                     stream, h->lg, h->col_logZ, h->phi, V, K, h->ldk);
   AUGUR_HIP_TRY(hipGetLastError());
   return AUGUR_OK;
 }
@@ -1193,6 +1193,7 @@ int augur_lda_create(const augur_lda_config* cfg, const int32_t* doc_len, const 
   AUGUR_REQUIRE(cfg->D > 0 && cfg->V > 0 && cfg->K > 0, "D, V, K must be positive (got %d, %d, %d)",
                 cfg->D, cfg->V, cfg->K);
   AUGUR_REQUIRE(cfg->K <= 1024, "K = %d is above the supported maximum of 1024 topics", cfg->K);
+  AUGUR_REQUIRE(cfg->V <= (1 << 24), "V = %d is above the supported maximum of 2^24 words", cfg->V);
   AUGUR_REQUIRE((int64_t)cfg->V * round_up(cfg->K, 4) <= (1LL << 30),
                 "V * K = %lld exceeds 2^30 table entries (phi rows are addressed with 32-bit "
                 "byte offsets)", (long long)cfg->V * cfg->K);
@@ -1368,7 +1369,7 @@ int augur_lda_create(const augur_lda_config* cfg, const int32_t* doc_len, const 
   }
   int rc = launch_count(h);
   if (rc == AUGUR_OK) rc = launch_theta(h, 0);
-  if (rc == AUGUR_OK) rc = launch_phi(h, 0);
+  if (rc == AUGUR_OK) rc = launch_phi(h, 0, h->stream);
   if (rc == AUGUR_OK && hipStreamSynchronize(h->stream) != hipSuccess) {
     set_error("initial sweep failed: %s", hipGetErrorString(hipGetLastError()));
     rc = AUGUR_ERR_HIP;
@@ -1407,7 +1408,7 @@ int augur_lda_step_resample_theta(augur_lda* h) {
 }
 int augur_lda_step_resample_phi(augur_lda* h) {
   AUGUR_CHECK_HANDLE(h);
-  return launch_phi(h, (uint32_t)(h->sweep + 1));
+  return launch_phi(h, (uint32_t)(h->sweep + 1), h->stream);
 }
 int augur_lda_step_finish(augur_lda* h) {
   AUGUR_REQUIRE(h != nullptr, "handle is NULL");
@@ -1415,12 +1416,14 @@ int augur_lda_step_finish(augur_lda* h) {
   return AUGUR_OK;
 }
 
-// One sweep with index t.  After the z step the two count tables are independent:
-// the document table feeds the theta step, the word table the phi step.  With
-// overlap on, the word table (bound by 4-byte gathers) is built on a second
-// stream beside the document table and the theta step (bound by fp64 arithmetic);
-// the phi step waits for both.  ev, if given, receives five events on the main
-// stream: before z, after z, after the document counts, after theta, after phi.
+// One sweep with index t.  After the z step the two halves are independent: the
+// document table feeds the theta step, the word table the phi step (Sect. 4.2:
+// theta and phi are conditionally independent given z).  With overlap on, the
+// word table (bound by 4-byte gathers) and the phi step run on a second stream
+// beside the document table and the theta step (bound by fp64 arithmetic); the
+// main stream then waits for the second.  ev, if given, receives five events on
+// the main stream: before z, after z, after the document counts, after theta,
+// after everything.
 static int run_sweep(augur_lda* h, uint32_t t, hipEvent_t* ev) {
 #define AUGUR_MARK(i)                                            \
   if (ev) AUGUR_HIP_TRY(hipEventRecord(ev[i], h->stream))
@@ -1454,11 +1457,12 @@ static int run_sweep(augur_lda* h, uint32_t t, hipEvent_t* ev) {
   AUGUR_TRY(launch_theta(h, t));
   if (h->overlap) {
     AUGUR_TRY(launch_count_words(h, h->side));
+    AUGUR_TRY(launch_phi(h, t, h->side));
     AUGUR_HIP_TRY(hipEventRecord(h->ev_join, h->side));
   }
   AUGUR_MARK(3);
   if (h->overlap) AUGUR_HIP_TRY(hipStreamWaitEvent(h->stream, h->ev_join, 0));
-  AUGUR_TRY(launch_phi(h, t));
+  else AUGUR_TRY(launch_phi(h, t, h->stream));
   AUGUR_MARK(4);
 #undef AUGUR_MARK
   h->sweep += 1;
