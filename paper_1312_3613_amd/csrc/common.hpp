@@ -179,7 +179,18 @@ __device__ __forceinline__ bool gamma_attempt(const GammaShape& g, const U4& b, 
   const double x2 = x * x;
   const double lv = log_pos(fabs(v));  // only used when t > 0 (then v is a positive normal)
   bool accept = U < 1.0 - 0.0331 * x2 * x2;
-  if (!accept) accept = log_pos(U) < 0.5 * x2 + g.d * (1.0 - v + lv);
+  if (!accept) {
+    // ln U < rhs.  A wave reaches this test on most attempts (any lane failing the squeeze
+    // brings all 64 here), so the fp64 logarithm is kept for the cases a single-precision one
+    // cannot decide: that one is good to 1e-6 + 2e-6 |ln U|, and a difference beyond four
+    // times that has the sign of the exact difference.
+    const double rhs = 0.5 * x2 + g.d * (1.0 - v + lv);
+    const float lf = __logf((float)U);
+    const float gap = lf - (float)rhs;
+    const float margin = 4e-6f + 8e-6f * fabsf(lf);
+    accept = gap < -margin;
+    if (__builtin_expect(fabsf(gap) <= margin, 0)) accept = log_pos(U) < rhs;
+  }
   accept = accept && t > 0.0;
   lg = g.ln_d + lv;
   if (g.inv_a > 1.0) lg += log_pos(u32d(b.w)) * g.inv_a;
