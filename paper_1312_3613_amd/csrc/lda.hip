@@ -8,6 +8,7 @@
 //   theta     float[D][ldk]     n_dk int32[D][ldk]
 //   phi       float[V][ldk]     n_wk int32[V][ldk]
 //   perm      int32[N]     token indices sorted by word (built once: w never changes)
+//   zb        uint8[N]     copy of z in one byte a token (K <= 256), for the word table's gathers
 //   word_off  int32[V+1]   start of each word's run in perm
 //   slice_base int32[V+1]  first slice id of each word (a word's run is cut into slices)
 #include "common.hpp"
@@ -319,7 +320,8 @@ void lda_sample_z_quad_kernel(
     const int32_t* __restrict__ w, const int64_t* __restrict__ doc_off,
     const int32_t* __restrict__ seg_base, int n_segs, const float* __restrict__ theta,
     const float* __restrict__ phi, int32_t* __restrict__ z, int32_t* __restrict__ n_dk, int D, int K,
-    int ldk, uint64_t seed, uint32_t sweep, unsigned long long* __restrict__ n_degenerate) {
+    int ldk, uint64_t seed, uint32_t sweep, unsigned long long* __restrict__ n_degenerate,
+    uint8_t* __restrict__ zb) {
   __shared__ uint2 strip_all[4][256];            // {Philox word, word id} per token of the chunk
   __shared__ __align__(16) float theta_all[4][16 * NS16];
   __shared__ int32_t hist_all[kCountDocs ? 4 : 1][kCountDocs ? 16 * NS16 : 1];
@@ -478,6 +480,7 @@ void lda_sample_z_quad_kernel(
       k = min(max(k, 0), K - 1);
       if (T.valid && q == 0) {
         z[T.i] = k;
+        zb[T.i] = (uint8_t)k;  // K <= 256 here
         if (kCountDocs) atomicAdd(&hist[k], 1);
       }
     };
@@ -521,6 +524,10 @@ __global__ __launch_bounds__(256) void lda_count_docs_kernel(
 
 // Words: tokens were sorted by word once (perm).  A word's run of tokens is cut
 // into slices; one wave per slice gathers z through perm into an LDS histogram.
+// The gathers touch a cache line per token.  For K <= 256 they read the one-byte
+// copy of z that the z kernel writes beside z: a quarter of the footprint, which
+// (75 MB at 75M tokens) stays in the 256 MB last-level cache where z itself
+// (300 MB) does not.
 // A word with a single slice stores its row directly; a word with several
 // slices stores one partial row per slice and lda_count_words_merge_kernel adds
 // them.  Every word has at least one slice, so every row is written each sweep.
@@ -533,8 +540,9 @@ __device__ __forceinline__ int word_of_slice(const int32_t* __restrict__ slice_b
   return lo;
 }
 
+template <typename ZT>
 __global__ __launch_bounds__(256) void lda_count_words_kernel(
-    const int32_t* __restrict__ z, const int32_t* __restrict__ perm,
+    const ZT* __restrict__ z, const int32_t* __restrict__ perm,
     const int32_t* __restrict__ word_off, const int32_t* __restrict__ slice_base,
     int32_t* __restrict__ n_wk, int32_t* __restrict__ part, int V, int ldk, int n_slices) {
   extern __shared__ int32_t hist_all[];
@@ -553,13 +561,13 @@ __global__ __launch_bounds__(256) void lda_count_words_kernel(
   int j = start + lane;
   for (; j + 192 < end; j += 256) {  // four gathers in flight per lane
     const int p0 = perm[j], p1 = perm[j + 64], p2 = perm[j + 128], p3 = perm[j + 192];
-    const int z0 = z[p0], z1 = z[p1], z2 = z[p2], z3 = z[p3];
+    const int z0 = (int)z[p0], z1 = (int)z[p1], z2 = (int)z[p2], z3 = (int)z[p3];
     atomicAdd(&hist[z0], 1);
     atomicAdd(&hist[z1], 1);
     atomicAdd(&hist[z2], 1);
     atomicAdd(&hist[z3], 1);
   }
-  for (; j < end; j += 64) atomicAdd(&hist[z[perm[j]]], 1);
+  for (; j < end; j += 64) atomicAdd(&hist[(int)z[perm[j]]], 1);
   wave_lds_fence();
   int32_t* dst = ns == 1 ? n_wk + (size_t)v * ldk : part + (size_t)s * ldk;
   for (int k = lane; k < ldk; k += 64) dst[k] = hist[k];
@@ -933,6 +941,8 @@ struct augur_lda {
   int32_t *w = nullptr, *z = nullptr, *n_dk = nullptr, *n_wk = nullptr;
   int64_t* doc_off = nullptr;
   int32_t *perm = nullptr, *word_off = nullptr, *slice_base = nullptr, *slice_part = nullptr;
+  uint8_t* zb = nullptr;    // z in bytes, written by the z kernel when K <= 256
+  bool zb_current = false;  // zb holds the z of the last z step
   int n_slices = 0;
   int32_t* seg_base = nullptr;  // NULL: every document is one segment
   int n_segs = 0;
@@ -957,6 +967,7 @@ void free_all(augur_lda* h) {
   (void)hipFree(h->doc_off); (void)hipFree(h->theta); (void)hipFree(h->phi); (void)hipFree(h->lg);
   (void)hipFree(h->col_partial); (void)hipFree(h->col_logZ); (void)hipFree(h->red);
   (void)hipFree(h->counters); (void)hipFree(h->perm); (void)hipFree(h->word_off);
+  (void)hipFree(h->zb);
   (void)hipFree(h->slice_base); (void)hipFree(h->slice_part);
   (void)hipFree(h->shapes_alpha); (void)hipFree(h->shapes_beta); (void)hipFree(h->seg_base);
   if (h->side) (void)hipStreamDestroy(h->side);
@@ -987,7 +998,7 @@ int launch_sample_z(augur_lda* h, uint32_t sweep, bool fuse_doc_counts = false,
   }
 #define AUGUR_ZQ_ARGS                                                                          \
   grid, block, 0, h->stream, h->w, h->doc_off, h->seg_base, h->n_segs, h->theta, h->phi, h->z,  \
-      h->n_dk, D, h->cfg.K, h->ldk, h->cfg.seed, sweep, h->counters
+      h->n_dk, D, h->cfg.K, h->ldk, h->cfg.seed, sweep, h->counters, h->zb
 #define AUGUR_Z_ARGS                                                                          \
   grid, block, 0, h->stream, h->w, h->doc_off, h->seg_base, h->n_segs, h->theta, h->phi, h->z, \
       D, h->cfg.K, h->ldk, h->cfg.seed, sweep, h->counters
@@ -1006,7 +1017,9 @@ int launch_sample_z(augur_lda* h, uint32_t sweep, bool fuse_doc_counts = false,
       AUGUR_ZQ_CASE(16)
     }
     if (did_count) *did_count = fuse_doc_counts;
+    h->zb_current = true;
   } else {
+    h->zb_current = false;
     switch (h->ns) {
       AUGUR_Z_CASE(5) AUGUR_Z_CASE(6) AUGUR_Z_CASE(7) AUGUR_Z_CASE(8) AUGUR_Z_CASE(9)
       AUGUR_Z_CASE(10) AUGUR_Z_CASE(11) AUGUR_Z_CASE(12) AUGUR_Z_CASE(13) AUGUR_Z_CASE(14)
@@ -1041,9 +1054,14 @@ int launch_count_docs(augur_lda* h, hipStream_t stream) {
 int launch_count_words(augur_lda* h, hipStream_t stream) {
   const int V = h->cfg.V;
   const size_t shm = sizeof(int32_t) * 4 * (size_t)h->ldk;
-  hipLaunchKernelGGL(lda_count_words_kernel, dim3((h->n_slices + 3) / 4), dim3(256), shm, stream,
-                     h->z, h->perm, h->word_off, h->slice_base, h->n_wk, h->slice_part, V, h->ldk,
-                     h->n_slices);
+  if (h->zb_current)
+    hipLaunchKernelGGL(lda_count_words_kernel<uint8_t>, dim3((h->n_slices + 3) / 4), dim3(256), shm,
+                       stream, h->zb, h->perm, h->word_off, h->slice_base, h->n_wk, h->slice_part, V,
+                       h->ldk, h->n_slices);
+  else
+    hipLaunchKernelGGL(lda_count_words_kernel<int32_t>, dim3((h->n_slices + 3) / 4), dim3(256), shm,
+                       stream, h->z, h->perm, h->word_off, h->slice_base, h->n_wk, h->slice_part, V,
+                       h->ldk, h->n_slices);
   hipLaunchKernelGGL(lda_count_words_merge_kernel, dim3(V), dim3(256), shm, stream, h->slice_base,
                      h->slice_part, h->n_wk, V, h->ldk);
   AUGUR_HIP_TRY(hipGetLastError());
@@ -1289,6 +1307,7 @@ int augur_lda_create(const augur_lda_config* cfg, const int32_t* doc_len, const 
   AUGUR_CREATE_TRY(hipMalloc(&h->w, sizeof(int32_t) * (n_alloc + 256)));
   AUGUR_CREATE_TRY(hipMemsetAsync(h->w, 0, sizeof(int32_t) * (n_alloc + 256), h->stream));
   AUGUR_CREATE_TRY(hipMalloc(&h->z, sizeof(int32_t) * n_alloc));
+  AUGUR_CREATE_TRY(hipMalloc(&h->zb, n_alloc));
   if (h->N > 0)
     AUGUR_CREATE_TRY(hipMemcpyAsync(h->w, w, sizeof(int32_t) * (size_t)h->N,
                                     dev ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice,
@@ -1598,6 +1617,7 @@ int augur_lda_set_state(augur_lda* h, const int32_t* z, const float* theta, cons
     AUGUR_HIP_TRY(hipMemcpyAsync(h->z, z, sizeof(int32_t) * (size_t)h->N,
                                  device_ptrs(h) ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice,
                                  h->stream));
+    h->zb_current = false;  // the word table reads z itself until the next z step
     AUGUR_TRY(launch_count(h));
   }
   if (theta) AUGUR_TRY(copy_in(h, h->theta, theta, sizeof(float), h->cfg.D));
