@@ -709,47 +709,51 @@ __global__ __launch_bounds__(256) void lda_resample_theta_kernel(
 // draws and keeps a running (max, sum) per column per block of rows, pass 2
 // merges the blocks, pass 3 writes exp(lg - L_k).  In pass 1 a thread owns one
 // column of its block of rows and retries on its own variable (see theta).
-__global__ __launch_bounds__(256) void lda_phi_draw_kernel(
+__global__ __launch_bounds__(1024) void lda_phi_draw_kernel(
     const int32_t* __restrict__ n_wk, double* __restrict__ lg, double2* __restrict__ partial, int V,
-    int K, int ldk, int rows_per_block, double beta, const GammaShape* __restrict__ shapes,
-    uint64_t seed, uint32_t sweep, unsigned long long* __restrict__ n_capped) {
-  const int v0 = blockIdx.x * rows_per_block;
-  const int v1 = min(V, v0 + rows_per_block);
+    int K, int ldk, int rows_per_block, int groups, int n_row_blocks, double beta,
+    const GammaShape* __restrict__ shapes, uint64_t seed, uint32_t sweep,
+    unsigned long long* __restrict__ n_capped) {
+  // thread t: column t % K of row block blockIdx.x * groups + t / K.  Several row blocks share
+  // a workgroup so that K need not be a multiple of the wave size to keep the lanes busy.
+  const int gi = (int)threadIdx.x / K;
+  const int k = (int)threadIdx.x - gi * K;
+  const int rb = blockIdx.x * groups + gi;
+  const bool active = gi < groups && rb < n_row_blocks;
+  const int v0 = active ? rb * rows_per_block : 0;
+  const int v1 = active ? min(V, v0 + rows_per_block) : 0;
   bool capped = false;
-  for (int k0 = 0; k0 < K; k0 += blockDim.x) {
-    const int k = k0 + threadIdx.x;
-    int v = k < K ? v0 : v1;
-    double m = -INFINITY, s = 0.0;
-    uint32_t attempt = 0;
-    GammaShape g = gamma_shape_count(shapes, beta, v < v1 ? n_wk[(size_t)v * ldk + k] : 0);
-    while (__any(v < v1)) {
-      if (v < v1) {
-        const size_t e = (size_t)v * ldk + k;
-        double x;
-        bool done = gamma_attempt(
-            g, random_block(seed, (uint64_t)v * (uint64_t)K + (uint64_t)k, sweep, kStreamPhi, attempt),
-            x);
-        if (!done && ++attempt == (uint32_t)kGammaAttemptCap) {
-          done = true;
-          capped = true;
-          x = g.ln_d;
+  int v = v0;
+  double m = -INFINITY, s = 0.0;
+  uint32_t attempt = 0;
+  GammaShape g = gamma_shape_count(shapes, beta, v < v1 ? n_wk[(size_t)v * ldk + k] : 0);
+  while (__any(v < v1)) {
+    if (v < v1) {
+      const size_t e = (size_t)v * ldk + k;
+      double x;
+      bool done = gamma_attempt(
+          g, random_block(seed, (uint64_t)v * (uint64_t)K + (uint64_t)k, sweep, kStreamPhi, attempt),
+          x);
+      if (!done && ++attempt == (uint32_t)kGammaAttemptCap) {
+        done = true;
+        capped = true;
+        x = g.ln_d;
+      }
+      if (done) {
+        lg[e] = x;
+        if (x > m) {
+          s = s * exp(m - x) + 1.0;  // exp(-inf) = 0 on the first row
+          m = x;
+        } else {
+          s += exp(x - m);
         }
-        if (done) {
-          lg[e] = x;
-          if (x > m) {
-            s = s * exp(m - x) + 1.0;  // exp(-inf) = 0 on the first row
-            m = x;
-          } else {
-            s += exp(x - m);
-          }
-          ++v;
-          attempt = 0;
-          if (v < v1) g = gamma_shape_count(shapes, beta, n_wk[(size_t)v * ldk + k]);
-        }
+        ++v;
+        attempt = 0;
+        if (v < v1) g = gamma_shape_count(shapes, beta, n_wk[(size_t)v * ldk + k]);
       }
     }
-    if (k < K) partial[(size_t)blockIdx.x * K + k] = make_double2(m, s);
   }
+  if (active) partial[(size_t)rb * K + k] = make_double2(m, s);
   if (capped) atomicAdd(n_capped, 1ULL);
 }
 
@@ -1151,10 +1155,22 @@ int launch_theta(augur_lda* h, uint32_t sweep) {
 
 int launch_phi(augur_lda* h, uint32_t sweep, hipStream_t stream) {
   const int V = h->cfg.V, K = h->cfg.K;
-  const int threads = (int)std::min<int64_t>(256, round_up(K, 64));
-  hipLaunchKernelGGL(lda_phi_draw_kernel, dim3(h->phi_blocks), dim3(threads), 0, stream, h->n_wk,
-                     h->lg, h->col_partial, V, K, h->ldk, h->phi_rows, h->beta, h->shapes_beta, h->cfg.seed, sweep,
-                     h->counters + 1);
+  // row blocks per workgroup: the count that leaves the fewest idle lanes, in workgroups of at
+  // most 512 threads (a CU holds 16 waves of this kernel: larger workgroups leave it half empty
+  // or drain it between workgroups)
+  int groups = 1;
+  double best = 0.0;
+  for (int g = 1; g == 1 || g * K <= 512; ++g) {
+    const double fill = (double)(g * K) / (double)round_up(g * K, 64);
+    if (fill > best + 1e-9) {
+      best = fill;
+      groups = g;
+    }
+  }
+  const int threads = (int)round_up(groups * K, 64);
+  hipLaunchKernelGGL(lda_phi_draw_kernel, dim3((h->phi_blocks + groups - 1) / groups), dim3(threads),
+                     0, stream, h->n_wk, h->lg, h->col_partial, V, K, h->ldk, h->phi_rows, groups,
+                     h->phi_blocks, h->beta, h->shapes_beta, h->cfg.seed, sweep, h->counters + 1);
   hipLaunchKernelGGL(lda_phi_norm_kernel, dim3(K), dim3(256), 0, stream, h->col_partial,
                      h->col_logZ, h->phi_blocks, K);
   const int64_t total = (int64_t)V * h->ldk;
