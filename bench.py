@@ -21,16 +21,17 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 
 # HBM bytes per sample_z launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by
 # the factors a plain 1 GiB copy shows for the same counters (reads x 2.0, writes x 1.0); the
-# runs and figures are in profiles/lda_large_kernel_trace_and_hbm_traffic.md.  None for workloads
+# runs and figures are in profiles/lda_large_and_medium_kernel_trace_and_hbm_traffic.md.  None for workloads
 # that have not been measured.
-MEASURED_TRAFFIC_BYTES = {"large": (6_977_240 * 2.0 + 702_776 * 1.0) * 1024}
+MEASURED_TRAFFIC_BYTES = {"large": (7_019_700 * 2.0 + 952_184 * 1.0) * 1024}
 
 
 def sample_z_algorithmic_bytes(N, D, K):
     """Per launch: every token reads its word id, its phi row and writes z; every document reads
     its theta row and its two offsets and (K <= 256, where the kernel also builds the document
-    count table) writes its row of n_dk."""
-    return N * (8 + 4 * K) + D * (4 * K + 8) + (D * 4 * K if K <= 256 else 0)
+    count table and the byte copy of z for the word table) writes its row of n_dk and a byte a
+    token."""
+    return N * (8 + 4 * K) + D * (4 * K + 8) + (D * 4 * K + N if K <= 256 else 0)
 
 
 def cpu_baseline(cfg, corpus, budget_s=20.0):
