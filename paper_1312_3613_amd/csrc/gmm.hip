@@ -20,8 +20,11 @@ using namespace augur;
 namespace {
 
 constexpr int kRedBlocks = 512;
-constexpr int kStatChunk = 1024;    // points per block of the statistics kernel, fp32 staging
-constexpr int kStatChunkSq = 512;   // with the sum of squares (fp64 staging)
+// Points per block of the statistics kernel.  Small chunks: a block has only K (dim + 1)
+// working threads, so it takes many resident blocks to fill a CU (measured at 10^6 points,
+// K dim = 128: 88 us with 1024-point chunks).
+constexpr int kStatChunk = 256;     // fp32 staging
+constexpr int kStatChunkSq = 256;   // with the sum of squares (fp64 staging)
 
 __global__ __launch_bounds__(256) void gmm_init_z_kernel(int32_t* __restrict__ z, int64_t N, int K,
                                                           uint64_t seed) {
@@ -345,13 +348,15 @@ int launch_z(augur_gmm* h, uint32_t sweep) {
 
 int launch_stats(augur_gmm* h) {
   const int K = h->cfg.K, dim = h->cfg.dim;
+  // one thread per (component, coordinate) pair; no more waves than that needs
+  const int threads = (int)std::min<int64_t>(256, round_up((int64_t)K * (dim + (h->unknown_var ? 1 : 0)), 64));
   if (h->unknown_var) {
     const size_t shm = sizeof(double) * (size_t)kStatChunkSq * (dim + 1) + sizeof(int32_t) * kStatChunkSq;
-    hipLaunchKernelGGL(gmm_stats_partial_kernel<true>, dim3(h->stat_blocks), dim3(256), shm,
+    hipLaunchKernelGGL(gmm_stats_partial_kernel<true>, dim3(h->stat_blocks), dim3(threads), shm,
                        h->stream, h->x, h->z, h->cfg.N, dim, K, h->part_s, h->part_n);
   } else {
     const size_t shm = sizeof(float) * (size_t)kStatChunk * dim + sizeof(int32_t) * kStatChunk;
-    hipLaunchKernelGGL(gmm_stats_partial_kernel<false>, dim3(h->stat_blocks), dim3(256), shm,
+    hipLaunchKernelGGL(gmm_stats_partial_kernel<false>, dim3(h->stat_blocks), dim3(threads), shm,
                        h->stream, h->x, h->z, h->cfg.N, dim, K, h->part_s, h->part_n);
   }
   const int W = dim + (h->unknown_var ? 1 : 0);
