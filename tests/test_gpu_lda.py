@@ -344,11 +344,12 @@ def test_medium_config_full_parity(B):
     g.close()
 
 
-def test_large_config_sampled_parity(B):
-    """BASELINE's K=200 configuration at full size (about 75M tokens), in the launch configuration
-    bench.py times.  The oracle checks z on ranges of documents it can redo one by one, the count
-    tables in full, theta on sampled ranges and phi in full."""
-    cfg = synth.LDA_CONFIGS["large"]
+@pytest.mark.parametrize("name", ["large", "widek"])
+def test_full_size_config_sampled_parity(B, name):
+    """BASELINE's K=200 (about 75M tokens) and K=1000 (about 10M tokens) configurations at full
+    size, in the launch configuration bench.py times.  The oracle checks z on ranges of documents
+    it can redo one by one, the count tables in full, theta on sampled ranges and phi in full."""
+    cfg = synth.LDA_CONFIGS[name]
     c = synth.lda_corpus(**cfg)
     D, V, K, N = cfg["D"], cfg["V"], cfg["K"], c["N"]
     alpha, beta, seed = float(np.float32(cfg["alpha"])), float(np.float32(cfg["beta"])), cfg["seed"]
@@ -361,7 +362,7 @@ def test_large_config_sampled_parity(B):
     z1 = g.get_state(theta=False, phi=False)[0]
     assert z1.min() >= 0 and z1.max() < K
     checked = 0
-    for d0 in (0, 123_456, D - 1500):
+    for d0 in (0, D // 2 + 3456, D - 1500):
         d1 = d0 + 1500
         sub_off = off[d0:d1 + 1]
         zo = z1.copy()
@@ -383,7 +384,7 @@ def test_large_config_sampled_parity(B):
             P._assert_boundary(cdf, t, int(z1[i]), int(zo[i]), f"token {i}",
                                float(theta[d, z1[i]]) * float(phi[c["w"][i], z1[i]]))
         checked += hi - lo
-    print("large: z checked on", checked, "tokens")
+    print(name, ": z checked on", checked, "tokens")
     # counts: the whole tables against the oracle's nested loops on the GPU's own z
     g.step_count()
     n_dk, n_wk = g.get_counts()
@@ -394,7 +395,7 @@ def test_large_config_sampled_parity(B):
     g.step_resample_theta()
     g.step_resample_phi()
     _, th1, ph1, _ = g.get_state(z=False)
-    for d0 in (0, 200_000, D - 2000):
+    for d0 in (0, 2 * D // 3, D - 2000):
         want = np.zeros((2000, K), dtype=np.float32)
         nd = np.ascontiguousarray(n_dk[d0:d0 + 2000])
         lg_first = d0 * K                         # variable index of entry (d, k) is d*K + k
