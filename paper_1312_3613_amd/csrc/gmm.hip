@@ -87,99 +87,79 @@ __global__ __launch_bounds__(256) void gmm_sample_z_kernel(
   if (i >= N) return;
   const float* xi = x + i * dim;
   double m = -INFINITY;
+  bool has_nan = false;
   for (int k = 0; k < K; ++k) {
     const double l = gmm_logw(xi, mu_s, lw_s, inv2v_s, k, dim);
     if (kCache) col[k * 256] = l;
+    has_nan = has_nan || !(l == l);
     m = l > m ? l : m;
   }
-  double S = 0.0;
-  for (int k = 0; k < K; ++k) {
-    const double p = exp((kCache ? col[k * 256] : gmm_logw(xi, mu_s, lw_s, inv2v_s, k, dim)) - m);
-    if (kCache) col[k * 256] = p;
-    S += p;
-  }
   const U4 blk = random_block(seed, (uint64_t)(i >> 2), sweep, kStreamZ, 0);
   const uint32_t r = word_of(blk, (uint32_t)(i & 3));
   int zi;
-  if (!(S > 0.0) || !(S <= DBL_MAX)) {
-    zi = u24_times(r, K);
-    atomicAdd(n_degenerate, 1ULL);
-  } else {
-    const double t = (double)u24(r) * S;
-    double C = 0.0;
-    int last = 0;
-    zi = -1;
-    for (int k = 0; k < K; ++k) {
-      const double p = kCache ? col[k * 256] : exp(gmm_logw(xi, mu_s, lw_s, inv2v_s, k, dim) - m);
-      const double Cn = C + p;
-      if (Cn > C) last = k;
-      C = Cn;
-      if (zi < 0 && C > t) zi = k;
+  if (kCache && K <= 32) {
+    // Only components within 40 of the largest log-weight get their exponential.  The others
+    // weigh less than e^-40 = 4e-18 of the largest term (which is exactly 1): their sum does not
+    // reach half an ulp of the total, and none of them can be drawn except where u S lies
+    // within that distance of a boundary.  A point typically keeps one to three components, and
+    // each lane walks its own list, so a wave takes as many turns as its busiest lane has
+    // components instead of K.
+    uint32_t live = 0;
+    for (int k = 0; k < K; ++k) live |= col[k * 256] - m > -40.0 ? 1u << k : 0u;
+    double S = has_nan ? NAN : 0.0;
+    for (uint32_t todo = live; __any(todo != 0);) {
+      if (todo != 0) {
+        const int k = __ffs(todo) - 1;
+        todo &= todo - 1;
+        const double p = exp(col[k * 256] - m);
+        col[k * 256] = p;
+        S += p;
+      }
     }
-    if (zi < 0) zi = last;
-  }
-  z[i] = zi;
-}
-
-// The same step for K <= 16: the K log-weights of a point stay in registers (the loops are
-// unrolled over 16 and predicated on k < K), so the kernel needs no LDS column per thread and
-// twice as many waves fit a CU.  Same arithmetic, same draws.
-__global__ __launch_bounds__(256) void gmm_sample_z_small_kernel(
-    const float* __restrict__ x, const float* __restrict__ pi, const float* __restrict__ mu,
-    const float* __restrict__ var, int32_t* __restrict__ z, int64_t N, int dim, int K, double sigma,
-    uint64_t seed, uint32_t sweep, unsigned long long* __restrict__ n_degenerate) {
-  extern __shared__ double sh[];
-  double* mu_s = sh;            // [K][dim]
-  double* lw_s = sh + K * dim;  // [K]
-  double* inv2v_s = lw_s + K;   // [K]
-  for (int e = threadIdx.x; e < K * dim; e += blockDim.x) mu_s[e] = (double)mu[e];
-  for (int k = threadIdx.x; k < K; k += blockDim.x) {
-    const double lp = log((double)pi[k]);
-    if (var != nullptr) {
-      const double v = (double)var[k];
-      lw_s[k] = lp - 0.5 * (double)dim * log(v);
-      inv2v_s[k] = 1.0 / (2.0 * v);
+    if (!(S > 0.0) || !(S <= DBL_MAX)) {
+      zi = u24_times(r, K);
+      atomicAdd(n_degenerate, 1ULL);
     } else {
-      lw_s[k] = lp;
-      inv2v_s[k] = 1.0 / (2.0 * sigma * sigma);
+      const double t = (double)u24(r) * S;
+      double C = 0.0;
+      zi = -1;
+      int last = 0;
+      for (uint32_t todo = live; __any(todo != 0);) {
+        if (todo != 0) {
+          const int k = __ffs(todo) - 1;
+          todo &= todo - 1;
+          const double Cn = C + col[k * 256];
+          if (Cn > C) last = k;
+          C = Cn;
+          if (zi < 0 && C > t) zi = k;
+        }
+      }
+      if (zi < 0) zi = last;
     }
-  }
-  __syncthreads();
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= N) return;
-  const float* xi = x + i * dim;
-  double l[16];
-  double m = -INFINITY;
-#pragma unroll
-  for (int k = 0; k < 16; ++k) {
-    l[k] = k < K ? gmm_logw(xi, mu_s, lw_s, inv2v_s, k, dim) : -INFINITY;
-    m = l[k] > m ? l[k] : m;
-  }
-  double S = 0.0;
-#pragma unroll
-  for (int k = 0; k < 16; ++k) {
-    l[k] = k < K ? exp(l[k] - m) : 0.0;
-    S += l[k];
-  }
-  const U4 blk = random_block(seed, (uint64_t)(i >> 2), sweep, kStreamZ, 0);
-  const uint32_t r = word_of(blk, (uint32_t)(i & 3));
-  int zi;
-  if (!(S > 0.0) || !(S <= DBL_MAX)) {
-    zi = u24_times(r, K);
-    atomicAdd(n_degenerate, 1ULL);
   } else {
-    const double t = (double)u24(r) * S;
-    double C = 0.0;
-    int last = 0;
-    zi = -1;
-#pragma unroll
-    for (int k = 0; k < 16; ++k) {
-      const double Cn = C + l[k];
-      if (Cn > C) last = k;
-      C = Cn;
-      if (zi < 0 && C > t) zi = k;
+    double S = 0.0;
+    for (int k = 0; k < K; ++k) {
+      const double p = exp((kCache ? col[k * 256] : gmm_logw(xi, mu_s, lw_s, inv2v_s, k, dim)) - m);
+      if (kCache) col[k * 256] = p;
+      S += p;
     }
-    if (zi < 0) zi = last;
+    if (!(S > 0.0) || !(S <= DBL_MAX)) {
+      zi = u24_times(r, K);
+      atomicAdd(n_degenerate, 1ULL);
+    } else {
+      const double t = (double)u24(r) * S;
+      double C = 0.0;
+      int last = 0;
+      zi = -1;
+      for (int k = 0; k < K; ++k) {
+        const double p = kCache ? col[k * 256] : exp(gmm_logw(xi, mu_s, lw_s, inv2v_s, k, dim) - m);
+        const double Cn = C + p;
+        if (Cn > C) last = k;
+        C = Cn;
+        if (zi < 0 && C > t) zi = k;
+      }
+      if (zi < 0) zi = last;
+    }
   }
   z[i] = zi;
 }
@@ -397,11 +377,7 @@ int launch_z(augur_gmm* h, uint32_t sweep) {
   const int64_t N = h->cfg.N;
   const size_t base_lds = sizeof(double) * ((size_t)K * dim + 2 * (size_t)K);
   const size_t cache_lds = base_lds + sizeof(double) * 256 * (size_t)K;
-  if (K <= 16)
-    hipLaunchKernelGGL(gmm_sample_z_small_kernel, dim3((unsigned)((N + 255) / 256)), dim3(256),
-                       base_lds, h->stream, h->x, h->pi, h->mu, h->var, h->z, N, dim, K, h->sigma,
-                       h->cfg.seed, sweep, h->counters);
-  else if (cache_lds <= 48 * 1024)
+  if (cache_lds <= 48 * 1024)
     hipLaunchKernelGGL(gmm_sample_z_kernel<true>, dim3((unsigned)((N + 255) / 256)), dim3(256),
                        cache_lds, h->stream, h->x, h->pi, h->mu, h->var, h->z, N, dim, K, h->sigma,
                        h->cfg.seed, sweep, h->counters);
