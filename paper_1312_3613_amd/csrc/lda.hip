@@ -11,6 +11,7 @@
 //   zb        uint8[N]     copy of z in one byte a token (K <= 256), for the word table's gathers
 //   word_off  int32[V+1]   start of each word's run in perm
 //   slice_base int32[V+1]  first slice id of each word (a word's run is cut into slices)
+//   slice_word int32[slices] word of each slice
 #include "common.hpp"
 
 #include <hipcub/hipcub.hpp>
@@ -531,27 +532,29 @@ __global__ __launch_bounds__(256) void lda_count_docs_kernel(
 // A word with a single slice stores its row directly; a word with several
 // slices stores one partial row per slice and lda_count_words_merge_kernel adds
 // them.  Every word has at least one slice, so every row is written each sweep.
-__device__ __forceinline__ int word_of_slice(const int32_t* __restrict__ slice_base, int V, int s) {
-  int lo = 0, hi = V;  // largest v with slice_base[v] <= s
-  while (hi - lo > 1) {
-    const int mid = (lo + hi) >> 1;
-    if (slice_base[mid] <= s) lo = mid; else hi = mid;
-  }
-  return lo;
+// slice_word[s] = word of slice s (a wave looks it up instead of searching slice_base: with
+// one short slice per rare word, 17 dependent loads per wave were most of the kernel's time
+// on small corpora).
+__global__ __launch_bounds__(256) void slice_words_kernel(const int32_t* __restrict__ slice_base,
+                                                           int V, int32_t* __restrict__ slice_word) {
+  const int v = blockIdx.x * blockDim.x + threadIdx.x;
+  if (v >= V) return;
+  for (int s = slice_base[v]; s < slice_base[v + 1]; ++s) slice_word[s] = v;
 }
 
 template <typename ZT>
 __global__ __launch_bounds__(256) void lda_count_words_kernel(
     const ZT* __restrict__ z, const int32_t* __restrict__ perm,
     const int32_t* __restrict__ word_off, const int32_t* __restrict__ slice_base,
-    int32_t* __restrict__ n_wk, int32_t* __restrict__ part, int V, int ldk, int n_slices) {
+    const int32_t* __restrict__ slice_word, int32_t* __restrict__ n_wk, int32_t* __restrict__ part,
+    int V, int ldk, int n_slices) {
   extern __shared__ int32_t hist_all[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int s = blockIdx.x * 4 + wave;
-  if (s >= n_slices) return;
   int32_t* hist = hist_all + (size_t)wave * ldk;
+  for (int s = blockIdx.x * 4 + wave; s < n_slices; s += gridDim.x * 4) {
+  wave_lds_fence();  // the previous slice's row has been read out
   for (int k = lane; k < ldk; k += 64) hist[k] = 0;
-  const int v = word_of_slice(slice_base, V, s);
+  const int v = slice_word[s];
   const int ns = slice_base[v + 1] - slice_base[v];
   const int q = s - slice_base[v];
   const int w0 = word_off[v], w1 = word_off[v + 1];
@@ -571,6 +574,7 @@ __global__ __launch_bounds__(256) void lda_count_words_kernel(
   wave_lds_fence();
   int32_t* dst = ns == 1 ? n_wk + (size_t)v * ldk : part + (size_t)s * ldk;
   for (int k = lane; k < ldk; k += 64) dst[k] = hist[k];
+  }
 }
 
 __global__ __launch_bounds__(256) void lda_count_words_merge_kernel(
@@ -945,6 +949,7 @@ struct augur_lda {
   int32_t *w = nullptr, *z = nullptr, *n_dk = nullptr, *n_wk = nullptr;
   int64_t* doc_off = nullptr;
   int32_t *perm = nullptr, *word_off = nullptr, *slice_base = nullptr, *slice_part = nullptr;
+  int32_t* slice_word = nullptr;
   uint8_t* zb = nullptr;    // z in bytes, written by the z kernel when K <= 256
   bool zb_current = false;  // zb holds the z of the last z step
   int n_slices = 0;
@@ -972,7 +977,7 @@ void free_all(augur_lda* h) {
   (void)hipFree(h->col_partial); (void)hipFree(h->col_logZ); (void)hipFree(h->red);
   (void)hipFree(h->counters); (void)hipFree(h->perm); (void)hipFree(h->word_off);
   (void)hipFree(h->zb);
-  (void)hipFree(h->slice_base); (void)hipFree(h->slice_part);
+  (void)hipFree(h->slice_base); (void)hipFree(h->slice_part); (void)hipFree(h->slice_word);
   (void)hipFree(h->shapes_alpha); (void)hipFree(h->shapes_beta); (void)hipFree(h->seg_base);
   if (h->side) (void)hipStreamDestroy(h->side);
   if (h->ev_fork) (void)hipEventDestroy(h->ev_fork);
@@ -1058,13 +1063,21 @@ int launch_count_docs(augur_lda* h, hipStream_t stream) {
 int launch_count_words(augur_lda* h, hipStream_t stream) {
   const int V = h->cfg.V;
   const size_t shm = sizeof(int32_t) * 4 * (size_t)h->ldk;
+  // One wave per slice when the slices are short (small corpora: the per-slice set-up dominates
+  // and parallelism hides it); 256 workgroups that loop over the slices when they are long.
+  // The kernel then runs beside the theta step (other stream), and the two slow each other
+  // down: with long slices a bounded grid keeps enough gathers in flight and lets the theta
+  // step finish sooner (large workload: sweep 5.06 ms with one wave per slice, 4.92 at 512
+  // workgroups, 4.83 at 256; medium: 0.323 / 0.344 / 0.368 ms).
+  const bool long_slices = h->N / std::max(h->n_slices, 1) >= 256;
+  const int cw_blocks = long_slices ? std::min((h->n_slices + 3) / 4, 256) : (h->n_slices + 3) / 4;
   if (h->zb_current)
-    hipLaunchKernelGGL(lda_count_words_kernel<uint8_t>, dim3((h->n_slices + 3) / 4), dim3(256), shm,
-                       stream, h->zb, h->perm, h->word_off, h->slice_base, h->n_wk, h->slice_part, V,
+    hipLaunchKernelGGL(lda_count_words_kernel<uint8_t>, dim3(cw_blocks), dim3(256), shm,
+                       stream, h->zb, h->perm, h->word_off, h->slice_base, h->slice_word, h->n_wk, h->slice_part, V,
                        h->ldk, h->n_slices);
   else
-    hipLaunchKernelGGL(lda_count_words_kernel<int32_t>, dim3((h->n_slices + 3) / 4), dim3(256), shm,
-                       stream, h->z, h->perm, h->word_off, h->slice_base, h->n_wk, h->slice_part, V,
+    hipLaunchKernelGGL(lda_count_words_kernel<int32_t>, dim3(cw_blocks), dim3(256), shm,
+                       stream, h->z, h->perm, h->word_off, h->slice_base, h->slice_word, h->n_wk, h->slice_part, V,
                        h->ldk, h->n_slices);
   hipLaunchKernelGGL(lda_count_words_merge_kernel, dim3(V), dim3(256), shm, stream, h->slice_base,
                      h->slice_part, h->n_wk, V, h->ldk);
@@ -1132,6 +1145,10 @@ int build_word_major(augur_lda* h) {
     h->n_slices = total;
     if (!check(hipMalloc(&h->slice_part, sizeof(int32_t) * (size_t)total * h->ldk),
                "hipMalloc(slice_part)")) break;
+    if (!check(hipMalloc(&h->slice_word, sizeof(int32_t) * (size_t)std::max(total, 1)),
+               "hipMalloc(slice_word)")) break;
+    hipLaunchKernelGGL(slice_words_kernel, dim3((V + 255) / 256), dim3(256), 0, h->stream,
+                       h->slice_base, V, h->slice_word);
   } while (false);
   (void)hipFree(temp); (void)hipFree(iota); (void)hipFree(sorted_w); (void)hipFree(ns);
   return rc;
@@ -1489,12 +1506,12 @@ static int run_sweep(augur_lda* h, uint32_t t, hipEvent_t* ev) {
     AUGUR_TRY(launch_count_words(h, h->stream));
   }
   AUGUR_MARK(2);
-  AUGUR_TRY(launch_theta(h, t));
   if (h->overlap) {
     AUGUR_TRY(launch_count_words(h, h->side));
     AUGUR_TRY(launch_phi(h, t, h->side));
     AUGUR_HIP_TRY(hipEventRecord(h->ev_join, h->side));
   }
+  AUGUR_TRY(launch_theta(h, t));
   AUGUR_MARK(3);
   if (h->overlap) AUGUR_HIP_TRY(hipStreamWaitEvent(h->stream, h->ev_join, 0));
   else AUGUR_TRY(launch_phi(h, t, h->stream));
