@@ -578,15 +578,14 @@ __global__ __launch_bounds__(256) void lda_count_words_kernel(
 }
 
 __global__ __launch_bounds__(256) void lda_count_words_merge_kernel(
-    const int32_t* __restrict__ slice_base, const int32_t* __restrict__ part,
-    int32_t* __restrict__ n_wk, int V, int ldk) {
-  // one workgroup per word; words with a single slice were stored directly.
-  // Wave g adds slices g, g + 4, ... (four rows in flight per lane); the four
-  // waves' sums meet in LDS.
+    const int32_t* __restrict__ slice_base, const int32_t* __restrict__ multi_words,
+    const int32_t* __restrict__ part, int32_t* __restrict__ n_wk, int ldk) {
+  // one workgroup per word that has several slices (listed in multi_words); words
+  // with a single slice were stored directly.  Wave g adds slices g, g + 4, ...
+  // (four rows in flight per lane); the four waves' sums meet in LDS.
   extern __shared__ int32_t acc[];  // [4][ldk]
-  const int v = blockIdx.x;
+  const int v = multi_words[blockIdx.x];
   const int s0 = slice_base[v], s1 = slice_base[v + 1];
-  if (s1 - s0 == 1) return;
   const int lane = threadIdx.x & 63, g = threadIdx.x >> 6;
   for (int k = lane; k < ldk; k += 64) {
     int32_t c0 = 0, c1 = 0, c2 = 0, c3 = 0;
@@ -762,13 +761,13 @@ __global__ __launch_bounds__(1024) void lda_phi_draw_kernel(
 }
 
 // One block per topic: merge the per-block (max, sum) pairs in a fixed order.
-__global__ __launch_bounds__(256) void lda_phi_norm_kernel(const double2* __restrict__ partial,
-                                                            double* __restrict__ logZ, int nblk,
-                                                            int K) {
-  __shared__ double sm[256], ss[256];
+__global__ __launch_bounds__(1024) void lda_phi_norm_kernel(const double2* __restrict__ partial,
+                                                             double* __restrict__ logZ, int nblk,
+                                                             int K) {
+  __shared__ double sm[1024], ss[1024];
   const int k = blockIdx.x;
   double m = -INFINITY, s = 0.0;
-  for (int b = threadIdx.x; b < nblk; b += 256) {
+  for (int b = threadIdx.x; b < nblk; b += 1024) {
     const double2 p = partial[(size_t)b * K + k];
     if (p.x > m) {
       s = s * exp(m - p.x) + p.y;
@@ -780,7 +779,7 @@ __global__ __launch_bounds__(256) void lda_phi_norm_kernel(const double2* __rest
   sm[threadIdx.x] = m;
   ss[threadIdx.x] = s;
   __syncthreads();
-  for (int o = 128; o > 0; o >>= 1) {
+  for (int o = 512; o > 0; o >>= 1) {
     if ((int)threadIdx.x < o) {
       const double m2 = sm[threadIdx.x + o], s2 = ss[threadIdx.x + o];
       double m1 = sm[threadIdx.x], s1 = ss[threadIdx.x];
@@ -950,6 +949,8 @@ struct augur_lda {
   int64_t* doc_off = nullptr;
   int32_t *perm = nullptr, *word_off = nullptr, *slice_base = nullptr, *slice_part = nullptr;
   int32_t* slice_word = nullptr;
+  int32_t* multi_words = nullptr;  // words with more than one slice
+  int n_multi = 0;
   uint8_t* zb = nullptr;    // z in bytes, written by the z kernel when K <= 256
   bool zb_current = false;  // zb holds the z of the last z step
   int n_slices = 0;
@@ -977,7 +978,7 @@ void free_all(augur_lda* h) {
   (void)hipFree(h->col_partial); (void)hipFree(h->col_logZ); (void)hipFree(h->red);
   (void)hipFree(h->counters); (void)hipFree(h->perm); (void)hipFree(h->word_off);
   (void)hipFree(h->zb);
-  (void)hipFree(h->slice_base); (void)hipFree(h->slice_part); (void)hipFree(h->slice_word);
+  (void)hipFree(h->slice_base); (void)hipFree(h->slice_part); (void)hipFree(h->slice_word); (void)hipFree(h->multi_words);
   (void)hipFree(h->shapes_alpha); (void)hipFree(h->shapes_beta); (void)hipFree(h->seg_base);
   if (h->side) (void)hipStreamDestroy(h->side);
   if (h->ev_fork) (void)hipEventDestroy(h->ev_fork);
@@ -1079,8 +1080,9 @@ int launch_count_words(augur_lda* h, hipStream_t stream) {
     hipLaunchKernelGGL(lda_count_words_kernel<int32_t>, dim3(cw_blocks), dim3(256), shm,
                        stream, h->z, h->perm, h->word_off, h->slice_base, h->slice_word, h->n_wk, h->slice_part, V,
                        h->ldk, h->n_slices);
-  hipLaunchKernelGGL(lda_count_words_merge_kernel, dim3(V), dim3(256), shm, stream, h->slice_base,
-                     h->slice_part, h->n_wk, V, h->ldk);
+  if (h->n_multi > 0)
+    hipLaunchKernelGGL(lda_count_words_merge_kernel, dim3(h->n_multi), dim3(256), shm, stream,
+                       h->slice_base, h->multi_words, h->slice_part, h->n_wk, h->ldk);
   AUGUR_HIP_TRY(hipGetLastError());
   return AUGUR_OK;
 }
@@ -1149,6 +1151,21 @@ int build_word_major(augur_lda* h) {
                "hipMalloc(slice_word)")) break;
     hipLaunchKernelGGL(slice_words_kernel, dim3((V + 255) / 256), dim3(256), 0, h->stream,
                        h->slice_base, V, h->slice_word);
+    {
+      // the few words with several slices, listed on the host (once)
+      std::vector<int32_t> base((size_t)V + 1), multi;
+      if (!check(hipMemcpyAsync(base.data(), h->slice_base, sizeof(int32_t) * base.size(),
+                                hipMemcpyDeviceToHost, h->stream), "hipMemcpyAsync")) break;
+      if (!check(hipStreamSynchronize(h->stream), "hipStreamSynchronize")) break;
+      for (int v = 0; v < V; ++v)
+        if (base[v + 1] - base[v] > 1) multi.push_back(v);
+      h->n_multi = (int)multi.size();
+      if (!check(hipMalloc(&h->multi_words, sizeof(int32_t) * std::max<size_t>(multi.size(), 1)),
+                 "hipMalloc(multi_words)")) break;
+      if (h->n_multi > 0 &&
+          !check(hipMemcpy(h->multi_words, multi.data(), sizeof(int32_t) * multi.size(),
+                           hipMemcpyHostToDevice), "hipMemcpy")) break;
+    }
   } while (false);
   (void)hipFree(temp); (void)hipFree(iota); (void)hipFree(sorted_w); (void)hipFree(ns);
   return rc;
@@ -1188,7 +1205,7 @@ int launch_phi(augur_lda* h, uint32_t sweep, hipStream_t stream) {
   hipLaunchKernelGGL(lda_phi_draw_kernel, dim3((h->phi_blocks + groups - 1) / groups), dim3(threads),
                      0, stream, h->n_wk, h->lg, h->col_partial, V, K, h->ldk, h->phi_rows, groups,
                      h->phi_blocks, h->beta, h->shapes_beta, h->cfg.seed, sweep, h->counters + 1);
-  hipLaunchKernelGGL(lda_phi_norm_kernel, dim3(K), dim3(256), 0, stream, h->col_partial,
+  hipLaunchKernelGGL(lda_phi_norm_kernel, dim3(K), dim3(1024), 0, stream, h->col_partial,
                      h->col_logZ, h->phi_blocks, K);
   const int64_t total = (int64_t)V * h->ldk;
   hipLaunchKernelGGL(lda_phi_write_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0,
