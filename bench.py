@@ -23,7 +23,7 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 # the factors a plain 1 GiB copy shows for the same counters (reads x 2.0, writes x 1.0); the
 # runs and figures are in profiles/lda_large_and_medium_kernel_trace_and_hbm_traffic.md.  None for workloads
 # that have not been measured.
-MEASURED_TRAFFIC_BYTES = {"large": (7_019_700 * 2.0 + 952_184 * 1.0) * 1024,
+MEASURED_TRAFFIC_BYTES = {"large": (7_019_758 * 2.0 + 951_364 * 1.0) * 1024,
                           "medium": (75_082 * 2.0 + 24_701 * 1.0) * 1024}
 
 
