@@ -24,7 +24,7 @@ using namespace augur;
 
 namespace {
 
-constexpr int kRedBlocks = 1024;       // partial sums of the log-likelihood reductions
+constexpr int kRedBlocks = 2048;       // partial sums of the log-likelihood reductions
 constexpr int kPhiRowsMax = 32;  // most rows of the Gamma matrix handled by one block
 
 // ------------------------------------------------------------------ DPP rows
@@ -821,12 +821,12 @@ __global__ __launch_bounds__(256) void lda_loglik_tokens_kernel(
     const int64_t* __restrict__ doc_off, const int32_t* __restrict__ seg_base, int n_segs,
     const float* __restrict__ theta, const float* __restrict__ phi, int D, int ldk,
     double* __restrict__ part_lik, double* __restrict__ part_marg) {
-  extern __shared__ float theta_lds[];  // [4][ldk16], ldk16 = ldk rounded up to 16
+  extern __shared__ double theta_lds[];  // [4][ldk16] as doubles, ldk16 = ldk rounded up to 16
   __shared__ double smem[8];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int tq = lane >> 2, q = lane & 3;
   const int ldk16 = (ldk + 15) & ~15;
-  float* th = theta_lds + (size_t)wave * ldk16;
+  double* th = theta_lds + (size_t)wave * ldk16;
   const int stripes = ldk16 / 16;
   const uint32_t row_bytes = 4u * (uint32_t)ldk;
   const char* phi_bytes = reinterpret_cast<const char*>(phi);
@@ -835,7 +835,7 @@ __global__ __launch_bounds__(256) void lda_loglik_tokens_kernel(
     const Segment sg = segment_of(doc_off, seg_base, D, seg);
     const int d = sg.d;
     wave_lds_fence();
-    for (int k = lane; k < ldk16; k += 64) th[k] = k < ldk ? theta[(size_t)d * ldk + k] : 0.f;
+    for (int k = lane; k < ldk16; k += 64) th[k] = k < ldk ? (double)theta[(size_t)d * ldk + k] : 0.0;
     wave_lds_fence();
     const int64_t a = sg.first > sg.a ? sg.first : sg.a, b = sg.end;
     for (int64_t i0 = a; i0 < b; i0 += 16) {
@@ -843,21 +843,22 @@ __global__ __launch_bounds__(256) void lda_loglik_tokens_kernel(
       const bool valid = i < b;
       const uint32_t row_off = (uint32_t)(valid ? w[i] : 0) * row_bytes;
       double s = 0.0;
+#pragma unroll 4
       for (int c = 0; c < stripes; ++c) {
         const uint32_t off = min(64u * (uint32_t)c + 16u * (uint32_t)q, row_bytes - 16u);
         const float4 y = *reinterpret_cast<const float4*>(phi_bytes + (row_off + off));
-        const float4 x = *reinterpret_cast<const float4*>(th + 16 * c + 4 * q);  // 0 past the row
-        s = fma((double)x.x, (double)y.x, s);
-        s = fma((double)x.y, (double)y.y, s);
-        s = fma((double)x.z, (double)y.z, s);
-        s = fma((double)x.w, (double)y.w, s);
+        const double* x = th + 16 * c + 4 * q;  // 0 past the row
+        s = fma(x[0], (double)y.x, s);
+        s = fma(x[1], (double)y.y, s);
+        s = fma(x[2], (double)y.z, s);
+        s = fma(x[3], (double)y.w, s);
       }
       s += __shfl_xor(s, 1, 64);
       s += __shfl_xor(s, 2, 64);
       if (valid && q == 0) {
         const int zi = z[i];
         marg += log(s);
-        lik += log((double)th[zi]) +
+        lik += log(th[zi]) +
                log((double)*reinterpret_cast<const float*>(phi_bytes + (row_off + 4u * (uint32_t)zi)));
       }
     }
@@ -1605,7 +1606,7 @@ int augur_lda_loglik(augur_lda* h, double* log_joint, double* log_marginal_w) {
   double* p_th = h->red + 2 * kRedBlocks;
   double* p_ph = h->red + 3 * kRedBlocks;
   hipLaunchKernelGGL(lda_loglik_tokens_kernel, dim3(kRedBlocks), dim3(256),
-                     sizeof(float) * 4 * (size_t)((h->ldk + 15) & ~15), h->stream, h->w, h->z,
+                     sizeof(double) * 4 * (size_t)((h->ldk + 15) & ~15), h->stream, h->w, h->z,
                      h->doc_off, h->seg_base, h->n_segs, h->theta, h->phi, D, h->ldk, p_lik, p_marg);
   hipLaunchKernelGGL(sum_log_kernel, dim3(kRedBlocks), dim3(256), 0, h->stream, h->theta,
                      (int64_t)D, K, h->ldk, p_th);
