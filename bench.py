@@ -147,7 +147,11 @@ def main():
         "roofline": {"bound": "hbm", "kernel": "lda_sample_z", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": traffic, "algorithmic_bytes_per_launch": bytes_z,
-                     "avg_launch_ms": t_z * 1e3},
+                     "avg_launch_ms": t_z * 1e3,
+                     # the measured traffic over the same launch time: what actually passes the L2
+                     # (the phi-row gathers are served by L1/L2 three times out of four)
+                     "traffic_GBs": None if traffic is None else traffic / t_z / 1e9,
+                     "traffic_frac": None if traffic is None else traffic / t_z / 1e9 / HBM_PEAK_GBS},
         "kernel_ms_per_sweep": {k: v / steps for k, v in ms.items()},
         "overlap_word_counts_with_theta": not args.no_overlap,
         "log_marginal_per_token": lm / max(N, 1),
