@@ -756,7 +756,7 @@ __global__ __launch_bounds__(1024) void lda_phi_draw_kernel(
       }
     }
   }
-  if (active) partial[(size_t)rb * K + k] = make_double2(m, s);
+  if (active) partial[(size_t)k * n_row_blocks + rb] = make_double2(m, s);  // [K][row blocks]
   if (capped) atomicAdd(n_capped, 1ULL);
 }
 
@@ -768,7 +768,7 @@ __global__ __launch_bounds__(1024) void lda_phi_norm_kernel(const double2* __res
   const int k = blockIdx.x;
   double m = -INFINITY, s = 0.0;
   for (int b = threadIdx.x; b < nblk; b += 1024) {
-    const double2 p = partial[(size_t)b * K + k];
+    const double2 p = partial[(size_t)k * nblk + b];
     if (p.x > m) {
       s = s * exp(m - p.x) + p.y;
       m = p.x;
