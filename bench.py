@@ -1,5 +1,6 @@
 #!/usr/bin/env python3
-"""Benchmark of the LDA Gibbs sweep on one MI355X.
+"""Benchmark of the LDA Gibbs sweep on one MI355X (default), and with --workload gmm of the
+Gaussian-mixture sweep.
 
 A step is one whole sweep (sample_z, count_accumulate, resample theta, resample phi) over a
 synthetic corpus that is already resident in HBM.  Prints ONE JSON line: whole-sweep tokens/s,
@@ -59,12 +60,90 @@ def cpu_baseline(cfg, corpus, budget_s=20.0):
                       f"and K={cfg['K']}, {sweeps} whole sweeps, single thread of {os.cpu_count()} visible"}
 
 
+FP64_VECTOR_PEAK_TFLOPS = 78.6  # MI355X published fp64 vector peak
+
+
+def gmm_z_flops(N, dim, K):
+    """Floating-point operations the z step of the mixture needs per launch, counted on the
+    formulas: per (point, component) dim subtractions and dim multiply-adds (2 dim) for the
+    distance plus 2 for the log-weight, one exponential counted as 1, and 2 for the running sums;
+    (3 dim + 5) K per point.  What the exponential really costs in instructions is not counted."""
+    return N * K * (3 * dim + 5)
+
+
+def bench_gmm(args, unknown_var):
+    """One step = one sweep of the Gaussian mixture (z, statistics, weights, means[, variances])
+    over the BASELINE configuration's point cloud, resident in HBM."""
+    import numpy as np
+    import torch
+    from paper_1312_3613_amd import binding as B, synth
+    cfg = synth.GMM_CONFIG
+    steps = args.steps if args.steps is not None else cfg["sweeps"]
+    t0 = time.perf_counter()
+    d = synth.gmm_points(**cfg)
+    t_gen = time.perf_counter() - t0
+    N, dim, K = cfg["N"], cfg["dim"], cfg["K"]
+    torch.cuda.set_device(0)
+    stream = torch.cuda.Stream()
+    x = torch.as_tensor(d["x"]).cuda()
+    torch.cuda.synchronize()
+    kw = dict(var_shape=1.0, var_scale=1.0) if unknown_var else {}
+    h = B.GMM(K, cfg["alpha"], cfg["prior_sd"], cfg["sigma"], cfg["seed"], x, stream=stream,
+              device_ptrs=True, **kw)
+    h.sweep(args.warmup)
+    h.sync()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ms = h.sweep_profile(steps)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    lj = h.loglik()
+    h.close()
+    t_z = ms["sample_z"] / steps * 1e-3
+    flops = gmm_z_flops(N, dim, K)
+    achieved = flops / t_z / 1e12
+    out = {
+        "metric": "Gibbs sweep points/sec (Gaussian mixture N=1e6, R^8, K=16)",
+        "value": N * steps / elapsed, "unit": "points/s", "n_gpus": 1, "steps": steps,
+        "warmup": args.warmup, "ms_per_step": elapsed / steps * 1e3, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+        "config": {"workload": f"GMM: N={N} dim={dim} K={K} alpha={cfg['alpha']} prior_sd={cfg['prior_sd']} "
+                               + ("variances unknown, InverseGamma(1,1)" if unknown_var else f"sigma={cfg['sigma']}")
+                               + f", points from the mixture's generative process (seed {cfg['seed']}), resident in HBM"},
+        "roofline": {"bound": "alu", "kernel": "gmm_sample_z", "achieved": achieved,
+                     "peak": FP64_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / FP64_VECTOR_PEAK_TFLOPS, "traffic": None,
+                     "algorithmic_flops_per_launch": flops, "avg_launch_ms": t_z * 1e3},
+        "kernel_ms_per_sweep": {k: v / steps for k, v in ms.items()},
+        "log_joint_per_point": lj / N,
+        "setup_s": {"generate_points": t_gen},
+    }
+    if not args.no_cpu_baseline:
+        from oracle import oracle as O
+        n = 200_000
+        xs = d["x"][:n]
+        o = (O.OracleGMMUV(K, cfg["alpha"], cfg["prior_sd"], 1.0, 1.0, cfg["seed"], xs) if unknown_var
+             else O.OracleGMM(K, cfg["alpha"], cfg["prior_sd"], cfg["sigma"], cfg["seed"], xs))
+        sweeps, t0 = 0, time.perf_counter()
+        while True:
+            o.sweep(1)
+            sweeps += 1
+            el = time.perf_counter() - t0
+            if sweeps >= 2 and (el > 10.0 or sweeps >= 20):
+                break
+        out["cpu_baseline"] = {"value": n * sweeps / el, "unit": "points/s", "cores": 1, "kind": "oracle",
+                               "sample": f"first {n} points of the same cloud, {sweeps} whole sweeps, "
+                                         f"single thread of {os.cpu_count()} visible"}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="large", choices=["tiny", "medium", "large", "widek", "paper_shape"])
+    ap.add_argument("--workload", default="large",
+                    choices=["tiny", "medium", "large", "widek", "paper_shape", "gmm", "gmm_unknown_variance"])
     ap.add_argument("--topics", type=int, default=None,
                     help="infer with this many topics instead of the number the corpus was drawn with")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -78,6 +157,10 @@ def main():
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)",
               file=sys.stderr)
         sys.exit(2)
+
+    if args.workload.startswith("gmm"):
+        bench_gmm(args, args.workload == "gmm_unknown_variance")
+        return
 
     import numpy as np
     import torch

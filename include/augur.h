@@ -164,6 +164,11 @@ void augur_gmm_destroy(augur_gmm* h);
  * mean.  The initial state (sweep index 0) has var_k = var_scale / var_shape
  * before its first draw. */
 int augur_gmm_sweep(augur_gmm* h, int32_t n_sweeps);
+/* Same as sweep, with events on the handle's stream around the steps; summed device time over
+ * the n_sweeps in ms: ms[0] z step, ms[1] statistics, ms[2] resampling, ms[3] whole sweep.
+ * Synchronises once at the end.  n_sweeps <= 4096. */
+#define AUGUR_GMM_NSTEPS 4
+int augur_gmm_sweep_profile(augur_gmm* h, int32_t n_sweeps, double* ms);
 int augur_gmm_step_sample_z(augur_gmm* h);
 int augur_gmm_step_stats(augur_gmm* h);
 int augur_gmm_step_resample(augur_gmm* h);

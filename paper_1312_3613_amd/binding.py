@@ -84,6 +84,7 @@ def lib():
         L.augur_gmm_destroy.argtypes = [vp]
         L.augur_gmm_destroy.restype = None
         L.augur_gmm_sweep.argtypes = [vp, C.c_int32]
+        L.augur_gmm_sweep_profile.argtypes = [vp, C.c_int32, C.POINTER(C.c_double)]
         for name in ("step_sample_z", "step_stats", "step_resample", "step_finish", "sync"):
             getattr(L, "augur_gmm_" + name).argtypes = [vp]
         L.augur_gmm_loglik.argtypes = [vp, C.POINTER(C.c_double)]
@@ -301,6 +302,11 @@ class GMM:
 
     def step_sample_z(self):
         _check(lib().augur_gmm_step_sample_z(self._h))
+
+    def sweep_profile(self, n=1):
+        ms = (C.c_double * 4)()
+        _check(lib().augur_gmm_sweep_profile(self._h, int(n), ms))
+        return dict(zip(("sample_z", "stats", "resample", "sweep"), list(ms)))
 
     def step_stats(self):
         _check(lib().augur_gmm_step_stats(self._h))

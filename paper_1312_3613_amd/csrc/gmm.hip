@@ -576,6 +576,56 @@ int augur_gmm_sweep(augur_gmm* h, int32_t n_sweeps) {
   return AUGUR_OK;
 }
 
+int augur_gmm_sweep_profile(augur_gmm* h, int32_t n_sweeps, double* ms) {
+  AUGUR_CHECK_HANDLE(h);
+  AUGUR_REQUIRE(n_sweeps >= 0 && n_sweeps <= 4096 && ms != nullptr,
+                "n_sweeps must lie in [0, 4096] and ms must not be NULL");
+  for (int i = 0; i < AUGUR_GMM_NSTEPS; ++i) ms[i] = 0.0;
+  // four events per sweep, recorded without a host wait; read back at the end
+  std::vector<hipEvent_t> ev((size_t)n_sweeps * 4, nullptr);
+  int rc = AUGUR_OK;
+  auto fail_hip = [&](hipError_t e, const char* what) {
+    if (e != hipSuccess && rc == AUGUR_OK) {
+      set_error("%s failed: %s", what, hipGetErrorString(e));
+      rc = AUGUR_ERR_HIP;
+    }
+    return e != hipSuccess;
+  };
+  for (auto& e : ev)
+    if (fail_hip(hipEventCreate(&e), "hipEventCreate")) break;
+  int done = 0;
+  for (int32_t s = 0; s < n_sweeps && rc == AUGUR_OK; ++s) {
+    hipEvent_t* e = &ev[(size_t)s * 4];
+    const uint32_t t = (uint32_t)(h->sweep + 1);
+    if (fail_hip(hipEventRecord(e[0], h->stream), "hipEventRecord")) break;
+    rc = launch_z(h, t);
+    if (rc == AUGUR_OK && fail_hip(hipEventRecord(e[1], h->stream), "hipEventRecord")) break;
+    if (rc == AUGUR_OK) rc = launch_stats(h);
+    if (rc == AUGUR_OK && fail_hip(hipEventRecord(e[2], h->stream), "hipEventRecord")) break;
+    if (rc == AUGUR_OK) rc = launch_resample(h, t);
+    if (rc == AUGUR_OK && fail_hip(hipEventRecord(e[3], h->stream), "hipEventRecord")) break;
+    if (rc == AUGUR_OK) {
+      h->sweep += 1;
+      ++done;
+    }
+  }
+  fail_hip(hipStreamSynchronize(h->stream), "hipStreamSynchronize");
+  for (int s = 0; s < done && rc == AUGUR_OK; ++s) {
+    hipEvent_t* e = &ev[(size_t)s * 4];
+    for (int i = 0; i < 3; ++i) {
+      float x = 0.f;
+      if (fail_hip(hipEventElapsedTime(&x, e[i], e[i + 1]), "hipEventElapsedTime")) break;
+      ms[i] += (double)x;
+    }
+    float x = 0.f;
+    if (fail_hip(hipEventElapsedTime(&x, e[0], e[3]), "hipEventElapsedTime")) break;
+    ms[3] += (double)x;
+  }
+  for (auto& e : ev)
+    if (e) (void)hipEventDestroy(e);
+  return rc;
+}
+
 int augur_gmm_loglik(augur_gmm* h, double* log_joint) {
   AUGUR_CHECK_HANDLE(h);
   AUGUR_REQUIRE(log_joint != nullptr, "log_joint is NULL");
