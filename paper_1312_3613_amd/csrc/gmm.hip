@@ -207,8 +207,75 @@ __global__ __launch_bounds__(256) void gmm_stats_partial_kernel(
       s += mine ? (double)xs[e * W + j] : 0.0;
       c += mine ? 1 : 0;
     }
-    part_s[(size_t)blockIdx.x * K * W + pair] = s;
-    if (j == 0) part_n[(size_t)blockIdx.x * K + k] = c;
+    part_s[(size_t)pair * gridDim.x + blockIdx.x] = s;  // [pair][block]: the merge reads rows
+    if (j == 0) part_n[(size_t)k * gridDim.x + blockIdx.x] = c;
+  }
+}
+
+// The same partial sums for K <= 64 without walking the whole chunk per component: the
+// chunk's points are first grouped by component, in index order (a stable counting sort: per
+// wave one ballot per component gives every point its rank among the wave's points of that
+// component; the four waves' counts are then prefixed), and thread (k, j) adds only the points
+// of its component, in the same order as the walk above, so the sums are bit-identical.
+// 256 threads, one per point of the chunk.
+template <bool kSumSq>
+__global__ __launch_bounds__(256) void gmm_stats_grouped_kernel(
+    const float* __restrict__ x, const int32_t* __restrict__ z, int64_t N, int dim, int K,
+    double* __restrict__ part_s, int32_t* __restrict__ part_n) {
+  using T = typename std::conditional<kSumSq, double, float>::type;
+  extern __shared__ __align__(8) unsigned char raw[];
+  constexpr int kChunk = 256;
+  const int W = dim + (kSumSq ? 1 : 0);
+  T* xs = reinterpret_cast<T*>(raw);  // [chunk][W]
+  __shared__ uint16_t order[kChunk];  // points grouped by component, index order inside a group
+  __shared__ int32_t cnt[4][64];      // per wave: points of each component
+  __shared__ int32_t first[65];       // start of each component's group in order[]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int64_t p0 = (int64_t)blockIdx.x * kChunk;
+  const int n = (int)std::min<int64_t>(kChunk, N - p0);
+  if (kSumSq) {
+    if (tid < n) {
+      double q = 0.0;
+      for (int j = 0; j < dim; ++j) {
+        const double v = (double)x[(p0 + tid) * dim + j];
+        xs[tid * W + j] = (T)v;
+        q += v * v;
+      }
+      xs[tid * W + dim] = (T)q;
+    }
+  } else {
+    for (int e = tid; e < n * dim; e += 256) xs[e] = (T)x[p0 * dim + e];
+  }
+  const int zi = tid < n ? z[p0 + tid] : -1;
+  int rank = 0;
+  for (int k = 0; k < K; ++k) {
+    const unsigned long long m = __ballot(zi == k);
+    if (zi == k) rank = __popcll(m & ((1ULL << lane) - 1ULL));
+    if (lane == 0) cnt[wave][k] = __popcll(m);
+  }
+  __syncthreads();
+  if (tid == 0) {
+    int run = 0;
+    for (int k = 0; k < K; ++k) {
+      first[k] = run;
+      run += cnt[0][k] + cnt[1][k] + cnt[2][k] + cnt[3][k];
+    }
+    first[K] = run;
+  }
+  __syncthreads();
+  if (zi >= 0) {
+    int at = first[zi] + rank;
+    for (int w = 0; w < wave; ++w) at += cnt[w][zi];
+    order[at] = (uint16_t)tid;
+  }
+  __syncthreads();
+  for (int pair = tid; pair < K * W; pair += 256) {
+    const int k = pair / W, j = pair - k * W;
+    const int e0 = first[k], e1 = first[k + 1];
+    double s = 0.0;
+    for (int e = e0; e < e1; ++e) s += (double)xs[(int)order[e] * W + j];
+    part_s[(size_t)pair * gridDim.x + blockIdx.x] = s;  // [pair][block]: the merge reads rows
+    if (j == 0) part_n[(size_t)k * gridDim.x + blockIdx.x] = e1 - e0;
   }
 }
 
@@ -227,8 +294,8 @@ __global__ __launch_bounds__(256) void gmm_stats_merge_kernel(const double* __re
   double s = 0.0;
   int32_t c = 0;
   for (int b = threadIdx.x; b < nblk; b += 256) {
-    s += part_s[(size_t)b * K * W + pair];
-    if (count) c += part_n[(size_t)b * K + k];
+    s += part_s[(size_t)pair * nblk + b];
+    if (count) c += part_n[(size_t)k * nblk + b];
   }
   ss[threadIdx.x] = s;
   sn[threadIdx.x] = c;
@@ -393,7 +460,16 @@ int launch_stats(augur_gmm* h) {
   const int K = h->cfg.K, dim = h->cfg.dim;
   // one thread per (component, coordinate) pair; no more waves than that needs
   const int threads = (int)std::min<int64_t>(256, round_up((int64_t)K * (dim + (h->unknown_var ? 1 : 0)), 64));
-  if (h->unknown_var) {
+  if (K <= 64 && kStatChunk == 256 && kStatChunkSq == 256) {
+    if (h->unknown_var)
+      hipLaunchKernelGGL(gmm_stats_grouped_kernel<true>, dim3(h->stat_blocks), dim3(256),
+                         sizeof(double) * 256 * (size_t)(dim + 1), h->stream, h->x, h->z, h->cfg.N,
+                         dim, K, h->part_s, h->part_n);
+    else
+      hipLaunchKernelGGL(gmm_stats_grouped_kernel<false>, dim3(h->stat_blocks), dim3(256),
+                         sizeof(float) * 256 * (size_t)dim, h->stream, h->x, h->z, h->cfg.N, dim, K,
+                         h->part_s, h->part_n);
+  } else if (h->unknown_var) {
     const size_t shm = sizeof(double) * (size_t)kStatChunkSq * (dim + 1) + sizeof(int32_t) * kStatChunkSq;
     hipLaunchKernelGGL(gmm_stats_partial_kernel<true>, dim3(h->stat_blocks), dim3(threads), shm,
                        h->stream, h->x, h->z, h->cfg.N, dim, K, h->part_s, h->part_n);
