@@ -41,13 +41,35 @@ __global__ __launch_bounds__(256) void gmm_init_z_kernel(int32_t* __restrict__ z
 // ln pi_k - (dim/2) ln v_k - |x - mu_k|^2 / (2 v_k) for one point; mu, the
 // constant part lw_k and 1/(2 v_k) in LDS.  With the variance known the
 // (dim/2) ln v term is the same for every k and left out.
-__device__ __forceinline__ double gmm_logw(const float* __restrict__ xi, const double* mu_s,
+// DIM > 0: the dimension is known at compile time and the point is held in registers as
+// doubles (converted once, not once per component); DIM == 0: any dimension, read from memory.
+template <int DIM>
+struct PointOf {
+  double v[DIM > 0 ? DIM : 1];
+  const float* p;
+  __device__ __forceinline__ explicit PointOf(const float* __restrict__ xi) : p(xi) {
+    if (DIM > 0) {
+#pragma unroll
+      for (int j = 0; j < DIM; ++j) v[j] = (double)xi[j];
+    }
+  }
+};
+template <int DIM>
+__device__ __forceinline__ double gmm_logw(const PointOf<DIM>& x, const double* mu_s,
                                            const double* lw_s, const double* inv2v_s, int k,
                                            int dim) {
   double q = 0.0;
-  for (int j = 0; j < dim; ++j) {
-    const double df = (double)xi[j] - mu_s[k * dim + j];
-    q += df * df;
+  if (DIM > 0) {
+#pragma unroll
+    for (int j = 0; j < DIM; ++j) {
+      const double df = x.v[j] - mu_s[k * DIM + j];
+      q += df * df;
+    }
+  } else {
+    for (int j = 0; j < dim; ++j) {
+      const double df = (double)x.p[j] - mu_s[k * dim + j];
+      q += df * df;
+    }
   }
   return lw_s[k] - q * inv2v_s[k];
 }
@@ -60,7 +82,7 @@ __device__ __forceinline__ double gmm_logw(const float* __restrict__ xi, const d
 // search); without it (K too large for LDS) they are recomputed.  Thread t of a
 // group of four computes the Philox block shared by points 4b..4b+3
 // redundantly (cheap at this size).
-template <bool kCache>
+template <bool kCache, int DIM>
 __global__ __launch_bounds__(256) void gmm_sample_z_kernel(
     const float* __restrict__ x, const float* __restrict__ pi, const float* __restrict__ mu,
     const float* __restrict__ var, int32_t* __restrict__ z, int64_t N, int dim, int K, double sigma,
@@ -85,7 +107,7 @@ __global__ __launch_bounds__(256) void gmm_sample_z_kernel(
   __syncthreads();
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= N) return;
-  const float* xi = x + i * dim;
+  const PointOf<DIM> xi(x + i * dim);
   double m = -INFINITY;
   bool has_nan = false;
   for (int k = 0; k < K; ++k) {
@@ -444,14 +466,23 @@ int launch_z(augur_gmm* h, uint32_t sweep) {
   const int64_t N = h->cfg.N;
   const size_t base_lds = sizeof(double) * ((size_t)K * dim + 2 * (size_t)K);
   const size_t cache_lds = base_lds + sizeof(double) * 256 * (size_t)K;
-  if (cache_lds <= 48 * 1024)
-    hipLaunchKernelGGL(gmm_sample_z_kernel<true>, dim3((unsigned)((N + 255) / 256)), dim3(256),
-                       cache_lds, h->stream, h->x, h->pi, h->mu, h->var, h->z, N, dim, K, h->sigma,
-                       h->cfg.seed, sweep, h->counters);
-  else
-    hipLaunchKernelGGL(gmm_sample_z_kernel<false>, dim3((unsigned)((N + 255) / 256)), dim3(256),
-                       base_lds, h->stream, h->x, h->pi, h->mu, h->var, h->z, N, dim, K, h->sigma,
-                       h->cfg.seed, sweep, h->counters);
+#define AUGUR_GMM_Z(CACHE, DIMV, LDS)                                                          \
+  hipLaunchKernelGGL((gmm_sample_z_kernel<CACHE, DIMV>), dim3((unsigned)((N + 255) / 256)),       \
+                     dim3(256), LDS, h->stream, h->x, h->pi, h->mu, h->var, h->z, N, dim, K,      \
+                     h->sigma, h->cfg.seed, sweep, h->counters)
+  if (cache_lds <= 48 * 1024) {
+    switch (dim) {
+      case 1: AUGUR_GMM_Z(true, 1, cache_lds); break;
+      case 2: AUGUR_GMM_Z(true, 2, cache_lds); break;
+      case 3: AUGUR_GMM_Z(true, 3, cache_lds); break;
+      case 4: AUGUR_GMM_Z(true, 4, cache_lds); break;
+      case 8: AUGUR_GMM_Z(true, 8, cache_lds); break;
+      default: AUGUR_GMM_Z(true, 0, cache_lds); break;
+    }
+  } else {
+    AUGUR_GMM_Z(false, 0, base_lds);
+  }
+#undef AUGUR_GMM_Z
   AUGUR_HIP_TRY(hipGetLastError());
   return AUGUR_OK;
 }
