@@ -54,6 +54,36 @@ def test_gamma_boost_uses_shape_plus_one():
     assert abs(lg[0] - (lg1[0] + np.log(O.uniform32(blk[3])) / a)) < 1e-12
 
 
+def test_squeeze_never_changes_a_draw():
+    # The squeeze U < 1 - 0.0331 x^4 is only a shortcut: it lies inside the region of the exact
+    # test (Marsaglia & Tsang 2000, Sect. 4), so a sampler that applies the exact test alone to
+    # the same random blocks must accept at the same attempt and return the same value.
+    n, seed, sweep = 4000, 21, 3
+    for a in (0.02, 0.6, 1.0, 7.5, 300.0):
+        lg, att, capped = O.gamma_log_draws(np.full(n, a), seed, 0, sweep, O.STREAM_THETA,
+                                            return_attempts=True)
+        assert capped == 0
+        a1 = a + 1.0 if a < 1.0 else a
+        d = a1 - 1.0 / 3.0
+        c = 1.0 / np.sqrt(9.0 * d)
+        squeeze_hits = 0
+        for i in range(n):
+            for j in range(64):
+                r = O.random_block(seed, i, sweep, O.STREAM_THETA, j)
+                x = np.sqrt(-2.0 * np.log(O.uniform32(r[0]))) * np.cos(2.0 * np.pi * O.uniform32(r[1]))
+                t = 1.0 + c * x
+                if t <= 0.0:
+                    continue
+                v, U = t ** 3, O.uniform32(r[2])
+                squeeze_hits += U < 1.0 - 0.0331 * x ** 4
+                if np.log(U) < 0.5 * x * x + d * (1.0 - v + np.log(v)):
+                    break
+            want = np.log(d) + np.log(v) + (np.log(O.uniform32(r[3])) / a if a < 1.0 else 0.0)
+            assert att[i] == j + 1, (a, i)
+            assert abs(lg[i] - want) <= 1e-12 * max(1.0, abs(want)), (a, i)
+        assert squeeze_hits > 0.9 * n          # the shortcut is the common path
+
+
 def test_dirichlet_rows_moments_and_simplex():
     D, K, alpha = 60_000, 4, 0.1
     c = np.array([0, 3, 1, 10], dtype=np.int32)

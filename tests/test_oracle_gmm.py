@@ -228,3 +228,22 @@ def test_uv_recovers_means_and_variances():
     for _ in range(3):
         b.step_sample_z(); b.step_stats(); b.step_resample(); b.step_finish()
     assert np.array_equal(a.z, b.z) and np.array_equal(a.mu, b.mu) and np.array_equal(a.var, b.var)
+
+
+def test_uv_initial_state_starts_from_the_prior_mean_variance():
+    # var^0 = b0 / a0 for every component, then pi, mu and var from their conditionals with
+    # sweep index 0 (the first sweep, index 1, draws from fresh random blocks)
+    rng = np.random.default_rng(4)
+    N, dim, K, a0, b0 = 600, 2, 3, 2.0, 3.0
+    x = rng.normal(0.0, 4.0, size=(N, dim)).astype(np.float32)
+    o = O.OracleGMMUV(K, 1.0, 10.0, a0, b0, 23, x)
+    z0 = O.lda_init_z(N, K, seed=23)      # the mixture shares the init stream of z
+    assert o.sweep_index == 0 and np.array_equal(o.z, z0)
+    n_k, s_k = O.gmm_stats(x, z0, K)
+    pi, mu, var = O.gmmuv_resample(x, z0, n_k, s_k, np.full(K, b0 / a0), 1.0, 10.0, a0, b0,
+                                   seed=23, sweep=0)
+    assert np.array_equal(o.pi, pi) and np.array_equal(o.mu, mu) and np.array_equal(o.var, var)
+    # the starting variance matters: another one moves the means' conditional
+    _, mu_other, _ = O.gmmuv_resample(x, z0, n_k, s_k, np.full(K, a0 / b0), 1.0, 10.0, a0, b0,
+                                      seed=23, sweep=0)
+    assert not np.array_equal(mu, mu_other)

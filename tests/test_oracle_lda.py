@@ -78,6 +78,53 @@ def test_inverse_cdf_rule_and_zero_mass_topics():
         assert np.allclose(cdf, want, rtol=1e-15)
 
 
+def test_inverse_cdf_rule_is_strict_at_a_tie():
+    # u is an odd multiple of 2^-24, so a tie C_k = u S needs products made for it:
+    # theta = (u, 1 - u), phi = (1, 1) gives C = (u, 1) exactly and t = u.  The smallest k with
+    # C_k > t is then 1 (u lies in [C_0, C_1), the half-open interval of topic 1).
+    seed, sweep, n = 11, 2, 64
+    u = O.datum_uniforms(seed, 0, n, sweep, O.STREAM_Z)
+    phi = np.ones((1, 2), dtype=np.float32)
+    w = np.zeros(n, dtype=np.int32)
+    for i in range(n):
+        theta = np.array([[u[i], 1.0 - u[i]]], dtype=np.float32)
+        assert float(theta[0, 0]) == u[i] and float(theta[0, 0]) + float(theta[0, 1]) == 1.0
+        # the token keeps its place i in a one-document corpus so that it keeps its uniform
+        z, deg = O.lda_sample_z(O.doc_offsets([n]), w, theta, phi, seed=seed, sweep=sweep)
+        cdf, t = O.lda_token_cdf(theta[0], phi[0], seed=seed, token=i, sweep=sweep)
+        assert deg == 0 and cdf[0] == t == u[i]
+        assert z[i] == 1
+    # one ulp below the tie the draw is topic 0 ... (u < C_0 = nextafter(u, 1))
+    theta = np.array([[np.nextafter(np.float32(u[0]), np.float32(1)), 0.0]], dtype=np.float32)
+    theta[0, 1] = np.float32(1.0) - theta[0, 0]
+    z, _ = O.lda_sample_z(O.doc_offsets([n]), w, theta, phi, seed=seed, sweep=sweep)
+    cdf, t = O.lda_token_cdf(theta[0], phi[0], seed=seed, token=0, sweep=sweep)
+    assert z[0] == (0 if cdf[0] > t else 1) == 0
+
+
+def test_initial_state_uses_sweep_index_zero():
+    # theta^0 and phi^0 are drawn with sweep index 0, so the first sweep (index 1) draws from
+    # fresh random blocks: a state drawn with index 1 would share its blocks with sweep 1.
+    cfg = dict(synth.LDA_CONFIGS["tiny"])
+    c = synth.lda_corpus(**cfg)
+    D, V, K = cfg["D"], cfg["V"], cfg["K"]
+    o = O.OracleLDA(D, V, K, cfg["alpha"], cfg["beta"], 17, c["doc_len"], c["w"])
+    assert o.sweep_index == 0
+    assert np.array_equal(o.z, O.lda_init_z(c["N"], K, seed=17))
+    n_dk, n_wk = O.lda_count(O.doc_offsets(c["doc_len"]), c["w"], o.z, D, V, K)
+    assert np.array_equal(o.theta, O.lda_resample_theta(n_dk, o.alpha, seed=17, sweep=0))
+    assert np.array_equal(o.phi, O.lda_resample_phi(n_wk, o.beta, seed=17, sweep=0))
+    th1 = O.lda_resample_theta(n_dk, o.alpha, seed=17, sweep=1)
+    assert not np.array_equal(o.theta, th1)
+    lt0, lt1 = np.log(o.theta.astype(np.float64)).ravel(), np.log(th1.astype(np.float64)).ravel()
+    # same counts, different blocks: the two draws are independent given the counts, so after
+    # removing the per-entry mean (a function of the count) they are uncorrelated
+    r0 = lt0 - special.digamma(cfg["alpha"] + n_dk.ravel())
+    r1 = lt1 - special.digamma(cfg["alpha"] + n_dk.ravel())
+    keep = (n_dk.ravel() > 0)
+    assert abs(np.corrcoef(r0[keep], r1[keep])[0, 1]) < 5 / np.sqrt(keep.sum())
+
+
 def test_degenerate_conditional_falls_back_to_uniform_index():
     theta = np.zeros((1, 4), dtype=np.float32)
     phi = np.full((2, 4), 0.25, dtype=np.float32)
