@@ -155,25 +155,37 @@ __global__ __launch_bounds__(256) void lda_init_z_kernel(int32_t* __restrict__ z
 //
 // One wave owns one document.  The wave is four 16-lane rows; each row draws one
 // token per iteration.  A row covers the K topics in NS stripes of 64: lane j
-// holds topics 64 m + 4 j + {0,1,2,3} of stripe m, so a row reads 256 contiguous
-// bytes of the phi row per load.  theta_d lives in registers for the whole
-// document.  Per stripe the lane sums its four products, the row scans the lane
-// sums with DPP, and the stripe total is carried into the next stripe.  The
-// crossing topic is found by every lane testing its own chunks against the
-// threshold and the row taking the minimum candidate index; a chunk or topic of
-// zero mass is never a candidate.
+// holds topics 64 m + 4 j + {0,1,2,3} of stripe m (its "chunk" of the stripe), so a
+// row reads 256 contiguous bytes of the phi row per load.  theta_d is staged in LDS
+// once per document (zero beyond the last topic).
+//
+// Pass 1 keeps one number per chunk, the sum of its four products.  The row scans
+// the chunk sums of each stripe with DPP and carries the stripe totals, which gives
+// every chunk the running sum before it.  Each lane then finds the first of its
+// chunks that the threshold falls into (a chunk of zero mass never qualifies).
+// Pass 2 reloads that one chunk (16 bytes of the phi row, a cache hit, and of theta),
+// repeats the same three multiply-adds, which give the same bits, and locates the
+// topic inside it; the row takes the minimum candidate index.  Keeping the products of
+// all stripes instead (and theta in registers) needs 256 registers a lane, one wave
+// per SIMD; this form needs half and the loads of several waves overlap.
 //
 // Random numbers: lane L computes the Philox block of tokens
 // base + 4 L .. base + 4 L + 3 (base a multiple of 4), parks the four words in
 // the wave's LDS strip, and each row then picks the word of its token: one
 // Philox evaluation per wave serves 256 tokens.
+//
+// Registers: up to 14 stripes the kernel is held to 128 registers (four waves per SIMD); with
+// 15 or 16 stripes that limit makes the compiler serialise the row loads, and three waves
+// with all loads of a row in flight are faster (K = 1000 on 10M tokens: 2.28 against 2.86 ms).
 template <int NS>
-__global__ __launch_bounds__(256) void lda_sample_z_kernel(
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NS >= 15 ? 3 : 4, NS >= 15 ? 3 : 8)))
+void lda_sample_z_kernel(
     const int32_t* __restrict__ w, const int64_t* __restrict__ doc_off,
     const int32_t* __restrict__ seg_base, int n_segs, const float* __restrict__ theta,
     const float* __restrict__ phi, int32_t* __restrict__ z, int D, int K, int ldk, uint64_t seed,
     uint32_t sweep, unsigned long long* __restrict__ n_degenerate) {
   __shared__ uint32_t rnd[4][256];
+  __shared__ __align__(16) float theta_s[4][NS * 64];
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   const int seg = blockIdx.x * 4 + wave;
@@ -182,17 +194,23 @@ __global__ __launch_bounds__(256) void lda_sample_z_kernel(
   const int d = sg.d;
   const int row = lane >> 4, j = lane & 15;
 
-  // theta_d in registers; chunks past the last topic hold 0.  Every lane's byte
-  // offset inside a phi row is fixed: full stripes sit 256 B apart, and the last
-  // stripe's lanes beyond the row are pointed at the row's last chunk (their
-  // theta is 0), so all loads are unconditional and stay inside the row.
-  float4 th[NS];
+  // theta_d into the wave's LDS strip; chunks past the last topic hold 0.  Every lane's
+  // byte offset inside a phi row is fixed: full stripes sit 256 B apart, and the last
+  // stripe's lanes beyond the row are pointed at the row's last chunk (their theta is 0),
+  // so all loads are unconditional and stay inside the row.
+  float* th = theta_s[wave];
 #pragma unroll
-  for (int m = 0; m < NS; ++m) {
-    const int col = 64 * m + 4 * j;
-    th[m] = col < ldk ? *reinterpret_cast<const float4*>(theta + (size_t)d * ldk + col)
-                      : make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int c = 4 * lane; c < NS * 64; c += 256) {
+    *reinterpret_cast<float4*>(th + c) =
+        c < ldk ? *reinterpret_cast<const float4*>(theta + (size_t)d * ldk + c)
+                : make_float4(0.f, 0.f, 0.f, 0.f);
   }
+  wave_lds_fence();
+  const float* th_lane = th + 4 * j;
+  // With five stripes there are registers to spare for a second set of row loads: the next
+  // group's rows are requested while pass 2 of this one waits for its chunk (K = 300, 3.2M
+  // tokens: 0.305 against 0.338 ms; with six to eight stripes the same costs more than it hides).
+  constexpr bool kPipelined = NS <= 5;
   const uint32_t lane_off = 16u * (uint32_t)j;
   const uint32_t last_off = 4u * (uint32_t)min(64 * (NS - 1) + 4 * j, ldk - 4);
   const char* phi_bytes = reinterpret_cast<const char*>(phi);
@@ -208,30 +226,50 @@ __global__ __launch_bounds__(256) void lda_sample_z_kernel(
     }
     const int64_t lo = a > base ? a : base;
     const int64_t hi = b < base + 256 ? b : base + 256;
-    for (int64_t i0 = lo; i0 < hi; i0 += 4) {
-      const int64_t i = i0 + row;
-      const bool valid = i < hi;
-      const uint32_t v = valid ? (uint32_t)w[i] : 0u;
-      const uint32_t r = rnd[wave][valid ? (int)(i - base) : 0];
+    // The token of this row in the group of four starting at i0 (a row past the end of the
+    // chunk reads word 0's row, in bounds, and stores nothing), and its phi row's loads.
+    struct Token {
+      int64_t i;
+      bool valid;
+      uint32_t r;
+      const char *rowp, *lastp;
+    };
+    auto fetch = [&](int64_t i0, Token& T, float4 (&q)[NS]) {
+      T.i = i0 + row;
+      T.valid = T.i < hi;
+      const uint32_t v = T.valid ? (uint32_t)w[T.i] : 0u;
+      T.r = rnd[wave][T.valid ? (int)(T.i - base) : 0];
       const uint32_t row_off = v * row_bytes;  // < 2^32: checked when the handle is created
-
-      const char* rowp = phi_bytes + (size_t)(row_off + lane_off);  // constant offsets fold into the loads
-      float4 q[NS];
+      T.rowp = phi_bytes + (size_t)(row_off + lane_off);  // constant offsets fold into the loads
+      T.lastp = phi_bytes + (size_t)(row_off + last_off);
 #pragma unroll
-      for (int m = 0; m < NS - 1; ++m) q[m] = *reinterpret_cast<const float4*>(rowp + 256 * m);
-      q[NS - 1] = *reinterpret_cast<const float4*>(phi_bytes + (row_off + last_off));
+      for (int m = 0; m < NS - 1; ++m) q[m] = *reinterpret_cast<const float4*>(T.rowp + 256 * m);
+      q[NS - 1] = *reinterpret_cast<const float4*>(T.lastp);
+    };
+    Token T, Tn;
+    float4 q[NS], qn[kPipelined ? NS : 1];
+    if (kPipelined) fetch(lo, T, q);
+    for (int64_t i0 = lo; i0 < hi; i0 += 4) {
+      if (!kPipelined) fetch(i0, T, q);
+      const int64_t i = T.i;
+      const bool valid = T.valid;
+      const uint32_t r = T.r;
+      const char* rowp = T.rowp;
+      const char* lastp = T.lastp;
 
-      // running sums: l?[m] = lane-local inclusive sums of stripe m, cbase[m] =
-      // sum of everything before this lane's chunk of stripe m.  The NS row
-      // scans are independent until the carries, so they are issued side by side.
-      float l0[NS], l1[NS], l2[NS], l3[NS], inc[NS], cbase[NS];
+      // ls[m] = sum of the lane's chunk of stripe m; inc[m] its inclusive row scan; cbase[m] =
+      // sum of everything before the chunk.  The NS row scans are independent until the
+      // carries, so they are issued side by side.
+      float ls[NS], inc[NS], cbase[NS];
 #pragma unroll
       for (int m = 0; m < NS; ++m) {
-        l0[m] = th[m].x * q[m].x;
-        l1[m] = fmaf(th[m].y, q[m].y, l0[m]);
-        l2[m] = fmaf(th[m].z, q[m].z, l1[m]);
-        l3[m] = fmaf(th[m].w, q[m].w, l2[m]);
-        inc[m] = l3[m];
+        const float4 t4 = *reinterpret_cast<const float4*>(th_lane + 64 * m);
+        float l = t4.x * q[m].x;
+        l = fmaf(t4.y, q[m].y, l);
+        l = fmaf(t4.z, q[m].z, l);
+        l = fmaf(t4.w, q[m].w, l);
+        ls[m] = l;
+        inc[m] = l;
       }
 #pragma unroll
       for (int m = 0; m < NS; ++m) inc[m] += dpp_f32<kRowShr1>(inc[m]);
@@ -250,14 +288,28 @@ __global__ __launch_bounds__(256) void lda_sample_z_kernel(
       const float S = carry;
       const float t = u24(r) * S;
 
-      // candidate = global topic index of the first topic of this lane's chunks
-      // whose running sum exceeds t and whose mass is positive
-      int cand = 0x7FFFFFFF;
+      // the first of this lane's chunks whose running sum exceeds t and whose mass is positive
+      int cm = -1;
+      float ctt = 0.f;
 #pragma unroll
       for (int m = NS - 1; m >= 0; --m) {
         const float tt = fmaxf(t - cbase[m], 0.f);
-        const int e = (l0[m] <= tt) + (l1[m] <= tt) + (l2[m] <= tt);
-        cand = l3[m] > tt ? 64 * m + 4 * j + e : cand;
+        const bool hit = ls[m] > tt;
+        cm = hit ? m : cm;
+        ctt = hit ? tt : ctt;
+      }
+      if constexpr (kPipelined) fetch(i0 + 4, Tn, qn);
+      // pass 2 on that chunk (stripe 0 for a lane without one; its result is not used)
+      int cand = 0x7FFFFFFF;
+      {
+        const int mm = cm < 0 ? 0 : cm;
+        const float4 q2 = *reinterpret_cast<const float4*>(mm == NS - 1 ? lastp : rowp + 256 * mm);
+        const float4 t4 = *reinterpret_cast<const float4*>(th_lane + 64 * mm);
+        const float l0 = t4.x * q2.x;
+        const float l1 = fmaf(t4.y, q2.y, l0);
+        const float l2 = fmaf(t4.z, q2.z, l1);
+        const int e = (l0 <= ctt) + (l1 <= ctt) + (l2 <= ctt);
+        cand = cm >= 0 ? 64 * cm + 4 * j + e : cand;
       }
       int k = row_allreduce_min(cand);
 
@@ -270,19 +322,29 @@ __global__ __launch_bounds__(256) void lda_sample_z_kernel(
         } else if (k == 0x7FFFFFFF) {
           // rounding pushed t to S: the last topic of positive mass
           int last = -1;
-#pragma unroll
           for (int m = 0; m < NS; ++m) {
+            const float4 q2 = *reinterpret_cast<const float4*>(m == NS - 1 ? lastp : rowp + 256 * m);
+            const float4 t4 = *reinterpret_cast<const float4*>(th_lane + 64 * m);
+            const float l0 = t4.x * q2.x;
+            const float l1 = fmaf(t4.y, q2.y, l0);
+            const float l2 = fmaf(t4.z, q2.z, l1);
+            const float l3 = fmaf(t4.w, q2.w, l2);
             const int kk = 64 * m + 4 * j;
-            if (l0[m] > 0.f) last = kk;
-            if (l1[m] > l0[m]) last = kk + 1;
-            if (l2[m] > l1[m]) last = kk + 2;
-            if (l3[m] > l2[m]) last = kk + 3;
+            if (l0 > 0.f) last = kk;
+            if (l1 > l0) last = kk + 1;
+            if (l2 > l1) last = kk + 2;
+            if (l3 > l2) last = kk + 3;
           }
           k = row_allreduce_max(last);
         }
       }
       // garbage parameters (negative or NaN entries) must not yield an index outside the tables
       if (valid && j == 0) z[i] = min(max(k, 0), K - 1);
+      if constexpr (kPipelined) {
+        T = Tn;
+#pragma unroll
+        for (int m = 0; m < NS; ++m) q[m] = qn[m];
+      }
     }
   }
 }
