@@ -377,8 +377,14 @@ constexpr int kNoTopic = 0x7FFFFFFF;
 // draws and stores it at the end (the document half of the counting phase, for
 // free: the wave already owns the document; a segment of a split document adds
 // to the row, which the host zeroes before the launch).
+//
+// Waves per SIMD: the kernel waits on its row loads, so a wave more per SIMD pays even when
+// the register limit that buys it spills a few values: the compiler's own choice sits 2 to 4
+// registers above a limit at 3, 5, 7 and 8 stripes.  Measured on 75M tokens, z step: K = 40,
+// 6 waves 1.13 against 1.24 ms; K = 80, 5 waves 1.51 against 1.71; K = 100, 5 waves 2.00 against
+// 2.38 (3 waves); K = 128, 4 waves 2.11 against 2.50 (3 waves), 5 waves 2.20.
 template <int NS16, bool kCountDocs>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NS16 > 8 ? 4 : 1)))
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NS16 > 7 ? 4 : NS16 > 4 ? 5 : 6)))
 void lda_sample_z_quad_kernel(
     const int32_t* __restrict__ w, const int64_t* __restrict__ doc_off,
     const int32_t* __restrict__ seg_base, int n_segs, const float* __restrict__ theta,
