@@ -135,8 +135,37 @@ __device__ __forceinline__ double log_pos(double x) {
   return fma(de, 0x1.62e42fee00000p-1, fma(de, 0x1.a39ef35793c76p-33, lm));
 }
 
+// cos(pi y) for y in [0, 2] (the Box-Muller angle is a whole turn times a uniform, so no wider
+// range reduction is needed).  y = k/2 + r with k = 0..4 and |r| <= 1/4, r exact;
+// cos(pi y) is +-cos(pi r) or +-sin(pi r) by quadrant; both are Taylor polynomials in r^2
+// (terms to r^15 and r^16: next term below 2^-54 of the first).  Within 2 ulp; a third of the
+// instructions of the general-purpose cospi, which was a seventh of a Gamma attempt.
+// (-1)^n pi^(2n+1)/(2n+1)!, n = 7..0, and (-1)^n pi^(2n)/(2n)!, n = 8..0.
+__constant__ double kSinPiSeries[8] = {-0x1.6fadb9f155744p-16, 0x1.e8f434d018d63p-12,
+                                       -0x1.e3074fde8871fp-8,  0x1.50783487ee782p-4,
+                                       -0x1.32d2cce62bd86p-1,  0x1.466bc6775aae2p+1,
+                                       -0x1.4abbce625be53p+2,  0x1.921fb54442d18p+1};
+__constant__ double kCosPiSeries[9] = {0x1.20c62c2f2d7f5p-18, -0x1.b6e24f44b128fp-14,
+                                       0x1.f9d38a3763cc3p-10, -0x1.a6d1f2a204a8cp-6,
+                                       0x1.e1f506891babbp-3,  -0x1.55d3c7e3cbffap+0,
+                                       0x1.03c1f081b5ac4p+2,  -0x1.3bd3cc9be45dep+2,
+                                       1.0};
+__device__ __forceinline__ double cospi_0_2(double y) {
+  const double k = rint(2.0 * y);
+  const double r = fma(-0.5, k, y);
+  const int q = (int)k;
+  const double z = r * r;
+  double ps = kSinPiSeries[0], pc = kCosPiSeries[0];
+#pragma unroll
+  for (int i = 1; i < 8; ++i) ps = fma(ps, z, kSinPiSeries[i]);
+#pragma unroll
+  for (int i = 1; i < 9; ++i) pc = fma(pc, z, kCosPiSeries[i]);
+  const double v = (q & 1) ? r * ps : pc;
+  return ((q + 1) & 2) ? -v : v;  // quadrants 1 and 2 are negated: -sin, -cos
+}
+
 __device__ __forceinline__ double normal_from(const U4& b) {
-  return sqrt(-2.0 * log_pos(u32d(b.x))) * cospi(2.0 * u32d(b.y));
+  return sqrt(-2.0 * log_pos(u32d(b.x))) * cospi_0_2(2.0 * u32d(b.y));
 }
 
 constexpr int kGammaAttemptCap = 64;

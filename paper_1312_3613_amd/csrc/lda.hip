@@ -812,12 +812,12 @@ __global__ __launch_bounds__(1024) void lda_phi_draw_kernel(
       }
       if (done) {
         lg[e] = x;
-        if (x > m) {
-          s = s * exp(m - x) + 1.0;  // exp(-inf) = 0 on the first row
-          m = x;
-        } else {
-          s += exp(x - m);
-        }
+        // running (max, sum of exp(. - max)); one exp and no branch, so lanes that raise
+        // their maximum and lanes that do not share the instructions
+        const double dx = x - m;               // +inf on the first row: e = 0, s = 1
+        const double ex = exp(-fabs(dx));
+        s = dx > 0.0 ? fma(s, ex, 1.0) : s + ex;
+        m = dx > 0.0 ? x : m;
         ++v;
         attempt = 0;
         if (v < v1) g = gamma_shape_count(shapes, beta, n_wk[(size_t)v * ldk + k]);
