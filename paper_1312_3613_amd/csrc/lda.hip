@@ -648,14 +648,18 @@ __global__ __launch_bounds__(256) void lda_count_words_kernel(
 __global__ __launch_bounds__(256) void lda_count_words_merge_kernel(
     const int32_t* __restrict__ slice_base, const int32_t* __restrict__ multi_words,
     const int32_t* __restrict__ part, int32_t* __restrict__ n_wk, int ldk) {
-  // one workgroup per word that has several slices (listed in multi_words); words
-  // with a single slice were stored directly.  Wave g adds slices g, g + 4, ...
-  // (four rows in flight per lane); the four waves' sums meet in LDS.
-  extern __shared__ int32_t acc[];  // [4][ldk]
+  // one workgroup per 64 columns of a word that has several slices (listed in multi_words);
+  // words with a single slice were stored directly.  Wave g adds slices g, g + 4, ... (four
+  // rows in flight per lane); the four waves' sums meet in LDS.  A lane owns one column: the
+  // most frequent word has hundreds of slices, and a lane that walked all of its columns one
+  // after the other made that word's workgroup the whole kernel's duration at K = 1000.
+  __shared__ int32_t acc[4][64];
   const int v = multi_words[blockIdx.x];
   const int s0 = slice_base[v], s1 = slice_base[v + 1];
   const int lane = threadIdx.x & 63, g = threadIdx.x >> 6;
-  for (int k = lane; k < ldk; k += 64) {
+  const int k = blockIdx.y * 64 + lane;
+  int32_t sum = 0;
+  if (k < ldk) {
     int32_t c0 = 0, c1 = 0, c2 = 0, c3 = 0;
     int s = s0 + g;
     for (; s + 12 < s1; s += 16) {
@@ -665,11 +669,12 @@ __global__ __launch_bounds__(256) void lda_count_words_merge_kernel(
       c3 += part[(size_t)(s + 12) * ldk + k];
     }
     for (; s < s1; s += 4) c0 += part[(size_t)s * ldk + k];
-    acc[g * ldk + k] = (c0 + c1) + (c2 + c3);
+    sum = (c0 + c1) + (c2 + c3);
   }
+  acc[g][lane] = sum;
   __syncthreads();
-  for (int k = threadIdx.x; k < ldk; k += 256)
-    n_wk[(size_t)v * ldk + k] = (acc[k] + acc[ldk + k]) + (acc[2 * ldk + k] + acc[3 * ldk + k]);
+  if (g == 0 && k < ldk)
+    n_wk[(size_t)v * ldk + k] = (acc[0][lane] + acc[1][lane]) + (acc[2][lane] + acc[3][lane]);
 }
 
 // ---- one-time structure of the corpus (create) ----
@@ -1152,8 +1157,9 @@ int launch_count_words(augur_lda* h, hipStream_t stream) {
                        stream, h->z, h->perm, h->word_off, h->slice_base, h->slice_word, h->n_wk, h->slice_part, V,
                        h->ldk, h->n_slices);
   if (h->n_multi > 0)
-    hipLaunchKernelGGL(lda_count_words_merge_kernel, dim3(h->n_multi), dim3(256), shm, stream,
-                       h->slice_base, h->multi_words, h->slice_part, h->n_wk, h->ldk);
+    hipLaunchKernelGGL(lda_count_words_merge_kernel, dim3(h->n_multi, (h->ldk + 63) / 64),
+                       dim3(256), 0, stream, h->slice_base, h->multi_words, h->slice_part, h->n_wk,
+                       h->ldk);
   AUGUR_HIP_TRY(hipGetLastError());
   return AUGUR_OK;
 }
