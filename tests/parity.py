@@ -30,16 +30,24 @@ def assert_z_lda(z_gpu, z_orc, doc_off, w, theta, phi, seed, sweep):
     assert z_gpu.shape == z_orc.shape
     assert N == 0 or (z_gpu.min() >= 0 and z_gpu.max() < K)
     mism = np.nonzero(z_gpu != z_orc)[0]
-    assert mism.size <= (1.0 - Z_AGREE) * N, f"{mism.size} of {N} z differ"
     if mism.size == 0:
         return 0
+    assert mism.size <= 1000, f"{mism.size} of {N} z differ"     # not rounding: do not walk them
     doc_of = np.searchsorted(doc_off, mism, side="right") - 1
     for i, d in zip(mism, doc_of):
         cdf, t = O.lda_token_cdf(theta[d], phi[w[i]], seed, int(i), sweep)
         # the mass of the GPU's topic is its own product (a running sum in fp64 may absorb it)
         mass = float(theta[d, z_gpu[i]]) * float(phi[w[i], z_gpu[i]])
         _assert_boundary(cdf, t, int(z_gpu[i]), int(z_orc[i]), f"token {i}", mass)
+    _assert_agreement(mism.size, N)
     return mism.size
+
+
+def _assert_agreement(n_mismatch, N):
+    """>= 99.99 % of the variables of a sweep agree.  On fewer than 10^4 variables one
+    disagreement is already below that mark, so there the rule is that a single
+    boundary case (checked as such by the caller) may occur."""
+    assert n_mismatch <= max(1.0, (1.0 - Z_AGREE) * N), f"{n_mismatch} of {N} z differ"
 
 
 def assert_z_gmm(z_gpu, z_orc, x, pi, mu, sigma, seed, sweep):
@@ -47,10 +55,11 @@ def assert_z_gmm(z_gpu, z_orc, x, pi, mu, sigma, seed, sweep):
     N = z_orc.size
     assert z_gpu.min() >= 0 and z_gpu.max() < pi.size
     mism = np.nonzero(z_gpu != z_orc)[0]
-    assert mism.size <= (1.0 - Z_AGREE) * N, f"{mism.size} of {N} z differ"
+    assert mism.size <= 1000, f"{mism.size} of {N} z differ"
     for i in mism:
         cdf, t = O.gmm_point_cdf(x[i], pi, mu, sigma, seed, int(i), sweep)
         _assert_boundary(cdf, t, int(z_gpu[i]), int(z_orc[i]), f"point {i}")
+    _assert_agreement(mism.size, N)
     return mism.size
 
 
@@ -59,10 +68,11 @@ def assert_z_gmmuv(z_gpu, z_orc, x, pi, mu, var, seed, sweep):
     N = z_orc.size
     assert z_gpu.min() >= 0 and z_gpu.max() < pi.size
     mism = np.nonzero(z_gpu != z_orc)[0]
-    assert mism.size <= (1.0 - Z_AGREE) * N, f"{mism.size} of {N} z differ"
+    assert mism.size <= 1000, f"{mism.size} of {N} z differ"
     for i in mism:
         cdf, t = O.gmmuv_point_cdf(x[i], pi, mu, var, seed, int(i), sweep)
         _assert_boundary(cdf, t, int(z_gpu[i]), int(z_orc[i]), f"point {i}")
+    _assert_agreement(mism.size, N)
     return mism.size
 
 

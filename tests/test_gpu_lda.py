@@ -113,7 +113,8 @@ def test_tiny_config_free_running(B):
     g.close()
 
 
-@pytest.mark.parametrize("K", [1, 2, 7, 10, 64, 65, 100, 200, 257, 1000, 1024])
+@pytest.mark.parametrize("K", [1, 2, 7, 10, 48, 64, 65, 96, 100, 128, 200, 224, 256, 257, 384, 500, 640, 900,
+                               1000, 1024])
 def test_topic_counts_span_stripes_and_tails(B, K):
     D, V = 40, 300
     lens, w = ragged_corpus(D, V, K, seed=K)
@@ -125,9 +126,11 @@ def test_topic_counts_span_stripes_and_tails(B, K):
     g.close()
 
 
-def test_dense_parameters_many_live_topics(B):
-    # alpha = beta = 1: every topic carries mass, the hard case for fp32 running sums
-    D, V, K = 64, 500, 200
+@pytest.mark.parametrize("K", [200, 700])
+def test_dense_parameters_many_live_topics(B, K):
+    # alpha = beta = 1: every topic carries mass, the hard case for fp32 running sums (and, above
+    # 256 topics, crossings in every stripe of the row sampler's second pass)
+    D, V = 64, 500
     lens, w = ragged_corpus(D, V, K, seed=5, mean_len=300)
     g, o = make_pair(B, D, V, K, 1.0, 1.0, 77, lens, w)
     for _ in range(3):
