@@ -10,8 +10,8 @@
 //   perm      int32[N]     token indices sorted by word (built once: w never changes)
 //   zb        uint8[N]     copy of z in one byte a token (K <= 256), for the word table's gathers
 //   word_off  int32[V+1]   start of each word's run in perm
-//   slice_base int32[V+1]  first slice id of each word (a word's run is cut into slices)
-//   slice_word int32[slices] word of each slice
+//   slice_desc int4[slices] a word's run is cut into slices: first, end (in perm), word, mode;
+//   item_off  int32[items+1] the slices a wave visits in one go (its "item")
 #include "common.hpp"
 
 #include <hipcub/hipcub.hpp>
@@ -592,89 +592,94 @@ __global__ __launch_bounds__(256) void lda_count_docs_kernel(
 }
 
 // Words: tokens were sorted by word once (perm).  A word's run of tokens is cut
-// into slices; one wave per slice gathers z through perm into an LDS histogram.
+// into slices; a wave gathers a slice's z through perm into an LDS histogram.
 // The gathers touch a cache line per token.  For K <= 256 they read the one-byte
 // copy of z that the z kernel writes beside z: a quarter of the footprint, which
 // (75 MB at 75M tokens) stays in the 256 MB last-level cache where z itself
 // (300 MB) does not.
-// A word with a single slice stores its row directly; a word with several
-// slices stores one partial row per slice and lda_count_words_merge_kernel adds
-// them.  Every word has at least one slice, so every row is written each sweep.
-// slice_word[s] = word of slice s (a wave looks it up instead of searching slice_base: with
-// one short slice per rare word, 17 dependent loads per wave were most of the kernel's time
-// on small corpora).
-__global__ __launch_bounds__(256) void slice_words_kernel(const int32_t* __restrict__ slice_base,
-                                                           int V, int32_t* __restrict__ slice_word) {
-  const int v = blockIdx.x * blockDim.x + threadIdx.x;
-  if (v >= V) return;
-  for (int s = slice_base[v]; s < slice_base[v + 1]; ++s) slice_word[s] = v;
-}
-
+// A word with a single slice stores its row; a word with several has its row zeroed
+// before the launch and every slice adds its non-zero bins with integer atomics (a
+// few thousand per address at most: cheap, unlike one atomic per token).  Every word
+// has at least one slice, so every row is written each sweep.
+//
+// The visit is planned once on the host (build_word_major).  The unit of work is an item: a
+// list of slices, slice_desc[item_off[i] .. item_off[i + 1]), of about 1500 tokens in all; a
+// slice is {first position in perm, end, word, 0 = store the row / 1 = add to it}.
+//
+// Frequent words are cut by position first.  The token positions 0..N are divided into `ranges`
+// equal parts; a frequent word's run (sorted by position) is cut where it passes from one part
+// to the next; the pieces of part r, in word order, are dealt into items of equal token counts,
+// and the items are visited part by part.  The waves in flight then all gather from the same
+// MiB or two of z, which an XCD's L2 holds, instead of from all of it: a line (128 tokens of
+// the byte copy) is fetched once per part and XCD rather than once per token (75M tokens: 26M
+// L2 misses instead of 50M).  The waves must stay in step for this, and they do not by
+// themselves (a wave whose gathers hit runs several times faster than one whose gathers
+// miss): a workgroup takes its next four items from a counter (one device-scope atomic per
+// workgroup and round; one per wave and slice on that single address cost more than the whole
+// kernel).  Rare words (fewer than 64 tokens a part) keep whole slices, bundled into items
+// after the parts: their gathers touch a line per token whatever the order.
 template <typename ZT>
 __global__ __launch_bounds__(256) void lda_count_words_kernel(
-    const ZT* __restrict__ z, const int32_t* __restrict__ perm,
-    const int32_t* __restrict__ word_off, const int32_t* __restrict__ slice_base,
-    const int32_t* __restrict__ slice_word, int32_t* __restrict__ n_wk, int32_t* __restrict__ part,
-    int V, int ldk, int n_slices) {
+    const ZT* __restrict__ z, const int32_t* __restrict__ perm, const int4* __restrict__ slice_desc,
+    const int32_t* __restrict__ item_off, int32_t* __restrict__ n_wk, int ldk, int n_items,
+    uint32_t* __restrict__ next) {
   extern __shared__ int32_t hist_all[];
+  __shared__ uint32_t grabbed[2];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   int32_t* hist = hist_all + (size_t)wave * ldk;
-  for (int s = blockIdx.x * 4 + wave; s < n_slices; s += gridDim.x * 4) {
-  wave_lds_fence();  // the previous slice's row has been read out
-  for (int k = lane; k < ldk; k += 64) hist[k] = 0;
-  const int v = slice_word[s];
-  const int ns = slice_base[v + 1] - slice_base[v];
-  const int q = s - slice_base[v];
-  const int w0 = word_off[v], w1 = word_off[v + 1];
-  const int len = (w1 - w0 + ns - 1) / ns;
-  const int start = min(w1, w0 + q * len), end = min(w1, start + len);
-  wave_lds_fence();
-  int j = start + lane;
-  for (; j + 192 < end; j += 256) {  // four gathers in flight per lane
-    const int p0 = perm[j], p1 = perm[j + 64], p2 = perm[j + 128], p3 = perm[j + 192];
-    const int z0 = (int)z[p0], z1 = (int)z[p1], z2 = (int)z[p2], z3 = (int)z[p3];
-    atomicAdd(&hist[z0], 1);
-    atomicAdd(&hist[z1], 1);
-    atomicAdd(&hist[z2], 1);
-    atomicAdd(&hist[z3], 1);
-  }
-  for (; j < end; j += 64) atomicAdd(&hist[(int)z[perm[j]]], 1);
-  wave_lds_fence();
-  int32_t* dst = ns == 1 ? n_wk + (size_t)v * ldk : part + (size_t)s * ldk;
-  for (int k = lane; k < ldk; k += 64) dst[k] = hist[k];
+  // next == NULL: one wave per item.  Otherwise the grid is smaller than the list and loops.
+  for (uint32_t round = 0;; ++round) {
+    uint32_t first = blockIdx.x * 4u;
+    if (next != nullptr) {
+      if (threadIdx.x == 0) grabbed[round & 1] = atomicAdd(next, 4u);
+      __syncthreads();  // grabbed[] alternates, so one barrier a round is enough
+      first = grabbed[round & 1];
+    }
+    if (first >= (uint32_t)n_items) break;  // the same for the four waves
+    const uint32_t it = first + (uint32_t)wave;
+    const int i0 = it < (uint32_t)n_items ? item_off[it] : 0;
+    const int i1 = it < (uint32_t)n_items ? item_off[it + 1] : 0;
+    for (int i = i0; i < i1; ++i) {
+      const int4 d = slice_desc[i];
+      wave_lds_fence();  // the previous row has been read out
+      for (int k = lane; k < ldk; k += 64) hist[k] = 0;
+      wave_lds_fence();
+      const int end = d.y;
+      int j = d.x + lane;
+      for (; j + 192 < end; j += 256) {  // four gathers in flight per lane
+        const int p0 = perm[j], p1 = perm[j + 64], p2 = perm[j + 128], p3 = perm[j + 192];
+        const int z0 = (int)z[p0], z1 = (int)z[p1], z2 = (int)z[p2], z3 = (int)z[p3];
+        atomicAdd(&hist[z0], 1);
+        atomicAdd(&hist[z1], 1);
+        atomicAdd(&hist[z2], 1);
+        atomicAdd(&hist[z3], 1);
+      }
+      for (; j < end; j += 64) atomicAdd(&hist[(int)z[perm[j]]], 1);
+      wave_lds_fence();
+      int32_t* dst = n_wk + (size_t)d.z * ldk;
+      if (d.w == 0) {
+        for (int k = lane; k < ldk; k += 64) dst[k] = hist[k];
+      } else {
+        for (int k = lane; k < ldk; k += 64) {
+          const int32_t c = hist[k];
+          if (c != 0) atomicAdd(&dst[k], c);
+        }
+      }
+    }
+    if (next == nullptr) break;
   }
 }
 
-__global__ __launch_bounds__(256) void lda_count_words_merge_kernel(
-    const int32_t* __restrict__ slice_base, const int32_t* __restrict__ multi_words,
-    const int32_t* __restrict__ part, int32_t* __restrict__ n_wk, int ldk) {
-  // one workgroup per 64 columns of a word that has several slices (listed in multi_words);
-  // words with a single slice were stored directly.  Wave g adds slices g, g + 4, ... (four
-  // rows in flight per lane); the four waves' sums meet in LDS.  A lane owns one column: the
-  // most frequent word has hundreds of slices, and a lane that walked all of its columns one
-  // after the other made that word's workgroup the whole kernel's duration at K = 1000.
-  __shared__ int32_t acc[4][64];
-  const int v = multi_words[blockIdx.x];
-  const int s0 = slice_base[v], s1 = slice_base[v + 1];
-  const int lane = threadIdx.x & 63, g = threadIdx.x >> 6;
-  const int k = blockIdx.y * 64 + lane;
-  int32_t sum = 0;
-  if (k < ldk) {
-    int32_t c0 = 0, c1 = 0, c2 = 0, c3 = 0;
-    int s = s0 + g;
-    for (; s + 12 < s1; s += 16) {
-      c0 += part[(size_t)s * ldk + k];
-      c1 += part[(size_t)(s + 4) * ldk + k];
-      c2 += part[(size_t)(s + 8) * ldk + k];
-      c3 += part[(size_t)(s + 12) * ldk + k];
-    }
-    for (; s < s1; s += 4) c0 += part[(size_t)s * ldk + k];
-    sum = (c0 + c1) + (c2 + c3);
-  }
-  acc[g][lane] = sum;
-  __syncthreads();
-  if (g == 0 && k < ldk)
-    n_wk[(size_t)v * ldk + k] = (acc[0][lane] + acc[1][lane]) + (acc[2][lane] + acc[3][lane]);
+// Zeroes the counter of the looping word-table kernel and the rows of the words whose slices
+// add to them (listed in multi_words).
+__global__ __launch_bounds__(256) void lda_count_words_prepare_kernel(
+    const int32_t* __restrict__ multi_words, int n_multi, int32_t* __restrict__ n_wk, int ldk,
+    uint32_t* __restrict__ next) {
+  if (blockIdx.x == 0 && threadIdx.x == 0) *next = 0u;
+  const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= (int64_t)n_multi * ldk) return;
+  const int m = (int)(t / ldk), k = (int)(t - (int64_t)m * ldk);
+  n_wk[(size_t)multi_words[m] * ldk + k] = 0;
 }
 
 // ---- one-time structure of the corpus (create) ----
@@ -695,17 +700,31 @@ __global__ __launch_bounds__(256) void word_offsets_kernel(const int32_t* __rest
   }
   word_off[v] = (int32_t)lo;
 }
-// Slices per word: runs are cut to about kSliceTokens tokens, at most
-// kMaxSlicesPerWord per word, at least one.
+// A rare word's run is cut to about kSliceTokens tokens (at most kMaxSlicesPerWord pieces, at
+// least one).
 constexpr int kSliceTokens = 4096;
 constexpr int kMaxSlicesPerWord = 512;
-__global__ __launch_bounds__(256) void slice_counts_kernel(const int32_t* __restrict__ word_off,
-                                                            int V, int32_t* __restrict__ ns) {
-  const int v = blockIdx.x * blockDim.x + threadIdx.x;
-  if (v > V) return;
-  if (v == V) { ns[v] = 0; return; }
-  const int f = word_off[v + 1] - word_off[v];
-  ns[v] = max(1, min(kMaxSlicesPerWord, (f + kSliceTokens - 1) / kSliceTokens));
+constexpr int kCountBlocks = 512;     // workgroups of the word-table kernel when it loops
+constexpr int kItemsPerRange = 512;   // items a part's frequent-word tokens are dealt into
+constexpr int kItemSlicesMax = 32;    // most rare-word slices bundled into one item
+// border[h * (ranges + 1) + r] = first index in the run of frequent word heavy[h] (in perm,
+// where a word's positions increase) whose position is at least r * range_len.
+__global__ __launch_bounds__(256) void range_borders_kernel(
+    const int32_t* __restrict__ word_off, const int32_t* __restrict__ perm,
+    const int32_t* __restrict__ heavy, int n_heavy, int ranges, int64_t range_len,
+    int32_t* __restrict__ border) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= n_heavy * (ranges + 1)) return;
+  const int hi_word = t / (ranges + 1), r = t - hi_word * (ranges + 1);
+  const int v = heavy[hi_word];
+  int lo = word_off[v], hi = word_off[v + 1];
+  if (r == ranges) { border[t] = hi; return; }
+  const int64_t pos = (int64_t)r * range_len;
+  while (lo < hi) {
+    const int mid = (lo + hi) >> 1;
+    if ((int64_t)perm[mid] < pos) lo = mid + 1; else hi = mid;
+  }
+  border[t] = lo;
 }
 
 // ------------------------------------------------------------ resample theta
@@ -1023,13 +1042,16 @@ struct augur_lda {
   double alpha = 0, beta = 0;
   int32_t *w = nullptr, *z = nullptr, *n_dk = nullptr, *n_wk = nullptr;
   int64_t* doc_off = nullptr;
-  int32_t *perm = nullptr, *word_off = nullptr, *slice_base = nullptr, *slice_part = nullptr;
-  int32_t* slice_word = nullptr;
-  int32_t* multi_words = nullptr;  // words with more than one slice
+  int32_t *perm = nullptr, *word_off = nullptr;
+  int4* slice_desc = nullptr;     // the slices in visiting order
+  int32_t* item_off = nullptr;    // [n_items + 1] into slice_desc
+  int n_items = 0;
+  bool count_loops = false;       // the word-table kernel takes items from cw_next
+  uint32_t* cw_next = nullptr;
+  int32_t* multi_words = nullptr;  // words with more than one slice (rows zeroed, slices add)
   int n_multi = 0;
   uint8_t* zb = nullptr;    // z in bytes, written by the z kernel when K <= 256
   bool zb_current = false;  // zb holds the z of the last z step
-  int n_slices = 0;
   int32_t* seg_base = nullptr;  // NULL: every document is one segment
   int n_segs = 0;
   float *theta = nullptr, *phi = nullptr;
@@ -1054,7 +1076,8 @@ void free_all(augur_lda* h) {
   (void)hipFree(h->col_partial); (void)hipFree(h->col_logZ); (void)hipFree(h->red);
   (void)hipFree(h->counters); (void)hipFree(h->perm); (void)hipFree(h->word_off);
   (void)hipFree(h->zb);
-  (void)hipFree(h->slice_base); (void)hipFree(h->slice_part); (void)hipFree(h->slice_word); (void)hipFree(h->multi_words);
+  (void)hipFree(h->slice_desc); (void)hipFree(h->item_off); (void)hipFree(h->cw_next);
+  (void)hipFree(h->multi_words);
   (void)hipFree(h->shapes_alpha); (void)hipFree(h->shapes_beta); (void)hipFree(h->seg_base);
   if (h->side) (void)hipStreamDestroy(h->side);
   if (h->ev_fork) (void)hipEventDestroy(h->ev_fork);
@@ -1138,28 +1161,21 @@ int launch_count_docs(augur_lda* h, hipStream_t stream) {
 }
 
 int launch_count_words(augur_lda* h, hipStream_t stream) {
-  const int V = h->cfg.V;
+  if (h->n_items == 0) return AUGUR_OK;
   const size_t shm = sizeof(int32_t) * 4 * (size_t)h->ldk;
-  // One wave per slice when the slices are short (small corpora: the per-slice set-up dominates
-  // and parallelism hides it); 256 workgroups that loop over the slices when they are long.
-  // The kernel then runs beside the theta step (other stream), and the two slow each other
-  // down: with long slices a bounded grid keeps enough gathers in flight and lets the theta
-  // step finish sooner (large workload: sweep 5.06 ms with one wave per slice, 4.92 at 512
-  // workgroups, 4.83 at 256; medium: 0.323 / 0.344 / 0.368 ms).
-  const bool long_slices = h->N / std::max(h->n_slices, 1) >= 256;
-  const int cw_blocks = long_slices ? std::min((h->n_slices + 3) / 4, 256) : (h->n_slices + 3) / 4;
+  {
+    const int64_t cells = (int64_t)h->n_multi * h->ldk;
+    hipLaunchKernelGGL(lda_count_words_prepare_kernel, dim3((unsigned)std::max<int64_t>(1, (cells + 255) / 256)),
+                       dim3(256), 0, stream, h->multi_words, h->n_multi, h->n_wk, h->ldk, h->cw_next);
+  }
+  const int cw_blocks = h->count_loops ? kCountBlocks : (h->n_items + 3) / 4;
+  uint32_t* next = h->count_loops ? h->cw_next : nullptr;
   if (h->zb_current)
-    hipLaunchKernelGGL(lda_count_words_kernel<uint8_t>, dim3(cw_blocks), dim3(256), shm,
-                       stream, h->zb, h->perm, h->word_off, h->slice_base, h->slice_word, h->n_wk, h->slice_part, V,
-                       h->ldk, h->n_slices);
+    hipLaunchKernelGGL(lda_count_words_kernel<uint8_t>, dim3(cw_blocks), dim3(256), shm, stream,
+                       h->zb, h->perm, h->slice_desc, h->item_off, h->n_wk, h->ldk, h->n_items, next);
   else
-    hipLaunchKernelGGL(lda_count_words_kernel<int32_t>, dim3(cw_blocks), dim3(256), shm,
-                       stream, h->z, h->perm, h->word_off, h->slice_base, h->slice_word, h->n_wk, h->slice_part, V,
-                       h->ldk, h->n_slices);
-  if (h->n_multi > 0)
-    hipLaunchKernelGGL(lda_count_words_merge_kernel, dim3(h->n_multi, (h->ldk + 63) / 64),
-                       dim3(256), 0, stream, h->slice_base, h->multi_words, h->slice_part, h->n_wk,
-                       h->ldk);
+    hipLaunchKernelGGL(lda_count_words_kernel<int32_t>, dim3(cw_blocks), dim3(256), shm, stream,
+                       h->z, h->perm, h->slice_desc, h->item_off, h->n_wk, h->ldk, h->n_items, next);
   AUGUR_HIP_TRY(hipGetLastError());
   return AUGUR_OK;
 }
@@ -1174,7 +1190,7 @@ int build_word_major(augur_lda* h) {
   const int64_t N = h->N;
   const int V = h->cfg.V;
   const size_t n_alloc = (size_t)std::max<int64_t>(N, 1);
-  int32_t *iota = nullptr, *sorted_w = nullptr, *ns = nullptr;
+  int32_t *iota = nullptr, *sorted_w = nullptr, *d_heavy = nullptr, *d_border = nullptr;
   void* temp = nullptr;
   int rc = AUGUR_OK;
   auto check = [&](hipError_t e, const char* what) {
@@ -1187,10 +1203,8 @@ int build_word_major(augur_lda* h) {
   do {
     if (!check(hipMalloc(&h->perm, sizeof(int32_t) * n_alloc), "hipMalloc(perm)")) break;
     if (!check(hipMalloc(&h->word_off, sizeof(int32_t) * ((size_t)V + 1)), "hipMalloc(word_off)")) break;
-    if (!check(hipMalloc(&h->slice_base, sizeof(int32_t) * ((size_t)V + 1)), "hipMalloc(slice_base)")) break;
     if (!check(hipMalloc(&iota, sizeof(int32_t) * n_alloc), "hipMalloc(iota)")) break;
     if (!check(hipMalloc(&sorted_w, sizeof(int32_t) * n_alloc), "hipMalloc(sorted_w)")) break;
-    if (!check(hipMalloc(&ns, sizeof(int32_t) * ((size_t)V + 1)), "hipMalloc(ns)")) break;
     if (N > 0) {
       hipLaunchKernelGGL(iota_kernel, dim3((unsigned)((N + 255) / 256)), dim3(256), 0, h->stream,
                          iota, N);
@@ -1209,42 +1223,130 @@ int build_word_major(augur_lda* h) {
     }
     hipLaunchKernelGGL(word_offsets_kernel, dim3((V + 256) / 256), dim3(256), 0, h->stream, sorted_w,
                        N, V, h->word_off);
-    hipLaunchKernelGGL(slice_counts_kernel, dim3((V + 256) / 256), dim3(256), 0, h->stream,
-                       h->word_off, V, ns);
-    size_t temp_bytes = 0;
-    if (!check(hipcub::DeviceScan::ExclusiveSum(nullptr, temp_bytes, ns, h->slice_base, V + 1,
-                                                h->stream), "scan (size query)")) break;
-    if (!check(hipMalloc(&temp, std::max<size_t>(temp_bytes, 16)), "hipMalloc(scan temp)")) break;
-    if (!check(hipcub::DeviceScan::ExclusiveSum(temp, temp_bytes, ns, h->slice_base, V + 1,
-                                                h->stream), "scan")) break;
-    int32_t total = 0;
-    if (!check(hipMemcpyAsync(&total, h->slice_base + V, sizeof(int32_t), hipMemcpyDeviceToHost,
-                              h->stream), "hipMemcpyAsync")) break;
+    // ---- the plan of the word-table kernel, made on the host from the word offsets ----
+    std::vector<int32_t> off((size_t)V + 1);
+    if (!check(hipMemcpyAsync(off.data(), h->word_off, sizeof(int32_t) * off.size(),
+                              hipMemcpyDeviceToHost, h->stream), "hipMemcpyAsync")) break;
     if (!check(hipStreamSynchronize(h->stream), "hipStreamSynchronize")) break;
-    h->n_slices = total;
-    if (!check(hipMalloc(&h->slice_part, sizeof(int32_t) * (size_t)total * h->ldk),
-               "hipMalloc(slice_part)")) break;
-    if (!check(hipMalloc(&h->slice_word, sizeof(int32_t) * (size_t)std::max(total, 1)),
-               "hipMalloc(slice_word)")) break;
-    hipLaunchKernelGGL(slice_words_kernel, dim3((V + 255) / 256), dim3(256), 0, h->stream,
-                       h->slice_base, V, h->slice_word);
-    {
-      // the few words with several slices, listed on the host (once)
-      std::vector<int32_t> base((size_t)V + 1), multi;
-      if (!check(hipMemcpyAsync(base.data(), h->slice_base, sizeof(int32_t) * base.size(),
+    auto rare_pieces = [](int f) {
+      return std::max(1, std::min(kMaxSlicesPerWord, (f + kSliceTokens - 1) / kSliceTokens));
+    };
+    int64_t n_basic = 0;
+    for (int v = 0; v < V; ++v) n_basic += rare_pieces(off[v + 1] - off[v]);
+    // One wave per slice when the slices are short (small corpora: the per-slice set-up
+    // dominates and parallelism hides it); kCountBlocks looping workgroups when they are long.
+    // The kernel then runs beside the theta step (other stream), and the two slow each other
+    // down: a bounded grid keeps enough gathers in flight, keeps the waves within two parts of
+    // the positions, and lets the theta step finish sooner (large workload, sweep: 4.73 ms at
+    // 256 workgroups, 4.52 at 512, 4.64 at 768; one wave per item is slower still).
+    const bool looping = n_basic > 4 * kCountBlocks && N / n_basic >= 256;
+    // parts of the positions for the frequent words: about 1 MiB of the gathered array each (a
+    // quarter of an XCD's L2); none if the whole array is a few MiB anyway
+    const int64_t gathered_bytes = N * (h->ldk <= 256 ? 1 : 4);
+    int ranges = looping ? (int)std::min<int64_t>(128, (gathered_bytes + (1 << 20) - 1) >> 20) : 1;
+    if (ranges <= 4) ranges = 1;
+    const int64_t range_len = std::max<int64_t>(1, (N + ranges - 1) / ranges);
+    const int heavy_min = 64 * ranges;
+    std::vector<int32_t> heavy, border;
+    if (ranges > 1)
+      for (int v = 0; v < V; ++v)
+        if (off[v + 1] - off[v] >= heavy_min) heavy.push_back(v);
+    const int n_heavy = (int)heavy.size();
+    if (n_heavy > 0) {
+      border.resize((size_t)n_heavy * (ranges + 1));
+      if (!check(hipMalloc(&d_heavy, sizeof(int32_t) * heavy.size()), "hipMalloc(heavy)")) break;
+      if (!check(hipMalloc(&d_border, sizeof(int32_t) * border.size()), "hipMalloc(border)")) break;
+      if (!check(hipMemcpyAsync(d_heavy, heavy.data(), sizeof(int32_t) * heavy.size(),
+                                hipMemcpyHostToDevice, h->stream), "hipMemcpyAsync")) break;
+      const int n_t = n_heavy * (ranges + 1);
+      hipLaunchKernelGGL(range_borders_kernel, dim3((n_t + 255) / 256), dim3(256), 0, h->stream,
+                         h->word_off, h->perm, d_heavy, n_heavy, ranges, range_len, d_border);
+      if (!check(hipMemcpyAsync(border.data(), d_border, sizeof(int32_t) * border.size(),
                                 hipMemcpyDeviceToHost, h->stream), "hipMemcpyAsync")) break;
       if (!check(hipStreamSynchronize(h->stream), "hipStreamSynchronize")) break;
-      for (int v = 0; v < V; ++v)
-        if (base[v + 1] - base[v] > 1) multi.push_back(v);
-      h->n_multi = (int)multi.size();
-      if (!check(hipMalloc(&h->multi_words, sizeof(int32_t) * std::max<size_t>(multi.size(), 1)),
-                 "hipMalloc(multi_words)")) break;
-      if (h->n_multi > 0 &&
-          !check(hipMemcpy(h->multi_words, multi.data(), sizeof(int32_t) * multi.size(),
-                           hipMemcpyHostToDevice), "hipMemcpy")) break;
     }
+    std::vector<int4> desc;            // x first, y end, z word, w: slice index of its word for now
+    std::vector<int32_t> item_off(1, 0);
+    std::vector<int32_t> pieces_of((size_t)V, 0);
+    auto add_slice = [&](int32_t start, int32_t end, int32_t v) {
+      desc.push_back(make_int4(start, end, v, 0));
+      ++pieces_of[(size_t)v];
+    };
+    auto close_item = [&]() {
+      if ((size_t)item_off.back() != desc.size()) item_off.push_back((int32_t)desc.size());
+    };
+    // frequent words: part by part, the pieces dealt into items of equal token counts
+    int64_t heavy_tokens = 0;
+    for (int r = 0; r < ranges && n_heavy > 0; ++r) {
+      int64_t total = 0;
+      for (int hw = 0; hw < n_heavy; ++hw)
+        total += border[(size_t)hw * (ranges + 1) + r + 1] - border[(size_t)hw * (ranges + 1) + r];
+      if (total == 0) continue;
+      heavy_tokens += total;
+      const int64_t share = (total + kItemsPerRange - 1) / kItemsPerRange;
+      int64_t pos = 0;
+      for (int hw = 0; hw < n_heavy; ++hw) {
+        int32_t a = border[(size_t)hw * (ranges + 1) + r];
+        const int32_t e = border[(size_t)hw * (ranges + 1) + r + 1];
+        while (a < e) {
+          const int64_t room = (pos / share + 1) * share - pos;
+          const int32_t take = (int32_t)std::min<int64_t>(room, e - a);
+          add_slice(a, a + take, heavy[(size_t)hw]);
+          a += take;
+          pos += take;
+          if (pos % share == 0) close_item();
+        }
+      }
+      close_item();
+    }
+    // rare words: whole slices; when the kernel loops, bundled into items of about the same size
+    {
+      const int64_t item_tokens =
+          heavy_tokens > 0 ? std::max<int64_t>(256, heavy_tokens / ((int64_t)ranges * kItemsPerRange))
+                           : 1536;
+      size_t next_heavy = 0;
+      int64_t in_item = 0;
+      for (int v = 0; v < V; ++v) {
+        if (next_heavy < heavy.size() && heavy[next_heavy] == v) { ++next_heavy; continue; }
+        const int f = off[v + 1] - off[v];
+        const int n = rare_pieces(f);
+        const int len = (f + n - 1) / n;
+        for (int q = 0; q < n; ++q) {
+          const int32_t start = std::min(off[v + 1], off[v] + q * len);
+          const int32_t end = std::min(off[v + 1], start + len);
+          add_slice(start, end, v);
+          in_item += end - start;
+          const bool full = !looping || in_item >= item_tokens ||
+                            (int64_t)desc.size() - item_off.back() >= kItemSlicesMax;
+          if (full) { close_item(); in_item = 0; }
+        }
+      }
+      close_item();
+    }
+    std::vector<int32_t> multi;
+    for (int v = 0; v < V; ++v)
+      if (pieces_of[(size_t)v] > 1) multi.push_back(v);
+    for (auto& d : desc) d.w = pieces_of[(size_t)d.z] > 1 ? 1 : 0;
+    h->n_items = (int)item_off.size() - 1;
+    h->count_loops = looping;
+    h->n_multi = (int)multi.size();
+    if (!check(hipMalloc(&h->slice_desc, sizeof(int4) * std::max<size_t>(desc.size(), 1)),
+               "hipMalloc(slice_desc)")) break;
+    if (!check(hipMalloc(&h->item_off, sizeof(int32_t) * item_off.size()), "hipMalloc(item_off)")) break;
+    if (!check(hipMalloc(&h->cw_next, sizeof(uint32_t)), "hipMalloc(cw_next)")) break;
+    if (!check(hipMalloc(&h->multi_words, sizeof(int32_t) * std::max<size_t>(multi.size(), 1)),
+               "hipMalloc(multi_words)")) break;
+    if (!desc.empty() &&
+        !check(hipMemcpy(h->slice_desc, desc.data(), sizeof(int4) * desc.size(), hipMemcpyHostToDevice),
+               "hipMemcpy")) break;
+    if (!check(hipMemcpy(h->item_off, item_off.data(), sizeof(int32_t) * item_off.size(),
+                         hipMemcpyHostToDevice), "hipMemcpy")) break;
+    if (h->n_multi > 0 &&
+        !check(hipMemcpy(h->multi_words, multi.data(), sizeof(int32_t) * multi.size(),
+                         hipMemcpyHostToDevice), "hipMemcpy")) break;
   } while (false);
-  (void)hipFree(temp); (void)hipFree(iota); (void)hipFree(sorted_w); (void)hipFree(ns);
+  (void)hipFree(temp); (void)hipFree(iota); (void)hipFree(sorted_w); (void)hipFree(d_heavy);
+  (void)hipFree(d_border);
   return rc;
 }
 
