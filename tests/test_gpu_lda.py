@@ -126,6 +126,38 @@ def test_topic_counts_span_stripes_and_tails(B, K):
     g.close()
 
 
+@pytest.mark.parametrize("D,mean_len,V,K", [
+    (1200, 1000, 3000, 50),     # long slices, kernel loops, gathered array of about 1 MB: no parts
+    (6000, 1000, 4000, 50),     # 6 MB of one-byte z: frequent words cut into 6 position parts
+    (2000, 1000, 2500, 300),    # K > 256: gathers from the int32 z, 8 MB, 8 parts
+])
+def test_word_table_plans(B, D, mean_len, V, K):
+    """The word table against numpy's histogram for every way its visit is planned (a wave per
+    slice is what the small corpora of the other tests use), from the int32 z (after set_state)
+    and from the one-byte copy (after a sweep)."""
+    rng = np.random.default_rng(D + K)
+    lens = rng.poisson(mean_len, size=D).astype(np.int32)
+    zipf = np.arange(1, V + 1) ** -1.1
+    w = rng.choice(V, size=int(lens.sum()), p=zipf / zipf.sum()).astype(np.int32)
+    N = w.size
+    doc = np.repeat(np.arange(D), lens)
+    g = B.LDA(D, V, K, 0.1, 0.01, 5, lens, w)
+
+    def check(z):
+        n_dk, n_wk = (np_(a) for a in g.get_counts())
+        assert np.array_equal(n_wk, np.bincount(w.astype(np.int64) * K + z, minlength=V * K).reshape(V, K))
+        assert np.array_equal(n_dk, np.bincount(doc * K + z, minlength=D * K).reshape(D, K))
+
+    check(np_(g.get_state(theta=False, phi=False)[0]))           # counts made by create
+    z = rng.integers(0, K, size=N).astype(np.int32)
+    g.set_state(z=z)
+    g.step_count()
+    check(z)
+    g.sweep(2)                                                   # K <= 256: from the byte copy
+    check(np_(g.get_state(theta=False, phi=False)[0]))
+    g.close()
+
+
 @pytest.mark.parametrize("K", [200, 700])
 def test_dense_parameters_many_live_topics(B, K):
     # alpha = beta = 1: every topic carries mass, the hard case for fp32 running sums (and, above
