@@ -306,6 +306,20 @@ def test_fold_in_with_phi_observed(B):
     train.close(); g.close()
 
 
+def test_heldout_curve_script_runs_and_improves(B, capsys, monkeypatch):
+    # the held-out log predictive against the number of samples (shape of the paper's figure)
+    import json
+    import sys
+    from paper_1312_3613_amd import heldout_curve
+    monkeypatch.setattr(sys, "argv", ["heldout_curve", "--topics", "20", "--max-samples", "32",
+                                      "--fold-in-sweeps", "10"])
+    heldout_curve.main()
+    out = json.loads(capsys.readouterr().out.strip().splitlines()[-1])
+    lp = out["log_predictive_per_token"]
+    assert out["samples"] == [0, 1, 2, 4, 8, 16, 32] and all(np.isfinite(lp))
+    assert lp[-1] > lp[0]
+
+
 def test_overlapped_and_serial_schedules_agree(B):
     cfg = dict(synth.LDA_CONFIGS["tiny"], D=300, V=800, K=40, mean_len=120)
     c = synth.lda_corpus(**cfg)
