@@ -17,6 +17,7 @@
 #include <hipcub/hipcub.hpp>
 
 #include <algorithm>
+#include <exception>
 #include <new>
 #include <vector>
 
@@ -1200,6 +1201,7 @@ int build_word_major(augur_lda* h) {
     }
     return rc == AUGUR_OK;
   };
+  try {
   do {
     if (!check(hipMalloc(&h->perm, sizeof(int32_t) * n_alloc), "hipMalloc(perm)")) break;
     if (!check(hipMalloc(&h->word_off, sizeof(int32_t) * ((size_t)V + 1)), "hipMalloc(word_off)")) break;
@@ -1345,6 +1347,10 @@ int build_word_major(augur_lda* h) {
         !check(hipMemcpy(h->multi_words, multi.data(), sizeof(int32_t) * multi.size(),
                          hipMemcpyHostToDevice), "hipMemcpy")) break;
   } while (false);
+  } catch (const std::exception& e) {  // the host-side plan allocates; nothing may throw out of the C ABI
+    set_error("planning the word table failed: %s", e.what());
+    rc = AUGUR_ERR_INVALID_ARG;
+  }
   (void)hipFree(temp); (void)hipFree(iota); (void)hipFree(sorted_w); (void)hipFree(d_heavy);
   (void)hipFree(d_border);
   return rc;
@@ -1518,7 +1524,12 @@ int augur_lda_create(const augur_lda_config* cfg, const int32_t* doc_len, const 
     if (bad) AUGUR_CREATE_FAIL("doc_len has %llu negative entries", bad);
     h->N = n;
   } else {
-    std::vector<int64_t> off((size_t)D + 1, 0);
+    std::vector<int64_t> off;
+    try {
+      off.assign((size_t)D + 1, 0);
+    } catch (const std::exception&) {
+      AUGUR_CREATE_FAIL("out of host memory for the offsets of %d documents", D);
+    }
     for (int d = 0; d < D; ++d) {
       if (doc_len[d] < 0) AUGUR_CREATE_FAIL("doc_len[%d] = %d is negative", d, doc_len[d]);
       off[d + 1] = off[d] + doc_len[d];
