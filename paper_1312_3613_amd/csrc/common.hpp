@@ -164,6 +164,47 @@ __device__ __forceinline__ double cospi_0_2(double y) {
   return ((q + 1) & 2) ? -v : v;  // quadrants 1 and 2 are negated: -sin, -cos
 }
 
+// The same logarithm with a table in LDS, for the kernels that take millions of them: x = m 2^e,
+// m in [1, 2); i = round(128 (m - 1)) in 0..128 picks c_i = 1 + i/128; the table holds 1/c_i
+// (rounded) and -ln of that stored value (minus ln 2 from i = 53 on, where c_i > sqrt 2 and e is
+// raised by one instead, so that x just below a power of two meets no cancellation).  Then
+// r = m / c_i - 1 is one exact fma, |r| <= 2^-8, and ln(1 + r) needs the series to r^6 only.
+// The ends of the table are exact (1/c = 1 and 1/2, ln = 0), so arguments next to 1 keep their
+// relative accuracy.  Within 6e-16 relative; 22 instructions against 37.
+constexpr int kLogTableSize = 129;
+constexpr int kLogTableFold = 53;  // first i with c_i > sqrt(2)
+inline void fill_log_table(double2* t) {  // host
+  for (int i = 0; i < kLogTableSize; ++i) {
+    const double inv = 1.0 / (1.0 + (double)i / 128.0);
+    long double l = -logl((long double)inv);
+    if (i >= kLogTableFold) l -= logl(2.0L);
+    if (i == 0 || i == kLogTableSize - 1) l = 0.0L;
+    t[i] = make_double2(inv, (double)l);
+  }
+}
+__device__ __forceinline__ double log_tab(double x, const double2* __restrict__ lt) {
+  const uint32_t hi = (uint32_t)__double2hiint(x), lo = (uint32_t)__double2loint(x);
+  const uint32_t idx = (((hi >> 12) & 0xFFu) + 1u) >> 1;
+  const double m = __hiloint2double((int)((hi & 0x000FFFFFu) | 0x3FF00000u), (int)lo);
+  const double2 t = lt[idx];
+  const int e = (int)(hi >> 20) - 1023 + (idx >= (uint32_t)kLogTableFold ? 1 : 0);
+  const double r = fma(m, t.x, -1.0);
+  double p = fma(r, -1.0 / 6.0, 0.2);
+  p = fma(p, r, -0.25);
+  p = fma(p, r, 1.0 / 3.0);
+  p = fma(p, r, -0.5);
+  const double lnr = fma(p, r * r, r);
+  const double de = (double)e;
+  return fma(de, 0x1.62e42fee00000p-1, fma(de, 0x1.a39ef35793c76p-33, t.y + lnr));
+}
+// One logarithm, by the table if the caller has one in LDS.
+__device__ __forceinline__ double log_of(double x, const double2* __restrict__ lt) {
+  return lt != nullptr ? log_tab(x, lt) : log_pos(x);
+}
+
+__device__ __forceinline__ double normal_from(const U4& b, const double2* __restrict__ lt) {
+  return sqrt(-2.0 * log_of(u32d(b.x), lt)) * cospi_0_2(2.0 * u32d(b.y));
+}
 __device__ __forceinline__ double normal_from(const U4& b) {
   return sqrt(-2.0 * log_pos(u32d(b.x))) * cospi_0_2(2.0 * u32d(b.y));
 }
@@ -199,13 +240,14 @@ __device__ __forceinline__ GammaShape gamma_shape_count(const GammaShape* __rest
   return gamma_shape(a0 + (double)n);
 }
 // One attempt; on acceptance writes ln(draw) and returns true.
-__device__ __forceinline__ bool gamma_attempt(const GammaShape& g, const U4& b, double& lg) {
-  const double x = normal_from(b);
+__device__ __forceinline__ bool gamma_attempt(const GammaShape& g, const U4& b, double& lg,
+                                              const double2* __restrict__ lt = nullptr) {
+  const double x = normal_from(b, lt);
   const double t = 1.0 + g.c * x;
   const double v = t * t * t;
   const double U = u32d(b.z);
   const double x2 = x * x;
-  const double lv = log_pos(fabs(v));  // only used when t > 0 (then v is a positive normal)
+  const double lv = log_of(fabs(v), lt);  // only used when t > 0 (then v is a positive normal)
   bool accept = U < 1.0 - 0.0331 * x2 * x2;
   if (!accept) {
     // ln U < rhs.  A wave reaches this test on most attempts (any lane failing the squeeze
@@ -221,7 +263,7 @@ __device__ __forceinline__ bool gamma_attempt(const GammaShape& g, const U4& b, 
   }
   accept = accept && t > 0.0;
   lg = g.ln_d + lv;
-  if (g.inv_a > 1.0) lg += log_pos(u32d(b.w)) * g.inv_a;
+  if (g.inv_a > 1.0) lg += log_of(u32d(b.w), lt) * g.inv_a;
   return accept;
 }
 // Loop form: attempts until accepted.  `capped` is raised if the cap is reached.

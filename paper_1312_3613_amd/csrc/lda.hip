@@ -740,9 +740,12 @@ __global__ __launch_bounds__(256) void range_borders_kernel(
 // wave's LDS strip; then each row is normalised by the whole wave.
 __global__ __launch_bounds__(256) void lda_resample_theta_kernel(
     const int32_t* __restrict__ n_dk, float* __restrict__ theta, int D, int K, int ldk, int rows,
-    double alpha, const GammaShape* __restrict__ shapes, uint64_t seed, uint32_t sweep,
-    unsigned long long* __restrict__ n_capped) {
+    double alpha, const GammaShape* __restrict__ shapes, const double2* __restrict__ log_table,
+    uint64_t seed, uint32_t sweep, unsigned long long* __restrict__ n_capped) {
   extern __shared__ double lg_all[];
+  __shared__ double2 lt[kLogTableSize];
+  for (int i = threadIdx.x; i < kLogTableSize; i += blockDim.x) lt[i] = log_table[i];
+  __syncthreads();
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int d0 = (blockIdx.x * 4 + wave) * rows;
   if (d0 >= D) return;
@@ -759,7 +762,7 @@ __global__ __launch_bounds__(256) void lda_resample_theta_kernel(
     if (e < total) {
       const uint64_t index = (uint64_t)(d0 + r) * (uint64_t)K + (uint64_t)k;
       double x;
-      bool done = gamma_attempt(g, random_block(seed, index, sweep, kStreamTheta, attempt), x);
+      bool done = gamma_attempt(g, random_block(seed, index, sweep, kStreamTheta, attempt), x, lt);
       if (!done && ++attempt == (uint32_t)kGammaAttemptCap) {
         done = true;
         capped = true;
@@ -808,8 +811,11 @@ __global__ __launch_bounds__(256) void lda_resample_theta_kernel(
 __global__ __launch_bounds__(1024) void lda_phi_draw_kernel(
     const int32_t* __restrict__ n_wk, double* __restrict__ lg, double2* __restrict__ partial, int V,
     int K, int ldk, int rows_per_block, int groups, int n_row_blocks, int col_w, double beta,
-    const GammaShape* __restrict__ shapes, uint64_t seed, uint32_t sweep,
-    unsigned long long* __restrict__ n_capped) {
+    const GammaShape* __restrict__ shapes, const double2* __restrict__ log_table, uint64_t seed,
+    uint32_t sweep, unsigned long long* __restrict__ n_capped) {
+  __shared__ double2 lt[kLogTableSize];
+  for (int i = threadIdx.x; i < kLogTableSize; i += blockDim.x) lt[i] = log_table[i];
+  __syncthreads();
   // The workgroup covers columns [blockIdx.y col_w, +col_w) (all K of them unless K > 512).
   // thread t: column t % col_w of that range, row block blockIdx.x * groups + t / col_w.
   // Several row blocks share a workgroup so that K need not be a multiple of the wave size
@@ -831,7 +837,7 @@ __global__ __launch_bounds__(1024) void lda_phi_draw_kernel(
       double x;
       bool done = gamma_attempt(
           g, random_block(seed, (uint64_t)v * (uint64_t)K + (uint64_t)k, sweep, kStreamPhi, attempt),
-          x);
+          x, lt);
       if (!done && ++attempt == (uint32_t)kGammaAttemptCap) {
         done = true;
         capped = true;
@@ -1060,6 +1066,7 @@ struct augur_lda {
   double2* col_partial = nullptr;  // [phi row blocks][K]
   double* col_logZ = nullptr;    // [K]
   GammaShape *shapes_alpha = nullptr, *shapes_beta = nullptr;  // [kShapeTable] each
+  double2* log_table = nullptr;                                // [kLogTableSize], see log_tab
   double* red = nullptr;         // [4][kRedBlocks] reduction partials
   unsigned long long* counters = nullptr;  // [0] degenerate tokens [1] capped draws [2] bad input
   int phi_blocks = 0, phi_rows = 0;
@@ -1080,6 +1087,7 @@ void free_all(augur_lda* h) {
   (void)hipFree(h->slice_desc); (void)hipFree(h->item_off); (void)hipFree(h->cw_next);
   (void)hipFree(h->multi_words);
   (void)hipFree(h->shapes_alpha); (void)hipFree(h->shapes_beta); (void)hipFree(h->seg_base);
+  (void)hipFree(h->log_table);
   if (h->side) (void)hipStreamDestroy(h->side);
   if (h->ev_fork) (void)hipEventDestroy(h->ev_fork);
   if (h->ev_join) (void)hipEventDestroy(h->ev_join);
@@ -1367,7 +1375,8 @@ int launch_theta(augur_lda* h, uint32_t sweep) {
   const int waves = (D + rows - 1) / rows;
   hipLaunchKernelGGL(lda_resample_theta_kernel, dim3((waves + 3) / 4), dim3(256),
                      sizeof(double) * 4 * (size_t)rows * K, h->stream, h->n_dk, h->theta, D, K,
-                     h->ldk, rows, h->alpha, h->shapes_alpha, h->cfg.seed, sweep, h->counters + 1);
+                     h->ldk, rows, h->alpha, h->shapes_alpha, h->log_table, h->cfg.seed, sweep,
+                     h->counters + 1);
   AUGUR_HIP_TRY(hipGetLastError());
   return AUGUR_OK;
 }
@@ -1392,8 +1401,8 @@ int launch_phi(augur_lda* h, uint32_t sweep, hipStream_t stream) {
   const int threads = (int)round_up(groups * col_w, 64);
   hipLaunchKernelGGL(lda_phi_draw_kernel, dim3((h->phi_blocks + groups - 1) / groups, col_parts),
                      dim3(threads), 0, stream, h->n_wk, h->lg, h->col_partial, V, K, h->ldk,
-                     h->phi_rows, groups, h->phi_blocks, col_w, h->beta, h->shapes_beta, h->cfg.seed,
-                     sweep, h->counters + 1);
+                     h->phi_rows, groups, h->phi_blocks, col_w, h->beta, h->shapes_beta, h->log_table,
+                     h->cfg.seed, sweep, h->counters + 1);
   hipLaunchKernelGGL(lda_phi_norm_kernel, dim3(K), dim3(1024), 0, stream, h->col_partial,
                      h->col_logZ, h->phi_blocks, K);
   const int64_t total = (int64_t)V * h->ldk;
@@ -1575,6 +1584,12 @@ int augur_lda_create(const augur_lda_config* cfg, const int32_t* doc_len, const 
   AUGUR_CREATE_TRY(hipMalloc(&h->col_partial, sizeof(double2) * (size_t)h->phi_blocks * K));
   AUGUR_CREATE_TRY(hipMalloc(&h->col_logZ, sizeof(double) * (size_t)K));
   AUGUR_CREATE_TRY(hipMalloc(&h->red, sizeof(double) * 4 * kRedBlocks));
+  {
+    double2 table[kLogTableSize];
+    fill_log_table(table);
+    AUGUR_CREATE_TRY(hipMalloc(&h->log_table, sizeof(table)));
+    AUGUR_CREATE_TRY(hipMemcpy(h->log_table, table, sizeof(table), hipMemcpyHostToDevice));
+  }
   AUGUR_CREATE_TRY(hipMalloc(&h->shapes_alpha, sizeof(GammaShape) * kShapeTable));
   AUGUR_CREATE_TRY(hipMalloc(&h->shapes_beta, sizeof(GammaShape) * kShapeTable));
   hipLaunchKernelGGL(shape_table_kernel, dim3(kShapeTable / 256), dim3(256), 0, h->stream,
