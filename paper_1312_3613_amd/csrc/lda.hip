@@ -741,10 +741,13 @@ __global__ __launch_bounds__(256) void range_borders_kernel(
 __global__ __launch_bounds__(256) void lda_resample_theta_kernel(
     const int32_t* __restrict__ n_dk, float* __restrict__ theta, int D, int K, int ldk, int rows,
     double alpha, const GammaShape* __restrict__ shapes, const double2* __restrict__ log_table,
-    uint64_t seed, uint32_t sweep, unsigned long long* __restrict__ n_capped) {
+    const double* __restrict__ exp_table, uint64_t seed, uint32_t sweep,
+    unsigned long long* __restrict__ n_capped) {
   extern __shared__ double lg_all[];
   __shared__ double2 lt[kLogTableSize];
+  __shared__ double et[kExpTableSize];
   for (int i = threadIdx.x; i < kLogTableSize; i += blockDim.x) lt[i] = log_table[i];
+  for (int i = threadIdx.x; i < kExpTableSize; i += blockDim.x) et[i] = exp_table[i];
   __syncthreads();
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int d0 = (blockIdx.x * 4 + wave) * rows;
@@ -786,7 +789,7 @@ __global__ __launch_bounds__(256) void lda_resample_theta_kernel(
     m = wave_allreduce_max(m);
     double sum = 0.0;
     for (int kk = lane; kk < K; kk += 64) {  // each lane revisits only its own entries
-      const double ex = exp(row[kk] - m);
+      const double ex = exp_tab(row[kk] - m, et);
       row[kk] = ex;
       sum += ex;
     }
@@ -811,10 +814,13 @@ __global__ __launch_bounds__(256) void lda_resample_theta_kernel(
 __global__ __launch_bounds__(1024) void lda_phi_draw_kernel(
     const int32_t* __restrict__ n_wk, double* __restrict__ lg, double2* __restrict__ partial, int V,
     int K, int ldk, int rows_per_block, int groups, int n_row_blocks, int col_w, double beta,
-    const GammaShape* __restrict__ shapes, const double2* __restrict__ log_table, uint64_t seed,
-    uint32_t sweep, unsigned long long* __restrict__ n_capped) {
+    const GammaShape* __restrict__ shapes, const double2* __restrict__ log_table,
+    const double* __restrict__ exp_table, uint64_t seed, uint32_t sweep,
+    unsigned long long* __restrict__ n_capped) {
   __shared__ double2 lt[kLogTableSize];
+  __shared__ double et[kExpTableSize];
   for (int i = threadIdx.x; i < kLogTableSize; i += blockDim.x) lt[i] = log_table[i];
+  for (int i = threadIdx.x; i < kExpTableSize; i += blockDim.x) et[i] = exp_table[i];
   __syncthreads();
   // The workgroup covers columns [blockIdx.y col_w, +col_w) (all K of them unless K > 512).
   // thread t: column t % col_w of that range, row block blockIdx.x * groups + t / col_w.
@@ -848,7 +854,7 @@ __global__ __launch_bounds__(1024) void lda_phi_draw_kernel(
         // running (max, sum of exp(. - max)); one exp and no branch, so lanes that raise
         // their maximum and lanes that do not share the instructions
         const double dx = x - m;               // +inf on the first row: e = 0, s = 1
-        const double ex = exp(-fabs(dx));
+        const double ex = exp_tab(-fabs(dx), et);
         s = dx > 0.0 ? fma(s, ex, 1.0) : s + ex;
         m = dx > 0.0 ? x : m;
         ++v;
@@ -1067,6 +1073,7 @@ struct augur_lda {
   double* col_logZ = nullptr;    // [K]
   GammaShape *shapes_alpha = nullptr, *shapes_beta = nullptr;  // [kShapeTable] each
   double2* log_table = nullptr;                                // [kLogTableSize], see log_tab
+  double* exp_table = nullptr;                                 // [kExpTableSize], see exp_tab
   double* red = nullptr;         // [4][kRedBlocks] reduction partials
   unsigned long long* counters = nullptr;  // [0] degenerate tokens [1] capped draws [2] bad input
   int phi_blocks = 0, phi_rows = 0;
@@ -1087,7 +1094,7 @@ void free_all(augur_lda* h) {
   (void)hipFree(h->slice_desc); (void)hipFree(h->item_off); (void)hipFree(h->cw_next);
   (void)hipFree(h->multi_words);
   (void)hipFree(h->shapes_alpha); (void)hipFree(h->shapes_beta); (void)hipFree(h->seg_base);
-  (void)hipFree(h->log_table);
+  (void)hipFree(h->log_table); (void)hipFree(h->exp_table);
   if (h->side) (void)hipStreamDestroy(h->side);
   if (h->ev_fork) (void)hipEventDestroy(h->ev_fork);
   if (h->ev_join) (void)hipEventDestroy(h->ev_join);
@@ -1375,8 +1382,8 @@ int launch_theta(augur_lda* h, uint32_t sweep) {
   const int waves = (D + rows - 1) / rows;
   hipLaunchKernelGGL(lda_resample_theta_kernel, dim3((waves + 3) / 4), dim3(256),
                      sizeof(double) * 4 * (size_t)rows * K, h->stream, h->n_dk, h->theta, D, K,
-                     h->ldk, rows, h->alpha, h->shapes_alpha, h->log_table, h->cfg.seed, sweep,
-                     h->counters + 1);
+                     h->ldk, rows, h->alpha, h->shapes_alpha, h->log_table, h->exp_table, h->cfg.seed,
+                     sweep, h->counters + 1);
   AUGUR_HIP_TRY(hipGetLastError());
   return AUGUR_OK;
 }
@@ -1402,7 +1409,7 @@ int launch_phi(augur_lda* h, uint32_t sweep, hipStream_t stream) {
   hipLaunchKernelGGL(lda_phi_draw_kernel, dim3((h->phi_blocks + groups - 1) / groups, col_parts),
                      dim3(threads), 0, stream, h->n_wk, h->lg, h->col_partial, V, K, h->ldk,
                      h->phi_rows, groups, h->phi_blocks, col_w, h->beta, h->shapes_beta, h->log_table,
-                     h->cfg.seed, sweep, h->counters + 1);
+                     h->exp_table, h->cfg.seed, sweep, h->counters + 1);
   hipLaunchKernelGGL(lda_phi_norm_kernel, dim3(K), dim3(1024), 0, stream, h->col_partial,
                      h->col_logZ, h->phi_blocks, K);
   const int64_t total = (int64_t)V * h->ldk;
@@ -1589,6 +1596,10 @@ int augur_lda_create(const augur_lda_config* cfg, const int32_t* doc_len, const 
     fill_log_table(table);
     AUGUR_CREATE_TRY(hipMalloc(&h->log_table, sizeof(table)));
     AUGUR_CREATE_TRY(hipMemcpy(h->log_table, table, sizeof(table), hipMemcpyHostToDevice));
+    double et[kExpTableSize];
+    fill_exp_table(et);
+    AUGUR_CREATE_TRY(hipMalloc(&h->exp_table, sizeof(et)));
+    AUGUR_CREATE_TRY(hipMemcpy(h->exp_table, et, sizeof(et), hipMemcpyHostToDevice));
   }
   AUGUR_CREATE_TRY(hipMalloc(&h->shapes_alpha, sizeof(GammaShape) * kShapeTable));
   AUGUR_CREATE_TRY(hipMalloc(&h->shapes_beta, sizeof(GammaShape) * kShapeTable));
