@@ -25,7 +25,7 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 # runs and figures are in profiles/lda_large_and_medium_kernel_trace_and_hbm_traffic.md.  None for workloads
 # that have not been measured.
 MEASURED_TRAFFIC_BYTES = {"large": (7_019_758 * 2.0 + 951_364 * 1.0) * 1024,
-                          "medium": (87_146 * 2.0 + 63_706 * 1.0) * 1024,
+                          "medium": (75_429 * 2.0 + 29_010 * 1.0) * 1024,
                           "widek": (6_890_064 * 2.0 + 159_777 * 1.0) * 1024}
 
 
