@@ -503,8 +503,15 @@ void lda_sample_z_quad_kernel(
 
       // pass 2: the 16 topics of stripe c*
       const int cs = min(cstar, NS16 - 1);
-      const uint32_t off2 = min(64u * (uint32_t)cs + lane_off, row_bytes - 16u);
-      const float4 p2 = *reinterpret_cast<const float4*>(phi_bytes + (T.row_off + off2));
+      float4 p2 = T.ph[0];  // the stripe's chunk is still in registers: select it, no second load
+#pragma unroll
+      for (int c = 1; c < NS16; ++c) {
+        const bool sel = cs == c;
+        p2.x = sel ? T.ph[c].x : p2.x;
+        p2.y = sel ? T.ph[c].y : p2.y;
+        p2.z = sel ? T.ph[c].z : p2.z;
+        p2.w = sel ? T.ph[c].w : p2.w;
+      }
       const float4 t2 = *reinterpret_cast<const float4*>(theta_s + 16 * cs + 4 * q);
       const float l0 = t2.x * p2.x;
       const float l1 = fmaf(t2.y, p2.y, l0);
