@@ -430,11 +430,11 @@ void lda_sample_z_quad_kernel(
   // the kernel at 128 registers: four waves per SIMD instead of three, and the
   // number of phi-row loads in flight is what bounds this kernel (measured on
   // K=200: 4.13 ms with theta in registers, 3.12 ms this way).  Below nine stripes, where
-  // the register limit is set by the waves-per-SIMD hint, which is faster depends on what the
-  // compiler makes of each stripe count (75M tokens, z step, registers against LDS: K = 40
-  // 1.13 / 1.07 ms, K = 64 1.31 / 1.25, K = 80 1.53 / 1.57, K = 96 1.64 / 1.70, K = 100
-  // 2.02 / 1.95, K = 128 2.12 / 2.17).
-  constexpr bool kThetaRegs = NS16 <= 2 || NS16 == 5 || NS16 == 6 || NS16 == 8;
+  // the register limit is set by the waves-per-SIMD hint, registers are a little faster except
+  // at seven stripes, where they spill (75M tokens, z step, registers against LDS: K = 40
+  // 0.94 / 0.98 ms, K = 64 1.10 / 1.11, K = 80 1.34 / 1.37, K = 96 1.48 / 1.48, K = 100
+  // 1.89 / 1.69, K = 128 1.86 / 1.92).
+  constexpr bool kThetaRegs = NS16 <= 8 && NS16 != 7;
   float4 th[kThetaRegs ? NS16 : 1];
 #pragma unroll
   for (int c = 0; c < NS16; ++c) {
