@@ -24,9 +24,9 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 # the factors a plain 1 GiB copy shows for the same counters (reads x 2.0, writes x 1.0); the
 # runs and figures are in profiles/lda_large_and_medium_kernel_trace_and_hbm_traffic.md.  None for workloads
 # that have not been measured.
-MEASURED_TRAFFIC_BYTES = {"large": (7_019_758 * 2.0 + 951_364 * 1.0) * 1024,
-                          "medium": (75_429 * 2.0 + 29_010 * 1.0) * 1024,
-                          "widek": (6_890_064 * 2.0 + 159_777 * 1.0) * 1024}
+MEASURED_TRAFFIC_BYTES = {"large": (7_112_850 * 2.0 + 1_503_585 * 1.0) * 1024,
+                          "medium": (75_375 * 2.0 + 26_395 * 1.0) * 1024,
+                          "widek": (6_892_705 * 2.0 + 159_196 * 1.0) * 1024}
 
 
 def sample_z_algorithmic_bytes(N, D, K):
