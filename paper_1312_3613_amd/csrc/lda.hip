@@ -164,8 +164,9 @@ __global__ __launch_bounds__(256) void lda_init_z_kernel(int32_t* __restrict__ z
 // the chunk sums of each stripe with DPP and carries the stripe totals, which gives
 // every chunk the running sum before it.  Each lane then finds the first of its
 // chunks that the threshold falls into (a chunk of zero mass never qualifies).
-// Pass 2 reloads that one chunk (16 bytes of the phi row, a cache hit, and of theta),
-// repeats the same three multiply-adds, which give the same bits, and locates the
+// Pass 2 takes that one chunk again (16 bytes of the phi row: from the registers that
+// still hold the row up to ten stripes, by a second load, a cache hit, beyond; and of
+// theta from LDS), repeats the same three multiply-adds, which give the same bits, and locates the
 // topic inside it; the row takes the minimum candidate index.  Keeping the products of
 // all stripes instead (and theta in registers) needs 256 registers a lane, one wave
 // per SIMD; this form needs half and the loads of several waves overlap.
@@ -375,8 +376,9 @@ void lda_sample_z_kernel(
 // Pass 1 keeps only the running stripe totals cum[c] (a quad-wide sum needs two
 // DPP adds and gives all four lanes the same bits).  With S = cum[last] and
 // t = u S the crossing stripe c* = #{c : cum[c] <= t} is found by comparing
-// registers.  Pass 2 reloads the 64 bytes of stripe c* (an L1 hit) and the
-// matching chunk of theta_d from LDS, rebuilds that stripe's running sums and
+// registers.  Pass 2 selects the 64 bytes of stripe c* from the registers that still
+// hold the row (loading them again, although an L1 hit, made every wave wait once more
+// per iteration), takes the matching chunk of theta_d from LDS, rebuilds that stripe's running sums and
 // finds the topic.  Against the 16-lane form this removes the per-stripe
 // 16-lane scans and all but one of the per-stripe searches: about a third of
 // the vector instructions per token.
