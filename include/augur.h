@@ -8,7 +8,9 @@
  * Conventions (all entry points)
  *   - Return value: AUGUR_OK (0) or a negative AUGUR_ERR_* code.  Nothing throws
  *     or aborts.  augur_last_error() gives the message of the last failing call
- *     on the calling thread.
+ *     on the calling thread.  A failing HIP call is reported through the return
+ *     value only: its error is cleared from the runtime's own per-thread state,
+ *     so that the caller's next HIP call does not find it there.
  *   - Data pointers are HOST pointers unless the handle was created with
  *     AUGUR_PTRS_DEVICE in config.flags, in which case every data pointer passed
  *     to create/get_x/set_x of that handle is a DEVICE pointer on config.device.
@@ -121,6 +123,10 @@ int augur_lda_step_finish(augur_lda* h);
  * conditional had zero or non-finite mass. */
 int augur_lda_loglik(augur_lda* h, double* log_joint, double* log_marginal_w);
 
+/* The state is the paper's `sig` bundle (Sect. 2.2, Fig. 3): the caller passes
+ * initial values of the latent variables in it and reads the results back from
+ * it.  get_state copies z int32[N], theta float[D][K], phi float[V][K] and the
+ * number of completed sweeps out; set_state copies them in. */
 int augur_lda_get_state(augur_lda* h, int32_t* z, float* theta, float* phi, int64_t* sweep);
 /* Any of z/theta/phi may be NULL (left as is); sweep < 0 leaves the index.
  * Setting z recomputes the counts.  z[i] must lie in [0,K). */
@@ -130,6 +136,26 @@ int augur_lda_get_counts(augur_lda* h, int32_t* n_dk, int32_t* n_wk);
 /* Number of tokens, over all sweeps so far, whose conditional was degenerate. */
 int augur_lda_get_degenerate(augur_lda* h, int64_t* count);
 int augur_lda_sync(augur_lda* h);
+
+/* ------------------------------------------------------------- measurement
+ * Not part of the sampler: the ceilings its kernels are held against, measured on
+ * the same device in the same run (the measurement protocol asks for the
+ * achievable bandwidths beside the achieved ones).  Both calls time with events on
+ * the stream they are given and synchronise it.
+ *
+ * probe_gather: the memory side of the z step of Sect. 4.2 alone: the handle's own
+ * word-id stream and phi table, walked and loaded exactly as the z kernel does
+ * it, with no random numbers, arithmetic or stores; one warm-up pass, then reps
+ * timed passes; *ms_per_pass is their mean duration.  State is not changed.
+ *
+ * probe_stream_copy: reps plain device copies of `bytes` bytes (a multiple of 16;
+ * src and dst are 16-byte aligned DEVICE buffers of that size, owned by the
+ * caller); *ms_per_copy is the mean duration of one copy, which reads and writes
+ * `bytes` each.  Also the launch of known size that scales a profiler's byte
+ * counters. */
+int augur_lda_probe_gather(augur_lda* h, int32_t reps, double* ms_per_pass);
+int augur_probe_stream_copy(const void* src, void* dst, int64_t bytes, int32_t reps, void* stream,
+                            double* ms_per_copy);
 
 /* ------------------------------------------------ Gaussian mixture (supplement)
  * pi ~ Dirichlet(alpha 1_K), mu_k ~ N(0, prior_sd^2 I), z_i ~ Categorical(pi),
@@ -174,6 +200,7 @@ int augur_gmm_step_stats(augur_gmm* h);
 int augur_gmm_step_resample(augur_gmm* h);
 int augur_gmm_step_finish(augur_gmm* h);
 int augur_gmm_loglik(augur_gmm* h, double* log_joint);
+/* The mixture's `sig` bundle (Sect. 2.2, Fig. 3), as for LDA. */
 int augur_gmm_get_state(augur_gmm* h, int32_t* z, float* pi, float* mu, int64_t* sweep);
 int augur_gmm_set_state(augur_gmm* h, const int32_t* z, const float* pi, const float* mu,
                         int64_t sweep);

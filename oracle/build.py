@@ -20,5 +20,18 @@ def build(force: bool = True) -> str:
     return LIB
 
 
+SAN_LIB = os.path.join(HERE, "liboracle_sanitized.so")
+
+
+def build_sanitized() -> str:
+    """The same source with AddressSanitizer and UndefinedBehaviorSanitizer (CPU only), for the
+    test that runs the small sweeps under them; a finding aborts the process."""
+    cmd = ["g++", "-std=c++17", "-O1", "-g", "-ffp-contract=off", "-fPIC", "-shared",
+           "-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-fno-omit-frame-pointer",
+           "-Wall", "-Wextra", "-o", SAN_LIB, SRC]
+    subprocess.run(cmd, check=True)
+    return SAN_LIB
+
+
 if __name__ == "__main__":
     print(build())

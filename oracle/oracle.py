@@ -23,9 +23,11 @@ def _p(a, ct):
 def lib():
     global _LIB
     if _LIB is None:
-        path = _build.LIB
-        if not os.path.exists(path) or os.path.getmtime(path) < os.path.getmtime(_build.SRC):
-            _build.build()
+        path = os.environ.get("AUGUR_ORACLE_LIB")   # e.g. the sanitizer build, made by its test
+        if not path:
+            path = _build.LIB
+            if not os.path.exists(path) or os.path.getmtime(path) < os.path.getmtime(_build.SRC):
+                _build.build()
         L = C.CDLL(path)
         L.orc_uniform24.restype = C.c_double
         L.orc_uniform24.argtypes = [C.c_uint32]

@@ -46,11 +46,13 @@ class MhRegConfig(C.Structure):
 
 
 def lib():
-    """Load libaugur_hip.so (building it first only if it does not exist)."""
+    """Load libaugur_hip.so, building it first if it is absent or was built from other sources
+    than the ones present (a digest of the sources is kept beside the library).  A failed build
+    raises: a library older than its sources is never loaded."""
     global _LIB
     if _LIB is None:
-        if not os.path.exists(_build.LIB):
-            _build.build()
+        if _build.stale():
+            _build.build(force=True)
         if not os.path.exists(_build.LIB):
             raise RuntimeError("HIP library libaugur_hip.so is missing and could not be built")
         # One HIP runtime per process: torch ships its own libamdhip64 (same soname as the
@@ -80,6 +82,8 @@ def lib():
         L.augur_lda_set_state.argtypes = [vp, vp, vp, vp, C.c_int64]
         L.augur_lda_get_counts.argtypes = [vp, vp, vp]
         L.augur_lda_get_degenerate.argtypes = [vp, C.POINTER(C.c_int64)]
+        L.augur_lda_probe_gather.argtypes = [vp, C.c_int32, C.POINTER(C.c_double)]
+        L.augur_probe_stream_copy.argtypes = [vp, vp, C.c_int64, C.c_int32, vp, C.POINTER(C.c_double)]
         L.augur_gmm_create.argtypes = [C.POINTER(GmmConfig), vp, C.POINTER(vp)]
         L.augur_gmm_destroy.argtypes = [vp]
         L.augur_gmm_destroy.restype = None
@@ -167,6 +171,17 @@ class _Arrays:
         return t
 
 
+def probe_stream_copy(src, dst, reps=10, stream=None):
+    """augur_probe_stream_copy on two equally sized torch CUDA tensors: ms per copy."""
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != nbytes:
+        raise ValueError("src and dst differ in size")
+    ms = C.c_double()
+    _check(lib().augur_probe_stream_copy(_ptr(src), _ptr(dst), nbytes, int(reps),
+                                         _stream_handle(stream), C.byref(ms)))
+    return ms.value
+
+
 class LDA:
     """augur_lda_* handle.  Method names are the ABI's."""
 
@@ -215,6 +230,11 @@ class LDA:
         _check(lib().augur_lda_sweep_profile(self._h, int(n), ms))
         return dict(zip(("sample_z", "count_accumulate", "resample_theta", "resample_phi", "sweep"),
                         list(ms)))
+
+    def probe_gather(self, reps=5):
+        ms = C.c_double()
+        _check(lib().augur_lda_probe_gather(self._h, int(reps), C.byref(ms)))
+        return ms.value
 
     def step_sample_z(self):
         _check(lib().augur_lda_step_sample_z(self._h))

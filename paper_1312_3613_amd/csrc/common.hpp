@@ -24,6 +24,7 @@ void set_error(const char* fmt, ...);
     if (e_ != hipSuccess) {                                                              \
       ::augur::set_error("%s failed: %s (%s:%d)", #expr, hipGetErrorString(e_), __FILE__, \
                          __LINE__);                                                      \
+      (void)hipGetLastError(); /* or the runtime hands it to the next caller */ \
       return AUGUR_ERR_HIP;                                                              \
     }                                                                                    \
   } while (0)

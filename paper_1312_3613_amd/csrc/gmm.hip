@@ -557,6 +557,10 @@ int augur_gmm_create(const augur_gmm_config* cfg, const float* x, augur_gmm** ou
   AUGUR_REQUIRE((int64_t)cfg->K * cfg->dim <= 4096 && cfg->dim <= 14,
                 "supported sizes: dim <= 14 and K * dim <= 4096 (got dim %d, K %d)", cfg->dim,
                 cfg->K);
+  // the z kernel keeps the means and two K-vectors as doubles in LDS: 8 (K dim + 2 K) bytes,
+  // which must fit the 64 KiB a workgroup may ask for
+  AUGUR_REQUIRE((int64_t)cfg->K * (cfg->dim + 2) <= 8192,
+                "supported sizes: K * (dim + 2) <= 8192 (got dim %d, K %d)", cfg->dim, cfg->K);
   const bool unknown_var = cfg->var_shape > 0.f;
   AUGUR_REQUIRE(std::isfinite(cfg->alpha) && cfg->alpha > 0.f && std::isfinite(cfg->prior_sd) &&
                     cfg->prior_sd > 0.f,
@@ -597,6 +601,7 @@ int augur_gmm_create(const augur_gmm_config* cfg, const float* x, augur_gmm** ou
     hipError_t e_ = (expr);                                                                 \
     if (e_ != hipSuccess) {                                                                 \
       set_error("%s failed: %s (%s:%d)", #expr, hipGetErrorString(e_), __FILE__, __LINE__); \
+      (void)hipGetLastError(); /* or the runtime hands it to the next caller */ \
       free_all(h);                                                                          \
       delete h;                                                                             \
       return AUGUR_ERR_HIP;                                                                 \
@@ -632,6 +637,7 @@ int augur_gmm_create(const augur_gmm_config* cfg, const float* x, augur_gmm** ou
   if (rc == AUGUR_OK) rc = launch_resample(h, 0);
   if (rc == AUGUR_OK && hipStreamSynchronize(h->stream) != hipSuccess) {
     set_error("initial sweep failed: %s", hipGetErrorString(hipGetLastError()));
+    (void)hipGetLastError();  // or the runtime hands the error to the next caller
     rc = AUGUR_ERR_HIP;
   }
   if (rc != AUGUR_OK) {
@@ -694,6 +700,7 @@ int augur_gmm_sweep_profile(augur_gmm* h, int32_t n_sweeps, double* ms) {
   auto fail_hip = [&](hipError_t e, const char* what) {
     if (e != hipSuccess && rc == AUGUR_OK) {
       set_error("%s failed: %s", what, hipGetErrorString(e));
+      (void)hipGetLastError();  // or the runtime hands the error to the next caller
       rc = AUGUR_ERR_HIP;
     }
     return e != hipSuccess;

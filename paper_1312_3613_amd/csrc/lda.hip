@@ -1,8 +1,8 @@
 // LDA (Fig. 1 of arXiv 1312.3613): the uncollapsed Gibbs sweep of Sect. 4.2 as
 // HIP kernels for gfx950, behind the augur_lda_* C ABI.
 //
-// Device layout (all row strides are ldk = K rounded up to a multiple of 4, so
-// every row starts 16-byte aligned; padding columns hold 0):
+// Device layout (all row strides are ldk = K rounded up to a multiple of 16, or of 64
+// above 256 topics, so every row starts 64- or 256-byte aligned; padding columns hold 0):
 //   w, z      int32[N]     doc-major
 //   doc_off   int64[D+1]
 //   theta     float[D][ldk]     n_dk int32[D][ldk]
@@ -373,23 +373,79 @@ void lda_sample_z_kernel(
 // 16; quad lane q holds topics 16 c + 4 q + {0..3} of stripe c, so a quad reads
 // 64 contiguous bytes of the phi row per load.
 //
-// Pass 1 keeps only the running stripe totals cum[c] (a quad-wide sum needs two
-// DPP adds and gives all four lanes the same bits).  With S = cum[last] and
-// t = u S the crossing stripe c* = #{c : cum[c] <= t} is found by comparing
-// registers.  Pass 2 selects the 64 bytes of stripe c* from the registers that still
-// hold the row (loading them again, although an L1 hit, made every wave wait once more
-// per iteration), takes the matching chunk of theta_d from LDS, rebuilds that stripe's running sums and
-// finds the topic.  Against the 16-lane form this removes the per-stripe
-// 16-lane scans and all but one of the per-stripe searches: about a third of
-// the vector instructions per token.
+// Pass 1 is one chain of multiply-adds per lane over all its topics; the value of the
+// chain after stripe c, a[c], is the lane's share of the running sum C at the end of
+// that stripe, and the sum of a[c] over the quad (two DPP adds; all four lanes get the
+// same bits) is C itself.  Only the last of these sums is formed outright: S, and
+// t = u S.  The crossing stripe c* = #{c : C(c) <= t} is then found by bisection over
+// c, which needs the quad sum of one a[.] per level (four levels for 16 stripes); the
+// a[.] wanted at a level is picked by the comparison masks of the levels before it.
+// The sums are non-decreasing in c (every product is >= 0 and rounding is monotone),
+// so bisection finds the same c* as a scan would.
+//
+// Pass 2 needs the 64 bytes of stripe c* of the row again, and theta's from LDS: it
+// rebuilds that stripe's running sums and finds the topic.  Those bytes are asked for
+// again (a cache hit or an L2 hit) as soon as c* is known, but not waited for: pass 2 of
+// an iteration runs in the next iteration, after the loads of that one have been
+// issued and before they are waited for.  So the row's registers die with pass 1, and no
+// wave waits for a second load.  (Keeping the row alive and selecting the chunk from the
+// registers cost 48 conditional moves a lane and iteration and the registers of a wave
+// per SIMD; loading it again and waiting on the spot cost one more wait.)
 //
 // The wave's LDS strip holds, for the 256 tokens of the current chunk, the
 // Philox word and the word id of each token, and theta_d padded with zeros to a
 // whole number of stripes.
 constexpr int kQpSwap1 = 0xB1;   // quad_perm [1,0,3,2]
 constexpr int kQpSwap2 = 0x4E;   // quad_perm [2,3,0,1]
-constexpr int kQpBcast0 = 0x00, kQpBcast1 = 0x55, kQpBcast2 = 0xAA;
+constexpr int kQpDown1 = 0x90;   // quad_perm [0,0,1,2]: lane q reads lane q - 1 (lane 0 itself)
+constexpr int kQpDown2 = 0x44;   // quad_perm [0,1,0,1]: lane q reads lane q - 2 (lanes 0, 1 themselves)
 constexpr int kNoTopic = 0x7FFFFFFF;
+
+__device__ __forceinline__ float quad_sum(float s) {
+  s += dpp_f32<kQpSwap1>(s);
+  s += dpp_f32<kQpSwap2>(s);
+  return s;
+}
+
+// Bisection over the M = NS16 - 1 stripe ends before the last one (if none of them
+// exceeds t the crossing stripe is the last).  A level has a step s (a power of two);
+// with p the number of stripes already known to lie at or below t, it tests stripe
+// p + s - 1.  p is different in every quad, so the value is picked from the
+// compile-time candidates {s - 1, 3 s - 1, 5 s - 1, ...} by the masks of the levels above
+// (m[j] belongs to step 2^j): a tree of conditional moves, one fewer than candidates.
+// Candidates past the end count as +infinity (never at or below t).
+template <int NS16, int STEP, int HS, int P>
+__device__ __forceinline__ float pick_stripe_end(const float (&a)[NS16], const bool (&m)[5]) {
+  if constexpr (HS == STEP) {
+    constexpr int idx = P + STEP - 1;
+    if constexpr (idx < NS16 - 1) return a[idx];
+    else return INFINITY;
+  } else {
+    constexpr int idx_lo = P + STEP - 1;  // the smallest candidate below this node
+    if constexpr (idx_lo >= NS16 - 1) {
+      return INFINITY;  // every candidate of this subtree is past the end
+    } else {
+      constexpr int bit = HS == 16 ? 4 : HS == 8 ? 3 : HS == 4 ? 2 : 1;  // log2(HS); HS >= 2 here
+      const float lo = pick_stripe_end<NS16, STEP, HS / 2, P>(a, m);
+      const float hi = pick_stripe_end<NS16, STEP, HS / 2, P + HS>(a, m);
+      return m[bit] ? hi : lo;
+    }
+  }
+}
+template <int NS16, int STEP, int TOP>
+__device__ __forceinline__ void bisect_level(const float (&a)[NS16], float t, bool (&m)[5], int& pos,
+                                             float& cprev) {
+  constexpr int bit = STEP == 16 ? 4 : STEP == 8 ? 3 : STEP == 4 ? 2 : STEP == 2 ? 1 : 0;
+  float x;
+  if constexpr (STEP == TOP) x = pick_stripe_end<NS16, STEP, STEP, 0>(a, m);
+  else x = pick_stripe_end<NS16, STEP, TOP, 0>(a, m);
+  const float qs = quad_sum(x);
+  const bool below = qs <= t;
+  m[bit] = below;
+  pos += below ? STEP : 0;
+  cprev = below ? qs : cprev;
+  if constexpr (STEP > 1) bisect_level<NS16, STEP / 2, TOP>(a, t, m, pos, cprev);
+}
 
 //
 // With kCountDocs the wave also builds its document's row of n_dk in LDS while it
@@ -398,12 +454,12 @@ constexpr int kNoTopic = 0x7FFFFFFF;
 // to the row, which the host zeroes before the launch).
 //
 // Waves per SIMD: the kernel waits on its row loads, so a wave more per SIMD pays even when
-// the register limit that buys it spills a few values: the compiler's own choice sits 2 to 4
-// registers above a limit at 3, 5, 7 and 8 stripes.  Measured on 75M tokens, z step: K = 40,
-// 6 waves 1.13 against 1.24 ms; K = 80, 5 waves 1.51 against 1.71; K = 100, 5 waves 2.00 against
-// 2.38 (3 waves); K = 128, 4 waves 2.11 against 2.50 (3 waves), 5 waves 2.20.
+// the register limit that buys it spills a few values.
+template <int NS16>
+constexpr int quad_waves_per_simd() { return NS16 > 10 ? 4 : NS16 > 6 ? 5 : NS16 > 3 ? 6 : 8; }
+
 template <int NS16, bool kCountDocs>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NS16 > 7 ? 4 : NS16 > 4 ? 5 : 6)))
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(quad_waves_per_simd<NS16>())))
 void lda_sample_z_quad_kernel(
     const int32_t* __restrict__ w, const int64_t* __restrict__ doc_off,
     const int32_t* __restrict__ seg_base, int n_segs, const float* __restrict__ theta,
@@ -413,8 +469,11 @@ void lda_sample_z_quad_kernel(
   __shared__ uint2 strip_all[4][256];            // {Philox word, word id} per token of the chunk
   __shared__ __align__(16) float theta_all[4][16 * NS16];
   __shared__ int32_t hist_all[kCountDocs ? 4 : 1][kCountDocs ? 16 * NS16 : 1];
+  __shared__ __align__(4) uint8_t zstage_all[4][256];  // the topics drawn for the current chunk
   const int lane = threadIdx.x & 63;
-  const int wave = threadIdx.x >> 6;
+  // the wave's number is the same in all its lanes: saying so keeps everything that follows
+  // from it (the segment, its offsets, the loop bounds) in scalar registers
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
   const int seg = blockIdx.x * 4 + wave;
   if (seg >= n_segs) return;
   const Segment sg = segment_of(doc_off, seg_base, D, seg);
@@ -423,176 +482,291 @@ void lda_sample_z_quad_kernel(
   uint2* strip = strip_all[wave];
   float* theta_s = theta_all[wave];
   int32_t* hist = hist_all[kCountDocs ? wave : 0];
+  uint8_t* zstage = zstage_all[wave];
   if (kCountDocs)
     for (int k = lane; k < 16 * NS16; k += 64) hist[k] = 0;
 
-  // theta_d: LDS copy for the dynamically indexed read of pass 2.  For pass 1 it
-  // sits in registers when the row is short; for long rows pass 1 reads it from
-  // LDS too (all quads read the same 16 bytes per lane: a broadcast), which keeps
-  // the kernel at 128 registers: four waves per SIMD instead of three, and the
-  // number of phi-row loads in flight is what bounds this kernel (measured on
-  // K=200: 4.13 ms with theta in registers, 3.12 ms this way).  Below nine stripes, where
-  // the register limit is set by the waves-per-SIMD hint, registers are a little faster except
-  // at seven stripes, where they spill (75M tokens, z step, registers against LDS: K = 40
-  // 0.94 / 0.98 ms, K = 64 1.10 / 1.11, K = 80 1.34 / 1.37, K = 96 1.48 / 1.48, K = 100
-  // 1.89 / 1.69, K = 128 1.86 / 1.92).
-  constexpr bool kThetaRegs = NS16 <= 8 && NS16 != 7;
-  float4 th[kThetaRegs ? NS16 : 1];
+  // theta_d in the wave's LDS strip, zero past the last topic.  Pass 1 reads it from there
+  // (all quads read the same 16 bytes per lane: a broadcast), which keeps the registers for
+  // the row loads in flight: their number is what bounds this kernel.
 #pragma unroll
   for (int c = 0; c < NS16; ++c) {
     const int col = 16 * c + 4 * q;
     const float4 v = col < ldk ? *reinterpret_cast<const float4*>(theta + (size_t)d * ldk + col)
                                : make_float4(0.f, 0.f, 0.f, 0.f);
-    if (kThetaRegs) th[c] = v;
     if (tq == 0) *reinterpret_cast<float4*>(theta_s + col) = v;
   }
   const uint32_t row_bytes = 4u * (uint32_t)ldk;
   const uint32_t lane_off = 16u * (uint32_t)q;
   const uint32_t last_off = min(64u * (NS16 - 1) + lane_off, row_bytes - 16u);
   const char* phi_bytes = reinterpret_cast<const char*>(phi);
+  const float* theta_q = theta_s + 4 * q;
+  const float from1 = q >= 1 ? 1.f : 0.f, from2 = q >= 2 ? 1.f : 0.f;  // see the scan in pass 2
+  // Tokens are addressed relative to the segment's first chunk base (an int: a segment has at
+  // most kSegTokens + 3 positions).
+  const int32_t* w_seg = w + sg.first;
+  int32_t* z_seg = z + sg.first;
+  uint8_t* zb_seg = zb + sg.first;
+  const int rel_a = (int)(sg.a - sg.first);  // 0..3: the first token of the document
+  const int rel_b = (int)(sg.end - sg.first);
 
-  const int64_t a = sg.a, b = sg.end;
-  for (int64_t base = sg.first; base < b; base += 256) {
+  // What pass 2 of a token needs, carried from the iteration that ran its pass 1.
+  struct Pending {
+    float4 p2;          // the lane's chunk of the crossing stripe (load in flight)
+    float t, cprev;     // threshold; running sum before the crossing stripe
+    int cs;             // crossing stripe
+    uint32_t r, row_off;
+    int rel;            // position of the token in the segment, or -1 for a quad without a token
+    bool ok, in_row;    // S positive and finite; t < S
+  };
+  auto finish = [&](const Pending& P) {
+    const bool valid = P.rel >= 0;
+    const int cs = P.cs;
+    const float4 t2 = *reinterpret_cast<const float4*>(theta_q + 16 * cs);
+    const float l0 = t2.x * P.p2.x;
+    const float l1 = fmaf(t2.y, P.p2.y, l0);
+    const float l2 = fmaf(t2.z, P.p2.z, l1);
+    const float l3 = fmaf(t2.w, P.p2.w, l2);
+    // sum of the chunks of the quad's lower lanes: an inclusive scan over the quad in two
+    // steps (a lane takes the value one, then two, lanes down; lanes without such a neighbour
+    // multiply what they get by 0), then moved up by one lane
+    float incl = fmaf(dpp_mov_f32<kQpDown1>(l3), from1, l3);
+    incl = fmaf(dpp_mov_f32<kQpDown2>(incl), from2, incl);
+    const float excl = dpp_mov_f32<kQpDown1>(incl) * from1;
+    const float tt = fmaxf(P.t - (P.cprev + excl), 0.f);
+    const int e = (l0 <= tt) + (l1 <= tt) + (l2 <= tt);
+    int cand = l3 > tt ? 4 * q + e : kNoTopic;
+    cand = min(cand, dpp_i32_keep<kQpSwap1>(cand));
+    cand = min(cand, dpp_i32_keep<kQpSwap2>(cand));
+    int k = 16 * cs + cand;
+
+    const bool found = P.in_row && cand != kNoTopic;
+    if (__builtin_expect(__any(valid && !(P.ok && found)), 0)) {
+      if (!P.ok) {
+        // zero or non-finite mass: z = floor(u K)
+        k = u24_times(P.r, K);
+        if (valid && q == 0) atomicAdd(n_degenerate, 1ULL);
+      } else if (!found) {
+        // rounding put t at or past the running sum that should exceed it: the
+        // last topic of positive mass in the crossing stripe (or overall)
+        const int limit = P.in_row ? 16 * (cs + 1) : 16 * NS16;
+        int last = -1;
+#pragma unroll 1
+        for (int c = 0; c < NS16; ++c) {  // rare: kept small, nothing precomputed outside
+          const uint32_t o = min(64u * (uint32_t)c + lane_off, row_bytes - 16u);
+          const float4 pp = *reinterpret_cast<const float4*>(phi_bytes + (P.row_off + o));
+          const float4 tp = *reinterpret_cast<const float4*>(theta_q + 16 * c);
+          const int kk = 16 * c + 4 * q;
+          if (kk < limit) {
+            if (tp.x * pp.x > 0.f) last = kk;
+            if (tp.y * pp.y > 0.f) last = kk + 1;
+            if (tp.z * pp.z > 0.f) last = kk + 2;
+            if (tp.w * pp.w > 0.f) last = kk + 3;
+          }
+        }
+        last = max(last, dpp_i32_keep<kQpSwap1>(last));
+        last = max(last, dpp_i32_keep<kQpSwap2>(last));
+        k = last;
+      }
+    }
+    // garbage parameters (negative or NaN entries) must not yield an index outside the tables
+    k = min(max(k, 0), K - 1);
+    if (valid && q == 0) {
+      zstage[P.rel & 255] = (uint8_t)k;  // K <= 256 here; stored to z and zb a chunk at a time
+      if (kCountDocs) atomicAdd(&hist[k], 1);
+    }
+  };
+  // Stores the staged topics of the chunk at rbase (tokens lo..hi-1 of the segment): lane L takes
+  // tokens rbase + 4 L .. + 3, so z leaves as one 16-byte and zb as one 4-byte store per lane
+  // instead of a 4-byte and a 1-byte store per token (a store instruction of 16 lanes costs the
+  // address path as much as one of 64).  Tokens outside lo..hi-1 belong to other waves: the
+  // lanes at the two ends store element by element.
+  auto flush_chunk = [&](int rbase, int lo, int hi) {
+    wave_lds_fence();
+    const int r0 = rbase + 4 * lane;
+    const uint32_t four = *reinterpret_cast<const uint32_t*>(zstage + 4 * lane);
+    const int k0 = (int)(four & 255u), k1 = (int)((four >> 8) & 255u), k2 = (int)((four >> 16) & 255u),
+              k3 = (int)(four >> 24);
+    if (r0 >= lo && r0 + 4 <= hi) {
+      *reinterpret_cast<int4*>(z_seg + r0) = make_int4(k0, k1, k2, k3);
+      *reinterpret_cast<uint32_t*>(zb_seg + r0) = four;
+    } else {
+      if (r0 + 0 >= lo && r0 + 0 < hi) { z_seg[r0 + 0] = k0; zb_seg[r0 + 0] = (uint8_t)k0; }
+      if (r0 + 1 >= lo && r0 + 1 < hi) { z_seg[r0 + 1] = k1; zb_seg[r0 + 1] = (uint8_t)k1; }
+      if (r0 + 2 >= lo && r0 + 2 < hi) { z_seg[r0 + 2] = k2; zb_seg[r0 + 2] = (uint8_t)k2; }
+      if (r0 + 3 >= lo && r0 + 3 < hi) { z_seg[r0 + 3] = k3; zb_seg[r0 + 3] = (uint8_t)k3; }
+    }
+    wave_lds_fence();  // before the next chunk's topics overwrite the stage
+  };
+
+  // at the start of a chunk: a quad without a token, which pass 2 runs through idly
+  Pending P;
+  auto idle = [&]() {
+    P.p2 = make_float4(0.f, 0.f, 0.f, 0.f);
+    P.t = 0.f;
+    P.cprev = 0.f;
+    P.cs = 0;
+    P.r = 0u;
+    P.row_off = 0u;
+    P.rel = -1;
+    P.ok = true;
+    P.in_row = true;
+  };
+  for (int rbase = 0; rbase < rel_b; rbase += 256) {
+    idle();
     {
-      // tokens base + 4 lane .. + 3: one Philox block and four word ids (w is
+      // tokens rbase + 4 lane .. + 3 of the segment: one Philox block and four word ids (w is
       // padded by 256 entries, so the vector load never leaves the allocation)
-      const U4 r = random_block(seed, (uint64_t)(base >> 2) + (uint64_t)lane, sweep, kStreamZ, 0);
-      const int4 wv = *reinterpret_cast<const int4*>(w + base + 4 * lane);
+      const U4 r = random_block(seed, (uint64_t)((sg.first + rbase) >> 2) + (uint64_t)lane, sweep,
+                                kStreamZ, 0);
+      const int4 wv = *reinterpret_cast<const int4*>(w_seg + rbase + 4 * lane);
       wave_lds_fence();  // earlier reads of the strip are done
       uint4* dst = reinterpret_cast<uint4*>(strip + 4 * lane);
       dst[0] = make_uint4(r.x, (uint32_t)wv.x, r.y, (uint32_t)wv.y);
       dst[1] = make_uint4(r.z, (uint32_t)wv.z, r.w, (uint32_t)wv.w);
       wave_lds_fence();
     }
-    const int64_t lo = a > base ? a : base;
-    const int64_t hi = b < base + 256 ? b : base + 256;
+    const int lo = max(rel_a, rbase);
+    const int hi = min(rel_b, rbase + 256);
 
-    // One token per quad.  (A two-register-set software pipeline of this loop
-    // was tried: it costs a wave of occupancy and ran slower.)
-    struct Tok {
+    for (int i0 = lo; i0 < hi; i0 += 16) {
+      // this iteration's token of the quad and the loads of its row
+      const int i = i0 + tq;
+      const bool valid = i < hi;
+      const uint2 rw = strip[(valid ? i : lo) - rbase];
+      const uint32_t row_off = __umul24(rw.y, row_bytes);  // both below 2^24; product below 2^32
+      const char* rowp = phi_bytes + (size_t)(row_off + lane_off);  // constant offsets fold into the loads
       float4 ph[NS16];
-      uint32_t r, row_off;
-      int64_t i;
-      bool valid;
-    };
-    auto fetch = [&](Tok& T, int64_t i0) {
-      T.i = i0 + tq;
-      T.valid = T.i < hi;
-      const uint2 rw = strip[T.valid ? (int)(T.i - base) : (int)(lo - base)];
-      T.r = rw.x;
-      T.row_off = __umul24(rw.y, row_bytes);  // both below 2^24; product below 2^32
-      const char* rowp = phi_bytes + (size_t)(T.row_off + lane_off);  // constant offsets fold into the loads
 #pragma unroll
-      for (int c = 0; c < NS16 - 1; ++c) T.ph[c] = *reinterpret_cast<const float4*>(rowp + 64 * c);
-      T.ph[NS16 - 1] = *reinterpret_cast<const float4*>(phi_bytes + (T.row_off + last_off));
-    };
-    auto draw = [&](const Tok& T) {
-      // pass 1: running stripe totals
+      for (int c = 0; c < NS16 - 1; ++c) ph[c] = *reinterpret_cast<const float4*>(rowp + 64 * c);
+      ph[NS16 - 1] = *reinterpret_cast<const float4*>(phi_bytes + (row_off + last_off));
+
+      // pass 2 of the previous iteration, while those loads are on their way.  The empty asm
+      // statement keeps the compiler from starting it (and waiting for its chunk) before the
+      // loads above have been issued: everything in pass 2 follows from the stripe number.
+      asm volatile("" : "+v"(P.cs)::"memory");
+      finish(P);
+
+      // pass 1: the lane's chain; a[c] = its value after stripe c.  theta_d does not change
+      // inside the loop, so the compiler would read all of it once and keep it in registers;
+      // an offset it cannot see through keeps the LDS reads (and four waves more per CU) here.
       int theta_off = 4 * q;
-      if (!kThetaRegs) asm volatile("" : "+v"(theta_off));  // keep the LDS reads inside the loop
-      const float* theta_q = theta_s + theta_off;
-      float cum[NS16];
-      float run = 0.f;
+      asm volatile("" : "+v"(theta_off));
+      const float* theta_p1 = theta_s + theta_off;
+      float ac[NS16];
+      float acc = 0.f;
 #pragma unroll
       for (int c = 0; c < NS16; ++c) {
-        const float4 tc = kThetaRegs ? th[kThetaRegs ? c : 0]
-                                     : *reinterpret_cast<const float4*>(theta_q + 16 * c);
-        float s = tc.x * T.ph[c].x;
-        s = fmaf(tc.y, T.ph[c].y, s);
-        s = fmaf(tc.z, T.ph[c].z, s);
-        s = fmaf(tc.w, T.ph[c].w, s);
-        s += dpp_f32<kQpSwap1>(s);
-        s += dpp_f32<kQpSwap2>(s);
-        run += s;
-        cum[c] = run;
+        const float4 tc = *reinterpret_cast<const float4*>(theta_p1 + 16 * c);
+        acc = c == 0 ? tc.x * ph[c].x : fmaf(tc.x, ph[c].x, acc);
+        acc = fmaf(tc.y, ph[c].y, acc);
+        acc = fmaf(tc.z, ph[c].z, acc);
+        acc = fmaf(tc.w, ph[c].w, acc);
+        ac[c] = acc;
       }
-      const float S = run;
-      const float t = u24(T.r) * S;
-
-      // crossing stripe and the total before it
-      int cstar = 0;
+      const float S = quad_sum(ac[NS16 - 1]);
+      const float t = u24(rw.x) * S;
+      int cs = 0;
       float cprev = 0.f;
-#pragma unroll
-      for (int c = 0; c < NS16; ++c) {
-        const bool below = cum[c] <= t;
-        cstar += below ? 1 : 0;
-        cprev = below ? cum[c] : cprev;
+      if constexpr (NS16 > 1) {
+        constexpr int M = NS16 - 1;
+        constexpr int TOP = M >= 8 ? 8 : M >= 4 ? 4 : M >= 2 ? 2 : 1;
+        bool m[5] = {false, false, false, false, false};
+        bisect_level<NS16, TOP, TOP>(ac, t, m, cs, cprev);
       }
-
-      // pass 2: the 16 topics of stripe c*
-      const int cs = min(cstar, NS16 - 1);
-      float4 p2 = T.ph[0];  // the stripe's chunk is still in registers: select it, no second load
-#pragma unroll
-      for (int c = 1; c < NS16; ++c) {
-        const bool sel = cs == c;
-        p2.x = sel ? T.ph[c].x : p2.x;
-        p2.y = sel ? T.ph[c].y : p2.y;
-        p2.z = sel ? T.ph[c].z : p2.z;
-        p2.w = sel ? T.ph[c].w : p2.w;
-      }
-      const float4 t2 = *reinterpret_cast<const float4*>(theta_s + 16 * cs + 4 * q);
-      const float l0 = t2.x * p2.x;
-      const float l1 = fmaf(t2.y, p2.y, l0);
-      const float l2 = fmaf(t2.z, p2.z, l1);
-      const float l3 = fmaf(t2.w, p2.w, l2);
-      const float b0 = dpp_mov_f32<kQpBcast0>(l3);
-      const float b01 = b0 + dpp_mov_f32<kQpBcast1>(l3);
-      const float b012 = b01 + dpp_mov_f32<kQpBcast2>(l3);
-      const float excl = q == 0 ? 0.f : q == 1 ? b0 : q == 2 ? b01 : b012;
-      const float tt = fmaxf(t - (cprev + excl), 0.f);
-      const int e = (l0 <= tt) + (l1 <= tt) + (l2 <= tt);
-      int cand = l3 > tt ? 4 * q + e : kNoTopic;
-      cand = min(cand, dpp_i32_keep<kQpSwap1>(cand));
-      cand = min(cand, dpp_i32_keep<kQpSwap2>(cand));
-      int k = 16 * cs + cand;
-
-      const bool ok = S > 0.f && S <= FLT_MAX;  // false for 0, inf and NaN
-      const bool found = cstar < NS16 && cand != kNoTopic;
-      if (__builtin_expect(__any(T.valid && !(ok && found)), 0)) {
-        if (!ok) {
-          // zero or non-finite mass: z = floor(u K)
-          k = u24_times(T.r, K);
-          if (T.valid && q == 0) atomicAdd(n_degenerate, 1ULL);
-        } else if (!found) {
-          // rounding put t at or past the running sum that should exceed it: the
-          // last topic of positive mass in the crossing stripe (or overall)
-          const int limit = cstar < NS16 ? 16 * (cs + 1) : 16 * NS16;
-          int last = -1;
-          for (int c = 0; c < NS16; ++c) {
-            const uint32_t o = min(64u * (uint32_t)c + lane_off, row_bytes - 16u);
-            const float4 pp = *reinterpret_cast<const float4*>(phi_bytes + (T.row_off + o));
-            const float4 tp = *reinterpret_cast<const float4*>(theta_s + 16 * c + 4 * q);
-            const int kk = 16 * c + 4 * q;
-            if (kk < limit) {
-              if (tp.x * pp.x > 0.f) last = kk;
-              if (tp.y * pp.y > 0.f) last = kk + 1;
-              if (tp.z * pp.z > 0.f) last = kk + 2;
-              if (tp.w * pp.w > 0.f) last = kk + 3;
-            }
-          }
-          last = max(last, dpp_i32_keep<kQpSwap1>(last));
-          last = max(last, dpp_i32_keep<kQpSwap2>(last));
-          k = last;
-        }
-      }
-      // garbage parameters (negative or NaN entries) must not yield an index outside the tables
-      k = min(max(k, 0), K - 1);
-      if (T.valid && q == 0) {
-        z[T.i] = k;
-        zb[T.i] = (uint8_t)k;  // K <= 256 here
-        if (kCountDocs) atomicAdd(&hist[k], 1);
-      }
-    };
-
-    for (int64_t i0 = lo; i0 < hi; i0 += 16) {
-      Tok A;
-      fetch(A, i0);
-      draw(A);
+      // the chunk of stripe cs again, for pass 2 in the next iteration
+      P.p2 = *reinterpret_cast<const float4*>(
+          phi_bytes + (row_off + min(64u * (uint32_t)cs + lane_off, row_bytes - 16u)));
+      P.t = t;
+      P.cprev = cprev;
+      P.cs = cs;
+      P.r = rw.x;
+      P.row_off = row_off;
+      P.rel = valid ? i : -1;
+      P.ok = S > 0.f && S <= FLT_MAX;  // false for 0, inf and NaN
+      P.in_row = S > t;
     }
+    finish(P);  // the chunk's last iteration
+    flush_chunk(rbase, lo, hi);
   }
   if (kCountDocs) {
     wave_lds_fence();
     flush_doc_histogram(hist, n_dk + (size_t)d * ldk, ldk, is_split(seg_base, d), lane);
+  }
+}
+
+// ------------------------------------------------- gather probe (measurement)
+// The memory side of the z step alone: the same walk over documents and tokens, the same
+// word-id stream and the same loads of phi rows (a quad per token reading 64 bytes a load
+// up to 256 topics, a 16-lane row reading 256 bytes a load beyond), with no random
+// numbers, no arithmetic and no stores.  Its duration is the floor that the memory
+// system sets for any z kernel of this load shape on this corpus; the sampler is held
+// against it.  The loaded registers are handed to an empty asm statement, which makes
+// the compiler wait for every load without spending an instruction on the values.
+template <int NS16>
+__global__ __launch_bounds__(256) void lda_gather_probe_quad_kernel(
+    const int32_t* __restrict__ w, const int64_t* __restrict__ doc_off,
+    const int32_t* __restrict__ seg_base, int n_segs, const float* __restrict__ phi, int D, int ldk) {
+  __shared__ uint32_t strip_all[4][256];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int seg = blockIdx.x * 4 + wave;
+  if (seg >= n_segs) return;
+  const Segment sg = segment_of(doc_off, seg_base, D, seg);
+  const int tq = lane >> 2, q = lane & 3;
+  uint32_t* strip = strip_all[wave];
+  const uint32_t row_bytes = 4u * (uint32_t)ldk;
+  const uint32_t lane_off = 16u * (uint32_t)q;
+  const uint32_t last_off = min(64u * (NS16 - 1) + lane_off, row_bytes - 16u);
+  const char* phi_bytes = reinterpret_cast<const char*>(phi);
+  const int64_t a = sg.a, b = sg.end;
+  for (int64_t base = sg.first; base < b; base += 256) {
+    const int4 wv = *reinterpret_cast<const int4*>(w + base + 4 * lane);
+    wave_lds_fence();
+    *reinterpret_cast<int4*>(strip + 4 * lane) = wv;
+    wave_lds_fence();
+    const int64_t lo = a > base ? a : base;
+    const int64_t hi = b < base + 256 ? b : base + 256;
+    for (int64_t i0 = lo; i0 < hi; i0 += 16) {
+      const int64_t i = i0 + tq;
+      const uint32_t v = strip[i < hi ? (int)(i - base) : (int)(lo - base)];
+      const uint32_t row_off = __umul24(v, row_bytes);
+      const char* rowp = phi_bytes + (size_t)(row_off + lane_off);
+      float4 ph[NS16];
+#pragma unroll
+      for (int c = 0; c < NS16 - 1; ++c) ph[c] = *reinterpret_cast<const float4*>(rowp + 64 * c);
+      ph[NS16 - 1] = *reinterpret_cast<const float4*>(phi_bytes + (row_off + last_off));
+#pragma unroll
+      for (int c = 0; c < NS16; ++c)
+        asm volatile("" ::"v"(ph[c].x), "v"(ph[c].y), "v"(ph[c].z), "v"(ph[c].w));
+    }
+  }
+}
+template <int NS>
+__global__ __launch_bounds__(256) void lda_gather_probe_row_kernel(
+    const int32_t* __restrict__ w, const int64_t* __restrict__ doc_off,
+    const int32_t* __restrict__ seg_base, int n_segs, const float* __restrict__ phi, int D, int ldk) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int seg = blockIdx.x * 4 + wave;
+  if (seg >= n_segs) return;
+  const Segment sg = segment_of(doc_off, seg_base, D, seg);
+  const int row = lane >> 4, j = lane & 15;
+  const uint32_t lane_off = 16u * (uint32_t)j;
+  const uint32_t last_off = 4u * (uint32_t)min(64 * (NS - 1) + 4 * j, ldk - 4);
+  const char* phi_bytes = reinterpret_cast<const char*>(phi);
+  const uint32_t row_bytes = 4u * (uint32_t)ldk;
+  const int64_t lo = sg.first > sg.a ? sg.first : sg.a, hi = sg.end;
+  for (int64_t i0 = lo; i0 < hi; i0 += 4) {
+    const int64_t i = i0 + row;
+    const uint32_t v = (uint32_t)w[i < hi ? i : lo];
+    const uint32_t row_off = v * row_bytes;
+    const char* rowp = phi_bytes + (size_t)(row_off + lane_off);
+    float4 qv[NS];
+#pragma unroll
+    for (int m = 0; m < NS - 1; ++m) qv[m] = *reinterpret_cast<const float4*>(rowp + 256 * m);
+    qv[NS - 1] = *reinterpret_cast<const float4*>(phi_bytes + (size_t)(row_off + last_off));
+#pragma unroll
+    for (int m = 0; m < NS; ++m)
+      asm volatile("" ::"v"(qv[m].x), "v"(qv[m].y), "v"(qv[m].z), "v"(qv[m].w));
   }
 }
 
@@ -950,70 +1124,172 @@ __global__ __launch_bounds__(256) void lda_phi_write_kernel(const double* __rest
 // Per-token terms of the log joint (Sect. 4.1: log space, terms evaluated in
 // parallel and summed): ln theta[d][z_i] + ln phi[w_i][z_i], and
 // ln sum_k theta[d][k] phi[w_i][k] for the marginal.  One wave per segment
-// slot (a whole document unless it is split) with theta_d in LDS, a quad per token (64 contiguous bytes of the phi row
-// per load, as in the sampler), fp64 products and sums.
+// slot (a whole document unless it is split) with theta_d as doubles in LDS and a quad
+// per token, 64 contiguous bytes of the phi row per load: the load shape of the
+// sampler.  Every product is formed in fp64 from its two fp32 factors (exact: 24 + 24
+// bits) and all sums are fp64, so the result differs from a sum in any other order by
+// fp64 rounding only.  The three logarithms of a token are taken side by side by three
+// lanes of its quad with the table logarithm.
+//
+// NS16 > 0: that many stripes of 16 topics, unrolled (K <= 256); NS16 = 0: the
+// number of stripes is read at run time (K <= 1024).  Columns k >= K of theta and
+// phi rows (padding up to the row stride) are never used, whatever they hold.
+// Word ids and topics are clamped into their tables, so that arrays that were
+// never validated cannot make the kernel read outside them.
+__device__ __forceinline__ double log_any(double x, const double2* __restrict__ lt) {
+  // the table logarithm needs a positive, finite, normal argument; zero, negative,
+  // non-finite and subnormal ones (degenerate states only) take the general routine
+  if (__builtin_expect(!(x >= DBL_MIN && x <= DBL_MAX), 0)) return log(x);
+  return log_tab(x, lt);
+}
+template <int NS16>
 __global__ __launch_bounds__(256) void lda_loglik_tokens_kernel(
     const int32_t* __restrict__ w, const int32_t* __restrict__ z,
     const int64_t* __restrict__ doc_off, const int32_t* __restrict__ seg_base, int n_segs,
-    const float* __restrict__ theta, const float* __restrict__ phi, int D, int ldk,
-    double* __restrict__ part_lik, double* __restrict__ part_marg) {
-  extern __shared__ double theta_lds[];  // [4][ldk16] as doubles, ldk16 = ldk rounded up to 16
+    const float* __restrict__ theta, const float* __restrict__ phi, int D, int V, int K, int ldk,
+    const double2* __restrict__ log_table, double* __restrict__ part_lik,
+    double* __restrict__ part_marg) {
+  extern __shared__ __align__(16) double theta_lds[];  // [4][16 * stripes]
+  __shared__ double2 lt[kLogTableSize];
   __shared__ double smem[8];
+  for (int i = threadIdx.x; i < kLogTableSize; i += blockDim.x) lt[i] = log_table[i];
+  __syncthreads();
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int tq = lane >> 2, q = lane & 3;
-  const int ldk16 = (ldk + 15) & ~15;
-  double* th = theta_lds + (size_t)wave * ldk16;
-  const int stripes = ldk16 / 16;
+  const int stripes = NS16 > 0 ? NS16 : (ldk + 15) >> 4;
+  double* th = theta_lds + (size_t)wave * 16 * stripes;
   const uint32_t row_bytes = 4u * (uint32_t)ldk;
+  const uint32_t lane_off = 16u * (uint32_t)q;
   const char* phi_bytes = reinterpret_cast<const char*>(phi);
+  // the lane's chunk of stripe c: 16 bytes of the row at 64 c + 16 q, pulled back into the row
+  // where the last stripe overhangs it; entries at or past column K count as zero
+  auto chunk = [&](uint32_t row_off, int c) {
+    const uint32_t off = min(64u * (uint32_t)c + lane_off, row_bytes - 16u);
+    float4 y = *reinterpret_cast<const float4*>(phi_bytes + (row_off + off));
+    const int col = 16 * c + 4 * q;
+    if (16 * c + 16 > K) {  // the same for the whole wave
+      y.x = col + 0 < K ? y.x : 0.f;
+      y.y = col + 1 < K ? y.y : 0.f;
+      y.z = col + 2 < K ? y.z : 0.f;
+      y.w = col + 3 < K ? y.w : 0.f;
+    }
+    return y;
+  };
   double lik = 0.0, marg = 0.0;
   for (int seg = blockIdx.x * 4 + wave; seg < n_segs; seg += gridDim.x * 4) {
     const Segment sg = segment_of(doc_off, seg_base, D, seg);
     const int d = sg.d;
-    wave_lds_fence();
-    for (int k = lane; k < ldk16; k += 64) th[k] = k < ldk ? (double)theta[(size_t)d * ldk + k] : 0.0;
+    wave_lds_fence();  // the previous document's reads are done
+    for (int k = lane; k < 16 * stripes; k += 64)
+      th[k] = k < K ? (double)theta[(size_t)d * ldk + k] : 0.0;
     wave_lds_fence();
     const int64_t a = sg.first > sg.a ? sg.first : sg.a, b = sg.end;
     for (int64_t i0 = a; i0 < b; i0 += 16) {
+      // theta_d does not change inside the loop; an offset the compiler cannot see through
+      // keeps it from reading the whole row once and holding it in registers
+      int theta_off = 4 * q;
+      asm volatile("" : "+v"(theta_off));
+      const double* th_q = th + theta_off;
       const int64_t i = i0 + tq;
       const bool valid = i < b;
-      const uint32_t row_off = (uint32_t)(valid ? w[i] : 0) * row_bytes;
+      const int64_t ii = valid ? i : a;  // a quad past the end redoes the first token; not counted
+      const int wi = min(max(w[ii], 0), V - 1);
+      const int zi = min(max(z[ii], 0), K - 1);
+      const uint32_t row_off = (uint32_t)wi * row_bytes;
       double s = 0.0;
+      if constexpr (NS16 > 0) {
+        float4 y[NS16];
+#pragma unroll
+        for (int c = 0; c < NS16; ++c) y[c] = chunk(row_off, c);
+#pragma unroll
+        for (int c = 0; c < NS16; ++c) {
+          const double2 x01 = *reinterpret_cast<const double2*>(th_q + 16 * c);
+          const double2 x23 = *reinterpret_cast<const double2*>(th_q + 16 * c + 2);
+          s = fma(x01.x, (double)y[c].x, s);
+          s = fma(x01.y, (double)y[c].y, s);
+          s = fma(x23.x, (double)y[c].z, s);
+          s = fma(x23.y, (double)y[c].w, s);
+        }
+      } else {
 #pragma unroll 4
-      for (int c = 0; c < stripes; ++c) {
-        const uint32_t off = min(64u * (uint32_t)c + 16u * (uint32_t)q, row_bytes - 16u);
-        const float4 y = *reinterpret_cast<const float4*>(phi_bytes + (row_off + off));
-        const double* x = th + 16 * c + 4 * q;  // 0 past the row
-        s = fma(x[0], (double)y.x, s);
-        s = fma(x[1], (double)y.y, s);
-        s = fma(x[2], (double)y.z, s);
-        s = fma(x[3], (double)y.w, s);
+        for (int c = 0; c < stripes; ++c) {
+          const float4 y = chunk(row_off, c);
+          const double2 x01 = *reinterpret_cast<const double2*>(th_q + 16 * c);
+          const double2 x23 = *reinterpret_cast<const double2*>(th_q + 16 * c + 2);
+          s = fma(x01.x, (double)y.x, s);
+          s = fma(x01.y, (double)y.y, s);
+          s = fma(x23.x, (double)y.z, s);
+          s = fma(x23.y, (double)y.w, s);
+        }
       }
       s += __shfl_xor(s, 1, 64);
       s += __shfl_xor(s, 2, 64);
-      if (valid && q == 0) {
-        const int zi = z[i];
-        marg += log(s);
-        lik += log(th[zi]) +
-               log((double)*reinterpret_cast<const float*>(phi_bytes + (row_off + 4u * (uint32_t)zi)));
-      }
+      // lane 0 of the quad: ln of the sum; lane 1: ln theta[d][z]; lane 2: ln phi[w][z]
+      const double th_z = th[zi];
+      const double ph_z =
+          (double)*reinterpret_cast<const float*>(phi_bytes + (row_off + 4u * (uint32_t)zi));
+      const double arg = q == 0 ? s : q == 1 ? th_z : q == 2 ? ph_z : 1.0;
+      const double lg = log_any(arg, lt);
+      marg += valid && q == 0 ? lg : 0.0;
+      lik += valid && (q == 1 || q == 2) ? lg : 0.0;
     }
   }
   block_partial_sum(lik, part_lik, smem);
   block_partial_sum(marg, part_marg, smem);
 }
 
-// Sum of ln x over the K real columns of a [rows][ldk] matrix.
+// Sum of ln x over the K real columns of a [rows][ldk] matrix (ldk a multiple of 4: a
+// thread takes four entries of one row at a time).
 __global__ __launch_bounds__(256) void sum_log_kernel(const float* __restrict__ x, int64_t rows,
-                                                       int K, int ldk, double* __restrict__ part) {
+                                                       int K, int ldk,
+                                                       const double2* __restrict__ log_table,
+                                                       double* __restrict__ part) {
+  __shared__ double2 lt[kLogTableSize];
   __shared__ double smem[8];
+  for (int i = threadIdx.x; i < kLogTableSize; i += blockDim.x) lt[i] = log_table[i];
+  __syncthreads();
   double s = 0.0;
-  const int64_t total = rows * ldk;
+  const int per_row = ldk >> 2;
+  const int64_t total = rows * per_row;
   for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total;
        e += (int64_t)gridDim.x * blockDim.x) {
-    if ((int)(e % ldk) < K) s += log((double)x[e]);
+    const int64_t r = e / per_row;
+    const int col = 4 * (int)(e - r * per_row);
+    const float4 v = *reinterpret_cast<const float4*>(x + r * ldk + col);
+    if (col + 0 < K) s += log_any((double)v.x, lt);
+    if (col + 1 < K) s += log_any((double)v.y, lt);
+    if (col + 2 < K) s += log_any((double)v.z, lt);
+    if (col + 3 < K) s += log_any((double)v.w, lt);
   }
   block_partial_sum(s, part, smem);
+}
+
+// Adds the block partials of the three kernels above in a fixed order and forms the two
+// outputs: out[0] = log joint = prior terms + token terms, out[1] = log marginal.
+// red = [4][kRedBlocks]: token terms, marginal terms, sum ln theta, sum ln phi.
+// c_theta, c_phi: the normalising constants of the two Dirichlet priors summed over
+// documents and topics; am1 = alpha - 1, bm1 = beta - 1.
+__global__ __launch_bounds__(256) void lda_loglik_finish_kernel(const double* __restrict__ red,
+                                                                 double c_theta, double am1,
+                                                                 double c_phi, double bm1,
+                                                                 double* __restrict__ out) {
+  __shared__ double sh[4][256];
+  const int t = threadIdx.x;
+  for (int g = 0; g < 4; ++g) {
+    double s = 0.0;
+    for (int i = t; i < kRedBlocks; i += 256) s += red[(size_t)g * kRedBlocks + i];
+    sh[g][t] = s;
+  }
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) {
+    if (t < o)
+      for (int g = 0; g < 4; ++g) sh[g][t] += sh[g][t + o];
+    __syncthreads();
+  }
+  if (t == 0) {
+    out[0] = (c_theta + am1 * sh[2][0]) + (c_phi + bm1 * sh[3][0]) + sh[0][0];
+    out[1] = sh[1][0];
+  }
 }
 
 // Per-handle tables of Gamma shape constants for a0 + n, n = 0 .. kShapeTable - 1.
@@ -1044,9 +1320,12 @@ __global__ __launch_bounds__(1024) void doc_offsets_kernel(const int32_t* __rest
   const int lo = min(D, t * per), hi = min(D, lo + per);
   int64_t s = 0;
   unsigned long long neg = 0;
+  // bad == NULL: nobody reads a count of negative entries; they are taken as 0, so that the
+  // offsets never decrease
+  const bool clamp = bad == nullptr;
   for (int d = lo; d < hi; ++d) {
     if (doc_len[d] < 0) ++neg;
-    s += doc_len[d];
+    s += clamp ? max(doc_len[d], 0) : doc_len[d];
   }
   chunk_sum[t] = s;
   __syncthreads();
@@ -1062,10 +1341,10 @@ __global__ __launch_bounds__(1024) void doc_offsets_kernel(const int32_t* __rest
   __syncthreads();
   int64_t run = chunk_sum[t];
   for (int d = lo; d < hi; ++d) {
-    run += doc_len[d];
+    run += clamp ? max(doc_len[d], 0) : doc_len[d];
     doc_off[d + 1] = run;
   }
-  if (neg) atomicAdd(bad, neg);
+  if (neg && !clamp) atomicAdd(bad, neg);
 }
 
 }  // namespace
@@ -1103,7 +1382,7 @@ struct augur_lda {
   GammaShape *shapes_alpha = nullptr, *shapes_beta = nullptr;  // [kShapeTable] each
   double2* log_table = nullptr;                                // [kLogTableSize], see log_tab
   double* exp_table = nullptr;                                 // [kExpTableSize], see exp_tab
-  double* red = nullptr;         // [4][kRedBlocks] reduction partials
+  double* red = nullptr;         // [4][kRedBlocks] reduction partials, then the two results
   unsigned long long* counters = nullptr;  // [0] degenerate tokens [1] capped draws [2] bad input
   int phi_blocks = 0, phi_rows = 0;
   int64_t sweep = 0;
@@ -1113,6 +1392,13 @@ struct augur_lda {
 namespace {
 
 bool device_ptrs(const augur_lda* h) { return (h->cfg.flags & AUGUR_PTRS_DEVICE) != 0; }
+
+// Row stride of the [.][K] tables, in elements.  A token's lanes read a row in pieces of 64
+// bytes (a quad, up to 256 topics) or 256 bytes (a 16-lane row, beyond); rows that start on
+// a multiple of that never have a piece straddle two 128-byte cache lines, which the
+// texture addresser pays for with a second pass (with K = 200 and a stride of 800 bytes a
+// quarter of the pieces did).
+int row_stride(int K) { return (int)round_up(K, K <= 256 ? 16 : 64); }
 
 void free_all(augur_lda* h) {
   (void)hipFree(h->w); (void)hipFree(h->z); (void)hipFree(h->n_dk); (void)hipFree(h->n_wk);
@@ -1241,6 +1527,7 @@ int build_word_major(augur_lda* h) {
   auto check = [&](hipError_t e, const char* what) {
     if (e != hipSuccess && rc == AUGUR_OK) {
       set_error("%s failed: %s", what, hipGetErrorString(e));
+      (void)hipGetLastError();  // or the runtime hands the error to the next caller
       rc = AUGUR_ERR_HIP;
     }
     return rc == AUGUR_OK;
@@ -1448,6 +1735,45 @@ int launch_phi(augur_lda* h, uint32_t sweep, hipStream_t stream) {
   return AUGUR_OK;
 }
 
+// The log joint and the log marginal of a state: three reduction kernels write block partials
+// into red ([4][kRedBlocks] doubles), a last one adds them and writes out[0], out[1] (device).
+// seg_base == NULL: one wave per document (n_segs = D).
+int launch_loglik(hipStream_t stream, const int32_t* w, const int32_t* z, const int64_t* doc_off,
+                  const int32_t* seg_base, int n_segs, const float* theta, const float* phi, int D,
+                  int V, int K, int ldk, double alpha, double beta, const double2* log_table,
+                  double* red, double* out) {
+  double* p_lik = red;
+  double* p_marg = red + kRedBlocks;
+  double* p_th = red + 2 * kRedBlocks;
+  double* p_ph = red + 3 * kRedBlocks;
+  const int stripes = (ldk + 15) / 16;
+  const size_t shm = sizeof(double) * 4 * 16 * (size_t)stripes;
+#define AUGUR_LL_ARGS                                                                            \
+  dim3(kRedBlocks), dim3(256), shm, stream, w, z, doc_off, seg_base, n_segs, theta, phi, D, V, K, \
+      ldk, log_table, p_lik, p_marg
+#define AUGUR_LL_CASE(N16) \
+  case N16: hipLaunchKernelGGL(lda_loglik_tokens_kernel<N16>, AUGUR_LL_ARGS); break;
+  switch (stripes <= 16 ? stripes : 0) {
+    AUGUR_LL_CASE(1) AUGUR_LL_CASE(2) AUGUR_LL_CASE(3) AUGUR_LL_CASE(4) AUGUR_LL_CASE(5)
+    AUGUR_LL_CASE(6) AUGUR_LL_CASE(7) AUGUR_LL_CASE(8) AUGUR_LL_CASE(9) AUGUR_LL_CASE(10)
+    AUGUR_LL_CASE(11) AUGUR_LL_CASE(12) AUGUR_LL_CASE(13) AUGUR_LL_CASE(14) AUGUR_LL_CASE(15)
+    AUGUR_LL_CASE(16)
+    default: hipLaunchKernelGGL(lda_loglik_tokens_kernel<0>, AUGUR_LL_ARGS); break;
+  }
+#undef AUGUR_LL_CASE
+#undef AUGUR_LL_ARGS
+  hipLaunchKernelGGL(sum_log_kernel, dim3(kRedBlocks), dim3(256), 0, stream, theta, (int64_t)D, K,
+                     ldk, log_table, p_th);
+  hipLaunchKernelGGL(sum_log_kernel, dim3(kRedBlocks), dim3(256), 0, stream, phi, (int64_t)V, K, ldk,
+                     log_table, p_ph);
+  const double c_theta = (double)D * (std::lgamma(K * alpha) - K * std::lgamma(alpha));
+  const double c_phi = (double)K * (std::lgamma(V * beta) - V * std::lgamma(beta));
+  hipLaunchKernelGGL(lda_loglik_finish_kernel, dim3(1), dim3(256), 0, stream, red, c_theta,
+                     alpha - 1.0, c_phi, beta - 1.0, out);
+  AUGUR_HIP_TRY(hipGetLastError());
+  return AUGUR_OK;
+}
+
 // Strided copies between the caller's dense [rows][K] arrays and the padded
 // device arrays.
 int copy_in(augur_lda* h, void* dst, const void* src, size_t elem, int64_t rows) {
@@ -1496,7 +1822,7 @@ int augur_lda_create(const augur_lda_config* cfg, const int32_t* doc_len, const 
                 cfg->D, cfg->V, cfg->K);
   AUGUR_REQUIRE(cfg->K <= 1024, "K = %d is above the supported maximum of 1024 topics", cfg->K);
   AUGUR_REQUIRE(cfg->V <= (1 << 24), "V = %d is above the supported maximum of 2^24 words", cfg->V);
-  AUGUR_REQUIRE((int64_t)cfg->V * round_up(cfg->K, 4) <= (1LL << 30),
+  AUGUR_REQUIRE((int64_t)cfg->V * row_stride(cfg->K) <= (1LL << 30),
                 "V * K = %lld exceeds 2^30 table entries (phi rows are addressed with 32-bit "
                 "byte offsets)", (long long)cfg->V * cfg->K);
   AUGUR_REQUIRE(std::isfinite(cfg->alpha) && cfg->alpha > 0.f && std::isfinite(cfg->beta) &&
@@ -1519,7 +1845,7 @@ int augur_lda_create(const augur_lda_config* cfg, const int32_t* doc_len, const 
   h->stream = (hipStream_t)cfg->stream;
   h->alpha = (double)cfg->alpha;
   h->beta = (double)cfg->beta;
-  h->ldk = (int)round_up(K, 4);
+  h->ldk = row_stride(K);
   h->ns = (h->ldk + 63) / 64;
   {
     // enough column-waves to fill the chip several times over, at most kPhiRowsMax rows each
@@ -1534,6 +1860,7 @@ int augur_lda_create(const augur_lda_config* cfg, const int32_t* doc_len, const 
     hipError_t e_ = (expr);                                                                 \
     if (e_ != hipSuccess) {                                                                 \
       set_error("%s failed: %s (%s:%d)", #expr, hipGetErrorString(e_), __FILE__, __LINE__); \
+      (void)hipGetLastError(); /* or the runtime hands it to the next caller */ \
       free_all(h);                                                                          \
       delete h;                                                                             \
       return AUGUR_ERR_HIP;                                                                 \
@@ -1619,7 +1946,7 @@ int augur_lda_create(const augur_lda_config* cfg, const int32_t* doc_len, const 
   AUGUR_CREATE_TRY(hipMalloc(&h->lg, sizeof(double) * vk));
   AUGUR_CREATE_TRY(hipMalloc(&h->col_partial, sizeof(double2) * (size_t)h->phi_blocks * K));
   AUGUR_CREATE_TRY(hipMalloc(&h->col_logZ, sizeof(double) * (size_t)K));
-  AUGUR_CREATE_TRY(hipMalloc(&h->red, sizeof(double) * 4 * kRedBlocks));
+  AUGUR_CREATE_TRY(hipMalloc(&h->red, sizeof(double) * (4 * kRedBlocks + 2)));
   {
     double2 table[kLogTableSize];
     fill_log_table(table);
@@ -1690,6 +2017,7 @@ int augur_lda_create(const augur_lda_config* cfg, const int32_t* doc_len, const 
   if (rc == AUGUR_OK) rc = launch_phi(h, 0, h->stream);
   if (rc == AUGUR_OK && hipStreamSynchronize(h->stream) != hipSuccess) {
     set_error("initial sweep failed: %s", hipGetErrorString(hipGetLastError()));
+    (void)hipGetLastError();  // or the runtime hands the error to the next caller
     rc = AUGUR_ERR_HIP;
   }
   if (rc != AUGUR_OK) {
@@ -1818,6 +2146,7 @@ int augur_lda_sweep_profile(augur_lda* h, int32_t n_sweeps, double* ms) {
   auto fail_hip = [&](hipError_t e, const char* what) {
     if (e != hipSuccess && rc == AUGUR_OK) {
       set_error("%s failed: %s", what, hipGetErrorString(e));
+      (void)hipGetLastError();  // or the runtime hands the error to the next caller
       rc = AUGUR_ERR_HIP;
     }
     return e != hipSuccess;
@@ -1846,33 +2175,69 @@ int augur_lda_sweep_profile(augur_lda* h, int32_t n_sweeps, double* ms) {
   return rc;
 }
 
+int augur_lda_probe_gather(augur_lda* h, int32_t reps, double* ms_per_pass) {
+  AUGUR_CHECK_HANDLE(h);
+  AUGUR_REQUIRE(reps > 0 && reps <= 4096 && ms_per_pass != nullptr,
+                "reps must lie in [1, 4096] and ms_per_pass must not be NULL");
+  *ms_per_pass = 0.0;
+  if (h->N == 0) return AUGUR_OK;
+  const dim3 grid((h->n_segs + 3) / 4), block(256);
+  auto launch = [&]() -> int {
+#define AUGUR_GP_ARGS \
+  grid, block, 0, h->stream, h->w, h->doc_off, h->seg_base, h->n_segs, h->phi, h->cfg.D, h->ldk
+#define AUGUR_GQ_CASE(N16) \
+  case N16: hipLaunchKernelGGL(lda_gather_probe_quad_kernel<N16>, AUGUR_GP_ARGS); break;
+#define AUGUR_GR_CASE(NSV) \
+  case NSV: hipLaunchKernelGGL(lda_gather_probe_row_kernel<NSV>, AUGUR_GP_ARGS); break;
+    if (h->ldk <= 256) {
+      switch ((h->ldk + 15) / 16) {
+        AUGUR_GQ_CASE(1) AUGUR_GQ_CASE(2) AUGUR_GQ_CASE(3) AUGUR_GQ_CASE(4) AUGUR_GQ_CASE(5)
+        AUGUR_GQ_CASE(6) AUGUR_GQ_CASE(7) AUGUR_GQ_CASE(8) AUGUR_GQ_CASE(9) AUGUR_GQ_CASE(10)
+        AUGUR_GQ_CASE(11) AUGUR_GQ_CASE(12) AUGUR_GQ_CASE(13) AUGUR_GQ_CASE(14) AUGUR_GQ_CASE(15)
+        AUGUR_GQ_CASE(16)
+      }
+    } else {
+      switch (h->ns) {
+        AUGUR_GR_CASE(5) AUGUR_GR_CASE(6) AUGUR_GR_CASE(7) AUGUR_GR_CASE(8) AUGUR_GR_CASE(9)
+        AUGUR_GR_CASE(10) AUGUR_GR_CASE(11) AUGUR_GR_CASE(12) AUGUR_GR_CASE(13) AUGUR_GR_CASE(14)
+        AUGUR_GR_CASE(15) AUGUR_GR_CASE(16)
+      }
+    }
+#undef AUGUR_GR_CASE
+#undef AUGUR_GQ_CASE
+#undef AUGUR_GP_ARGS
+    AUGUR_HIP_TRY(hipGetLastError());
+    return AUGUR_OK;
+  };
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  AUGUR_HIP_TRY(hipEventCreate(&e0));
+  hipError_t err = hipEventCreate(&e1);
+  int rc = err == hipSuccess ? launch() : AUGUR_OK;  // warm-up pass
+  if (err == hipSuccess && rc == AUGUR_OK) err = hipEventRecord(e0, h->stream);
+  for (int r = 0; r < reps && err == hipSuccess && rc == AUGUR_OK; ++r) rc = launch();
+  if (err == hipSuccess && rc == AUGUR_OK) err = hipEventRecord(e1, h->stream);
+  if (err == hipSuccess) err = hipStreamSynchronize(h->stream);
+  float ms = 0.f;
+  if (err == hipSuccess && rc == AUGUR_OK) err = hipEventElapsedTime(&ms, e0, e1);
+  (void)hipEventDestroy(e0);
+  if (e1) (void)hipEventDestroy(e1);
+  if (rc != AUGUR_OK) return rc;
+  AUGUR_HIP_TRY(err);
+  *ms_per_pass = (double)ms / reps;
+  return AUGUR_OK;
+}
+
 int augur_lda_loglik(augur_lda* h, double* log_joint, double* log_marginal_w) {
   AUGUR_CHECK_HANDLE(h);
-  const int D = h->cfg.D, V = h->cfg.V, K = h->cfg.K;
-  double* p_lik = h->red;
-  double* p_marg = h->red + kRedBlocks;
-  double* p_th = h->red + 2 * kRedBlocks;
-  double* p_ph = h->red + 3 * kRedBlocks;
-  hipLaunchKernelGGL(lda_loglik_tokens_kernel, dim3(kRedBlocks), dim3(256),
-                     sizeof(double) * 4 * (size_t)((h->ldk + 15) & ~15), h->stream, h->w, h->z,
-                     h->doc_off, h->seg_base, h->n_segs, h->theta, h->phi, D, h->ldk, p_lik, p_marg);
-  hipLaunchKernelGGL(sum_log_kernel, dim3(kRedBlocks), dim3(256), 0, h->stream, h->theta,
-                     (int64_t)D, K, h->ldk, p_th);
-  hipLaunchKernelGGL(sum_log_kernel, dim3(kRedBlocks), dim3(256), 0, h->stream, h->phi, (int64_t)V,
-                     K, h->ldk, p_ph);
-  AUGUR_HIP_TRY(hipGetLastError());
-  std::vector<double> host(4 * kRedBlocks);
-  AUGUR_HIP_TRY(hipMemcpyAsync(host.data(), h->red, sizeof(double) * host.size(),
-                               hipMemcpyDeviceToHost, h->stream));
+  double* out = h->red + 4 * kRedBlocks;
+  AUGUR_TRY(launch_loglik(h->stream, h->w, h->z, h->doc_off, h->seg_base, h->n_segs, h->theta, h->phi,
+                          h->cfg.D, h->cfg.V, h->cfg.K, h->ldk, h->alpha, h->beta, h->log_table,
+                          h->red, out));
+  double host[2] = {0.0, 0.0};
+  AUGUR_HIP_TRY(hipMemcpyAsync(host, out, sizeof(host), hipMemcpyDeviceToHost, h->stream));
   AUGUR_HIP_TRY(hipStreamSynchronize(h->stream));
-  double s[4] = {0, 0, 0, 0};
-  for (int g = 0; g < 4; ++g)
-    for (int i = 0; i < kRedBlocks; ++i) s[g] += host[(size_t)g * kRedBlocks + i];
-  const double a = h->alpha, b = h->beta;
-  const double prior_theta = (double)D * (std::lgamma(K * a) - K * std::lgamma(a)) + (a - 1.0) * s[2];
-  const double prior_phi = (double)K * (std::lgamma(V * b) - V * std::lgamma(b)) + (b - 1.0) * s[3];
-  if (log_joint) *log_joint = prior_theta + prior_phi + s[0];
-  if (log_marginal_w) *log_marginal_w = s[1];
+  if (log_joint) *log_joint = host[0];
+  if (log_marginal_w) *log_marginal_w = host[1];
   unsigned long long deg = 0;
   AUGUR_TRY(read_counter(h, 0, &deg));
   if (deg > h->degenerate_reported) {

@@ -532,6 +532,7 @@ int augur_mhreg_create(const augur_mhreg_config* cfg, const float* x, const floa
     hipError_t e_ = (expr);                                                                 \
     if (e_ != hipSuccess) {                                                                 \
       set_error("%s failed: %s (%s:%d)", #expr, hipGetErrorString(e_), __FILE__, __LINE__); \
+      (void)hipGetLastError(); /* or the runtime hands it to the next caller */ \
       free_all(h);                                                                          \
       delete h;                                                                             \
       return AUGUR_ERR_HIP;                                                                 \
@@ -600,6 +601,7 @@ int augur_mhreg_create(const augur_mhreg_config* cfg, const float* x, const floa
   }
   if (rc == AUGUR_OK && hipStreamSynchronize(h->stream) != hipSuccess) {
     set_error("initial evaluation failed: %s", hipGetErrorString(hipGetLastError()));
+    (void)hipGetLastError();  // or the runtime hands the error to the next caller
     rc = AUGUR_ERR_HIP;
   }
   if (rc != AUGUR_OK) {
@@ -634,6 +636,7 @@ int augur_mhreg_run(augur_mhreg* h, int64_t n_steps, double* trace) {
   if (rc == AUGUR_OK && (hipMemcpyAsync(trace, dev, bytes, hipMemcpyDeviceToHost, h->stream) != hipSuccess ||
                          hipStreamSynchronize(h->stream) != hipSuccess)) {
     set_error("trace download failed: %s", hipGetErrorString(hipGetLastError()));
+    (void)hipGetLastError();  // or the runtime hands the error to the next caller
     rc = AUGUR_ERR_HIP;
   }
   (void)hipStreamSynchronize(h->stream);

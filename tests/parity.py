@@ -11,6 +11,21 @@ Z_AGREE = 0.9999
 Z_BOUNDARY_RTOL = 1e-6
 REAL_RTOL = 1e-5
 
+# Topic counts of the parity tests, chosen to reach every instance of the two z kernels: the
+# quad kernel is compiled once per number of 16-topic stripes of the padded row (1..16, K up to
+# 256), the 16-lane-row kernel once per number of 64-topic stripes (5..16, K up to 1024); plus
+# the smallest cases and rows that end inside a stripe.
+QUAD_TOPIC_COUNTS = [1, 2, 7, 10, 20, 48, 64, 65, 96, 100, 128, 130, 150, 170, 190, 200, 224, 230, 256]
+ROW_TOPIC_COUNTS = [257, 300, 384, 420, 500, 560, 640, 700, 760, 820, 880, 900, 1000, 1024]
+
+
+def quad_stripes(K):
+    return ((K + 3) // 4 * 4 + 15) // 16
+
+
+def row_stripes(K):
+    return ((K + 3) // 4 * 4 + 63) // 64
+
 
 def assert_real_close(got, want, what, rtol=REAL_RTOL, floor=FLT_MIN):
     got = np.asarray(got, dtype=np.float64)
@@ -44,10 +59,11 @@ def assert_z_lda(z_gpu, z_orc, doc_off, w, theta, phi, seed, sweep):
 
 
 def _assert_agreement(n_mismatch, N):
-    """>= 99.99 % of the variables of a sweep agree.  On fewer than 10^4 variables one
-    disagreement is already below that mark, so there the rule is that a single
-    boundary case (checked as such by the caller) may occur."""
-    assert n_mismatch <= max(1.0, (1.0 - Z_AGREE) * N), f"{n_mismatch} of {N} z differ"
+    """>= 99.99 % of the variables of a sweep agree.  Only on fewer than 10^4 variables, where
+    one disagreement is already below that mark (the edge-case corpora), the rule is that a
+    single boundary case (checked as such by the caller) may occur."""
+    allowed = (1.0 - Z_AGREE) * N if N >= 10_000 else max(1.0, (1.0 - Z_AGREE) * N)
+    assert n_mismatch <= allowed, f"{n_mismatch} of {N} z differ"
 
 
 def assert_z_gmm(z_gpu, z_orc, x, pi, mu, sigma, seed, sweep):

@@ -113,16 +113,25 @@ def test_tiny_config_free_running(B):
     g.close()
 
 
-@pytest.mark.parametrize("K", [1, 2, 7, 10, 48, 64, 65, 96, 100, 128, 200, 224, 256, 257, 384, 500, 640, 900,
-                               1000, 1024])
+@pytest.mark.parametrize("K", P.QUAD_TOPIC_COUNTS + P.ROW_TOPIC_COUNTS)
 def test_topic_counts_span_stripes_and_tails(B, K):
-    D, V = 40, 300
-    lens, w = ragged_corpus(D, V, K, seed=K)
+    D, V = 120, 300
+    lens, w = ragged_corpus(D, V, K, seed=K, mean_len=100)
+    assert w.size >= 10_000          # so that the 99.99 % rule applies as written
     g, o = make_pair(B, D, V, K, 0.1, 0.01, 1000 + K, lens, w)
     z0 = g.get_state(theta=False, phi=False)[0]
     assert np.array_equal(z0, o.z)
     for _ in range(2):
         lockstep_sweep(g, o, check_loglik=True)
+    # the sweep entry point runs other instances of the kernels (document counts built inside
+    # the z kernel, word table and phi step on a second stream): bit-identical to the steps
+    g.set_state(z=o.z, theta=o.theta, phi=o.phi, sweep=o.sweep_index)
+    g.sweep(1)
+    swept = [np_(a).copy() for a in g.get_state()[:3] + g.get_counts()]
+    g.set_state(z=o.z, theta=o.theta, phi=o.phi, sweep=o.sweep_index)
+    g.step_sample_z(); g.step_count(); g.step_resample_theta(); g.step_resample_phi(); g.step_finish()
+    for x, y in zip(swept, g.get_state()[:3] + g.get_counts()):
+        assert np.array_equal(x, np_(y))
     g.close()
 
 
@@ -393,11 +402,42 @@ def test_medium_config_full_parity(B):
     g.close()
 
 
+def _oracle_z_on_ranges(c, off, theta, phi, seed, sweep, z_gpu, D, K, ranges):
+    """The oracle redraws z for the documents of each range from (theta, phi) and the result is
+    compared with z_gpu under the boundary rule; returns the number of tokens checked."""
+    import ctypes as Ct
+    lib = O.lib()
+    checked = 0
+    for d0, d1 in ranges:
+        sub_off = off[d0:d1 + 1]
+        zo = z_gpu.copy()
+        # the oracle writes its draws for documents d0..d1-1 into zo at their global positions
+        lib.orc_lda_sample_z(Ct.c_int32(d1 - d0), Ct.c_int32(K), sub_off.ctypes.data_as(Ct.POINTER(Ct.c_int64)),
+                             c["w"].ctypes.data_as(Ct.POINTER(Ct.c_int32)),
+                             theta[d0:d1].ctypes.data_as(Ct.POINTER(Ct.c_float)),
+                             phi.ctypes.data_as(Ct.POINTER(Ct.c_float)), Ct.c_uint64(seed), Ct.c_uint32(sweep),
+                             zo.ctypes.data_as(Ct.POINTER(Ct.c_int32)))
+        lo, hi = int(off[d0]), int(off[d1])
+        sub = np.arange(lo, hi)
+        mism = sub[z_gpu[lo:hi] != zo[lo:hi]]
+        assert mism.size <= (1 - P.Z_AGREE) * (hi - lo)
+        doc_of = np.searchsorted(off, mism, side="right") - 1
+        for i, d in zip(mism, doc_of):
+            cdf, t = O.lda_token_cdf(theta[d], phi[c["w"][i]], seed, int(i), sweep)
+            P._assert_boundary(cdf, t, int(z_gpu[i]), int(zo[i]), f"token {i}",
+                               float(theta[d, z_gpu[i]]) * float(phi[c["w"][i], z_gpu[i]]))
+        checked += hi - lo
+    return checked
+
+
 @pytest.mark.parametrize("name", ["large", "widek"])
 def test_full_size_config_sampled_parity(B, name):
     """BASELINE's K=200 (about 75M tokens) and K=1000 (about 10M tokens) configurations at full
-    size, in the launch configuration bench.py times.  The oracle checks z on ranges of documents
-    it can redo one by one, the count tables in full, theta on sampled ranges and phi in full."""
+    size, through the entry point and in the launch configuration bench.py times: sweep().  The
+    oracle checks the z of that sweep on ranges of documents it can redo one by one, both count
+    tables in full on the sweep's own z, theta on sampled ranges and phi in full.  The step-wise
+    calls from the same state must then give the same bits."""
+    from scipy import special
     cfg = synth.LDA_CONFIGS[name]
     c = synth.lda_corpus(**cfg)
     D, V, K, N = cfg["D"], cfg["V"], cfg["K"], c["N"]
@@ -407,52 +447,102 @@ def test_full_size_config_sampled_parity(B, name):
     g.sweep(2)                                   # a state two sweeps in, as in the benchmark
     z0, theta, phi, sw = g.get_state()
     assert sw == 2
-    g.step_sample_z()
-    z1 = g.get_state(theta=False, phi=False)[0]
-    assert z1.min() >= 0 and z1.max() < K
-    checked = 0
-    for d0 in (0, D // 2 + 3456, D - 1500):
-        d1 = d0 + 1500
-        sub_off = off[d0:d1 + 1]
-        zo = z1.copy()
-        # the oracle writes its draws for documents d0..d1-1 into zo at their global positions
-        lib = O.lib()
-        import ctypes as Ct
-        lib.orc_lda_sample_z(Ct.c_int32(d1 - d0), Ct.c_int32(K), sub_off.ctypes.data_as(Ct.POINTER(Ct.c_int64)),
-                             c["w"].ctypes.data_as(Ct.POINTER(Ct.c_int32)),
-                             theta[d0:d1].ctypes.data_as(Ct.POINTER(Ct.c_float)),
-                             phi.ctypes.data_as(Ct.POINTER(Ct.c_float)), Ct.c_uint64(seed), Ct.c_uint32(3),
-                             zo.ctypes.data_as(Ct.POINTER(Ct.c_int32)))
-        lo, hi = int(off[d0]), int(off[d1])
-        sub = np.arange(lo, hi)
-        mism = sub[z1[lo:hi] != zo[lo:hi]]
-        assert mism.size <= (1 - P.Z_AGREE) * (hi - lo)
-        doc_of = np.searchsorted(off, mism, side="right") - 1
-        for i, d in zip(mism, doc_of):
-            cdf, t = O.lda_token_cdf(theta[d], phi[c["w"][i]], seed, int(i), 3)
-            P._assert_boundary(cdf, t, int(z1[i]), int(zo[i]), f"token {i}",
-                               float(theta[d, z1[i]]) * float(phi[c["w"][i], z1[i]]))
-        checked += hi - lo
+    g.sweep(1)                                   # the sweep under test: index 3
+    z1, th1, ph1, sw = g.get_state()
+    assert sw == 3 and z1.min() >= 0 and z1.max() < K
+    ranges = [(d0, d0 + 1500) for d0 in (0, D // 2 + 3456, D - 1500)]
+    checked = _oracle_z_on_ranges(c, off, theta, phi, seed, 3, z1, D, K, ranges)
     print(name, ": z checked on", checked, "tokens")
-    # counts: the whole tables against the oracle's nested loops on the GPU's own z
-    g.step_count()
+    # counts of the sweep (document table from inside the z kernel where K <= 256, word table
+    # from the second stream): the whole tables against the oracle's nested loops on the sweep's z
     n_dk, n_wk = g.get_counts()
     o_dk, o_wk = O.lda_count(off, c["w"], z1, D, V, K)
     assert np.array_equal(n_dk, o_dk) and np.array_equal(n_wk, o_wk)
     del o_dk, o_wk
-    # theta on sampled document ranges, phi in full
-    g.step_resample_theta()
-    g.step_resample_phi()
-    _, th1, ph1, _ = g.get_state(z=False)
+    # theta of the sweep on sampled document ranges, phi in full
     for d0 in (0, 2 * D // 3, D - 2000):
-        want = np.zeros((2000, K), dtype=np.float32)
         nd = np.ascontiguousarray(n_dk[d0:d0 + 2000])
-        lg_first = d0 * K                         # variable index of entry (d, k) is d*K + k
-        lg = O.gamma_log_draws((alpha + nd).ravel(), seed, first=lg_first, sweep=3,
+        lg = O.gamma_log_draws((alpha + nd).ravel(), seed, first=d0 * K, sweep=3,   # variable (d, k) is d*K + k
                                stream=O.STREAM_THETA).reshape(2000, K)
-        from scipy import special
         want = np.exp(lg - special.logsumexp(lg, axis=1, keepdims=True))
         want = np.maximum(want, P.FLT_MIN)
         P.assert_real_close(th1[d0:d0 + 2000], want.astype(np.float32), "theta rows")
     P.assert_real_close(ph1, O.lda_resample_phi(n_wk, beta, seed, 3), "phi")
+    # the step-wise calls from the same state: identical bits
+    g.set_state(z=z0, theta=theta, phi=phi, sweep=2)
+    g.step_sample_z(); g.step_count(); g.step_resample_theta(); g.step_resample_phi(); g.step_finish()
+    z2, th2, ph2, sw = g.get_state()
+    assert sw == 3 and np.array_equal(z2, z1) and np.array_equal(th2, th1) and np.array_equal(ph2, ph1)
+    s_dk, s_wk = g.get_counts()
+    assert np.array_equal(s_dk, n_dk) and np.array_equal(s_wk, n_wk)
     g.close()
+
+
+def test_create_that_cannot_fit_in_device_memory_fails_cleanly(B):
+    """Sizes inside the argument limits whose theta table (D x K floats) is larger than the
+    device's memory: create must give AUGUR_ERR_HIP, leave nothing allocated, and the device must
+    serve the next handle."""
+    import torch
+    _, total = torch.cuda.mem_get_info()
+    K = 1024
+    D = int(total // (4 * K)) + 1_000_000            # theta alone exceeds the whole device
+    lens = torch.zeros(D, dtype=torch.int32, device="cuda")     # every document empty: N = 0
+    w = torch.zeros(4, dtype=torch.int32, device="cuda")
+
+    def failing_create():
+        with pytest.raises(B.AugurError) as e:
+            B.LDA(D, 50, K, 0.1, 0.1, 1, lens, w[:0], device_ptrs=True)
+        assert e.value.code == B.ERR_HIP and "hipMalloc" in str(e.value)
+        torch.cuda.synchronize()
+        return torch.cuda.mem_get_info()[0]
+
+    # The free memory that the runtime reports lags behind hipFree (seen: 1.2 GB less right after
+    # the first failure, 0.6 GB of it back two failures later), so the check is one-sided: what
+    # create took before failing (the document offsets, 8 bytes a document: 0.6 GB here) must
+    # come back every time, i.e. further failures may not lower the free memory again.
+    free_a = failing_create()
+    failing_create()
+    free_b = failing_create()
+    assert free_b >= free_a - (64 << 20), (free_a, free_b)
+    del lens, w
+    cfg = synth.LDA_CONFIGS["tiny"]
+    c = synth.lda_corpus(**cfg)
+    g, o = make_pair(B, cfg["D"], cfg["V"], cfg["K"], cfg["alpha"], cfg["beta"], 5, c["doc_len"], c["w"])
+    lockstep_sweep(g, o)
+    g.close()
+
+
+def test_create_destroy_loop_returns_all_device_memory(B):
+    import torch
+    cfg = dict(synth.LDA_CONFIGS["tiny"], D=400, V=2000, K=64, mean_len=80)
+    c = synth.lda_corpus(**cfg)
+    args = (cfg["D"], cfg["V"], cfg["K"], cfg["alpha"], cfg["beta"], 9, c["doc_len"], c["w"])
+    for _ in range(3):                               # code objects, streams and pools settle
+        h = B.LDA(*args); h.sweep(1); h.loglik(); h.close()
+    torch.cuda.synchronize()
+    free0, _ = torch.cuda.mem_get_info()
+    for _ in range(100):
+        h = B.LDA(*args)
+        h.sweep(1)
+        h.loglik()
+        h.close()
+    torch.cuda.synchronize()
+    free1, _ = torch.cuda.mem_get_info()
+    assert abs(free1 - free0) <= (2 << 20), (free0, free1)
+
+
+def test_measurement_probes(B):
+    import torch
+    cfg = dict(synth.LDA_CONFIGS["tiny"], D=300, V=800, K=40, mean_len=120)
+    c = synth.lda_corpus(**cfg)
+    for K in (40, 300):                              # the quad-shaped and the row-shaped gather
+        g = B.LDA(cfg["D"], cfg["V"], K, 0.1, 0.01, 31, c["doc_len"], c["w"])
+        before = g.get_state() + g.get_counts()
+        assert g.probe_gather(3) > 0.0
+        for x, y in zip(before, g.get_state() + g.get_counts()):
+            assert np.array_equal(x, y)              # the probe changes nothing
+        g.close()
+    src = torch.arange(1 << 20, dtype=torch.float32, device="cuda")
+    dst = torch.zeros_like(src)
+    assert B.probe_stream_copy(src, dst, reps=3) > 0.0
+    assert torch.equal(src, dst)
