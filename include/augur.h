@@ -137,6 +137,45 @@ int augur_lda_get_counts(augur_lda* h, int32_t* n_dk, int32_t* n_wk);
 int augur_lda_get_degenerate(augur_lda* h, int64_t* count);
 int augur_lda_sync(augur_lda* h);
 
+/* augur_lda_loglik for callers that cannot allocate device memory: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  It needs
+ * no handle: the caller passes the corpus and the state as DEVICE arrays and gets
+ * the same two numbers back in DEVICE memory, out[0] = log joint, out[1] = log
+ * marginal of w (see augur_lda_loglik).  The call allocates and frees nothing,
+ * on the device or through any library, and does not synchronise: its kernels
+ * are enqueued on args->stream and `out` is valid once they have run.
+ *
+ * Its working memory (the document offsets it forms from doc_len, the block
+ * partials of its sums, a logarithm table: about 8.1 MiB) is a static device
+ * array of the library, one per GPU, held until the process ends.  That fixes
+ * the largest input: D <= 1048576 documents (AUGUR_ERR_INVALID_ARG beyond, as
+ * for K > 1024, V * ld > 2^30, ld < K or ld not a multiple of 4, NULL or
+ * misaligned pointers); the handle-based call has no such limit.  All calls on one
+ * GPU share the array: calls that may overlap on a GPU (different streams,
+ * different threads) race and must be ordered by the caller.  No call depends on
+ * what an earlier one left in the array.
+ *
+ * Layout: doc_len int32[D]; w, z int32[N], N = sum of doc_len <= 2^31-1,
+ * doc-major; theta float[D][ld], phi float[V][ld] with row stride ld >= K, a
+ * multiple of 4 (rows 16-byte aligned); columns K..ld-1 may hold anything.
+ * Not validated (validation would need a host wait): a negative doc_len counts
+ * as 0, word ids and topics outside their tables are clamped into them; w and z
+ * must hold at least N entries.  Every document is walked by one wave, so a
+ * corpus of very few, very long documents is served faster by a handle. */
+typedef struct {
+  int32_t D, V, K;
+  int32_t ld;             /* row stride of theta and phi, in elements */
+  float alpha, beta;      /* > 0, finite */
+  const int32_t* doc_len; /* device */
+  const int32_t* w;       /* device */
+  const int32_t* z;       /* device */
+  const float* theta;     /* device, 16-byte aligned */
+  const float* phi;       /* device, 16-byte aligned */
+  int32_t device;         /* HIP device ordinal */
+  void* stream;           /* hipStream_t or NULL */
+} augur_lda_static_args;
+int augur_lda_loglik_static(const augur_lda_static_args* args, double* out /* device double[2] */);
+
 /* ------------------------------------------------------------- measurement
  * Not part of the sampler: the ceilings its kernels are held against, measured on
  * the same device in the same run (the measurement protocol asks for the

@@ -38,6 +38,13 @@ class GmmConfig(C.Structure):
                 ("device", C.c_int32), ("stream", C.c_void_p), ("flags", C.c_uint32)]
 
 
+class LdaStaticArgs(C.Structure):
+    _fields_ = [("D", C.c_int32), ("V", C.c_int32), ("K", C.c_int32), ("ld", C.c_int32),
+                ("alpha", C.c_float), ("beta", C.c_float), ("doc_len", C.c_void_p),
+                ("w", C.c_void_p), ("z", C.c_void_p), ("theta", C.c_void_p), ("phi", C.c_void_p),
+                ("device", C.c_int32), ("stream", C.c_void_p)]
+
+
 class MhRegConfig(C.Structure):
     _fields_ = [("N", C.c_int64), ("K", C.c_int32), ("prior_sd", C.c_float),
                 ("tau_shape", C.c_float), ("tau_scale", C.c_float), ("x_lo", C.c_float),
@@ -84,6 +91,7 @@ def lib():
         L.augur_lda_get_degenerate.argtypes = [vp, C.POINTER(C.c_int64)]
         L.augur_lda_probe_gather.argtypes = [vp, C.c_int32, C.POINTER(C.c_double)]
         L.augur_probe_stream_copy.argtypes = [vp, vp, C.c_int64, C.c_int32, vp, C.POINTER(C.c_double)]
+        L.augur_lda_loglik_static.argtypes = [C.POINTER(LdaStaticArgs), vp]
         L.augur_gmm_create.argtypes = [C.POINTER(GmmConfig), vp, C.POINTER(vp)]
         L.augur_gmm_destroy.argtypes = [vp]
         L.augur_gmm_destroy.restype = None
@@ -169,6 +177,15 @@ class _Arrays:
         if size is not None and n != size:
             raise ValueError(f"array has {n} elements, expected {size}")
         return t
+
+
+def lda_loglik_static(D, V, K, ld, alpha, beta, doc_len, w, z, theta, phi, out, device=0,
+                      stream=None):
+    """augur_lda_loglik_static: every array is a torch CUDA tensor the caller owns (out: two
+    float64); nothing is allocated, copied or waited for here."""
+    a = LdaStaticArgs(int(D), int(V), int(K), int(ld), float(alpha), float(beta), _ptr(doc_len),
+                      _ptr(w), _ptr(z), _ptr(theta), _ptr(phi), int(device), _stream_handle(stream))
+    _check(lib().augur_lda_loglik_static(C.byref(a), _ptr(out)))
 
 
 def probe_stream_copy(src, dst, reps=10, stream=None):

@@ -18,6 +18,7 @@
 
 #include <algorithm>
 #include <exception>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -1347,7 +1348,32 @@ __global__ __launch_bounds__(1024) void doc_offsets_kernel(const int32_t* __rest
   if (neg && !clamp) atomicAdd(bad, neg);
 }
 
+// The table of log_tab built on the device (fill_log_table is its host twin; the two may
+// differ in the last bit of an entry).
+__global__ __launch_bounds__(256) void log_table_kernel(double2* __restrict__ t) {
+  const int i = threadIdx.x;
+  if (i >= kLogTableSize) return;
+  const double inv = 1.0 / (1.0 + (double)i / 128.0);
+  // from the fold on the entry is -ln(inv) - ln 2 = -ln(2 inv); 2 inv is exact, so no cancellation
+  double l = i >= kLogTableFold ? -log(2.0 * inv) : -log(inv);
+  if (i == 0 || i == kLogTableSize - 1) l = 0.0;
+  t[i] = make_double2(inv, l);
+}
+
 }  // namespace
+
+// ------------------------------------------- scratch of augur_lda_loglik_static
+// Device memory of the entry point that allocates nothing: the document offsets it forms
+// from the caller's lengths, the block partials of its reductions and the logarithm table.
+// One copy per GPU, held until the process ends; its contents are whatever the last call
+// left.  Host code never uses this name as an address: it asks the runtime for the array's
+// device address once per device (static_scratch) and passes that.
+constexpr int kStaticMaxDocs = 1 << 20;
+constexpr size_t kScratchOffBytes = (sizeof(int64_t) * ((size_t)kStaticMaxDocs + 1) + 255) / 256 * 256;
+constexpr size_t kScratchRedBytes = (sizeof(double) * (4 * (size_t)kRedBlocks + 2) + 255) / 256 * 256;
+constexpr size_t kScratchTabBytes = (sizeof(double2) * (size_t)kLogTableSize + 255) / 256 * 256;
+constexpr size_t kScratchBytes = kScratchOffBytes + kScratchRedBytes + kScratchTabBytes;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
 
 // ======================================================================= host
 struct augur_lda {
@@ -2312,6 +2338,68 @@ int augur_lda_sync(augur_lda* h) {
   AUGUR_CHECK_HANDLE(h);
   AUGUR_HIP_TRY(hipStreamSynchronize(h->stream));
   return AUGUR_OK;
+}
+
+// ---------------------------------------------------- the call that allocates nothing
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+unsigned char* g_scratch_ptr[kMaxDevices] = {};
+// Device address of `scratch` on the current device (asked for once per device).
+int static_scratch(int device, unsigned char** out) {
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[device] == nullptr) {
+    void* p = nullptr;
+    AUGUR_HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    AUGUR_REQUIRE(p != nullptr, "the runtime returned no address for the scratch array");
+    g_scratch_ptr[device] = static_cast<unsigned char*>(p);
+  }
+  *out = g_scratch_ptr[device];
+  return AUGUR_OK;
+}
+}  // namespace
+
+int augur_lda_loglik_static(const augur_lda_static_args* a, double* out) {
+  AUGUR_REQUIRE(a != nullptr && out != nullptr, "args or out is NULL");
+  AUGUR_REQUIRE(a->D > 0 && a->V > 0 && a->K > 0, "D, V, K must be positive (got %d, %d, %d)", a->D,
+                a->V, a->K);
+  AUGUR_REQUIRE(a->D <= kStaticMaxDocs,
+                "D = %d exceeds the %d documents whose offsets fit the library's static scratch "
+                "memory; use a handle (augur_lda_create, augur_lda_loglik) for larger corpora",
+                a->D, kStaticMaxDocs);
+  AUGUR_REQUIRE(a->K <= 1024, "K = %d is above the supported maximum of 1024 topics", a->K);
+  AUGUR_REQUIRE(a->ld >= a->K && a->ld % 4 == 0,
+                "ld = %d must be a multiple of 4 and at least K = %d", a->ld, a->K);
+  AUGUR_REQUIRE((int64_t)a->V * a->ld <= (1LL << 30), "V * ld = %lld exceeds 2^30 table entries",
+                (long long)a->V * a->ld);
+  AUGUR_REQUIRE(std::isfinite(a->alpha) && a->alpha > 0.f && std::isfinite(a->beta) && a->beta > 0.f,
+                "alpha and beta must be positive and finite");
+  AUGUR_REQUIRE(a->doc_len != nullptr && a->w != nullptr && a->z != nullptr && a->theta != nullptr &&
+                    a->phi != nullptr,
+                "doc_len, w, z, theta and phi must not be NULL");
+  AUGUR_REQUIRE(((uintptr_t)a->theta & 15) == 0 && ((uintptr_t)a->phi & 15) == 0 &&
+                    ((uintptr_t)out & 7) == 0,
+                "theta and phi must be 16-byte aligned and out 8-byte aligned");
+  AUGUR_REQUIRE(a->device >= 0 && a->device < kMaxDevices, "device %d out of range", a->device);
+  int ndev = 0;
+  AUGUR_HIP_TRY(hipGetDeviceCount(&ndev));
+  AUGUR_REQUIRE(a->device < ndev, "device %d out of range (%d present)", a->device, ndev);
+  DeviceGuard guard(a->device);
+  AUGUR_REQUIRE(guard.ok, "cannot select device %d", a->device);
+  unsigned char* base = nullptr;
+  AUGUR_TRY(static_scratch(a->device, &base));
+  int64_t* doc_off = reinterpret_cast<int64_t*>(base);
+  double* red = reinterpret_cast<double*>(base + kScratchOffBytes);
+  double2* table = reinterpret_cast<double2*>(base + kScratchOffBytes + kScratchRedBytes);
+  hipStream_t stream = (hipStream_t)a->stream;
+  // every part of the scratch memory that the kernels below read is written first, on this
+  // stream: the offsets [0, D], all block partials, the table; nothing needs clearing
+  hipLaunchKernelGGL(doc_offsets_kernel, dim3(1), dim3(1024), 0, stream, a->doc_len, doc_off, a->D,
+                     (unsigned long long*)nullptr);
+  hipLaunchKernelGGL(log_table_kernel, dim3(1), dim3(256), 0, stream, table);
+  AUGUR_HIP_TRY(hipGetLastError());
+  return launch_loglik(stream, a->w, a->z, doc_off, nullptr, a->D, a->theta, a->phi, a->D, a->V, a->K,
+                       a->ld, (double)a->alpha, (double)a->beta, table, red, out);
 }
 
 }  // extern "C"
