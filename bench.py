@@ -222,8 +222,11 @@ def run_lda(name, cfg, corpus, steps, warmup, repeats, with_ceilings, overlap=Tr
         ceil = {"hbm_copy_GBs": 2 * 4 * n_copy / (copy_ms * 1e-3) / 1e9,
                 "hbm_copy_note": "plain device copy of 1 GiB (read + write bytes over its time)",
                 "gather_only_ms": gather_ms,
-                "gather_only_note": "the z kernel's walk and phi-row loads over the same word stream, no "
-                                    "arithmetic, random numbers or stores",
+                "gather_only_note": "the z kernel's walk over the same word stream with every phi row loaded "
+                                    "from memory (a quad per token, 64 bytes a load), no arithmetic, random "
+                                    "numbers or stores: the floor that the texture addresser sets for that "
+                                    "load shape; the resident form of the z kernel reads the rows of the most "
+                                    "frequent words from LDS instead and can be faster",
                 "gather_only_algorithmic_GBs": bytes_z / (gather_ms * 1e-3) / 1e9,
                 "sample_z_ms": t_z * 1e3, "gather_only_over_sample_z": gather_ms / (t_z * 1e3)}
         if counters is not None:

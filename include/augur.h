@@ -97,6 +97,16 @@ int augur_lda_set_observed(augur_lda* h, uint32_t mask);
  * flight. */
 int augur_lda_set_overlap(augur_lda* h, int32_t on);
 
+/* The z step (Sect. 4.2) has two forms up to 256 topics, which draw the same bits.  One
+ * gives every wave a document and reads every phi row from memory.  The other keeps
+ * workgroups resident, one per CU, with the phi rows of the corpus's most frequent
+ * words in LDS (as many as fit: about 100 at K = 200), and reads the rows of those
+ * words from there; it pays when there are several documents for every wave of
+ * the chip.  mode 0 (default): the library chooses by the number of documents;
+ * 1: the resident form whenever it is available (K <= 256, at least 8 rows fit);
+ * 2: never.  Not to be changed while a sweep is in flight. */
+int augur_lda_set_z_cache(augur_lda* h, int32_t mode);
+
 /* Same as sweep, but records events on the handle's stream around the steps and
  * returns the summed device time over the n_sweeps, in ms: ms[0] sample_z;
  * ms[1] count_accumulate (with overlap on: the document table only; the word

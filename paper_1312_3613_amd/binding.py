@@ -80,6 +80,7 @@ def lib():
         L.augur_lda_sweep.argtypes = [vp, C.c_int32]
         L.augur_lda_sweep_profile.argtypes = [vp, C.c_int32, C.POINTER(C.c_double)]
         L.augur_lda_set_overlap.argtypes = [vp, C.c_int32]
+        L.augur_lda_set_z_cache.argtypes = [vp, C.c_int32]
         L.augur_lda_set_observed.argtypes = [vp, C.c_uint32]
         for name in ("step_sample_z", "step_count", "step_resample_theta", "step_resample_phi",
                      "step_finish", "sync"):
@@ -241,6 +242,9 @@ class LDA:
 
     def set_overlap(self, on):
         _check(lib().augur_lda_set_overlap(self._h, 1 if on else 0))
+
+    def set_z_cache(self, mode):
+        _check(lib().augur_lda_set_z_cache(self._h, int(mode)))
 
     def sweep_profile(self, n=1):
         ms = (C.c_double * LDA_NSTEPS)()

@@ -454,10 +454,182 @@ __device__ __forceinline__ void bisect_level(const float (&a)[NS16], float t, bo
 // free: the wave already owns the document; a segment of a split document adds
 // to the row, which the host zeroes before the launch).
 //
-// Waves per SIMD: the kernel waits on its row loads, so a wave more per SIMD pays even when
-// the register limit that buys it spills a few values.
+// The kernel comes in two forms that draw the same bits.  The plain form gives every wave one
+// segment and takes every phi row from memory.  The kernel is bound by the texture addresser
+// (96 % busy at K = 200: about 21 cycles for every 64-lane load of 16 bytes a lane, whatever
+// the cache level that answers), so the second form takes the rows of the most frequent words
+// from LDS instead, which has a path of its own: workgroups of 16 waves stay resident, one per
+// CU, copy the rows of the H most frequent words (H as many as fit beside the waves' own
+// strips: about 100 at K = 200) into LDS once per launch, and walk the tokens of every
+// 256-token chunk in an order fixed at create time: tokens of cached words first.  An
+// iteration whose 16 tokens are all cached reads its rows from LDS and issues no load.
+//
+// Waves per SIMD (plain form): the kernel waits on its row loads, so a wave more per SIMD pays.
 template <int NS16>
 constexpr int quad_waves_per_simd() { return NS16 > 10 ? 4 : NS16 > 6 ? 5 : NS16 > 3 ? 6 : 8; }
+
+// What pass 2 of a token needs, carried from the iteration that ran its pass 1.
+struct QuadPending {
+  float4 p2;          // the lane's chunk of the crossing stripe (load in flight)
+  float t, cprev;     // threshold; running sum before the crossing stripe
+  int cs;             // crossing stripe
+  uint32_t r, row_off;
+  int pos;            // position of the token in its chunk (0..255), or -1 for a quad without a token
+  bool ok, in_row;    // S positive and finite; t < S
+  __device__ __forceinline__ void idle() {  // a quad without a token, which pass 2 runs through idly
+    p2 = make_float4(0.f, 0.f, 0.f, 0.f);
+    t = 0.f;
+    cprev = 0.f;
+    cs = 0;
+    r = 0u;
+    row_off = 0u;
+    pos = -1;
+    ok = true;
+    in_row = true;
+  }
+};
+// The lane-constant part of a quad's view of the tables.
+struct QuadLane {
+  int q;                 // lane within the quad
+  uint32_t lane_off;     // 16 q: the lane's byte offset inside a 64-byte piece of a row
+  uint32_t row_bytes;    // 4 ldk
+  float from1, from2;    // 1 for lanes that have a neighbour one / two lanes down in the quad, else 0
+  const char* phi_bytes;
+  const float* theta_q;  // the wave's copy of theta_d in LDS, + 4 q
+};
+
+// Pass 1 and the bisection: from the row's chunks to S, t = u S, the crossing stripe and the
+// running sum before it.  theta_p1 is theta_q behind an offset the compiler cannot see through
+// (theta_d does not change inside the token loop, so it would otherwise be read once and
+// held in registers, at the price of a wave per SIMD).
+template <int NS16>
+__device__ __forceinline__ void quad_pass1(const float4 (&ph)[NS16], const float* theta_p1, uint32_t r,
+                                           float& S, float& t, int& cs, float& cprev) {
+  float ac[NS16];
+  float acc = 0.f;
+#pragma unroll
+  for (int c = 0; c < NS16; ++c) {
+    const float4 tc = *reinterpret_cast<const float4*>(theta_p1 + 16 * c);
+    acc = c == 0 ? tc.x * ph[c].x : fmaf(tc.x, ph[c].x, acc);
+    acc = fmaf(tc.y, ph[c].y, acc);
+    acc = fmaf(tc.z, ph[c].z, acc);
+    acc = fmaf(tc.w, ph[c].w, acc);
+    ac[c] = acc;
+  }
+  S = quad_sum(ac[NS16 - 1]);
+  t = u24(r) * S;
+  cs = 0;
+  cprev = 0.f;
+  if constexpr (NS16 > 1) {
+    constexpr int M = NS16 - 1;
+    constexpr int TOP = M >= 8 ? 8 : M >= 4 ? 4 : M >= 2 ? 2 : 1;
+    bool m[5] = {false, false, false, false, false};
+    bisect_level<NS16, TOP, TOP>(ac, t, m, cs, cprev);
+  }
+}
+
+// Pass 2: the topic inside the crossing stripe; the drawn topic goes to the chunk's stage
+// (and the document histogram).
+template <int NS16, bool kCountDocs>
+__device__ __forceinline__ void quad_finish(const QuadPending& P, const QuadLane& L, int K,
+                                            unsigned long long* __restrict__ n_degenerate,
+                                            uint8_t* zstage, int32_t* hist) {
+  const bool valid = P.pos >= 0;
+  const int cs = P.cs;
+  const int q = L.q;
+  const float4 t2 = *reinterpret_cast<const float4*>(L.theta_q + 16 * cs);
+  const float l0 = t2.x * P.p2.x;
+  const float l1 = fmaf(t2.y, P.p2.y, l0);
+  const float l2 = fmaf(t2.z, P.p2.z, l1);
+  const float l3 = fmaf(t2.w, P.p2.w, l2);
+  // sum of the chunks of the quad's lower lanes: an inclusive scan over the quad in two
+  // steps (a lane takes the value one, then two, lanes down; lanes without such a neighbour
+  // multiply what they get by 0), then moved up by one lane
+  float incl = fmaf(dpp_mov_f32<kQpDown1>(l3), L.from1, l3);
+  incl = fmaf(dpp_mov_f32<kQpDown2>(incl), L.from2, incl);
+  const float excl = dpp_mov_f32<kQpDown1>(incl) * L.from1;
+  const float tt = fmaxf(P.t - (P.cprev + excl), 0.f);
+  const int e = (l0 <= tt) + (l1 <= tt) + (l2 <= tt);
+  int cand = l3 > tt ? 4 * q + e : kNoTopic;
+  cand = min(cand, dpp_i32_keep<kQpSwap1>(cand));
+  cand = min(cand, dpp_i32_keep<kQpSwap2>(cand));
+  int k = 16 * cs + cand;
+
+  const bool found = P.in_row && cand != kNoTopic;
+  if (__builtin_expect(__any(valid && !(P.ok && found)), 0)) {
+    if (!P.ok) {
+      // zero or non-finite mass: z = floor(u K)
+      k = u24_times(P.r, K);
+      if (valid && q == 0) atomicAdd(n_degenerate, 1ULL);
+    } else if (!found) {
+      // rounding put t at or past the running sum that should exceed it: the
+      // last topic of positive mass in the crossing stripe (or overall)
+      const int limit = P.in_row ? 16 * (cs + 1) : 16 * NS16;
+      int last = -1;
+#pragma unroll 1
+      for (int c = 0; c < NS16; ++c) {  // rare: kept small, nothing precomputed outside
+        const uint32_t o = min(64u * (uint32_t)c + L.lane_off, L.row_bytes - 16u);
+        const float4 pp = *reinterpret_cast<const float4*>(L.phi_bytes + (P.row_off + o));
+        const float4 tp = *reinterpret_cast<const float4*>(L.theta_q + 16 * c);
+        const int kk = 16 * c + 4 * q;
+        if (kk < limit) {
+          if (tp.x * pp.x > 0.f) last = kk;
+          if (tp.y * pp.y > 0.f) last = kk + 1;
+          if (tp.z * pp.z > 0.f) last = kk + 2;
+          if (tp.w * pp.w > 0.f) last = kk + 3;
+        }
+      }
+      last = max(last, dpp_i32_keep<kQpSwap1>(last));
+      last = max(last, dpp_i32_keep<kQpSwap2>(last));
+      k = last;
+    }
+  }
+  // garbage parameters (negative or NaN entries) must not yield an index outside the tables
+  k = min(max(k, 0), K - 1);
+  if (valid && q == 0) {
+    zstage[P.pos] = (uint8_t)k;  // K <= 256 here; stored to z and zb a chunk at a time
+    if (kCountDocs) atomicAdd(&hist[k], 1);
+  }
+}
+
+// Stores the staged topics of the chunk at rbase (tokens lo..hi-1 of the segment): lane L takes
+// tokens rbase + 4 L .. + 3, so z leaves as one 16-byte and zb as one 4-byte store per lane
+// instead of a 4-byte and a 1-byte store per token (a store instruction of 16 lanes costs the
+// address path as much as one of 64).  Tokens outside lo..hi-1 belong to other waves: the
+// lanes at the two ends store element by element.
+__device__ __forceinline__ void quad_flush_chunk(const uint8_t* zstage, int32_t* z_seg, uint8_t* zb_seg,
+                                                 int rbase, int lo, int hi, int lane) {
+  wave_lds_fence();
+  const int r0 = rbase + 4 * lane;
+  const uint32_t four = *reinterpret_cast<const uint32_t*>(zstage + 4 * lane);
+  const int k0 = (int)(four & 255u), k1 = (int)((four >> 8) & 255u), k2 = (int)((four >> 16) & 255u),
+            k3 = (int)(four >> 24);
+  if (r0 >= lo && r0 + 4 <= hi) {
+    *reinterpret_cast<int4*>(z_seg + r0) = make_int4(k0, k1, k2, k3);
+    *reinterpret_cast<uint32_t*>(zb_seg + r0) = four;
+  } else {
+    if (r0 + 0 >= lo && r0 + 0 < hi) { z_seg[r0 + 0] = k0; zb_seg[r0 + 0] = (uint8_t)k0; }
+    if (r0 + 1 >= lo && r0 + 1 < hi) { z_seg[r0 + 1] = k1; zb_seg[r0 + 1] = (uint8_t)k1; }
+    if (r0 + 2 >= lo && r0 + 2 < hi) { z_seg[r0 + 2] = k2; zb_seg[r0 + 2] = (uint8_t)k2; }
+    if (r0 + 3 >= lo && r0 + 3 < hi) { z_seg[r0 + 3] = k3; zb_seg[r0 + 3] = (uint8_t)k3; }
+  }
+  wave_lds_fence();  // before the next chunk's topics overwrite the stage
+}
+
+// theta_d into the wave's LDS strip, zero past the last topic.  Pass 1 reads it from there
+// (all quads read the same 16 bytes per lane: a broadcast), which keeps the registers for
+// the row loads in flight.
+template <int NS16>
+__device__ __forceinline__ void quad_stage_theta(const float* __restrict__ theta, int d, int ldk,
+                                                 float* theta_s, int tq, int q) {
+#pragma unroll
+  for (int c = 0; c < NS16; ++c) {
+    const int col = 16 * c + 4 * q;
+    const float4 v = col < ldk ? *reinterpret_cast<const float4*>(theta + (size_t)d * ldk + col)
+                               : make_float4(0.f, 0.f, 0.f, 0.f);
+    if (tq == 0) *reinterpret_cast<float4*>(theta_s + col) = v;
+  }
+}
 
 template <int NS16, bool kCountDocs>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(quad_waves_per_simd<NS16>())))
@@ -486,23 +658,16 @@ void lda_sample_z_quad_kernel(
   uint8_t* zstage = zstage_all[wave];
   if (kCountDocs)
     for (int k = lane; k < 16 * NS16; k += 64) hist[k] = 0;
-
-  // theta_d in the wave's LDS strip, zero past the last topic.  Pass 1 reads it from there
-  // (all quads read the same 16 bytes per lane: a broadcast), which keeps the registers for
-  // the row loads in flight: their number is what bounds this kernel.
-#pragma unroll
-  for (int c = 0; c < NS16; ++c) {
-    const int col = 16 * c + 4 * q;
-    const float4 v = col < ldk ? *reinterpret_cast<const float4*>(theta + (size_t)d * ldk + col)
-                               : make_float4(0.f, 0.f, 0.f, 0.f);
-    if (tq == 0) *reinterpret_cast<float4*>(theta_s + col) = v;
-  }
-  const uint32_t row_bytes = 4u * (uint32_t)ldk;
-  const uint32_t lane_off = 16u * (uint32_t)q;
-  const uint32_t last_off = min(64u * (NS16 - 1) + lane_off, row_bytes - 16u);
-  const char* phi_bytes = reinterpret_cast<const char*>(phi);
-  const float* theta_q = theta_s + 4 * q;
-  const float from1 = q >= 1 ? 1.f : 0.f, from2 = q >= 2 ? 1.f : 0.f;  // see the scan in pass 2
+  quad_stage_theta<NS16>(theta, d, ldk, theta_s, tq, q);
+  QuadLane L;
+  L.q = q;
+  L.lane_off = 16u * (uint32_t)q;
+  L.row_bytes = 4u * (uint32_t)ldk;
+  L.from1 = q >= 1 ? 1.f : 0.f;
+  L.from2 = q >= 2 ? 1.f : 0.f;
+  L.phi_bytes = reinterpret_cast<const char*>(phi);
+  L.theta_q = theta_s + 4 * q;
+  const uint32_t last_off = min(64u * (NS16 - 1) + L.lane_off, L.row_bytes - 16u);
   // Tokens are addressed relative to the segment's first chunk base (an int: a segment has at
   // most kSegTokens + 3 positions).
   const int32_t* w_seg = w + sg.first;
@@ -511,110 +676,9 @@ void lda_sample_z_quad_kernel(
   const int rel_a = (int)(sg.a - sg.first);  // 0..3: the first token of the document
   const int rel_b = (int)(sg.end - sg.first);
 
-  // What pass 2 of a token needs, carried from the iteration that ran its pass 1.
-  struct Pending {
-    float4 p2;          // the lane's chunk of the crossing stripe (load in flight)
-    float t, cprev;     // threshold; running sum before the crossing stripe
-    int cs;             // crossing stripe
-    uint32_t r, row_off;
-    int rel;            // position of the token in the segment, or -1 for a quad without a token
-    bool ok, in_row;    // S positive and finite; t < S
-  };
-  auto finish = [&](const Pending& P) {
-    const bool valid = P.rel >= 0;
-    const int cs = P.cs;
-    const float4 t2 = *reinterpret_cast<const float4*>(theta_q + 16 * cs);
-    const float l0 = t2.x * P.p2.x;
-    const float l1 = fmaf(t2.y, P.p2.y, l0);
-    const float l2 = fmaf(t2.z, P.p2.z, l1);
-    const float l3 = fmaf(t2.w, P.p2.w, l2);
-    // sum of the chunks of the quad's lower lanes: an inclusive scan over the quad in two
-    // steps (a lane takes the value one, then two, lanes down; lanes without such a neighbour
-    // multiply what they get by 0), then moved up by one lane
-    float incl = fmaf(dpp_mov_f32<kQpDown1>(l3), from1, l3);
-    incl = fmaf(dpp_mov_f32<kQpDown2>(incl), from2, incl);
-    const float excl = dpp_mov_f32<kQpDown1>(incl) * from1;
-    const float tt = fmaxf(P.t - (P.cprev + excl), 0.f);
-    const int e = (l0 <= tt) + (l1 <= tt) + (l2 <= tt);
-    int cand = l3 > tt ? 4 * q + e : kNoTopic;
-    cand = min(cand, dpp_i32_keep<kQpSwap1>(cand));
-    cand = min(cand, dpp_i32_keep<kQpSwap2>(cand));
-    int k = 16 * cs + cand;
-
-    const bool found = P.in_row && cand != kNoTopic;
-    if (__builtin_expect(__any(valid && !(P.ok && found)), 0)) {
-      if (!P.ok) {
-        // zero or non-finite mass: z = floor(u K)
-        k = u24_times(P.r, K);
-        if (valid && q == 0) atomicAdd(n_degenerate, 1ULL);
-      } else if (!found) {
-        // rounding put t at or past the running sum that should exceed it: the
-        // last topic of positive mass in the crossing stripe (or overall)
-        const int limit = P.in_row ? 16 * (cs + 1) : 16 * NS16;
-        int last = -1;
-#pragma unroll 1
-        for (int c = 0; c < NS16; ++c) {  // rare: kept small, nothing precomputed outside
-          const uint32_t o = min(64u * (uint32_t)c + lane_off, row_bytes - 16u);
-          const float4 pp = *reinterpret_cast<const float4*>(phi_bytes + (P.row_off + o));
-          const float4 tp = *reinterpret_cast<const float4*>(theta_q + 16 * c);
-          const int kk = 16 * c + 4 * q;
-          if (kk < limit) {
-            if (tp.x * pp.x > 0.f) last = kk;
-            if (tp.y * pp.y > 0.f) last = kk + 1;
-            if (tp.z * pp.z > 0.f) last = kk + 2;
-            if (tp.w * pp.w > 0.f) last = kk + 3;
-          }
-        }
-        last = max(last, dpp_i32_keep<kQpSwap1>(last));
-        last = max(last, dpp_i32_keep<kQpSwap2>(last));
-        k = last;
-      }
-    }
-    // garbage parameters (negative or NaN entries) must not yield an index outside the tables
-    k = min(max(k, 0), K - 1);
-    if (valid && q == 0) {
-      zstage[P.rel & 255] = (uint8_t)k;  // K <= 256 here; stored to z and zb a chunk at a time
-      if (kCountDocs) atomicAdd(&hist[k], 1);
-    }
-  };
-  // Stores the staged topics of the chunk at rbase (tokens lo..hi-1 of the segment): lane L takes
-  // tokens rbase + 4 L .. + 3, so z leaves as one 16-byte and zb as one 4-byte store per lane
-  // instead of a 4-byte and a 1-byte store per token (a store instruction of 16 lanes costs the
-  // address path as much as one of 64).  Tokens outside lo..hi-1 belong to other waves: the
-  // lanes at the two ends store element by element.
-  auto flush_chunk = [&](int rbase, int lo, int hi) {
-    wave_lds_fence();
-    const int r0 = rbase + 4 * lane;
-    const uint32_t four = *reinterpret_cast<const uint32_t*>(zstage + 4 * lane);
-    const int k0 = (int)(four & 255u), k1 = (int)((four >> 8) & 255u), k2 = (int)((four >> 16) & 255u),
-              k3 = (int)(four >> 24);
-    if (r0 >= lo && r0 + 4 <= hi) {
-      *reinterpret_cast<int4*>(z_seg + r0) = make_int4(k0, k1, k2, k3);
-      *reinterpret_cast<uint32_t*>(zb_seg + r0) = four;
-    } else {
-      if (r0 + 0 >= lo && r0 + 0 < hi) { z_seg[r0 + 0] = k0; zb_seg[r0 + 0] = (uint8_t)k0; }
-      if (r0 + 1 >= lo && r0 + 1 < hi) { z_seg[r0 + 1] = k1; zb_seg[r0 + 1] = (uint8_t)k1; }
-      if (r0 + 2 >= lo && r0 + 2 < hi) { z_seg[r0 + 2] = k2; zb_seg[r0 + 2] = (uint8_t)k2; }
-      if (r0 + 3 >= lo && r0 + 3 < hi) { z_seg[r0 + 3] = k3; zb_seg[r0 + 3] = (uint8_t)k3; }
-    }
-    wave_lds_fence();  // before the next chunk's topics overwrite the stage
-  };
-
-  // at the start of a chunk: a quad without a token, which pass 2 runs through idly
-  Pending P;
-  auto idle = [&]() {
-    P.p2 = make_float4(0.f, 0.f, 0.f, 0.f);
-    P.t = 0.f;
-    P.cprev = 0.f;
-    P.cs = 0;
-    P.r = 0u;
-    P.row_off = 0u;
-    P.rel = -1;
-    P.ok = true;
-    P.in_row = true;
-  };
+  QuadPending P;
   for (int rbase = 0; rbase < rel_b; rbase += 256) {
-    idle();
+    P.idle();
     {
       // tokens rbase + 4 lane .. + 3 of the segment: one Philox block and four word ids (w is
       // padded by 256 entries, so the vector load never leaves the allocation)
@@ -635,64 +699,295 @@ void lda_sample_z_quad_kernel(
       const int i = i0 + tq;
       const bool valid = i < hi;
       const uint2 rw = strip[(valid ? i : lo) - rbase];
-      const uint32_t row_off = __umul24(rw.y, row_bytes);  // both below 2^24; product below 2^32
-      const char* rowp = phi_bytes + (size_t)(row_off + lane_off);  // constant offsets fold into the loads
+      const uint32_t row_off = __umul24(rw.y, L.row_bytes);  // both below 2^24; product below 2^32
+      const char* rowp = L.phi_bytes + (size_t)(row_off + L.lane_off);  // constant offsets fold into the loads
       float4 ph[NS16];
 #pragma unroll
       for (int c = 0; c < NS16 - 1; ++c) ph[c] = *reinterpret_cast<const float4*>(rowp + 64 * c);
-      ph[NS16 - 1] = *reinterpret_cast<const float4*>(phi_bytes + (row_off + last_off));
+      ph[NS16 - 1] = *reinterpret_cast<const float4*>(L.phi_bytes + (row_off + last_off));
 
       // pass 2 of the previous iteration, while those loads are on their way.  The empty asm
       // statement keeps the compiler from starting it (and waiting for its chunk) before the
       // loads above have been issued: everything in pass 2 follows from the stripe number.
       asm volatile("" : "+v"(P.cs)::"memory");
-      finish(P);
+      quad_finish<NS16, kCountDocs>(P, L, K, n_degenerate, zstage, hist);
 
-      // pass 1: the lane's chain; a[c] = its value after stripe c.  theta_d does not change
-      // inside the loop, so the compiler would read all of it once and keep it in registers;
-      // an offset it cannot see through keeps the LDS reads (and four waves more per CU) here.
       int theta_off = 4 * q;
       asm volatile("" : "+v"(theta_off));
-      const float* theta_p1 = theta_s + theta_off;
-      float ac[NS16];
-      float acc = 0.f;
-#pragma unroll
-      for (int c = 0; c < NS16; ++c) {
-        const float4 tc = *reinterpret_cast<const float4*>(theta_p1 + 16 * c);
-        acc = c == 0 ? tc.x * ph[c].x : fmaf(tc.x, ph[c].x, acc);
-        acc = fmaf(tc.y, ph[c].y, acc);
-        acc = fmaf(tc.z, ph[c].z, acc);
-        acc = fmaf(tc.w, ph[c].w, acc);
-        ac[c] = acc;
-      }
-      const float S = quad_sum(ac[NS16 - 1]);
-      const float t = u24(rw.x) * S;
-      int cs = 0;
-      float cprev = 0.f;
-      if constexpr (NS16 > 1) {
-        constexpr int M = NS16 - 1;
-        constexpr int TOP = M >= 8 ? 8 : M >= 4 ? 4 : M >= 2 ? 2 : 1;
-        bool m[5] = {false, false, false, false, false};
-        bisect_level<NS16, TOP, TOP>(ac, t, m, cs, cprev);
-      }
+      float S, t, cprev;
+      int cs;
+      quad_pass1<NS16>(ph, theta_s + theta_off, rw.x, S, t, cs, cprev);
       // the chunk of stripe cs again, for pass 2 in the next iteration
       P.p2 = *reinterpret_cast<const float4*>(
-          phi_bytes + (row_off + min(64u * (uint32_t)cs + lane_off, row_bytes - 16u)));
+          L.phi_bytes + (row_off + min(64u * (uint32_t)cs + L.lane_off, L.row_bytes - 16u)));
       P.t = t;
       P.cprev = cprev;
       P.cs = cs;
       P.r = rw.x;
       P.row_off = row_off;
-      P.rel = valid ? i : -1;
+      P.pos = valid ? i - rbase : -1;
       P.ok = S > 0.f && S <= FLT_MAX;  // false for 0, inf and NaN
       P.in_row = S > t;
     }
-    finish(P);  // the chunk's last iteration
-    flush_chunk(rbase, lo, hi);
+    quad_finish<NS16, kCountDocs>(P, L, K, n_degenerate, zstage, hist);  // the chunk's last iteration
+    quad_flush_chunk(zstage, z_seg, zb_seg, rbase, lo, hi, lane);
   }
   if (kCountDocs) {
     wave_lds_fence();
     flush_doc_histogram(hist, n_dk + (size_t)d * ldk, ldk, is_split(seg_base, d), lane);
+  }
+}
+
+// ---- the resident form, with the rows of the most frequent words in LDS ----
+// wz / ord: for every 256-token chunk of every segment, its tokens in processing order (cached
+// words first, each group in position order): wz = word id | (cache slot + 1) << 24 (0: not
+// cached), ord = position in the chunk; both indexed from the chunk's first token.  Built once
+// (lda_build_order_kernel): words never change.
+constexpr int kHotWaves = 16;              // waves of a resident workgroup
+constexpr int kHotMinStripes = 5;          // shortest rows for which the library picks this form itself
+// Cached rows lie 64 NS16 (+ pad) bytes apart.  A quad reads 64 contiguous bytes, half of the
+// LDS banks; two quads served together do not collide when their pieces start half the banks
+// apart, which random rows do half of the time if the row pitch is an odd multiple of 64 bytes,
+// and never if it is an even one.
+__host__ __device__ constexpr int hot_row_pad_bytes(int ns16) { return ns16 % 2 == 0 ? 64 : 0; }
+__host__ __device__ constexpr int hot_wave_bytes(int ns16, bool count_docs) {
+  // Philox words by position, wz by order, ord by order, theta_d, [document histogram], stage
+  return 1024 + 1024 + 256 + 64 * ns16 + (count_docs ? 64 * ns16 : 0) + 256;
+}
+template <int NS16, bool kCountDocs>
+__global__ __launch_bounds__(64 * kHotWaves) void lda_sample_z_hot_kernel(
+    const int32_t* __restrict__ wz, const uint8_t* __restrict__ ord, const int64_t* __restrict__ doc_off,
+    const int32_t* __restrict__ seg_base, int n_segs, const float* __restrict__ theta,
+    const float* __restrict__ phi, int32_t* __restrict__ z, int32_t* __restrict__ n_dk, int D, int K,
+    int ldk, uint64_t seed, uint32_t sweep, unsigned long long* __restrict__ n_degenerate,
+    uint8_t* __restrict__ zb, const int32_t* __restrict__ hot_words, int n_hot) {
+  extern __shared__ __align__(16) unsigned char lds[];
+  constexpr int kRowLds = 64 * NS16 + hot_row_pad_bytes(NS16);  // bytes between cached rows
+  constexpr int kWaveBytes = hot_wave_bytes(NS16, kCountDocs);
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  const uint32_t row_bytes = 4u * (uint32_t)ldk;  // 64 NS16: rows of tables with up to 256 topics are whole stripes
+  // the cache: row s = phi row of hot_words[s], 16 bytes a thread and trip
+  {
+    const int pieces = 4 * NS16;  // 16-byte pieces of a row
+    for (int e = threadIdx.x; e < n_hot * pieces; e += blockDim.x) {
+      const int s = e / pieces, pc = e - s * pieces;
+      const float4 v = *reinterpret_cast<const float4*>(reinterpret_cast<const char*>(phi) +
+                                                       ((size_t)(uint32_t)hot_words[s] * row_bytes + 16u * pc));
+      *reinterpret_cast<float4*>(lds + (size_t)s * kRowLds + 16 * pc) = v;
+    }
+  }
+  __syncthreads();  // the only barrier: every wave passes it before it looks for work
+  unsigned char* mine = lds + (size_t)n_hot * kRowLds + (size_t)wave * kWaveBytes;
+  uint32_t* strip_r = reinterpret_cast<uint32_t*>(mine);           // Philox word of position p
+  uint32_t* strip_w = reinterpret_cast<uint32_t*>(mine + 1024);    // wz of the j-th token in order
+  uint8_t* strip_o = mine + 2048;                                  // its position
+  float* theta_s = reinterpret_cast<float*>(mine + 2304);
+  int32_t* hist = reinterpret_cast<int32_t*>(mine + 2304 + 64 * NS16);
+  uint8_t* zstage = mine + 2304 + 64 * NS16 + (kCountDocs ? 64 * NS16 : 0);
+  const int tq = lane >> 2, q = lane & 3;
+  QuadLane L;
+  L.q = q;
+  L.lane_off = 16u * (uint32_t)q;
+  L.row_bytes = row_bytes;
+  L.from1 = q >= 1 ? 1.f : 0.f;
+  L.from2 = q >= 2 ? 1.f : 0.f;
+  L.phi_bytes = reinterpret_cast<const char*>(phi);
+  L.theta_q = theta_s + 4 * q;
+  const unsigned char* cache_q = lds + 16 * q;
+
+  for (int seg = blockIdx.x * kHotWaves + wave; seg < n_segs; seg += gridDim.x * kHotWaves) {
+    const Segment sg = segment_of(doc_off, seg_base, D, seg);
+    const int d = sg.d;
+    wave_lds_fence();  // the previous segment's reads of theta and the histogram are done
+    if (kCountDocs)
+      for (int k = lane; k < 16 * NS16; k += 64) hist[k] = 0;
+    quad_stage_theta<NS16>(theta, d, ldk, theta_s, tq, q);
+    int32_t* z_seg = z + sg.first;
+    uint8_t* zb_seg = zb + sg.first;
+    const int rel_a = (int)(sg.a - sg.first);
+    const int rel_b = (int)(sg.end - sg.first);
+
+    QuadPending P;
+    for (int rbase = 0; rbase < rel_b; rbase += 256) {
+      P.idle();
+      const int lo = max(rel_a, rbase);
+      const int hi = min(rel_b, rbase + 256);
+      const int n_valid = hi - lo;
+      int n_cached = 0;
+      {
+        const U4 r = random_block(seed, (uint64_t)((sg.first + rbase) >> 2) + (uint64_t)lane, sweep,
+                                  kStreamZ, 0);
+        // the chunk's order: entries lane, lane + 64, ... of the lists that start at its first token
+        const int32_t* wz_c = wz + (sg.first + lo);
+        const uint8_t* ord_c = ord + (sg.first + lo);
+        uint32_t wv[4];
+        uint8_t ov[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int j = lane + 64 * e;
+          wv[e] = j < n_valid ? (uint32_t)wz_c[j] : 0u;
+          ov[e] = j < n_valid ? ord_c[j] : (uint8_t)0;
+        }
+        wave_lds_fence();  // earlier reads of the strips are done
+        *reinterpret_cast<uint4*>(strip_r + 4 * lane) = make_uint4(r.x, r.y, r.z, r.w);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          strip_w[lane + 64 * e] = wv[e];
+          strip_o[lane + 64 * e] = ov[e];
+          n_cached += __popcll(__ballot((wv[e] >> 24) != 0u));
+        }
+        wave_lds_fence();
+      }
+      // The first 16 * n_hot_iters tokens of the order are cached: whole iterations that read
+      // LDS only.  The rest read memory.  One trip of the loop takes an iteration of each kind:
+      // it issues the row loads of the memory one, runs the LDS one from start to end while
+      // they are on their way, then pass 2 of the previous memory iteration and pass 1 of this
+      // one.  (Both counts are the same for the whole wave.)
+      const int n_hot_iters = __builtin_amdgcn_readfirstlane(n_cached) >> 4;
+      const int cold0 = 16 * n_hot_iters;
+      const int n_cold_iters = (n_valid - cold0 + 15) >> 4;
+      const int n_trips = max(n_hot_iters, n_cold_iters);
+      for (int it = 0; it < n_trips; ++it) {
+        const bool do_cold = it < n_cold_iters, do_hot = it < n_hot_iters;
+        float4 ph[NS16];
+        uint32_t r_c = 0u, row_off_c = 0u;
+        int pos_c = -1;
+        if (do_cold) {
+          const int j0 = cold0 + 16 * it;
+          const int j = j0 + tq;
+          const bool valid = j < n_valid;
+          const int jj = valid ? j : j0;  // a quad past the end redoes the iteration's first token
+          const uint32_t wv = strip_w[jj];
+          const int pos = (int)strip_o[jj];
+          r_c = strip_r[pos];
+          row_off_c = __umul24(wv & 0xFFFFFFu, row_bytes);
+          pos_c = valid ? pos : -1;
+          const char* rowp = L.phi_bytes + (size_t)(row_off_c + L.lane_off);
+#pragma unroll
+          for (int c = 0; c < NS16; ++c) ph[c] = *reinterpret_cast<const float4*>(rowp + 64 * c);
+        }
+        asm volatile("" ::: "memory");  // the loads above are issued before anything below starts
+        if (do_hot) {
+          const int j = 16 * it + tq;
+          const uint32_t wv = strip_w[j];
+          const int pos = (int)strip_o[j];
+          const uint32_t r = strip_r[pos];
+          const unsigned char* crow = cache_q + (size_t)((wv >> 24) - 1u) * kRowLds;
+          int theta_off = 4 * q;
+          asm volatile("" : "+v"(theta_off));
+          const float* theta_p1 = theta_s + theta_off;
+          // pass 1 with the row's pieces read from LDS as they are needed
+          float ac[NS16];
+          float acc = 0.f;
+#pragma unroll
+          for (int c = 0; c < NS16; ++c) {
+            const float4 tc = *reinterpret_cast<const float4*>(theta_p1 + 16 * c);
+            const float4 pc = *reinterpret_cast<const float4*>(crow + 64 * c);
+            acc = c == 0 ? tc.x * pc.x : fmaf(tc.x, pc.x, acc);
+            acc = fmaf(tc.y, pc.y, acc);
+            acc = fmaf(tc.z, pc.z, acc);
+            acc = fmaf(tc.w, pc.w, acc);
+            ac[c] = acc;
+          }
+          QuadPending H;
+          const float S = quad_sum(ac[NS16 - 1]);
+          H.t = u24(r) * S;
+          // t is a rounded fp32 product everywhere else (it crosses an iteration in a register);
+          // here pass 2 follows at once, and the compiler would fuse this product into pass 2's
+          // subtraction, unrounded: another threshold in the last bit, and other draws than the
+          // plain form's once in a million tokens
+          asm volatile("" : "+v"(H.t));
+          H.cs = 0;
+          H.cprev = 0.f;
+          if constexpr (NS16 > 1) {
+            constexpr int M = NS16 - 1;
+            constexpr int TOP = M >= 8 ? 8 : M >= 4 ? 4 : M >= 2 ? 2 : 1;
+            bool m[5] = {false, false, false, false, false};
+            bisect_level<NS16, TOP, TOP>(ac, H.t, m, H.cs, H.cprev);
+          }
+          H.p2 = *reinterpret_cast<const float4*>(crow + 64 * H.cs);
+          H.r = r;
+          H.row_off = __umul24(wv & 0xFFFFFFu, row_bytes);
+          H.pos = pos;
+          H.ok = S > 0.f && S <= FLT_MAX;
+          H.in_row = S > H.t;
+          quad_finish<NS16, kCountDocs>(H, L, K, n_degenerate, zstage, hist);
+        }
+        if (do_cold) {
+          asm volatile("" : "+v"(P.cs)::"memory");
+          quad_finish<NS16, kCountDocs>(P, L, K, n_degenerate, zstage, hist);
+          int theta_off = 4 * q;
+          asm volatile("" : "+v"(theta_off));
+          float S, t, cprev;
+          int cs;
+          quad_pass1<NS16>(ph, theta_s + theta_off, r_c, S, t, cs, cprev);
+          // the chunk of stripe cs again, for pass 2 in the next trip
+          P.p2 = *reinterpret_cast<const float4*>(L.phi_bytes + (row_off_c + 64u * (uint32_t)cs + L.lane_off));
+          P.t = t;
+          P.cprev = cprev;
+          P.cs = cs;
+          P.r = r_c;
+          P.row_off = row_off_c;
+          P.pos = pos_c;
+          P.ok = S > 0.f && S <= FLT_MAX;
+          P.in_row = S > t;
+        }
+      }
+      quad_finish<NS16, kCountDocs>(P, L, K, n_degenerate, zstage, hist);
+      quad_flush_chunk(zstage, z_seg, zb_seg, rbase, lo, hi, lane);
+    }
+    if (kCountDocs) {
+      wave_lds_fence();
+      flush_doc_histogram(hist, n_dk + (size_t)d * ldk, ldk, is_split(seg_base, d), lane);
+    }
+  }
+}
+
+// The processing order of the resident form: one wave per segment; for every 256-token chunk
+// a stable partition of its tokens into cached and other words.  slot_of[v] = cache slot + 1
+// of word v, or 0.
+__global__ __launch_bounds__(256) void lda_build_order_kernel(
+    const int32_t* __restrict__ w, const int64_t* __restrict__ doc_off,
+    const int32_t* __restrict__ seg_base, int n_segs, int D, const uint8_t* __restrict__ slot_of,
+    int32_t* __restrict__ wz, uint8_t* __restrict__ ord) {
+  const int lane = threadIdx.x & 63;
+  const int seg = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (seg >= n_segs) return;
+  const Segment sg = segment_of(doc_off, seg_base, D, seg);
+  const int rel_a = (int)(sg.a - sg.first), rel_b = (int)(sg.end - sg.first);
+  for (int rbase = 0; rbase < rel_b; rbase += 256) {
+    const int lo = max(rel_a, rbase), hi = min(rel_b, rbase + 256);
+    int word[4], slot[4];
+    bool valid[4];
+    int n_c = 0, n_o = 0;  // this lane's cached / other tokens
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int rel = rbase + 4 * lane + e;
+      valid[e] = rel >= lo && rel < hi;
+      word[e] = valid[e] ? w[sg.first + rel] : 0;
+      slot[e] = valid[e] ? (int)slot_of[word[e]] : 0;
+      n_c += valid[e] && slot[e] != 0;
+      n_o += valid[e] && slot[e] == 0;
+    }
+    // exclusive sums over the lower lanes, and the wave's number of cached tokens
+    int before_c = n_c, before_o = n_o;
+    for (int o = 1; o < 64; o <<= 1) {
+      const int uc = __shfl_up(before_c, o, 64), uo = __shfl_up(before_o, o, 64);
+      if (lane >= o) { before_c += uc; before_o += uo; }
+    }
+    const int total_c = __shfl(before_c, 63, 64);
+    before_c -= n_c;
+    before_o -= n_o;
+    int32_t* wz_c = wz + (sg.first + lo);
+    uint8_t* ord_c = ord + (sg.first + lo);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      if (!valid[e]) continue;
+      const int j = slot[e] != 0 ? before_c++ : total_c + before_o++;
+      wz_c[j] = word[e] | (slot[e] << 24);
+      ord_c[j] = (uint8_t)(4 * lane + e);
+    }
   }
 }
 
@@ -1401,6 +1696,15 @@ struct augur_lda {
   bool zb_current = false;  // zb holds the z of the last z step
   int32_t* seg_base = nullptr;  // NULL: every document is one segment
   int n_segs = 0;
+  // the resident form of the z kernel (K <= 256): rows of the most frequent words in LDS
+  std::vector<int32_t> hot_host;  // words by falling frequency (the most frequent 255 that occur)
+  int32_t* hot_words = nullptr;   // [n_hot] the cached words, slot order
+  int n_hot = 0;                  // cached rows per workgroup (0: form not available)
+  int32_t* wz = nullptr;          // [N] word | slot << 24 in processing order
+  uint8_t* ord = nullptr;         // [N] position in the chunk, in processing order
+  int z_cache_mode = 0;           // 0 automatic, 1 always (when available), 2 never
+  int num_cus = 0;
+  size_t hot_lds_bytes = 0;       // dynamic LDS of a resident workgroup
   float *theta = nullptr, *phi = nullptr;
   double* lg = nullptr;          // [V][ldk] ln Gamma draws of the phi step
   double2* col_partial = nullptr;  // [phi row blocks][K]
@@ -1436,6 +1740,7 @@ void free_all(augur_lda* h) {
   (void)hipFree(h->multi_words);
   (void)hipFree(h->shapes_alpha); (void)hipFree(h->shapes_beta); (void)hipFree(h->seg_base);
   (void)hipFree(h->log_table); (void)hipFree(h->exp_table);
+  (void)hipFree(h->hot_words); (void)hipFree(h->wz); (void)hipFree(h->ord);
   if (h->side) (void)hipStreamDestroy(h->side);
   if (h->ev_fork) (void)hipEventDestroy(h->ev_fork);
   if (h->ev_join) (void)hipEventDestroy(h->ev_join);
@@ -1475,7 +1780,36 @@ int launch_sample_z(augur_lda* h, uint32_t sweep, bool fuse_doc_counts = false,
     break;
 #define AUGUR_Z_CASE(NSV) \
   case NSV: hipLaunchKernelGGL(lda_sample_z_kernel<NSV>, AUGUR_Z_ARGS); break;
-  if (h->ldk <= 256) {
+  // by itself the library takes the resident form when every wave of the chip gets at least 16
+  // documents (fewer leave the waves unevenly loaded and the copy of the cached rows unpaid
+  // for: 3M tokens in 20,000 documents at K = 100 take 0.081 against 0.075 ms) and rows are at
+  // least five stripes long (shorter rows are too cheap to load for the detour to pay)
+  const bool resident = h->n_hot > 0 && h->z_cache_mode != 2 &&
+                        (h->z_cache_mode == 1 ||
+                         (h->n_segs >= 16 * kHotWaves * h->num_cus && h->ldk >= 16 * kHotMinStripes));
+  if (resident) {
+    // one workgroup per CU (fewer if there is not a segment for every wave), resident until done
+    const dim3 hgrid((unsigned)std::min(h->num_cus, (h->n_segs + kHotWaves - 1) / kHotWaves));
+#define AUGUR_ZH_ARGS                                                                               \
+  hgrid, dim3(64 * kHotWaves), h->hot_lds_bytes, h->stream, h->wz, h->ord, h->doc_off, h->seg_base, \
+      h->n_segs, h->theta, h->phi, h->z, h->n_dk, D, h->cfg.K, h->ldk, h->cfg.seed, sweep,          \
+      h->counters, h->zb, h->hot_words, h->n_hot
+#define AUGUR_ZH_CASE(N16)                                                                      \
+  case N16:                                                                                     \
+    if (fuse_doc_counts) hipLaunchKernelGGL((lda_sample_z_hot_kernel<N16, true>), AUGUR_ZH_ARGS);  \
+    else hipLaunchKernelGGL((lda_sample_z_hot_kernel<N16, false>), AUGUR_ZH_ARGS);              \
+    break;
+    switch (h->ldk / 16) {
+      AUGUR_ZH_CASE(1) AUGUR_ZH_CASE(2) AUGUR_ZH_CASE(3) AUGUR_ZH_CASE(4) AUGUR_ZH_CASE(5)
+      AUGUR_ZH_CASE(6) AUGUR_ZH_CASE(7) AUGUR_ZH_CASE(8) AUGUR_ZH_CASE(9) AUGUR_ZH_CASE(10)
+      AUGUR_ZH_CASE(11) AUGUR_ZH_CASE(12) AUGUR_ZH_CASE(13) AUGUR_ZH_CASE(14) AUGUR_ZH_CASE(15)
+      AUGUR_ZH_CASE(16)
+    }
+#undef AUGUR_ZH_CASE
+#undef AUGUR_ZH_ARGS
+    if (did_count) *did_count = fuse_doc_counts;
+    h->zb_current = true;
+  } else if (h->ldk <= 256) {
     switch ((h->ldk + 15) / 16) {
       AUGUR_ZQ_CASE(1) AUGUR_ZQ_CASE(2) AUGUR_ZQ_CASE(3) AUGUR_ZQ_CASE(4) AUGUR_ZQ_CASE(5)
       AUGUR_ZQ_CASE(6) AUGUR_ZQ_CASE(7) AUGUR_ZQ_CASE(8) AUGUR_ZQ_CASE(9) AUGUR_ZQ_CASE(10)
@@ -1587,6 +1921,19 @@ int build_word_major(augur_lda* h) {
     if (!check(hipMemcpyAsync(off.data(), h->word_off, sizeof(int32_t) * off.size(),
                               hipMemcpyDeviceToHost, h->stream), "hipMemcpyAsync")) break;
     if (!check(hipStreamSynchronize(h->stream), "hipStreamSynchronize")) break;
+    {
+      // the words whose phi rows the resident z kernel may keep in LDS: the most frequent ones
+      std::vector<int32_t> by_freq;
+      for (int v = 0; v < V; ++v)
+        if (off[v + 1] > off[v]) by_freq.push_back(v);
+      const size_t keep = std::min<size_t>(255, by_freq.size());
+      std::partial_sort(by_freq.begin(), by_freq.begin() + keep, by_freq.end(), [&](int32_t x, int32_t y) {
+        const int fx = off[x + 1] - off[x], fy = off[y + 1] - off[y];
+        return fx != fy ? fx > fy : x < y;
+      });
+      by_freq.resize(keep);
+      h->hot_host = std::move(by_freq);
+    }
     auto rare_pieces = [](int f) {
       return std::max(1, std::min(kMaxSlicesPerWord, (f + kSliceTokens - 1) / kSliceTokens));
     };
@@ -1711,6 +2058,68 @@ int build_word_major(augur_lda* h) {
   (void)hipFree(temp); (void)hipFree(iota); (void)hipFree(sorted_w); (void)hipFree(d_heavy);
   (void)hipFree(d_border);
   return rc;
+}
+
+// The resident form of the z kernel (K <= 256): how many phi rows fit in LDS beside the
+// strips of 16 waves, which words they are, and the tokens of every chunk in processing
+// order.  Leaves n_hot = 0 (form not available) when fewer than 8 rows would fit.
+constexpr int kHotLdsBudget = 152 * 1024;  // of the 160 KiB of a CU
+const void* hot_kernel_ptr(int ns16, bool count_docs) {
+#define AUGUR_HP_CASE(N16)                                                                     \
+  case N16:                                                                                    \
+    return count_docs ? reinterpret_cast<const void*>(&lda_sample_z_hot_kernel<N16, true>)      \
+                      : reinterpret_cast<const void*>(&lda_sample_z_hot_kernel<N16, false>);
+  switch (ns16) {
+    AUGUR_HP_CASE(1) AUGUR_HP_CASE(2) AUGUR_HP_CASE(3) AUGUR_HP_CASE(4) AUGUR_HP_CASE(5)
+    AUGUR_HP_CASE(6) AUGUR_HP_CASE(7) AUGUR_HP_CASE(8) AUGUR_HP_CASE(9) AUGUR_HP_CASE(10)
+    AUGUR_HP_CASE(11) AUGUR_HP_CASE(12) AUGUR_HP_CASE(13) AUGUR_HP_CASE(14) AUGUR_HP_CASE(15)
+    AUGUR_HP_CASE(16)
+  }
+#undef AUGUR_HP_CASE
+  return nullptr;
+}
+int setup_resident_form(augur_lda* h) {
+  h->n_hot = 0;
+  if (h->ldk > 256 || h->N == 0 || h->hot_host.empty()) return AUGUR_OK;
+  int cus = 0;
+  AUGUR_HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, h->cfg.device));
+  h->num_cus = std::max(1, cus);
+  const int ns16 = h->ldk / 16;  // rows of tables with up to 256 topics are whole stripes
+  const int row_lds = 64 * ns16 + hot_row_pad_bytes(ns16);
+  const int waves_bytes = kHotWaves * hot_wave_bytes(ns16, true);
+  const int rows = std::min<int>((int)h->hot_host.size(), std::min(255, (kHotLdsBudget - waves_bytes) / row_lds));
+  if (rows < 8) return AUGUR_OK;
+  h->hot_lds_bytes = (size_t)rows * row_lds + (size_t)waves_bytes;
+  for (int cd = 0; cd < 2; ++cd)
+    AUGUR_HIP_TRY(hipFuncSetAttribute(hot_kernel_ptr(ns16, cd != 0), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                      (int)h->hot_lds_bytes));
+  const int V = h->cfg.V;
+  std::vector<uint8_t> slot_of;
+  try {
+    slot_of.assign((size_t)V, 0);
+  } catch (const std::exception&) {
+    set_error("out of host memory for the cache slots of %d words", V);
+    return AUGUR_ERR_INVALID_ARG;
+  }
+  for (int s = 0; s < rows; ++s) slot_of[(size_t)h->hot_host[(size_t)s]] = (uint8_t)(s + 1);
+  uint8_t* d_slot = nullptr;  // only needed here; the handle's own arrays are freed with the handle
+  AUGUR_HIP_TRY(hipMalloc(&h->hot_words, sizeof(int32_t) * (size_t)rows));
+  AUGUR_HIP_TRY(hipMalloc(&h->wz, sizeof(int32_t) * (size_t)h->N));
+  AUGUR_HIP_TRY(hipMalloc(&h->ord, (size_t)h->N));
+  hipError_t e = hipMalloc(&d_slot, (size_t)V);
+  if (e == hipSuccess)
+    e = hipMemcpy(h->hot_words, h->hot_host.data(), sizeof(int32_t) * (size_t)rows, hipMemcpyHostToDevice);
+  if (e == hipSuccess) e = hipMemcpy(d_slot, slot_of.data(), (size_t)V, hipMemcpyHostToDevice);
+  if (e == hipSuccess) {
+    hipLaunchKernelGGL(lda_build_order_kernel, dim3((h->n_segs + 3) / 4), dim3(256), 0, h->stream, h->w,
+                       h->doc_off, h->seg_base, h->n_segs, h->cfg.D, d_slot, h->wz, h->ord);
+    e = hipGetLastError();
+  }
+  if (e == hipSuccess) e = hipStreamSynchronize(h->stream);
+  (void)hipFree(d_slot);
+  AUGUR_HIP_TRY(e);
+  h->n_hot = rows;
+  return AUGUR_OK;
 }
 
 // Documents per wave in the theta step: about 1000 variables per wave (16 per
@@ -2031,6 +2440,15 @@ int augur_lda_create(const augur_lda_config* cfg, const int32_t* doc_len, const 
     }
   }
 
+  {
+    const int rc_hot = setup_resident_form(h);
+    if (rc_hot != AUGUR_OK) {
+      free_all(h);
+      delete h;
+      return rc_hot;
+    }
+  }
+
   // initial state (sweep index 0)
   if (h->N > 0) {
     const int64_t blocks4 = (h->N + 3) / 4;
@@ -2152,6 +2570,13 @@ int augur_lda_set_observed(augur_lda* h, uint32_t mask) {
   AUGUR_REQUIRE(h != nullptr, "handle is NULL");
   AUGUR_REQUIRE((mask & ~AUGUR_OBSERVE_PHI) == 0, "unknown observed-variable bits 0x%x", mask);
   h->phi_observed = (mask & AUGUR_OBSERVE_PHI) != 0;
+  return AUGUR_OK;
+}
+
+int augur_lda_set_z_cache(augur_lda* h, int32_t mode) {
+  AUGUR_REQUIRE(h != nullptr, "handle is NULL");
+  AUGUR_REQUIRE(mode >= 0 && mode <= 2, "mode must be 0 (automatic), 1 (always) or 2 (never), got %d", mode);
+  h->z_cache_mode = mode;
   return AUGUR_OK;
 }
 

@@ -125,13 +125,22 @@ def test_topic_counts_span_stripes_and_tails(B, K):
         lockstep_sweep(g, o, check_loglik=True)
     # the sweep entry point runs other instances of the kernels (document counts built inside
     # the z kernel, word table and phi step on a second stream): bit-identical to the steps
-    g.set_state(z=o.z, theta=o.theta, phi=o.phi, sweep=o.sweep_index)
-    g.sweep(1)
-    swept = [np_(a).copy() for a in g.get_state()[:3] + g.get_counts()]
-    g.set_state(z=o.z, theta=o.theta, phi=o.phi, sweep=o.sweep_index)
-    g.step_sample_z(); g.step_count(); g.step_resample_theta(); g.step_resample_phi(); g.step_finish()
-    for x, y in zip(swept, g.get_state()[:3] + g.get_counts()):
-        assert np.array_equal(x, np_(y))
+    # and so is the resident form of the z kernel (rows of frequent words in LDS), which the
+    # library would not choose by itself for so few documents
+    results = []
+    for mode in (2, 1):
+        g.set_z_cache(mode)
+        g.set_state(z=o.z, theta=o.theta, phi=o.phi, sweep=o.sweep_index)
+        g.sweep(1)
+        results.append([np_(a).copy() for a in g.get_state()[:3] + g.get_counts()])
+    for mode in (2, 1):
+        g.set_z_cache(mode)
+        g.set_state(z=o.z, theta=o.theta, phi=o.phi, sweep=o.sweep_index)
+        g.step_sample_z(); g.step_count(); g.step_resample_theta(); g.step_resample_phi(); g.step_finish()
+        results.append([np_(a).copy() for a in g.get_state()[:3] + g.get_counts()])
+    for other in results[1:]:
+        for x, y in zip(results[0], other):
+            assert np.array_equal(x, y)
     g.close()
 
 
@@ -243,8 +252,10 @@ def test_long_documents_are_cut_into_segments(B, K):
         lockstep_sweep(g, o, check_loglik=True)
     # the sweep entry point (fused / overlapped schedule) against the step-wise one
     g2 = B.LDA(D, V, K, 0.1, 0.01, 500 + K, lens, w)
+    g2.set_z_cache(1)            # the resident form of the z kernel (a no-op above 256 topics)
     g2.sweep(3)
     g3 = B.LDA(D, V, K, 0.1, 0.01, 500 + K, lens, w)
+    g3.set_z_cache(2)
     for _ in range(3):
         g3.step_sample_z(); g3.step_count(); g3.step_resample_theta(); g3.step_resample_phi(); g3.step_finish()
     for x, y in zip(g2.get_state() + g2.get_counts(), g3.get_state() + g3.get_counts()):
@@ -268,6 +279,8 @@ def test_categorical_mixture_is_one_long_document(B, K, V, N):
     # step-wise calls
     g2 = B.LDA(1, V, K, 0.5, 0.5, 41, lens, d["x"])
     g3 = B.LDA(1, V, K, 0.5, 0.5, 41, lens, d["x"])
+    g2.set_z_cache(1)            # the resident form of the z kernel over the segments
+    g3.set_z_cache(2)
     g2.sweep(3)
     for _ in range(3):
         g3.step_sample_z(); g3.step_count(); g3.step_resample_theta(); g3.step_resample_phi(); g3.step_finish()
