@@ -230,7 +230,8 @@ def run_lda(name, cfg, corpus, steps, warmup, repeats, with_ceilings, overlap=Tr
                 "gather_only_algorithmic_GBs": bytes_z / (gather_ms * 1e-3) / 1e9,
                 "sample_z_ms": t_z * 1e3, "gather_only_over_sample_z": gather_ms / (t_z * 1e3)}
         if counters is not None:
-            for k in ("valu_instr_per_token", "valu_busy", "l1_hit_rate", "l2_hit_rate", "scratch_bytes_per_lane"):
+            for k in ("valu_instr_per_token", "valu_busy", "texture_addresser_busy", "lds_busy", "l1_hit_rate",
+                      "l2_hit_rate", "scratch_bytes_per_lane"):
                 if k in counters:
                     ceil[k] = counters[k]
             ceil["counters_source"] = "rocprofv3 --pmc run recorded in profiles/hbm_traffic.json"
