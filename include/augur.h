@@ -97,6 +97,16 @@ int augur_lda_set_observed(augur_lda* h, uint32_t mask);
  * flight. */
 int augur_lda_set_overlap(augur_lda* h, int32_t on);
 
+/* sweep() enqueues about ten kernels per sweep on two streams.  With a stream of the
+ * caller's in config.stream the library records that sequence once as a HIP graph
+ * (the sweep index comes from a counter in device memory that the graph itself
+ * advances) and replays it: the same kernels, the same results, shorter gaps
+ * between launches.  On by default when config.stream is not NULL (the default
+ * stream cannot be recorded); on = 0 turns it off, on = 1 on again.  The step
+ * calls and sweep_profile always launch directly.  Like every call on a handle,
+ * sweep must not run while another thread uses the same stream. */
+int augur_lda_set_graph(augur_lda* h, int32_t on);
+
 /* The z step (Sect. 4.2) has two forms up to 256 topics, which draw the same bits.  One
  * gives every wave a document and reads every phi row from memory.  The other keeps
  * workgroups resident, one per CU, with the phi rows of the corpus's most frequent
@@ -239,6 +249,9 @@ void augur_gmm_destroy(augur_gmm* h);
  * mean.  The initial state (sweep index 0) has var_k = var_scale / var_shape
  * before its first draw. */
 int augur_gmm_sweep(augur_gmm* h, int32_t n_sweeps);
+/* As augur_lda_set_graph: sweep() replays a recorded HIP graph when the handle has a
+ * stream of the caller's (the default), or launches directly (on = 0). */
+int augur_gmm_set_graph(augur_gmm* h, int32_t on);
 /* Same as sweep, with events on the handle's stream around the steps; summed device time over
  * the n_sweeps in ms: ms[0] z step, ms[1] statistics, ms[2] resampling, ms[3] whole sweep.
  * Synchronises once at the end.  n_sweeps <= 4096. */

@@ -81,6 +81,7 @@ def lib():
         L.augur_lda_sweep_profile.argtypes = [vp, C.c_int32, C.POINTER(C.c_double)]
         L.augur_lda_set_overlap.argtypes = [vp, C.c_int32]
         L.augur_lda_set_z_cache.argtypes = [vp, C.c_int32]
+        L.augur_lda_set_graph.argtypes = [vp, C.c_int32]
         L.augur_lda_set_observed.argtypes = [vp, C.c_uint32]
         for name in ("step_sample_z", "step_count", "step_resample_theta", "step_resample_phi",
                      "step_finish", "sync"):
@@ -97,6 +98,7 @@ def lib():
         L.augur_gmm_destroy.argtypes = [vp]
         L.augur_gmm_destroy.restype = None
         L.augur_gmm_sweep.argtypes = [vp, C.c_int32]
+        L.augur_gmm_set_graph.argtypes = [vp, C.c_int32]
         L.augur_gmm_sweep_profile.argtypes = [vp, C.c_int32, C.POINTER(C.c_double)]
         for name in ("step_sample_z", "step_stats", "step_resample", "step_finish", "sync"):
             getattr(L, "augur_gmm_" + name).argtypes = [vp]
@@ -246,6 +248,9 @@ class LDA:
     def set_z_cache(self, mode):
         _check(lib().augur_lda_set_z_cache(self._h, int(mode)))
 
+    def set_graph(self, on):
+        _check(lib().augur_lda_set_graph(self._h, 1 if on else 0))
+
     def sweep_profile(self, n=1):
         ms = (C.c_double * LDA_NSTEPS)()
         _check(lib().augur_lda_sweep_profile(self._h, int(n), ms))
@@ -340,6 +345,9 @@ class GMM:
 
     def sweep(self, n=1):
         _check(lib().augur_gmm_sweep(self._h, int(n)))
+
+    def set_graph(self, on):
+        _check(lib().augur_gmm_set_graph(self._h, 1 if on else 0))
 
     def step_sample_z(self):
         _check(lib().augur_gmm_step_sample_z(self._h))

@@ -301,6 +301,17 @@ __device__ __forceinline__ double gamma_log_draw(double a, uint64_t seed, uint64
   return g.ln_d;
 }
 
+// The sweep index of a launch: a value (eager launches), or a value plus a counter in device
+// memory (launches recorded in a HIP graph, which replays the same arguments every time: the
+// counter is advanced by a kernel at the end of each recorded sweep).
+struct SweepRef {
+  uint32_t base;
+  const uint32_t* dev;
+  __device__ __forceinline__ uint32_t get() const { return base + (dev != nullptr ? *dev : 0u); }
+};
+__global__ void sweep_counter_add_kernel(uint32_t* counter, uint32_t add);   // *counter += add
+__global__ void sweep_counter_set_kernel(uint32_t* counter, uint32_t value); // *counter = value
+
 // --------------------------------------------------------------- wave helpers
 // Orders LDS traffic between lanes of one wave (no cross-wave barrier).
 __device__ __forceinline__ void wave_lds_fence() {

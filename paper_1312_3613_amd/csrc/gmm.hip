@@ -86,7 +86,8 @@ template <bool kCache, int DIM>
 __global__ __launch_bounds__(256) void gmm_sample_z_kernel(
     const float* __restrict__ x, const float* __restrict__ pi, const float* __restrict__ mu,
     const float* __restrict__ var, int32_t* __restrict__ z, int64_t N, int dim, int K, double sigma,
-    uint64_t seed, uint32_t sweep, unsigned long long* __restrict__ n_degenerate) {
+    uint64_t seed, SweepRef sweep_ref, unsigned long long* __restrict__ n_degenerate) {
+  const uint32_t sweep = sweep_ref.get();
   extern __shared__ double sh[];
   double* mu_s = sh;                // [K][dim]
   double* lw_s = sh + K * dim;      // [K]
@@ -347,8 +348,9 @@ __global__ __launch_bounds__(256) void gmm_stats_merge_kernel(const double* __re
 __global__ __launch_bounds__(256) void gmm_resample_kernel(
     const int32_t* __restrict__ n_k, const double* __restrict__ s_k, const double* __restrict__ q_k,
     float* __restrict__ pi, float* __restrict__ mu, float* __restrict__ var, int dim, int K,
-    double alpha, double prior_sd, double sigma, double a0, double b0, uint64_t seed, uint32_t sweep,
+    double alpha, double prior_sd, double sigma, double a0, double b0, uint64_t seed, SweepRef sweep_ref,
     unsigned long long* __restrict__ n_capped) {
+  const uint32_t sweep = sweep_ref.get();
   extern __shared__ double lg[];                            // [K]
   float* mu_new = reinterpret_cast<float*>(lg + K);         // [K][dim]
   bool capped = false;
@@ -449,6 +451,11 @@ struct augur_gmm {
   int stat_blocks = 0;
   int64_t sweep = 0;
   unsigned long long degenerate_reported = 0;
+  // sweep() as a recorded graph
+  bool use_graph = true;
+  hipGraph_t graph = nullptr;
+  hipGraphExec_t graph_exec = nullptr;
+  int64_t counter_value = -1;  // what the device's sweep counter (counters[3]) holds once the stream has drained
 };
 
 namespace {
@@ -459,9 +466,11 @@ void free_all(augur_gmm* h) {
   (void)hipFree(h->x); (void)hipFree(h->pi); (void)hipFree(h->mu); (void)hipFree(h->z);
   (void)hipFree(h->n_k); (void)hipFree(h->part_n); (void)hipFree(h->s_k); (void)hipFree(h->part_s);
   (void)hipFree(h->red); (void)hipFree(h->counters); (void)hipFree(h->var); (void)hipFree(h->q_k);
+  if (h->graph_exec) (void)hipGraphExecDestroy(h->graph_exec);
+  if (h->graph) (void)hipGraphDestroy(h->graph);
 }
 
-int launch_z(augur_gmm* h, uint32_t sweep) {
+int launch_z(augur_gmm* h, SweepRef sweep) {
   const int K = h->cfg.K, dim = h->cfg.dim;
   const int64_t N = h->cfg.N;
   const size_t base_lds = sizeof(double) * ((size_t)K * dim + 2 * (size_t)K);
@@ -516,7 +525,7 @@ int launch_stats(augur_gmm* h) {
   return AUGUR_OK;
 }
 
-int launch_resample(augur_gmm* h, uint32_t sweep) {
+int launch_resample(augur_gmm* h, SweepRef sweep) {
   const size_t shm = sizeof(double) * (size_t)h->cfg.K + sizeof(float) * (size_t)h->cfg.K * h->cfg.dim;
   hipLaunchKernelGGL(gmm_resample_kernel, dim3(1), dim3(256), shm, h->stream, h->n_k, h->s_k, h->q_k,
                      h->pi, h->mu, h->var, h->cfg.dim, h->cfg.K, h->alpha, h->prior_sd, h->sigma,
@@ -584,6 +593,7 @@ int augur_gmm_create(const augur_gmm_config* cfg, const float* x, augur_gmm** ou
   AUGUR_REQUIRE(h != nullptr, "out of host memory");
   h->cfg = *cfg;
   h->stream = (hipStream_t)cfg->stream;
+  h->use_graph = h->stream != nullptr;  // the default stream cannot be recorded
   h->alpha = (double)cfg->alpha;
   h->prior_sd = (double)cfg->prior_sd;
   h->sigma = (double)cfg->sigma;
@@ -634,7 +644,7 @@ int augur_gmm_create(const augur_gmm_config* cfg, const float* x, augur_gmm** ou
                      h->stream, h->z, N, K, cfg->seed);
   AUGUR_CREATE_TRY(hipGetLastError());
   int rc = launch_stats(h);
-  if (rc == AUGUR_OK) rc = launch_resample(h, 0);
+  if (rc == AUGUR_OK) rc = launch_resample(h, SweepRef{0u, nullptr});
   if (rc == AUGUR_OK && hipStreamSynchronize(h->stream) != hipSuccess) {
     set_error("initial sweep failed: %s", hipGetErrorString(hipGetLastError()));
     (void)hipGetLastError();  // or the runtime hands the error to the next caller
@@ -660,7 +670,7 @@ void augur_gmm_destroy(augur_gmm* h) {
 
 int augur_gmm_step_sample_z(augur_gmm* h) {
   AUGUR_CHECK_HANDLE(h);
-  return launch_z(h, (uint32_t)(h->sweep + 1));
+  return launch_z(h, SweepRef{(uint32_t)(h->sweep + 1), nullptr});
 }
 int augur_gmm_step_stats(augur_gmm* h) {
   AUGUR_CHECK_HANDLE(h);
@@ -668,7 +678,7 @@ int augur_gmm_step_stats(augur_gmm* h) {
 }
 int augur_gmm_step_resample(augur_gmm* h) {
   AUGUR_CHECK_HANDLE(h);
-  return launch_resample(h, (uint32_t)(h->sweep + 1));
+  return launch_resample(h, SweepRef{(uint32_t)(h->sweep + 1), nullptr});
 }
 int augur_gmm_step_finish(augur_gmm* h) {
   AUGUR_REQUIRE(h != nullptr, "handle is NULL");
@@ -679,13 +689,69 @@ int augur_gmm_step_finish(augur_gmm* h) {
 int augur_gmm_sweep(augur_gmm* h, int32_t n_sweeps) {
   AUGUR_CHECK_HANDLE(h);
   AUGUR_REQUIRE(n_sweeps >= 0, "n_sweeps = %d is negative", n_sweeps);
-  for (int32_t s = 0; s < n_sweeps; ++s) {
-    const uint32_t t = (uint32_t)(h->sweep + 1);
-    AUGUR_TRY(launch_z(h, t));
-    AUGUR_TRY(launch_stats(h));
-    AUGUR_TRY(launch_resample(h, t));
-    h->sweep += 1;
+  if (!h->use_graph || n_sweeps == 0) {
+    for (int32_t s = 0; s < n_sweeps; ++s) {
+      const SweepRef t{(uint32_t)(h->sweep + 1), nullptr};
+      AUGUR_TRY(launch_z(h, t));
+      AUGUR_TRY(launch_stats(h));
+      AUGUR_TRY(launch_resample(h, t));
+      h->sweep += 1;
+    }
+    return AUGUR_OK;
   }
+  // One sweep recorded as a HIP graph (its four or five launches, the sweep index read from a
+  // counter in device memory that the graph's last kernel advances), then replayed.
+  uint32_t* counter = reinterpret_cast<uint32_t*>(h->counters + 3);
+  if (h->graph_exec == nullptr) {
+    AUGUR_HIP_TRY(hipStreamBeginCapture(h->stream, hipStreamCaptureModeThreadLocal));
+    const SweepRef t{0u, counter};
+    int rc = launch_z(h, t);
+    if (rc == AUGUR_OK) rc = launch_stats(h);
+    if (rc == AUGUR_OK) rc = launch_resample(h, t);
+    if (rc == AUGUR_OK) {
+      hipLaunchKernelGGL(sweep_counter_add_kernel, dim3(1), dim3(1), 0, h->stream, counter, 1u);
+      if (hipGetLastError() != hipSuccess) rc = AUGUR_ERR_HIP;
+    }
+    hipGraph_t g = nullptr;
+    const hipError_t e = hipStreamEndCapture(h->stream, &g);  // also ends a failed recording
+    if (rc != AUGUR_OK || e != hipSuccess || g == nullptr) {
+      if (g) (void)hipGraphDestroy(g);
+      if (rc == AUGUR_OK) {
+        set_error("recording the sweep as a graph failed: %s", hipGetErrorString(e));
+        rc = AUGUR_ERR_HIP;
+      }
+      (void)hipGetLastError();
+      return rc;
+    }
+    const hipError_t ei = hipGraphInstantiate(&h->graph_exec, g, nullptr, nullptr, 0);
+    if (ei != hipSuccess) {
+      set_error("hipGraphInstantiate failed: %s", hipGetErrorString(ei));
+      (void)hipGetLastError();
+      (void)hipGraphDestroy(g);
+      h->graph_exec = nullptr;
+      return AUGUR_ERR_HIP;
+    }
+    h->graph = g;
+  }
+  if (h->counter_value != h->sweep + 1) {
+    hipLaunchKernelGGL(sweep_counter_set_kernel, dim3(1), dim3(1), 0, h->stream, counter,
+                       (uint32_t)(h->sweep + 1));
+    AUGUR_HIP_TRY(hipGetLastError());
+    h->counter_value = h->sweep + 1;
+  }
+  for (int32_t s = 0; s < n_sweeps; ++s) {
+    AUGUR_HIP_TRY(hipGraphLaunch(h->graph_exec, h->stream));
+    h->sweep += 1;
+    h->counter_value += 1;
+  }
+  return AUGUR_OK;
+}
+
+int augur_gmm_set_graph(augur_gmm* h, int32_t on) {
+  AUGUR_REQUIRE(h != nullptr, "handle is NULL");
+  AUGUR_REQUIRE(on == 0 || h->stream != nullptr,
+                "sweeps can only be recorded on a stream of the caller's (config.stream), not on the default stream");
+  h->use_graph = on != 0;
   return AUGUR_OK;
 }
 
@@ -712,11 +778,11 @@ int augur_gmm_sweep_profile(augur_gmm* h, int32_t n_sweeps, double* ms) {
     hipEvent_t* e = &ev[(size_t)s * 4];
     const uint32_t t = (uint32_t)(h->sweep + 1);
     if (fail_hip(hipEventRecord(e[0], h->stream), "hipEventRecord")) break;
-    rc = launch_z(h, t);
+    rc = launch_z(h, SweepRef{t, nullptr});
     if (rc == AUGUR_OK && fail_hip(hipEventRecord(e[1], h->stream), "hipEventRecord")) break;
     if (rc == AUGUR_OK) rc = launch_stats(h);
     if (rc == AUGUR_OK && fail_hip(hipEventRecord(e[2], h->stream), "hipEventRecord")) break;
-    if (rc == AUGUR_OK) rc = launch_resample(h, t);
+    if (rc == AUGUR_OK) rc = launch_resample(h, SweepRef{t, nullptr});
     if (rc == AUGUR_OK && fail_hip(hipEventRecord(e[3], h->stream), "hipEventRecord")) break;
     if (rc == AUGUR_OK) {
       h->sweep += 1;

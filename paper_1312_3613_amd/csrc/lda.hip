@@ -186,8 +186,9 @@ void lda_sample_z_kernel(
     const int32_t* __restrict__ w, const int64_t* __restrict__ doc_off,
     const int32_t* __restrict__ seg_base, int n_segs, const float* __restrict__ theta,
     const float* __restrict__ phi, int32_t* __restrict__ z, int D, int K, int ldk, uint64_t seed,
-    uint32_t sweep, unsigned long long* __restrict__ n_degenerate) {
+    SweepRef sweep_ref, unsigned long long* __restrict__ n_degenerate) {
   __shared__ uint32_t rnd[4][256];
+  const uint32_t sweep = sweep_ref.get();
   __shared__ __align__(16) float theta_s[4][NS * 64];
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
@@ -637,9 +638,10 @@ void lda_sample_z_quad_kernel(
     const int32_t* __restrict__ w, const int64_t* __restrict__ doc_off,
     const int32_t* __restrict__ seg_base, int n_segs, const float* __restrict__ theta,
     const float* __restrict__ phi, int32_t* __restrict__ z, int32_t* __restrict__ n_dk, int D, int K,
-    int ldk, uint64_t seed, uint32_t sweep, unsigned long long* __restrict__ n_degenerate,
+    int ldk, uint64_t seed, SweepRef sweep_ref, unsigned long long* __restrict__ n_degenerate,
     uint8_t* __restrict__ zb) {
   __shared__ uint2 strip_all[4][256];            // {Philox word, word id} per token of the chunk
+  const uint32_t sweep = sweep_ref.get();
   __shared__ __align__(16) float theta_all[4][16 * NS16];
   __shared__ int32_t hist_all[kCountDocs ? 4 : 1][kCountDocs ? 16 * NS16 : 1];
   __shared__ __align__(4) uint8_t zstage_all[4][256];  // the topics drawn for the current chunk
@@ -759,9 +761,10 @@ __global__ __launch_bounds__(64 * kHotWaves) void lda_sample_z_hot_kernel(
     const int32_t* __restrict__ wz, const uint8_t* __restrict__ ord, const int64_t* __restrict__ doc_off,
     const int32_t* __restrict__ seg_base, int n_segs, const float* __restrict__ theta,
     const float* __restrict__ phi, int32_t* __restrict__ z, int32_t* __restrict__ n_dk, int D, int K,
-    int ldk, uint64_t seed, uint32_t sweep, unsigned long long* __restrict__ n_degenerate,
+    int ldk, uint64_t seed, SweepRef sweep_ref, unsigned long long* __restrict__ n_degenerate,
     uint8_t* __restrict__ zb, const int32_t* __restrict__ hot_words, int n_hot) {
   extern __shared__ __align__(16) unsigned char lds[];
+  const uint32_t sweep = sweep_ref.get();
   constexpr int kRowLds = 64 * NS16 + hot_row_pad_bytes(NS16);  // bytes between cached rows
   constexpr int kWaveBytes = hot_wave_bytes(NS16, kCountDocs);
   const int lane = threadIdx.x & 63;
@@ -1240,9 +1243,10 @@ __global__ __launch_bounds__(256) void range_borders_kernel(
 __global__ __launch_bounds__(256) void lda_resample_theta_kernel(
     const int32_t* __restrict__ n_dk, float* __restrict__ theta, int D, int K, int ldk, int rows,
     double alpha, const GammaShape* __restrict__ shapes, const double2* __restrict__ log_table,
-    const double* __restrict__ exp_table, uint64_t seed, uint32_t sweep,
+    const double* __restrict__ exp_table, uint64_t seed, SweepRef sweep_ref,
     unsigned long long* __restrict__ n_capped) {
   extern __shared__ double lg_all[];
+  const uint32_t sweep = sweep_ref.get();
   __shared__ double2 lt[kLogTableSize];
   __shared__ double et[kExpTableSize];
   for (int i = threadIdx.x; i < kLogTableSize; i += blockDim.x) lt[i] = log_table[i];
@@ -1314,9 +1318,10 @@ __global__ __launch_bounds__(1024) void lda_phi_draw_kernel(
     const int32_t* __restrict__ n_wk, double* __restrict__ lg, double2* __restrict__ partial, int V,
     int K, int ldk, int rows_per_block, int groups, int n_row_blocks, int col_w, double beta,
     const GammaShape* __restrict__ shapes, const double2* __restrict__ log_table,
-    const double* __restrict__ exp_table, uint64_t seed, uint32_t sweep,
+    const double* __restrict__ exp_table, uint64_t seed, SweepRef sweep_ref,
     unsigned long long* __restrict__ n_capped) {
   __shared__ double2 lt[kLogTableSize];
+  const uint32_t sweep = sweep_ref.get();
   __shared__ double et[kExpTableSize];
   for (int i = threadIdx.x; i < kLogTableSize; i += blockDim.x) lt[i] = log_table[i];
   for (int i = threadIdx.x; i < kExpTableSize; i += blockDim.x) et[i] = exp_table[i];
@@ -1713,10 +1718,16 @@ struct augur_lda {
   double2* log_table = nullptr;                                // [kLogTableSize], see log_tab
   double* exp_table = nullptr;                                 // [kExpTableSize], see exp_tab
   double* red = nullptr;         // [4][kRedBlocks] reduction partials, then the two results
-  unsigned long long* counters = nullptr;  // [0] degenerate tokens [1] capped draws [2] bad input
+  unsigned long long* counters = nullptr;  // [0] degenerate tokens [1] capped draws [2] bad input [3] sweep counter of the graph (low word)
   int phi_blocks = 0, phi_rows = 0;
   int64_t sweep = 0;
   unsigned long long degenerate_reported = 0;
+  // sweep() as a recorded graph
+  bool use_graph = true;
+  hipGraph_t graph = nullptr;
+  hipGraphExec_t graph_exec = nullptr;
+  int graph_for = -1;          // the switches the graph was recorded with
+  int64_t counter_value = -1;  // what the device's sweep counter (counters[3]) holds once the stream has drained
 };
 
 namespace {
@@ -1741,6 +1752,8 @@ void free_all(augur_lda* h) {
   (void)hipFree(h->shapes_alpha); (void)hipFree(h->shapes_beta); (void)hipFree(h->seg_base);
   (void)hipFree(h->log_table); (void)hipFree(h->exp_table);
   (void)hipFree(h->hot_words); (void)hipFree(h->wz); (void)hipFree(h->ord);
+  if (h->graph_exec) (void)hipGraphExecDestroy(h->graph_exec);
+  if (h->graph) (void)hipGraphDestroy(h->graph);
   if (h->side) (void)hipStreamDestroy(h->side);
   if (h->ev_fork) (void)hipEventDestroy(h->ev_fork);
   if (h->ev_join) (void)hipEventDestroy(h->ev_join);
@@ -1757,7 +1770,7 @@ int zero_split_rows(augur_lda* h, hipStream_t stream) {
 
 // fused: the kernel also writes the document table n_dk (K <= 256 only); returns
 // whether it did through *did_count.
-int launch_sample_z(augur_lda* h, uint32_t sweep, bool fuse_doc_counts = false,
+int launch_sample_z(augur_lda* h, SweepRef sweep, bool fuse_doc_counts = false,
                     bool* did_count = nullptr) {
   const int D = h->cfg.D;
   if (did_count) *did_count = false;
@@ -2127,7 +2140,7 @@ int setup_resident_form(augur_lda* h) {
 // (rows * K doubles each) at 32 KiB, so several workgroups share a CU.
 int theta_rows_per_wave(int K) { return std::max(1, std::min(16, 1024 / K)); }
 
-int launch_theta(augur_lda* h, uint32_t sweep) {
+int launch_theta(augur_lda* h, SweepRef sweep) {
   const int D = h->cfg.D, K = h->cfg.K;
   const int rows = theta_rows_per_wave(K);
   const int waves = (D + rows - 1) / rows;
@@ -2139,7 +2152,7 @@ int launch_theta(augur_lda* h, uint32_t sweep) {
   return AUGUR_OK;
 }
 
-int launch_phi(augur_lda* h, uint32_t sweep, hipStream_t stream) {
+int launch_phi(augur_lda* h, SweepRef sweep, hipStream_t stream) {
   const int V = h->cfg.V, K = h->cfg.K;
   // Columns per workgroup: all K up to 512, else K cut into equal parts of at most 512 (a
   // workgroup of 1024 threads fills a CU alone and holds it until its slowest wave ends: at
@@ -2278,6 +2291,7 @@ int augur_lda_create(const augur_lda_config* cfg, const int32_t* doc_len, const 
   AUGUR_REQUIRE(h != nullptr, "out of host memory");
   h->cfg = *cfg;
   h->stream = (hipStream_t)cfg->stream;
+  h->use_graph = h->stream != nullptr;  // the default stream cannot be recorded
   h->alpha = (double)cfg->alpha;
   h->beta = (double)cfg->beta;
   h->ldk = row_stride(K);
@@ -2457,8 +2471,8 @@ int augur_lda_create(const augur_lda_config* cfg, const int32_t* doc_len, const 
     AUGUR_CREATE_TRY(hipGetLastError());
   }
   int rc = launch_count(h);
-  if (rc == AUGUR_OK) rc = launch_theta(h, 0);
-  if (rc == AUGUR_OK) rc = launch_phi(h, 0, h->stream);
+  if (rc == AUGUR_OK) rc = launch_theta(h, SweepRef{0u, nullptr});
+  if (rc == AUGUR_OK) rc = launch_phi(h, SweepRef{0u, nullptr}, h->stream);
   if (rc == AUGUR_OK && hipStreamSynchronize(h->stream) != hipSuccess) {
     set_error("initial sweep failed: %s", hipGetErrorString(hipGetLastError()));
     (void)hipGetLastError();  // or the runtime hands the error to the next caller
@@ -2486,7 +2500,7 @@ void augur_lda_destroy(augur_lda* h) {
 
 int augur_lda_step_sample_z(augur_lda* h) {
   AUGUR_CHECK_HANDLE(h);
-  return launch_sample_z(h, (uint32_t)(h->sweep + 1));
+  return launch_sample_z(h, SweepRef{(uint32_t)(h->sweep + 1), nullptr});
 }
 int augur_lda_step_count(augur_lda* h) {
   AUGUR_CHECK_HANDLE(h);
@@ -2494,11 +2508,11 @@ int augur_lda_step_count(augur_lda* h) {
 }
 int augur_lda_step_resample_theta(augur_lda* h) {
   AUGUR_CHECK_HANDLE(h);
-  return launch_theta(h, (uint32_t)(h->sweep + 1));
+  return launch_theta(h, SweepRef{(uint32_t)(h->sweep + 1), nullptr});
 }
 int augur_lda_step_resample_phi(augur_lda* h) {
   AUGUR_CHECK_HANDLE(h);
-  return launch_phi(h, (uint32_t)(h->sweep + 1), h->stream);
+  return launch_phi(h, SweepRef{(uint32_t)(h->sweep + 1), nullptr}, h->stream);
 }
 int augur_lda_step_finish(augur_lda* h) {
   AUGUR_REQUIRE(h != nullptr, "handle is NULL");
@@ -2514,7 +2528,7 @@ int augur_lda_step_finish(augur_lda* h) {
 // main stream then waits for the second.  ev, if given, receives five events on
 // the main stream: before z, after z, after the document counts, after theta,
 // after everything.
-static int run_sweep(augur_lda* h, uint32_t t, hipEvent_t* ev) {
+static int run_sweep(augur_lda* h, SweepRef t, hipEvent_t* ev) {
 #define AUGUR_MARK(i)                                            \
   if (ev) AUGUR_HIP_TRY(hipEventRecord(ev[i], h->stream))
   AUGUR_MARK(0);
@@ -2559,10 +2573,84 @@ static int run_sweep(augur_lda* h, uint32_t t, hipEvent_t* ev) {
   return AUGUR_OK;
 }
 
+// One sweep recorded as a HIP graph: the launches of run_sweep (both streams, joined) with the
+// sweep index read from the handle's device counter, then a kernel that advances the counter.
+// Recorded again when a switch that changes the sequence of launches has been flipped.
+static void drop_graph(augur_lda* h) {
+  if (h->graph_exec) (void)hipGraphExecDestroy(h->graph_exec);
+  if (h->graph) (void)hipGraphDestroy(h->graph);
+  h->graph_exec = nullptr;
+  h->graph = nullptr;
+}
+static int graph_key(const augur_lda* h) {
+  return (h->overlap ? 1 : 0) | (h->phi_observed ? 2 : 0) | (h->z_cache_mode << 2);
+}
+static int record_graph(augur_lda* h) {
+  drop_graph(h);
+  uint32_t* counter = reinterpret_cast<uint32_t*>(h->counters + 3);
+  AUGUR_HIP_TRY(hipStreamBeginCapture(h->stream, hipStreamCaptureModeThreadLocal));
+  const int64_t sweep_before = h->sweep;
+  int rc = run_sweep(h, SweepRef{0u, counter}, nullptr);
+  h->sweep = sweep_before;  // nothing has run yet
+  if (rc == AUGUR_OK) {
+    hipLaunchKernelGGL(sweep_counter_add_kernel, dim3(1), dim3(1), 0, h->stream, counter, 1u);
+    if (hipGetLastError() != hipSuccess) rc = AUGUR_ERR_HIP;
+  }
+  hipGraph_t g = nullptr;
+  const hipError_t e = hipStreamEndCapture(h->stream, &g);  // also ends a failed recording
+  if (rc != AUGUR_OK || e != hipSuccess || g == nullptr) {
+    if (g) (void)hipGraphDestroy(g);
+    if (rc == AUGUR_OK) {
+      set_error("recording the sweep as a graph failed: %s", hipGetErrorString(e));
+      rc = AUGUR_ERR_HIP;
+    }
+    (void)hipGetLastError();
+    return rc;
+  }
+  h->graph = g;
+  const hipError_t ei = hipGraphInstantiate(&h->graph_exec, g, nullptr, nullptr, 0);
+  if (ei != hipSuccess) {
+    set_error("hipGraphInstantiate failed: %s", hipGetErrorString(ei));
+    (void)hipGetLastError();
+    drop_graph(h);
+    return AUGUR_ERR_HIP;
+  }
+  h->graph_for = graph_key(h);
+  return AUGUR_OK;
+}
+
 int augur_lda_sweep(augur_lda* h, int32_t n_sweeps) {
   AUGUR_CHECK_HANDLE(h);
   AUGUR_REQUIRE(n_sweeps >= 0, "n_sweeps = %d is negative", n_sweeps);
-  for (int32_t s = 0; s < n_sweeps; ++s) AUGUR_TRY(run_sweep(h, (uint32_t)(h->sweep + 1), nullptr));
+  if (!h->use_graph || n_sweeps == 0) {
+    for (int32_t s = 0; s < n_sweeps; ++s)
+      AUGUR_TRY(run_sweep(h, SweepRef{(uint32_t)(h->sweep + 1), nullptr}, nullptr));
+    return AUGUR_OK;
+  }
+  if (h->graph_exec == nullptr || h->graph_for != graph_key(h)) AUGUR_TRY(record_graph(h));
+  // the device counter holds the index of the next sweep; steps, profiled sweeps and set_state
+  // move the host's count without it
+  uint32_t* counter = reinterpret_cast<uint32_t*>(h->counters + 3);
+  if (h->counter_value != h->sweep + 1) {
+    hipLaunchKernelGGL(sweep_counter_set_kernel, dim3(1), dim3(1), 0, h->stream, counter,
+                       (uint32_t)(h->sweep + 1));
+    AUGUR_HIP_TRY(hipGetLastError());
+    h->counter_value = h->sweep + 1;
+  }
+  for (int32_t s = 0; s < n_sweeps; ++s) {
+    AUGUR_HIP_TRY(hipGraphLaunch(h->graph_exec, h->stream));
+    h->sweep += 1;
+    h->counter_value += 1;
+  }
+  h->zb_current = h->ldk <= 256;  // as the recorded z step leaves it
+  return AUGUR_OK;
+}
+
+int augur_lda_set_graph(augur_lda* h, int32_t on) {
+  AUGUR_REQUIRE(h != nullptr, "handle is NULL");
+  AUGUR_REQUIRE(on == 0 || h->stream != nullptr,
+                "sweeps can only be recorded on a stream of the caller's (config.stream), not on the default stream");
+  h->use_graph = on != 0;
   return AUGUR_OK;
 }
 
@@ -2606,7 +2694,7 @@ int augur_lda_sweep_profile(augur_lda* h, int32_t n_sweeps, double* ms) {
     if (fail_hip(hipEventCreate(&e), "hipEventCreate")) break;
   int done = 0;
   for (int32_t s = 0; s < n_sweeps && rc == AUGUR_OK; ++s) {
-    rc = run_sweep(h, (uint32_t)(h->sweep + 1), &ev[(size_t)s * 5]);
+    rc = run_sweep(h, SweepRef{(uint32_t)(h->sweep + 1), nullptr}, &ev[(size_t)s * 5]);
     if (rc == AUGUR_OK) ++done;
   }
   fail_hip(hipStreamSynchronize(h->stream), "hipStreamSynchronize");

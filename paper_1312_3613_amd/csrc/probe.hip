@@ -20,6 +20,15 @@ __global__ __launch_bounds__(256) void stream_copy_kernel(const float4* __restri
 
 }  // namespace
 
+namespace augur {
+__global__ void sweep_counter_add_kernel(uint32_t* counter, uint32_t add) {
+  if (blockIdx.x == 0 && threadIdx.x == 0) *counter += add;
+}
+__global__ void sweep_counter_set_kernel(uint32_t* counter, uint32_t value) {
+  if (blockIdx.x == 0 && threadIdx.x == 0) *counter = value;
+}
+}  // namespace augur
+
 extern "C" {
 
 int augur_probe_stream_copy(const void* src, void* dst, int64_t bytes, int32_t reps, void* stream,

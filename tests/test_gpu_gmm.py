@@ -220,3 +220,35 @@ def test_gmm_unknown_variances_errors(B):
     with pytest.raises(B.AugurError):
         k.get_var()
     k.close()
+
+
+@pytest.mark.parametrize("unknown_var", [False, True])
+def test_gmm_sweeps_replayed_from_a_graph_match_direct_launches(B, unknown_var):
+    import torch
+    d = synth.gmm_points(N=20011, dim=8, K=16, seed=4)
+    kw = dict(var_shape=1.0, var_scale=1.0) if unknown_var else {}
+    stream = torch.cuda.Stream()
+    a = B.GMM(16, 1.0, 10.0, 1.0, 5, d["x"], stream=stream, **kw)     # records
+    b = B.GMM(16, 1.0, 10.0, 1.0, 5, d["x"], **kw)                    # default stream: direct launches
+
+    def same():
+        for x, y in zip(a.get_state() + a.get_stats(), b.get_state() + b.get_stats()):
+            assert np.array_equal(x, y)
+        assert a.loglik() == b.loglik()
+
+    a.sweep(3); b.sweep(3); same()
+    a.sweep(1); b.sweep(1); same()
+    for h in (a, b):
+        h.step_sample_z(); h.step_stats(); h.step_resample(); h.step_finish()
+    same()
+    a.sweep(2); b.sweep(2); same()
+    a.sweep_profile(2); b.sweep_profile(2); same()
+    z, pi, mu, sw = b.get_state()
+    for h in (a, b):
+        h.set_state(z=z, pi=pi, mu=mu, sweep=2)
+    a.sweep(3); b.sweep(3); same()
+    a.set_graph(False)
+    a.sweep(2); b.sweep(2); same()
+    with pytest.raises(B.AugurError):
+        b.set_graph(True)
+    a.close(); b.close()

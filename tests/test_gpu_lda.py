@@ -559,3 +559,48 @@ def test_measurement_probes(B):
     dst = torch.zeros_like(src)
     assert B.probe_stream_copy(src, dst, reps=3) > 0.0
     assert torch.equal(src, dst)
+
+
+@pytest.mark.parametrize("K,forced_cache", [(40, 0), (100, 1), (300, 0)])
+def test_sweeps_replayed_from_a_graph_match_direct_launches(B, K, forced_cache):
+    """sweep() on a stream of the caller's replays a recorded graph.  Several replays, with
+    direct launches, state changes and waits between them, against a handle that never records;
+    every comparison is bit for bit."""
+    import torch
+    cfg = dict(synth.LDA_CONFIGS["tiny"], D=500, V=900, K=K, mean_len=90)
+    c = synth.lda_corpus(**cfg)
+    lens = [2600, 1, 0, 1030] + list(c["doc_len"][4:])          # split documents too
+    lens, w = ragged_corpus(len(lens), cfg["V"], K, seed=3, lens=lens)
+    args = (len(lens), cfg["V"], K, cfg["alpha"], cfg["beta"], 17, lens, w)
+    stream = torch.cuda.Stream()
+    a = B.LDA(*args, stream=stream)        # records
+    b = B.LDA(*args)                       # default stream: always direct launches
+    for h in (a, b):
+        h.set_z_cache(forced_cache)
+
+    def same():
+        for x, y in zip(a.get_state() + a.get_counts(), b.get_state() + b.get_counts()):
+            assert np.array_equal(x, y)
+        assert a.loglik() == b.loglik()
+
+    a.sweep(3); b.sweep(3); same()                                     # record + three replays
+    a.sweep(1); b.sweep(1); same()                                     # one more replay
+    for h in (a, b):                                                   # direct launches in between
+        h.step_sample_z(); h.step_count(); h.step_resample_theta(); h.step_resample_phi(); h.step_finish()
+    same()
+    a.sweep(2); b.sweep(2); same()                                     # the counter is set again first
+    a.sweep_profile(2); b.sweep_profile(2); same()
+    z, th, ph, sw = b.get_state()
+    for h in (a, b):
+        h.set_state(z=z, theta=th, phi=ph, sweep=3)                    # back in time
+    a.sweep(4); b.sweep(4); same()
+    a.set_overlap(False); b.set_overlap(False)                         # another sequence: recorded anew
+    a.sweep(2); b.sweep(2); same()
+    a.set_graph(False)
+    a.sweep(2); b.sweep(2); same()
+    a.set_graph(True)
+    a.set_observed(phi=True); b.set_observed(phi=True)
+    a.sweep(2); b.sweep(2); same()
+    with pytest.raises(B.AugurError):
+        b.set_graph(True)                                              # no stream of its own
+    a.close(); b.close()
