@@ -41,7 +41,10 @@
 //     counter = (index lo, index hi, sweep, stream<<24 | attempt).
 //   * Inverse-CDF rule: z = smallest k with C_k > u*S (strict), C_k the running
 //     sum of the K products in index order, accumulated in fp64.
-//   * Stored theta/phi/pi are fp32, clamped below at FLT_MIN.
+//   * Stored theta/phi/pi are fp32, clamped below at FLT_MIN.  LDA also has an fp64
+//     state mode (the exported functions ending in _f64): theta and phi are stored
+//     as doubles, clamped below at DBL_MIN; everything else is the same code.  The
+//     paper's experiments ran in double precision (Sect. 5, experimental setup).
 //
 // parity pins: every exported function is pinned by tests/test_oracle_*.py
 // (brute-force enumeration, closed-form posteriors, library CDFs, invariants).
@@ -50,6 +53,7 @@
 #include <cmath>
 #include <cstdint>
 #include <cstring>
+#include <limits>
 #include <vector>
 
 namespace {
@@ -154,18 +158,21 @@ double gamma_log_draw(double a, uint64_t seed, uint64_t index, uint32_t sweep,
   return std::log(d);
 }
 
-// Normalise K log-Gamma draws into a Dirichlet draw stored as fp32 with the
-// FLT_MIN floor.  lg has stride `stride`; out has the same stride.
-void normalise_log_draws(const double* lg, int64_t n, int64_t stride, float* out) {
+// Normalise K log-Gamma draws into a Dirichlet draw stored as T (fp32 or fp64) with
+// the floor at T's smallest positive normal number (FLT_MIN or DBL_MIN).  lg has
+// stride `stride`; out has the same stride.
+template <typename T>
+void normalise_log_draws(const double* lg, int64_t n, int64_t stride, T* out) {
   double m = lg[0];
   for (int64_t j = 1; j < n; ++j) if (lg[j * stride] > m) m = lg[j * stride];
   double s = 0.0;
   for (int64_t j = 0; j < n; ++j) s += std::exp(lg[j * stride] - m);
   const double L = m + std::log(s);
+  const double floor_t = (double)std::numeric_limits<T>::min();
   for (int64_t j = 0; j < n; ++j) {
     double p = std::exp(lg[j * stride] - L);
-    if (p < (double)FLT_MIN) p = (double)FLT_MIN;
-    out[j * stride] = (float)p;
+    if (p < floor_t) p = floor_t;
+    out[j * stride] = (T)p;
   }
 }
 
@@ -178,7 +185,8 @@ int inverse_cdf(const double* cdf, int K, double t) {
 }
 
 // Running sums C_k of theta_d[k] * phi[v][k], products and sums in fp64.
-void lda_token_cdf(const float* theta_d, const float* phi_v, int K, double* cdf) {
+template <typename T>
+void lda_token_cdf(const T* theta_d, const T* phi_v, int K, double* cdf) {
   double C = 0.0;
   for (int k = 0; k < K; ++k) {
     C += (double)theta_d[k] * (double)phi_v[k];
@@ -186,8 +194,9 @@ void lda_token_cdf(const float* theta_d, const float* phi_v, int K, double* cdf)
   }
 }
 
-// ln Dirichlet(x; a 1_n) density, x given as fp32 with stride.
-double log_dirichlet_sym(const float* x, int64_t n, int64_t stride, double a) {
+// ln Dirichlet(x; a 1_n) density, x given as fp32 or fp64 with stride.
+template <typename T>
+double log_dirichlet_sym(const T* x, int64_t n, int64_t stride, double a) {
   double s = 0.0;
   for (int64_t j = 0; j < n; ++j) s += std::log((double)x[j * stride]);
   return std::lgamma((double)n * a) - (double)n * std::lgamma(a) + (a - 1.0) * s;
@@ -290,12 +299,29 @@ void orc_lda_init_z(int64_t N, int32_t K, uint64_t seed, int32_t* z) {
   }
 }
 
+// Counting phase (Sect. 4.2): c_m and c_k as two tables, n_dk[D][K], n_wk[V][K].
+void orc_lda_count(int32_t D, int32_t V, int32_t K, const int64_t* doc_off, const int32_t* w,
+                   const int32_t* z, int32_t* n_dk, int32_t* n_wk) {
+  std::memset(n_dk, 0, sizeof(int32_t) * (size_t)D * K);
+  std::memset(n_wk, 0, sizeof(int32_t) * (size_t)V * K);
+  for (int32_t d = 0; d < D; ++d)
+    for (int64_t i = doc_off[d]; i < doc_off[d + 1]; ++i) {
+      n_dk[(int64_t)d * K + z[i]] += 1;
+      n_wk[(int64_t)w[i] * K + z[i]] += 1;
+    }
+}
+
+}  // extern "C"
+
+namespace {
+
 // Gibbs step for every z (Sect. 4.2, last conditional): token i of document d
 // with word v draws from p(k) proportional to theta[d][k] * phi[v][k].
 // Returns the number of tokens whose conditional had zero or non-finite mass
 // (those take z = floor(u K)).
-int64_t orc_lda_sample_z(int32_t D, int32_t K, const int64_t* doc_off, const int32_t* w,
-                         const float* theta, const float* phi, uint64_t seed,
+template <typename T>
+int64_t lda_sample_z_impl(int32_t D, int32_t K, const int64_t* doc_off, const int32_t* w,
+                         const T* theta, const T* phi, uint64_t seed,
                          uint32_t sweep, int32_t* z) {
   std::vector<double> cdf(K);
   int64_t degenerate = 0;
@@ -317,28 +343,18 @@ int64_t orc_lda_sample_z(int32_t D, int32_t K, const int64_t* doc_off, const int
 
 // The running sums C_k and the threshold t = u S of one token, for judging a
 // disagreement about its draw.
-void orc_lda_token_cdf(int32_t K, const float* theta_d, const float* phi_v, uint64_t seed,
+template <typename T>
+void lda_token_cdf_impl(int32_t K, const T* theta_d, const T* phi_v, uint64_t seed,
                        uint64_t token, uint32_t sweep, double* cdf, double* t) {
   lda_token_cdf(theta_d, phi_v, K, cdf);
   *t = datum_uniform(seed, token, sweep, STREAM_Z) * cdf[K - 1];
 }
 
-// Counting phase (Sect. 4.2): c_m and c_k as two tables, n_dk[D][K], n_wk[V][K].
-void orc_lda_count(int32_t D, int32_t V, int32_t K, const int64_t* doc_off, const int32_t* w,
-                   const int32_t* z, int32_t* n_dk, int32_t* n_wk) {
-  std::memset(n_dk, 0, sizeof(int32_t) * (size_t)D * K);
-  std::memset(n_wk, 0, sizeof(int32_t) * (size_t)V * K);
-  for (int32_t d = 0; d < D; ++d)
-    for (int64_t i = doc_off[d]; i < doc_off[d + 1]; ++i) {
-      n_dk[(int64_t)d * K + z[i]] += 1;
-      n_wk[(int64_t)w[i] * K + z[i]] += 1;
-    }
-}
-
 // theta_d ~ Dirichlet(alpha + n_dk[d][.]) for every document (App. B, Alg. 2).
 // Variable index of entry (d,k) is d*K + k.  Returns capped-draw count.
-int orc_lda_resample_theta(int32_t D, int32_t K, double alpha, const int32_t* n_dk,
-                           uint64_t seed, uint32_t sweep, float* theta) {
+template <typename T>
+int lda_resample_theta_impl(int32_t D, int32_t K, double alpha, const int32_t* n_dk,
+                           uint64_t seed, uint32_t sweep, T* theta) {
   std::vector<double> lg(K);
   int capped = 0;
   for (int32_t d = 0; d < D; ++d) {
@@ -355,8 +371,9 @@ int orc_lda_resample_theta(int32_t D, int32_t K, double alpha, const int32_t* n_
 // phi_k ~ Dirichlet(beta + n_wk[.][k]) for every topic (Sect. 4.3, Alg. 1): a
 // V x K matrix of Gamma draws, each topic's column normalised over the words.
 // Variable index of entry (v,k) is v*K + k.
-int orc_lda_resample_phi(int32_t V, int32_t K, double beta, const int32_t* n_wk,
-                         uint64_t seed, uint32_t sweep, float* phi) {
+template <typename T>
+int lda_resample_phi_impl(int32_t V, int32_t K, double beta, const int32_t* n_wk,
+                         uint64_t seed, uint32_t sweep, T* phi) {
   std::vector<double> lg((size_t)V * K);
   int capped = 0;
   for (int32_t v = 0; v < V; ++v)
@@ -371,44 +388,48 @@ int orc_lda_resample_phi(int32_t V, int32_t K, double beta, const int32_t* n_wk,
 
 // One sweep tau -> tau+1 in the order z, counts, theta, phi, all with sweep
 // index `sweep`.
-int64_t orc_lda_sweep(int32_t D, int32_t V, int32_t K, double alpha, double beta,
+template <typename T>
+int64_t lda_sweep_impl(int32_t D, int32_t V, int32_t K, double alpha, double beta,
                       const int64_t* doc_off, const int32_t* w, uint64_t seed, uint32_t sweep,
-                      int32_t* z, float* theta, float* phi, int32_t* n_dk, int32_t* n_wk) {
-  const int64_t deg = orc_lda_sample_z(D, K, doc_off, w, theta, phi, seed, sweep, z);
+                      int32_t* z, T* theta, T* phi, int32_t* n_dk, int32_t* n_wk) {
+  const int64_t deg = lda_sample_z_impl<T>(D, K, doc_off, w, theta, phi, seed, sweep, z);
   orc_lda_count(D, V, K, doc_off, w, z, n_dk, n_wk);
-  orc_lda_resample_theta(D, K, alpha, n_dk, seed, sweep, theta);
-  orc_lda_resample_phi(V, K, beta, n_wk, seed, sweep, phi);
+  lda_resample_theta_impl<T>(D, K, alpha, n_dk, seed, sweep, theta);
+  lda_resample_phi_impl<T>(V, K, beta, n_wk, seed, sweep, phi);
   return deg;
 }
 
 // The same sweep with phi observed (Fig. 3, second call: the variable set
 // {"phi"} is added to the observed ones): only z and theta are inferred.
-int64_t orc_lda_sweep_phi_observed(int32_t D, int32_t V, int32_t K, double alpha,
+template <typename T>
+int64_t lda_sweep_phi_observed_impl(int32_t D, int32_t V, int32_t K, double alpha,
                                    const int64_t* doc_off, const int32_t* w, uint64_t seed,
-                                   uint32_t sweep, int32_t* z, float* theta, const float* phi,
+                                   uint32_t sweep, int32_t* z, T* theta, const T* phi,
                                    int32_t* n_dk, int32_t* n_wk_scratch) {
-  const int64_t deg = orc_lda_sample_z(D, K, doc_off, w, theta, phi, seed, sweep, z);
+  const int64_t deg = lda_sample_z_impl<T>(D, K, doc_off, w, theta, phi, seed, sweep, z);
   orc_lda_count(D, V, K, doc_off, w, z, n_dk, n_wk_scratch);
-  orc_lda_resample_theta(D, K, alpha, n_dk, seed, sweep, theta);
+  lda_resample_theta_impl<T>(D, K, alpha, n_dk, seed, sweep, theta);
   return deg;
 }
 
 // Default initial state: z from the init stream, counts, then theta and phi
 // drawn from their conditionals with sweep index 0.
-void orc_lda_init(int32_t D, int32_t V, int32_t K, double alpha, double beta,
+template <typename T>
+void lda_init_impl(int32_t D, int32_t V, int32_t K, double alpha, double beta,
                   const int64_t* doc_off, const int32_t* w, uint64_t seed, int32_t* z,
-                  float* theta, float* phi, int32_t* n_dk, int32_t* n_wk) {
+                  T* theta, T* phi, int32_t* n_dk, int32_t* n_wk) {
   orc_lda_init_z(doc_off[D], K, seed, z);
   orc_lda_count(D, V, K, doc_off, w, z, n_dk, n_wk);
-  orc_lda_resample_theta(D, K, alpha, n_dk, seed, 0, theta);
-  orc_lda_resample_phi(V, K, beta, n_wk, seed, 0, phi);
+  lda_resample_theta_impl<T>(D, K, alpha, n_dk, seed, 0, theta);
+  lda_resample_phi_impl<T>(V, K, beta, n_wk, seed, 0, phi);
 }
 
 // Log joint density ln p(phi, theta, z, w) of Fig. 1's program and the log
 // likelihood of the words with z summed out, ln p(w | theta, phi).
-void orc_lda_loglik(int32_t D, int32_t V, int32_t K, double alpha, double beta,
+template <typename T>
+void lda_loglik_impl(int32_t D, int32_t V, int32_t K, double alpha, double beta,
                     const int64_t* doc_off, const int32_t* w, const int32_t* z,
-                    const float* theta, const float* phi, double* log_joint,
+                    const T* theta, const T* phi, double* log_joint,
                     double* log_marginal_w) {
   double prior = 0.0;
   for (int32_t d = 0; d < D; ++d) prior += log_dirichlet_sym(theta + (int64_t)d * K, K, 1, alpha);
@@ -417,8 +438,8 @@ void orc_lda_loglik(int32_t D, int32_t V, int32_t K, double alpha, double beta,
   std::vector<double> cdf(K);
   for (int32_t d = 0; d < D; ++d)
     for (int64_t i = doc_off[d]; i < doc_off[d + 1]; ++i) {
-      const float* th = theta + (int64_t)d * K;
-      const float* ph = phi + (int64_t)w[i] * K;
+      const T* th = theta + (int64_t)d * K;
+      const T* ph = phi + (int64_t)w[i] * K;
       lik += std::log((double)th[z[i]]) + std::log((double)ph[z[i]]);
       lda_token_cdf(th, ph, K, cdf.data());
       marg += std::log(cdf[K - 1]);
@@ -426,6 +447,57 @@ void orc_lda_loglik(int32_t D, int32_t V, int32_t K, double alpha, double beta,
   if (log_joint) *log_joint = prior + lik;
   if (log_marginal_w) *log_marginal_w = marg;
 }
+
+}  // namespace
+
+extern "C" {
+
+// The exported LDA functions: fp32 state (the benchmark's) and fp64 state (_f64).
+#define ORC_LDA_EXPORTS(SUFFIX, T)                                                                      \
+  int64_t orc_lda_sample_z##SUFFIX(int32_t D, int32_t K, const int64_t* doc_off, const int32_t* w,      \
+                                   const T* theta, const T* phi, uint64_t seed, uint32_t sweep,         \
+                                   int32_t* z) {                                                        \
+    return lda_sample_z_impl<T>(D, K, doc_off, w, theta, phi, seed, sweep, z);                          \
+  }                                                                                                     \
+  void orc_lda_token_cdf##SUFFIX(int32_t K, const T* theta_d, const T* phi_v, uint64_t seed,            \
+                                 uint64_t token, uint32_t sweep, double* cdf, double* t) {              \
+    lda_token_cdf_impl<T>(K, theta_d, phi_v, seed, token, sweep, cdf, t);                               \
+  }                                                                                                     \
+  int orc_lda_resample_theta##SUFFIX(int32_t D, int32_t K, double alpha, const int32_t* n_dk,           \
+                                     uint64_t seed, uint32_t sweep, T* theta) {                         \
+    return lda_resample_theta_impl<T>(D, K, alpha, n_dk, seed, sweep, theta);                           \
+  }                                                                                                     \
+  int orc_lda_resample_phi##SUFFIX(int32_t V, int32_t K, double beta, const int32_t* n_wk,              \
+                                   uint64_t seed, uint32_t sweep, T* phi) {                             \
+    return lda_resample_phi_impl<T>(V, K, beta, n_wk, seed, sweep, phi);                                \
+  }                                                                                                     \
+  int64_t orc_lda_sweep##SUFFIX(int32_t D, int32_t V, int32_t K, double alpha, double beta,             \
+                                const int64_t* doc_off, const int32_t* w, uint64_t seed,                \
+                                uint32_t sweep, int32_t* z, T* theta, T* phi, int32_t* n_dk,            \
+                                int32_t* n_wk) {                                                        \
+    return lda_sweep_impl<T>(D, V, K, alpha, beta, doc_off, w, seed, sweep, z, theta, phi, n_dk, n_wk); \
+  }                                                                                                     \
+  int64_t orc_lda_sweep_phi_observed##SUFFIX(int32_t D, int32_t V, int32_t K, double alpha,             \
+                                             const int64_t* doc_off, const int32_t* w, uint64_t seed,   \
+                                             uint32_t sweep, int32_t* z, T* theta, const T* phi,        \
+                                             int32_t* n_dk, int32_t* n_wk_scratch) {                    \
+    return lda_sweep_phi_observed_impl<T>(D, V, K, alpha, doc_off, w, seed, sweep, z, theta, phi, n_dk, \
+                                          n_wk_scratch);                                                \
+  }                                                                                                     \
+  void orc_lda_init##SUFFIX(int32_t D, int32_t V, int32_t K, double alpha, double beta,                 \
+                            const int64_t* doc_off, const int32_t* w, uint64_t seed, int32_t* z,        \
+                            T* theta, T* phi, int32_t* n_dk, int32_t* n_wk) {                           \
+    lda_init_impl<T>(D, V, K, alpha, beta, doc_off, w, seed, z, theta, phi, n_dk, n_wk);                \
+  }                                                                                                     \
+  void orc_lda_loglik##SUFFIX(int32_t D, int32_t V, int32_t K, double alpha, double beta,               \
+                              const int64_t* doc_off, const int32_t* w, const int32_t* z,               \
+                              const T* theta, const T* phi, double* log_joint,                          \
+                              double* log_marginal_w) {                                                 \
+    lda_loglik_impl<T>(D, V, K, alpha, beta, doc_off, w, z, theta, phi, log_joint, log_marginal_w);     \
+  }
+ORC_LDA_EXPORTS(, float)
+ORC_LDA_EXPORTS(_f64, double)
+#undef ORC_LDA_EXPORTS
 
 // ------------------------------------------------------------- Gaussian mixture
 void orc_gmm_init_z(int64_t N, int32_t K, uint64_t seed, int32_t* z) {

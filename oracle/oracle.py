@@ -37,6 +37,11 @@ def lib():
         L.orc_lda_sample_z.restype = C.c_int64
         L.orc_lda_sweep.restype = C.c_int64
         L.orc_lda_sweep_phi_observed.restype = C.c_int64
+        L.orc_lda_sample_z_f64.restype = C.c_int64
+        L.orc_lda_sweep_f64.restype = C.c_int64
+        L.orc_lda_sweep_phi_observed_f64.restype = C.c_int64
+        L.orc_lda_resample_theta_f64.restype = C.c_int
+        L.orc_lda_resample_phi_f64.restype = C.c_int
         L.orc_gmm_sample_z.restype = C.c_int64
         L.orc_gmm_sweep.restype = C.c_int64
         L.orc_gmm_loglik.restype = C.c_double
@@ -121,6 +126,13 @@ def gamma_log_draws(a, seed, first=0, sweep=0, stream=STREAM_THETA, return_attem
 
 
 # ------------------------------------------------------------------------ LDA
+# f64=True selects the oracle's fp64 state mode (theta and phi stored as doubles): the exported
+# functions ending in _f64.
+def _state(f64):
+    """(array converter, ctypes element type, numpy dtype, function-name suffix) of a state mode."""
+    return (_f64, C.c_double, np.float64, "_f64") if f64 else (_f32, C.c_float, np.float32, "")
+
+
 def doc_offsets(doc_len):
     off = np.zeros(len(doc_len) + 1, dtype=np.int64)
     np.cumsum(np.asarray(doc_len, dtype=np.int64), out=off[1:])
@@ -133,24 +145,26 @@ def lda_init_z(N, K, seed):
     return z
 
 
-def lda_sample_z(doc_off, w, theta, phi, seed, sweep):
-    doc_off, w, theta, phi = _i64(doc_off), _i32(w), _f32(theta), _f32(phi)
+def lda_sample_z(doc_off, w, theta, phi, seed, sweep, f64=False):
+    conv, ct, _, sfx = _state(f64)
+    doc_off, w, theta, phi = _i64(doc_off), _i32(w), conv(theta), conv(phi)
     D, K = theta.shape
     z = np.zeros(w.size, dtype=np.int32)
-    deg = lib().orc_lda_sample_z(C.c_int32(D), C.c_int32(K), _p(doc_off, C.c_int64),
-                                 _p(w, C.c_int32), _p(theta, C.c_float), _p(phi, C.c_float),
-                                 C.c_uint64(seed), C.c_uint32(sweep), _p(z, C.c_int32))
+    deg = getattr(lib(), "orc_lda_sample_z" + sfx)(
+        C.c_int32(D), C.c_int32(K), _p(doc_off, C.c_int64), _p(w, C.c_int32), _p(theta, ct),
+        _p(phi, ct), C.c_uint64(seed), C.c_uint32(sweep), _p(z, C.c_int32))
     return z, deg
 
 
-def lda_token_cdf(theta_d, phi_v, seed, token, sweep):
-    theta_d, phi_v = _f32(theta_d), _f32(phi_v)
+def lda_token_cdf(theta_d, phi_v, seed, token, sweep, f64=False):
+    conv, ct, _, sfx = _state(f64)
+    theta_d, phi_v = conv(theta_d), conv(phi_v)
     K = theta_d.size
     cdf = np.zeros(K, dtype=np.float64)
     t = C.c_double(0.0)
-    lib().orc_lda_token_cdf(C.c_int32(K), _p(theta_d, C.c_float), _p(phi_v, C.c_float),
-                            C.c_uint64(seed), C.c_uint64(token), C.c_uint32(sweep),
-                            _p(cdf, C.c_double), C.byref(t))
+    getattr(lib(), "orc_lda_token_cdf" + sfx)(
+        C.c_int32(K), _p(theta_d, ct), _p(phi_v, ct), C.c_uint64(seed), C.c_uint64(token),
+        C.c_uint32(sweep), _p(cdf, C.c_double), C.byref(t))
     return cdf, t.value
 
 
@@ -164,34 +178,38 @@ def lda_count(doc_off, w, z, D, V, K):
     return n_dk, n_wk
 
 
-def lda_resample_theta(n_dk, alpha, seed, sweep):
+def lda_resample_theta(n_dk, alpha, seed, sweep, f64=False):
+    _, ct, dt, sfx = _state(f64)
     n_dk = _i32(n_dk)
     D, K = n_dk.shape
-    theta = np.zeros((D, K), dtype=np.float32)
-    lib().orc_lda_resample_theta(C.c_int32(D), C.c_int32(K), C.c_double(alpha),
-                                 _p(n_dk, C.c_int32), C.c_uint64(seed), C.c_uint32(sweep),
-                                 _p(theta, C.c_float))
+    theta = np.zeros((D, K), dtype=dt)
+    getattr(lib(), "orc_lda_resample_theta" + sfx)(
+        C.c_int32(D), C.c_int32(K), C.c_double(alpha), _p(n_dk, C.c_int32), C.c_uint64(seed),
+        C.c_uint32(sweep), _p(theta, ct))
     return theta
 
 
-def lda_resample_phi(n_wk, beta, seed, sweep):
+def lda_resample_phi(n_wk, beta, seed, sweep, f64=False):
+    _, ct, dt, sfx = _state(f64)
     n_wk = _i32(n_wk)
     V, K = n_wk.shape
-    phi = np.zeros((V, K), dtype=np.float32)
-    lib().orc_lda_resample_phi(C.c_int32(V), C.c_int32(K), C.c_double(beta), _p(n_wk, C.c_int32),
-                               C.c_uint64(seed), C.c_uint32(sweep), _p(phi, C.c_float))
+    phi = np.zeros((V, K), dtype=dt)
+    getattr(lib(), "orc_lda_resample_phi" + sfx)(
+        C.c_int32(V), C.c_int32(K), C.c_double(beta), _p(n_wk, C.c_int32), C.c_uint64(seed),
+        C.c_uint32(sweep), _p(phi, ct))
     return phi
 
 
-def lda_loglik(doc_off, w, z, theta, phi, alpha, beta):
-    doc_off, w, z, theta, phi = _i64(doc_off), _i32(w), _i32(z), _f32(theta), _f32(phi)
+def lda_loglik(doc_off, w, z, theta, phi, alpha, beta, f64=False):
+    conv, ct, _, sfx = _state(f64)
+    doc_off, w, z, theta, phi = _i64(doc_off), _i32(w), _i32(z), conv(theta), conv(phi)
     D, K = theta.shape
     V = phi.shape[0]
     lj, lm = C.c_double(0.0), C.c_double(0.0)
-    lib().orc_lda_loglik(C.c_int32(D), C.c_int32(V), C.c_int32(K), C.c_double(alpha),
-                         C.c_double(beta), _p(doc_off, C.c_int64), _p(w, C.c_int32),
-                         _p(z, C.c_int32), _p(theta, C.c_float), _p(phi, C.c_float),
-                         C.byref(lj), C.byref(lm))
+    getattr(lib(), "orc_lda_loglik" + sfx)(
+        C.c_int32(D), C.c_int32(V), C.c_int32(K), C.c_double(alpha), C.c_double(beta),
+        _p(doc_off, C.c_int64), _p(w, C.c_int32), _p(z, C.c_int32), _p(theta, ct), _p(phi, ct),
+        C.byref(lj), C.byref(lm))
     return lj.value, lm.value
 
 
@@ -199,7 +217,9 @@ class OracleLDA:
     """State holder around the oracle's LDA functions; same call names as the
     HIP binding so a test can drive both in lock-step."""
 
-    def __init__(self, D, V, K, alpha, beta, seed, doc_len, w):
+    def __init__(self, D, V, K, alpha, beta, seed, doc_len, w, f64=False):
+        self.f64 = bool(f64)
+        self._conv, self._ct, self._dt, self._sfx = _state(self.f64)
         self.D, self.V, self.K = int(D), int(V), int(K)
         self.alpha, self.beta, self.seed = float(np.float32(alpha)), float(np.float32(beta)), int(seed)
         self.doc_off = doc_offsets(doc_len)
@@ -207,19 +227,18 @@ class OracleLDA:
         self.N = int(self.doc_off[-1])
         assert self.w.size == self.N
         self.z = np.zeros(self.N, dtype=np.int32)
-        self.theta = np.zeros((self.D, self.K), dtype=np.float32)
-        self.phi = np.zeros((self.V, self.K), dtype=np.float32)
+        self.theta = np.zeros((self.D, self.K), dtype=self._dt)
+        self.phi = np.zeros((self.V, self.K), dtype=self._dt)
         self.n_dk = np.zeros((self.D, self.K), dtype=np.int32)
         self.n_wk = np.zeros((self.V, self.K), dtype=np.int32)
         self.sweep_index = 0
         self.degenerate = 0
         self.phi_observed = False
-        lib().orc_lda_init(C.c_int32(self.D), C.c_int32(self.V), C.c_int32(self.K),
-                           C.c_double(self.alpha), C.c_double(self.beta),
-                           _p(self.doc_off, C.c_int64), _p(self.w, C.c_int32),
-                           C.c_uint64(self.seed), _p(self.z, C.c_int32),
-                           _p(self.theta, C.c_float), _p(self.phi, C.c_float),
-                           _p(self.n_dk, C.c_int32), _p(self.n_wk, C.c_int32))
+        getattr(lib(), "orc_lda_init" + self._sfx)(
+            C.c_int32(self.D), C.c_int32(self.V), C.c_int32(self.K), C.c_double(self.alpha),
+            C.c_double(self.beta), _p(self.doc_off, C.c_int64), _p(self.w, C.c_int32),
+            C.c_uint64(self.seed), _p(self.z, C.c_int32), _p(self.theta, self._ct),
+            _p(self.phi, self._ct), _p(self.n_dk, C.c_int32), _p(self.n_wk, C.c_int32))
 
     def set_observed(self, phi=False):
         self.phi_observed = bool(phi)
@@ -229,41 +248,42 @@ class OracleLDA:
             t = self.sweep_index + 1
             if self.phi_observed:
                 scratch = np.zeros_like(self.n_wk)
-                self.degenerate += lib().orc_lda_sweep_phi_observed(
+                self.degenerate += getattr(lib(), "orc_lda_sweep_phi_observed" + self._sfx)(
                     C.c_int32(self.D), C.c_int32(self.V), C.c_int32(self.K), C.c_double(self.alpha),
                     _p(self.doc_off, C.c_int64), _p(self.w, C.c_int32), C.c_uint64(self.seed),
-                    C.c_uint32(t), _p(self.z, C.c_int32), _p(self.theta, C.c_float),
-                    _p(self.phi, C.c_float), _p(self.n_dk, C.c_int32), _p(scratch, C.c_int32))
+                    C.c_uint32(t), _p(self.z, C.c_int32), _p(self.theta, self._ct),
+                    _p(self.phi, self._ct), _p(self.n_dk, C.c_int32), _p(scratch, C.c_int32))
                 self.sweep_index = t
                 continue
-            self.degenerate += lib().orc_lda_sweep(
+            self.degenerate += getattr(lib(), "orc_lda_sweep" + self._sfx)(
                 C.c_int32(self.D), C.c_int32(self.V), C.c_int32(self.K), C.c_double(self.alpha),
                 C.c_double(self.beta), _p(self.doc_off, C.c_int64), _p(self.w, C.c_int32),
                 C.c_uint64(self.seed), C.c_uint32(t), _p(self.z, C.c_int32),
-                _p(self.theta, C.c_float), _p(self.phi, C.c_float), _p(self.n_dk, C.c_int32),
+                _p(self.theta, self._ct), _p(self.phi, self._ct), _p(self.n_dk, C.c_int32),
                 _p(self.n_wk, C.c_int32))
             self.sweep_index = t
 
     # step-level calls: all use sweep index sweep_index + 1; step_finish advances it
     def step_sample_z(self):
         self.z, deg = lda_sample_z(self.doc_off, self.w, self.theta, self.phi, self.seed,
-                                   self.sweep_index + 1)
+                                   self.sweep_index + 1, f64=self.f64)
         self.degenerate += deg
 
     def step_count(self):
         self.n_dk, self.n_wk = lda_count(self.doc_off, self.w, self.z, self.D, self.V, self.K)
 
     def step_resample_theta(self):
-        self.theta = lda_resample_theta(self.n_dk, self.alpha, self.seed, self.sweep_index + 1)
+        self.theta = lda_resample_theta(self.n_dk, self.alpha, self.seed, self.sweep_index + 1, f64=self.f64)
 
     def step_resample_phi(self):
-        self.phi = lda_resample_phi(self.n_wk, self.beta, self.seed, self.sweep_index + 1)
+        self.phi = lda_resample_phi(self.n_wk, self.beta, self.seed, self.sweep_index + 1, f64=self.f64)
 
     def step_finish(self):
         self.sweep_index += 1
 
     def loglik(self):
-        return lda_loglik(self.doc_off, self.w, self.z, self.theta, self.phi, self.alpha, self.beta)
+        return lda_loglik(self.doc_off, self.w, self.z, self.theta, self.phi, self.alpha, self.beta,
+                          f64=self.f64)
 
     def get_state(self):
         return self.z.copy(), self.theta.copy(), self.phi.copy(), self.sweep_index
@@ -273,9 +293,9 @@ class OracleLDA:
             self.z = _i32(z).copy()
             self.step_count()
         if theta is not None:
-            self.theta = _f32(theta).reshape(self.D, self.K).copy()
+            self.theta = self._conv(theta).reshape(self.D, self.K).copy()
         if phi is not None:
-            self.phi = _f32(phi).reshape(self.V, self.K).copy()
+            self.phi = self._conv(phi).reshape(self.V, self.K).copy()
         if sweep is not None:
             self.sweep_index = int(sweep)
 
