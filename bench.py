@@ -17,6 +17,7 @@ workload (LDA large, K = 200) it holds
   ceilings              what the memory system allows, measured in this run: a plain
                         streaming copy and a gather-only pass over the same word stream and phi
                         table; plus the instruction counters of the profiled launch
+  state_f64             the sweep with theta and phi held in fp64, beside the fp32 figure
   k100                  the same figures for the K = 100 workload (LDA medium)
   cpu_baseline          the oracle on one pinned host core, per step on a bounded sample,
                         composed to the full corpus
@@ -138,7 +139,8 @@ def oracle_per_step(cfg, corpus, target_tokens, z_reps):
                      "usable_cores": len(old)}}
 
 
-def run_lda(name, cfg, corpus, steps, warmup, repeats, with_ceilings, overlap=True, topics=None):
+def run_lda(name, cfg, corpus, steps, warmup, repeats, with_ceilings, overlap=True, topics=None,
+            with_f64=True):
     """All GPU measurements of one LDA workload.  Returns (fields of the main line, extras)."""
     import torch
     from paper_1312_3613_amd import binding as B
@@ -255,6 +257,36 @@ def run_lda(name, cfg, corpus, steps, warmup, repeats, with_ceilings, overlap=Tr
                     ceil[k] = counters[k]
             ceil["counters_source"] = "rocprofv3 --pmc run recorded in profiles/hbm_traffic.json"
         extra["ceilings"] = ceil
+
+    if with_f64:
+        # the same sweep with theta and phi held in fp64 (the precision of the paper's own runs)
+        f_steps = max(1, min(steps, 10))
+        t0 = time.perf_counter()
+        h64 = B.LDA(D, V, K, cfg["alpha"], cfg["beta"], cfg["seed"], doc_len_d, w_d, stream=stream,
+                    device_ptrs=True, state_f64=True)
+        t_create64 = time.perf_counter() - t0
+        h64.set_overlap(overlap)
+        h64.sweep(warmup)
+        h64.sync()
+        walls64 = []
+        for _ in range(repeats):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            h64.sweep(f_steps)
+            h64.sync()
+            torch.cuda.synchronize()
+            walls64.append(time.perf_counter() - t0)
+        ms64 = h64.sweep_profile(f_steps)
+        e64 = sorted(walls64)[len(walls64) // 2]
+        extra["state_f64"] = {
+            "ms_per_step": e64 / f_steps * 1e3, "value": N * f_steps / e64, "unit": "tokens/s",
+            "steps": f_steps, "over_f32_sweep": e64 / f_steps / (elapsed / steps),
+            "kernel_ms_per_sweep": {k: v / f_steps for k, v in ms64.items()},
+            "log_marginal_per_token": h64.loglik()[1] / max(N, 1), "create_s": t_create64,
+            "note": "theta and phi stored and multiplied as fp64 (AUGUR_STATE_F64); same protocol as value "
+                    "(median of %d regions of %d sweeps through sweep()); the z kernel of this mode is a plain "
+                    "one written for checking against the fp64 oracle" % (repeats, f_steps)}
+        h64.close()
 
     lj, lm = h.loglik()
     extra["log_marginal_per_token"] = lm / max(N, 1)
@@ -374,6 +406,8 @@ def main():
                     help="build the word-count table on the main stream instead of beside the theta step")
     ap.add_argument("--no-ceilings", action="store_true",
                     help="leave out the z + count leg and the copy and gather probes")
+    ap.add_argument("--no-state-f64", action="store_true",
+                    help="leave out the sweep with theta and phi held in fp64")
     ap.add_argument("--no-k100", action="store_true",
                     help="with the default workload: leave out the K = 100 (LDA medium) block")
     args = ap.parse_args()
@@ -396,7 +430,8 @@ def main():
     t_gen = time.perf_counter() - t0
     torch.cuda.set_device(0)
     main_fields, extra = run_lda(args.workload, cfg, corpus, steps, args.warmup, args.repeats,
-                                 not args.no_ceilings, overlap=not args.no_overlap, topics=args.topics)
+                                 not args.no_ceilings, overlap=not args.no_overlap, topics=args.topics,
+                                 with_f64=not args.no_state_f64)
     K = args.topics if args.topics is not None else cfg["K"]
     out = {
         "metric": "Gibbs sweep tokens/sec (LDA K=100/200) + achieved HBM GB/s vs peak",
@@ -432,7 +467,8 @@ def main():
         mcorpus = synth.lda_corpus(**mcfg)
         t_mgen = time.perf_counter() - t0
         mmain, mextra = run_lda("medium", mcfg, mcorpus, mcfg["sweeps"], args.warmup, args.repeats,
-                                not args.no_ceilings, overlap=not args.no_overlap)
+                                not args.no_ceilings, overlap=not args.no_overlap,
+                                with_f64=not args.no_state_f64)
         k100 = {"config": {"workload": f"LDA medium: D={mcfg['D']} V={mcfg['V']} K={mcfg['K']} N={mcorpus['N']} "
                                        f"alpha={mcfg['alpha']} beta={mcfg['beta']} (seed {mcfg['seed']}), "
                                        f"inputs resident in HBM"},

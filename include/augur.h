@@ -43,6 +43,13 @@ extern "C" {
 #define AUGUR_ERR_UNIMPLEMENTED (-4)
 
 #define AUGUR_PTRS_DEVICE 1u
+/* LDA only: theta and phi are stored, read and multiplied as fp64 (the precision the paper's
+ * own experiments ran in, Sect. 5) instead of fp32.  The draws (Philox stream, Gamma variates,
+ * normalisation in fp64) are the same; what changes is the rounding of the stored
+ * probabilities (floored at DBL_MIN instead of FLT_MIN) and of the z step's products and
+ * running sums.  The z step of such a handle is a plain kernel written for checking, several
+ * times slower than the fp32 one; theta, phi, the counts and the log densities cost the same. */
+#define AUGUR_STATE_F64 2u
 
 const char* augur_last_error(void); /* thread-local; valid until the next call on this thread */
 const char* augur_version(void);
@@ -61,7 +68,7 @@ typedef struct {
   uint64_t seed;
   int32_t device;       /* HIP device ordinal */
   void* stream;         /* hipStream_t or NULL */
-  uint32_t flags;       /* AUGUR_PTRS_DEVICE or 0 */
+  uint32_t flags;       /* 0 or any of AUGUR_PTRS_DEVICE, AUGUR_STATE_F64 */
 } augur_lda_config;
 
 /* Builds the sampler state for a corpus.  doc_len[D] >= 0 (empty documents
@@ -148,6 +155,12 @@ int augur_lda_loglik(augur_lda* h, double* log_joint, double* log_marginal_w);
  * it.  get_state copies z int32[N], theta float[D][K], phi float[V][K] and the
  * number of completed sweeps out; set_state copies them in. */
 int augur_lda_get_state(augur_lda* h, int32_t* z, float* theta, float* phi, int64_t* sweep);
+/* The same for a handle created with AUGUR_STATE_F64: theta double[D][K], phi double[V][K].
+ * Each pair serves its own kind of handle; asked for theta or phi of the other kind it
+ * returns AUGUR_ERR_INVALID_ARG (z and sweep alone are served by either). */
+int augur_lda_get_state_f64(augur_lda* h, int32_t* z, double* theta, double* phi, int64_t* sweep);
+int augur_lda_set_state_f64(augur_lda* h, const int32_t* z, const double* theta, const double* phi,
+                            int64_t sweep);
 /* Any of z/theta/phi may be NULL (left as is); sweep < 0 leaves the index.
  * Setting z recomputes the counts.  z[i] must lie in [0,K). */
 int augur_lda_set_state(augur_lda* h, const int32_t* z, const float* theta, const float* phi,

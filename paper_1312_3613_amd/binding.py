@@ -14,6 +14,7 @@ from . import build as _build
 
 OK, ERR_INVALID_ARG, ERR_HIP, ERR_DEGENERATE, ERR_UNIMPLEMENTED = 0, -1, -2, -3, -4
 PTRS_DEVICE = 1
+STATE_F64 = 2
 LDA_NSTEPS = 5
 
 _LIB = None
@@ -89,6 +90,8 @@ def lib():
         L.augur_lda_loglik.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_double)]
         L.augur_lda_get_state.argtypes = [vp, vp, vp, vp, C.POINTER(C.c_int64)]
         L.augur_lda_set_state.argtypes = [vp, vp, vp, vp, C.c_int64]
+        L.augur_lda_get_state_f64.argtypes = [vp, vp, vp, vp, C.POINTER(C.c_int64)]
+        L.augur_lda_set_state_f64.argtypes = [vp, vp, vp, vp, C.c_int64]
         L.augur_lda_get_counts.argtypes = [vp, vp, vp]
         L.augur_lda_get_degenerate.argtypes = [vp, C.POINTER(C.c_int64)]
         L.augur_lda_probe_gather.argtypes = [vp, C.c_int32, C.POINTER(C.c_double)]
@@ -203,11 +206,14 @@ def probe_stream_copy(src, dst, reps=10, stream=None):
 
 
 class LDA:
-    """augur_lda_* handle.  Method names are the ABI's."""
+    """augur_lda_* handle.  Method names are the ABI's.  state_f64=True asks for the fp64 state
+    (AUGUR_STATE_F64): get_state and set_state then carry theta and phi as float64 through the
+    _f64 entry points."""
 
     def __init__(self, D, V, K, alpha, beta, seed, doc_len, w, device=0, stream=None,
-                 device_ptrs=False):
+                 device_ptrs=False, state_f64=False):
         self._h = None
+        self.state_f64 = bool(state_f64)
         self.D, self.V, self.K = int(D), int(V), int(K)
         self._arr = _Arrays(device_ptrs, device)
         doc_len_a = self._arr.input(doc_len, "i32")
@@ -220,7 +226,8 @@ class LDA:
         if n_tok != self.N:
             raise ValueError(f"w has {n_tok} entries, sum(doc_len) = {self.N}")
         cfg = LdaConfig(self.D, self.V, self.K, float(alpha), float(beta), int(seed), int(device),
-                        _stream_handle(stream), PTRS_DEVICE if device_ptrs else 0)
+                        _stream_handle(stream),
+                        (PTRS_DEVICE if device_ptrs else 0) | (STATE_F64 if state_f64 else 0))
         h = C.c_void_p()
         _check(lib().augur_lda_create(C.byref(cfg), _ptr(doc_len_a), _ptr(w_a), C.byref(h)))
         self._h = h
@@ -288,18 +295,21 @@ class LDA:
 
     def get_state(self, z=True, theta=True, phi=True):
         za = self._arr.empty((self.N,), "i32") if z else None
-        ta = self._arr.empty((self.D, self.K), "f32") if theta else None
-        pa = self._arr.empty((self.V, self.K), "f32") if phi else None
+        kind = "f64" if self.state_f64 else "f32"
+        ta = self._arr.empty((self.D, self.K), kind) if theta else None
+        pa = self._arr.empty((self.V, self.K), kind) if phi else None
         sw = C.c_int64()
-        _check(lib().augur_lda_get_state(self._h, _ptr(za), _ptr(ta), _ptr(pa), C.byref(sw)))
+        get = lib().augur_lda_get_state_f64 if self.state_f64 else lib().augur_lda_get_state
+        _check(get(self._h, _ptr(za), _ptr(ta), _ptr(pa), C.byref(sw)))
         return za, ta, pa, sw.value
 
     def set_state(self, z=None, theta=None, phi=None, sweep=None):
         za = self._arr.input(z, "i32", self.N)
-        ta = self._arr.input(theta, "f32", self.D * self.K)
-        pa = self._arr.input(phi, "f32", self.V * self.K)
-        _check(lib().augur_lda_set_state(self._h, _ptr(za), _ptr(ta), _ptr(pa),
-                                         -1 if sweep is None else int(sweep)))
+        kind = "f64" if self.state_f64 else "f32"
+        ta = self._arr.input(theta, kind, self.D * self.K)
+        pa = self._arr.input(phi, kind, self.V * self.K)
+        put = lib().augur_lda_set_state_f64 if self.state_f64 else lib().augur_lda_set_state
+        _check(put(self._h, _ptr(za), _ptr(ta), _ptr(pa), -1 if sweep is None else int(sweep)))
 
     def get_counts(self):
         n_dk = self._arr.empty((self.D, self.K), "i32")

@@ -27,6 +27,14 @@ using namespace augur;
 namespace {
 
 constexpr int kRedBlocks = 2048;       // partial sums of the log-likelihood reductions
+
+// theta and phi are stored as fp32 (the benchmark's state) or, in the fp64 state mode, as fp64;
+// a stored probability is never below the type's smallest positive normal number, so that its
+// logarithm stays finite.
+template <typename T>
+__host__ __device__ constexpr double state_floor() {
+  return sizeof(T) == sizeof(float) ? (double)FLT_MIN : DBL_MIN;
+}
 constexpr int kPhiRowsMax = 32;  // most rows of the Gamma matrix handled by one block
 
 // ------------------------------------------------------------------ DPP rows
@@ -1069,6 +1077,137 @@ __global__ __launch_bounds__(256) void lda_gather_probe_row_kernel(
   }
 }
 
+// ------------------------------------------------------- fp64 state: sample z
+// The same draw with theta and phi stored as doubles (the precision the paper's experiments
+// ran in): every product and sum in fp64, so the result differs from a sum in index order by
+// fp64 rounding only.  Written for any K up to 1024 and for checking rather than for speed:
+// a quad per token, theta_d as doubles in LDS, three walks over the row (the total; the
+// crossing stripe; the topic inside it), the row re-read from cache each time.
+__device__ __forceinline__ double quad_sum_f64(double s) {
+  s += __shfl_xor(s, 1, 64);
+  s += __shfl_xor(s, 2, 64);
+  return s;
+}
+template <bool kCountDocs>
+__global__ __launch_bounds__(256) void lda_sample_z_f64_kernel(
+    const int32_t* __restrict__ w, const int64_t* __restrict__ doc_off,
+    const int32_t* __restrict__ seg_base, int n_segs, const double* __restrict__ theta,
+    const double* __restrict__ phi, int32_t* __restrict__ z, int32_t* __restrict__ n_dk, int D, int K,
+    int ldk, uint64_t seed, SweepRef sweep_ref, unsigned long long* __restrict__ n_degenerate,
+    uint8_t* __restrict__ zb) {
+  extern __shared__ __align__(16) double lds_f64[];  // per wave: theta_d [ldk16], then the histogram [ldk16] ints
+  const uint32_t sweep = sweep_ref.get();
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int seg = blockIdx.x * 4 + wave;
+  if (seg >= n_segs) return;
+  const Segment sg = segment_of(doc_off, seg_base, D, seg);
+  const int d = sg.d;
+  const int tq = lane >> 2, q = lane & 3;
+  const int ldk16 = (ldk + 15) & ~15;
+  const int stripes = ldk16 >> 4;
+  double* th = lds_f64 + (size_t)wave * ldk16;
+  int32_t* hist = reinterpret_cast<int32_t*>(lds_f64 + (size_t)4 * ldk16) + (size_t)wave * ldk16;
+  for (int k = lane; k < ldk16; k += 64) {
+    th[k] = k < K ? theta[(size_t)d * ldk + k] : 0.0;
+    if (kCountDocs) hist[k] = 0;
+  }
+  wave_lds_fence();
+  const double* th_q = th + 4 * q;
+  // the lane's four entries of stripe c of row `row`; entries at or past column K count as zero
+  // (and are not read past the row's end)
+  auto chunk = [&](const double* row, int c, double (&y)[4]) {
+    const int col = 16 * c + 4 * q;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) y[e] = col + e < K ? row[col + e] : 0.0;
+  };
+  const int64_t a = sg.first > sg.a ? sg.first : sg.a, b = sg.end;
+  for (int64_t i0 = a; i0 < b; i0 += 16) {
+    const int64_t i = i0 + tq;
+    const bool valid = i < b;
+    const int64_t ii = valid ? i : a;
+    const double* row = phi + (size_t)w[ii] * ldk;
+    const uint32_t r = word_of(random_block(seed, (uint64_t)(ii >> 2), sweep, kStreamZ, 0), (uint32_t)(ii & 3));
+    // walk 1: the total
+    double acc = 0.0;
+    for (int c = 0; c < stripes; ++c) {
+      double y[4];
+      chunk(row, c, y);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) acc = fma(th_q[16 * c + e], y[e], acc);
+    }
+    const double S = quad_sum_f64(acc);
+    const double t = (double)u24(r) * S;
+    // walk 2: the crossing stripe among all but the last, and the running sum before it
+    int cs = 0;
+    double cprev = 0.0;
+    acc = 0.0;
+    for (int c = 0; c < stripes - 1; ++c) {
+      double y[4];
+      chunk(row, c, y);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) acc = fma(th_q[16 * c + e], y[e], acc);
+      const double cum = quad_sum_f64(acc);
+      const bool below = cum <= t;
+      cs += below ? 1 : 0;
+      cprev = below ? cum : cprev;
+    }
+    // walk 3: the topic inside stripe cs
+    double y[4];
+    chunk(row, cs, y);
+    const double* t2 = th_q + 16 * cs;
+    const double l0 = t2[0] * y[0];
+    const double l1 = fma(t2[1], y[1], l0);
+    const double l2 = fma(t2[2], y[2], l1);
+    const double l3 = fma(t2[3], y[3], l2);
+    const int qb = lane & ~3;
+    const double v0 = __shfl(l3, qb + 0, 64), v1 = __shfl(l3, qb + 1, 64), v2 = __shfl(l3, qb + 2, 64);
+    const double excl = q == 0 ? 0.0 : q == 1 ? v0 : q == 2 ? v0 + v1 : (v0 + v1) + v2;
+    const double tt = fmax(t - (cprev + excl), 0.0);
+    const int e = (l0 <= tt) + (l1 <= tt) + (l2 <= tt);
+    int cand = l3 > tt ? 4 * q + e : kNoTopic;
+    cand = min(cand, __shfl_xor(cand, 1, 64));
+    cand = min(cand, __shfl_xor(cand, 2, 64));
+    int k = 16 * cs + cand;
+    const bool ok = S > 0.0 && S <= DBL_MAX;  // false for 0, inf and NaN
+    const bool in_row = S > t;
+    const bool found = in_row && cand != kNoTopic;
+    if (__builtin_expect(__any(valid && !(ok && found)), 0)) {
+      if (!ok) {
+        k = u24_times(r, K);  // zero or non-finite mass: z = floor(u K)
+        if (valid && q == 0) atomicAdd(n_degenerate, 1ULL);
+      } else if (!found) {
+        // rounding put t at or past the running sum that should exceed it: the last topic
+        // of positive mass in the crossing stripe (or overall)
+        const int limit = in_row ? 16 * (cs + 1) : 16 * stripes;
+        int last = -1;
+        for (int c = 0; c < stripes; ++c) {
+          double yy[4];
+          chunk(row, c, yy);
+          const int kk = 16 * c + 4 * q;
+          if (kk < limit) {
+#pragma unroll
+            for (int ee = 0; ee < 4; ++ee)
+              if (th_q[16 * c + ee] * yy[ee] > 0.0) last = kk + ee;
+          }
+        }
+        last = max(last, __shfl_xor(last, 1, 64));
+        last = max(last, __shfl_xor(last, 2, 64));
+        k = last;
+      }
+    }
+    k = min(max(k, 0), K - 1);
+    if (valid && q == 0) {
+      z[i] = k;
+      if (zb != nullptr) zb[i] = (uint8_t)k;
+      if (kCountDocs) atomicAdd(&hist[k], 1);
+    }
+  }
+  if (kCountDocs) {
+    wave_lds_fence();
+    flush_doc_histogram(hist, n_dk + (size_t)d * ldk, ldk, is_split(seg_base, d), lane);
+  }
+}
+
 // --------------------------------------------------------------- count step
 // Counting phase (Sect. 4.2): n_dk[d][k] = tokens of document d with z = k;
 // n_wk[v][k] = tokens of word v with z = k.  No global atomics: both tables are
@@ -1233,15 +1372,17 @@ __global__ __launch_bounds__(256) void range_borders_kernel(
 // ------------------------------------------------------------ resample theta
 // theta_d ~ Dirichlet(alpha + n_dk[d][.]) for every document in parallel
 // (Sect. 4.3; App. B, Alg. 2): K Gamma draws in the log domain, normalised by
-// their sum (log-sum-exp in fp64), stored as fp32 floored at FLT_MIN.
+// their sum (log-sum-exp in fp64), stored as fp32 floored at FLT_MIN (fp64 state: as doubles
+// floored at DBL_MIN).
 //
 // One wave owns `rows` consecutive documents (rows * K variables, about 25 per
 // lane).  Rejection sampling diverges, so each lane walks its own variables:
 // every trip of the loop is one attempt on the lane's current variable, and an
 // accepted lane moves on without waiting for the others.  The draws wait in the
 // wave's LDS strip; then each row is normalised by the whole wave.
+template <typename T>
 __global__ __launch_bounds__(256) void lda_resample_theta_kernel(
-    const int32_t* __restrict__ n_dk, float* __restrict__ theta, int D, int K, int ldk, int rows,
+    const int32_t* __restrict__ n_dk, T* __restrict__ theta, int D, int K, int ldk, int rows,
     double alpha, const GammaShape* __restrict__ shapes, const double2* __restrict__ log_table,
     const double* __restrict__ exp_table, uint64_t seed, SweepRef sweep_ref,
     unsigned long long* __restrict__ n_capped) {
@@ -1300,8 +1441,8 @@ __global__ __launch_bounds__(256) void lda_resample_theta_kernel(
     const double inv = 1.0 / sum;
     for (int kk = lane; kk < K; kk += 64) {
       double p = row[kk] * inv;
-      p = p < (double)FLT_MIN ? (double)FLT_MIN : p;
-      theta[(size_t)(d0 + rr) * ldk + kk] = (float)p;
+      p = p < state_floor<T>() ? state_floor<T>() : p;
+      theta[(size_t)(d0 + rr) * ldk + kk] = (T)p;
     }
   }
   if (capped) atomicAdd(n_capped, 1ULL);
@@ -1408,17 +1549,18 @@ __global__ __launch_bounds__(1024) void lda_phi_norm_kernel(const double2* __res
   if (threadIdx.x == 0) logZ[k] = sm[0] + log(ss[0]);
 }
 
+template <typename T>
 __global__ __launch_bounds__(256) void lda_phi_write_kernel(const double* __restrict__ lg,
                                                              const double* __restrict__ logZ,
-                                                             float* __restrict__ phi, int V, int K,
+                                                             T* __restrict__ phi, int V, int K,
                                                              int ldk) {
   const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (e >= (int64_t)V * ldk) return;
   const int k = (int)(e % ldk);
   if (k >= K) return;
   double p = exp(lg[e] - logZ[k]);
-  p = p < (double)FLT_MIN ? (double)FLT_MIN : p;
-  phi[e] = (float)p;
+  p = p < state_floor<T>() ? state_floor<T>() : p;
+  phi[e] = (T)p;
 }
 
 // -------------------------------------------------------------------- loglik
@@ -1539,9 +1681,58 @@ __global__ __launch_bounds__(256) void lda_loglik_tokens_kernel(
   block_partial_sum(marg, part_marg, smem);
 }
 
+// The same per-token terms for the fp64 state: theta and phi are doubles, nothing is converted.
+__global__ __launch_bounds__(256) void lda_loglik_tokens_f64_kernel(
+    const int32_t* __restrict__ w, const int32_t* __restrict__ z,
+    const int64_t* __restrict__ doc_off, const int32_t* __restrict__ seg_base, int n_segs,
+    const double* __restrict__ theta, const double* __restrict__ phi, int D, int V, int K, int ldk,
+    const double2* __restrict__ log_table, double* __restrict__ part_lik,
+    double* __restrict__ part_marg) {
+  extern __shared__ __align__(16) double theta_lds[];  // [4][ldk16]
+  __shared__ double2 lt[kLogTableSize];
+  __shared__ double smem[8];
+  for (int i = threadIdx.x; i < kLogTableSize; i += blockDim.x) lt[i] = log_table[i];
+  __syncthreads();
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int tq = lane >> 2, q = lane & 3;
+  const int ldk16 = (ldk + 15) & ~15;
+  const int stripes = ldk16 >> 4;
+  double* th = theta_lds + (size_t)wave * ldk16;
+  double lik = 0.0, marg = 0.0;
+  for (int seg = blockIdx.x * 4 + wave; seg < n_segs; seg += gridDim.x * 4) {
+    const Segment sg = segment_of(doc_off, seg_base, D, seg);
+    wave_lds_fence();
+    for (int k = lane; k < ldk16; k += 64) th[k] = k < K ? theta[(size_t)sg.d * ldk + k] : 0.0;
+    wave_lds_fence();
+    const int64_t a = sg.first > sg.a ? sg.first : sg.a, b = sg.end;
+    for (int64_t i0 = a; i0 < b; i0 += 16) {
+      const int64_t i = i0 + tq;
+      const bool valid = i < b;
+      const int64_t ii = valid ? i : a;
+      const int wi = min(max(w[ii], 0), V - 1);
+      const int zi = min(max(z[ii], 0), K - 1);
+      const double* row = phi + (size_t)wi * ldk;
+      double s = 0.0;
+      for (int c = 0; c < stripes; ++c) {
+        const int col = 16 * c + 4 * q;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) s = fma(th[col + e], col + e < K ? row[col + e] : 0.0, s);
+      }
+      s = quad_sum_f64(s);
+      const double arg = q == 0 ? s : q == 1 ? th[zi] : q == 2 ? row[zi] : 1.0;
+      const double lg = log_any(arg, lt);
+      marg += valid && q == 0 ? lg : 0.0;
+      lik += valid && (q == 1 || q == 2) ? lg : 0.0;
+    }
+  }
+  block_partial_sum(lik, part_lik, smem);
+  block_partial_sum(marg, part_marg, smem);
+}
+
 // Sum of ln x over the K real columns of a [rows][ldk] matrix (ldk a multiple of 4: a
 // thread takes four entries of one row at a time).
-__global__ __launch_bounds__(256) void sum_log_kernel(const float* __restrict__ x, int64_t rows,
+template <typename T>
+__global__ __launch_bounds__(256) void sum_log_kernel(const T* __restrict__ x, int64_t rows,
                                                        int K, int ldk,
                                                        const double2* __restrict__ log_table,
                                                        double* __restrict__ part) {
@@ -1556,11 +1747,20 @@ __global__ __launch_bounds__(256) void sum_log_kernel(const float* __restrict__ 
        e += (int64_t)gridDim.x * blockDim.x) {
     const int64_t r = e / per_row;
     const int col = 4 * (int)(e - r * per_row);
-    const float4 v = *reinterpret_cast<const float4*>(x + r * ldk + col);
-    if (col + 0 < K) s += log_any((double)v.x, lt);
-    if (col + 1 < K) s += log_any((double)v.y, lt);
-    if (col + 2 < K) s += log_any((double)v.z, lt);
-    if (col + 3 < K) s += log_any((double)v.w, lt);
+    // rows are padded to a multiple of 16 entries: four at a time stay inside the row
+    T v[4];
+    if constexpr (sizeof(T) == sizeof(float)) {
+      const float4 f = *reinterpret_cast<const float4*>(x + r * ldk + col);
+      v[0] = f.x; v[1] = f.y; v[2] = f.z; v[3] = f.w;
+    } else {
+      const double2 lo = *reinterpret_cast<const double2*>(x + r * ldk + col);
+      const double2 hi = *reinterpret_cast<const double2*>(x + r * ldk + col + 2);
+      v[0] = lo.x; v[1] = lo.y; v[2] = hi.x; v[3] = hi.y;
+    }
+    if (col + 0 < K) s += log_any((double)v[0], lt);
+    if (col + 1 < K) s += log_any((double)v[1], lt);
+    if (col + 2 < K) s += log_any((double)v[2], lt);
+    if (col + 3 < K) s += log_any((double)v[3], lt);
   }
   block_partial_sum(s, part, smem);
 }
@@ -1711,6 +1911,8 @@ struct augur_lda {
   int num_cus = 0;
   size_t hot_lds_bytes = 0;       // dynamic LDS of a resident workgroup
   float *theta = nullptr, *phi = nullptr;
+  bool f64 = false;                          // fp64 state: theta64 and phi64 hold the state, theta and phi stay NULL
+  double *theta64 = nullptr, *phi64 = nullptr;
   double* lg = nullptr;          // [V][ldk] ln Gamma draws of the phi step
   double2* col_partial = nullptr;  // [phi row blocks][K]
   double* col_logZ = nullptr;    // [K]
@@ -1752,6 +1954,7 @@ void free_all(augur_lda* h) {
   (void)hipFree(h->shapes_alpha); (void)hipFree(h->shapes_beta); (void)hipFree(h->seg_base);
   (void)hipFree(h->log_table); (void)hipFree(h->exp_table);
   (void)hipFree(h->hot_words); (void)hipFree(h->wz); (void)hipFree(h->ord);
+  (void)hipFree(h->theta64); (void)hipFree(h->phi64);
   if (h->graph_exec) (void)hipGraphExecDestroy(h->graph_exec);
   if (h->graph) (void)hipGraphDestroy(h->graph);
   if (h->side) (void)hipStreamDestroy(h->side);
@@ -1776,6 +1979,25 @@ int launch_sample_z(augur_lda* h, SweepRef sweep, bool fuse_doc_counts = false,
   if (did_count) *did_count = false;
   if (D == 0 || h->N == 0) return AUGUR_OK;
   const dim3 grid((h->n_segs + 3) / 4), block(256);
+  if (h->f64) {
+    if (fuse_doc_counts) {
+      const int rc = zero_split_rows(h, h->stream);
+      if (rc != AUGUR_OK) return rc;
+    }
+    // per wave: theta_d as doubles, then the histogram
+    const size_t shm = (sizeof(double) + sizeof(int32_t)) * 4 * (size_t)h->ldk;
+    uint8_t* zb = h->ldk <= 256 ? h->zb : nullptr;
+#define AUGUR_ZD_ARGS                                                                             \
+  grid, block, shm, h->stream, h->w, h->doc_off, h->seg_base, h->n_segs, h->theta64, h->phi64, h->z, \
+      h->n_dk, D, h->cfg.K, h->ldk, h->cfg.seed, sweep, h->counters, zb
+    if (fuse_doc_counts) hipLaunchKernelGGL(lda_sample_z_f64_kernel<true>, AUGUR_ZD_ARGS);
+    else hipLaunchKernelGGL(lda_sample_z_f64_kernel<false>, AUGUR_ZD_ARGS);
+#undef AUGUR_ZD_ARGS
+    AUGUR_HIP_TRY(hipGetLastError());
+    if (did_count) *did_count = fuse_doc_counts;
+    h->zb_current = zb != nullptr;
+    return AUGUR_OK;
+  }
   if (fuse_doc_counts && h->ldk <= 256) {
     const int rc = zero_split_rows(h, h->stream);
     if (rc != AUGUR_OK) return rc;
@@ -2093,7 +2315,7 @@ const void* hot_kernel_ptr(int ns16, bool count_docs) {
 }
 int setup_resident_form(augur_lda* h) {
   h->n_hot = 0;
-  if (h->ldk > 256 || h->N == 0 || h->hot_host.empty()) return AUGUR_OK;
+  if (h->f64 || h->ldk > 256 || h->N == 0 || h->hot_host.empty()) return AUGUR_OK;
   int cus = 0;
   AUGUR_HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, h->cfg.device));
   h->num_cus = std::max(1, cus);
@@ -2144,10 +2366,16 @@ int launch_theta(augur_lda* h, SweepRef sweep) {
   const int D = h->cfg.D, K = h->cfg.K;
   const int rows = theta_rows_per_wave(K);
   const int waves = (D + rows - 1) / rows;
-  hipLaunchKernelGGL(lda_resample_theta_kernel, dim3((waves + 3) / 4), dim3(256),
-                     sizeof(double) * 4 * (size_t)rows * K, h->stream, h->n_dk, h->theta, D, K,
-                     h->ldk, rows, h->alpha, h->shapes_alpha, h->log_table, h->exp_table, h->cfg.seed,
-                     sweep, h->counters + 1);
+  if (h->f64)
+    hipLaunchKernelGGL(lda_resample_theta_kernel<double>, dim3((waves + 3) / 4), dim3(256),
+                       sizeof(double) * 4 * (size_t)rows * K, h->stream, h->n_dk, h->theta64, D, K,
+                       h->ldk, rows, h->alpha, h->shapes_alpha, h->log_table, h->exp_table,
+                       h->cfg.seed, sweep, h->counters + 1);
+  else
+    hipLaunchKernelGGL(lda_resample_theta_kernel<float>, dim3((waves + 3) / 4), dim3(256),
+                       sizeof(double) * 4 * (size_t)rows * K, h->stream, h->n_dk, h->theta, D, K,
+                       h->ldk, rows, h->alpha, h->shapes_alpha, h->log_table, h->exp_table,
+                       h->cfg.seed, sweep, h->counters + 1);
   AUGUR_HIP_TRY(hipGetLastError());
   return AUGUR_OK;
 }
@@ -2177,8 +2405,12 @@ int launch_phi(augur_lda* h, SweepRef sweep, hipStream_t stream) {
   hipLaunchKernelGGL(lda_phi_norm_kernel, dim3(K), dim3(1024), 0, stream, h->col_partial,
                      h->col_logZ, h->phi_blocks, K);
   const int64_t total = (int64_t)V * h->ldk;
-  hipLaunchKernelGGL(lda_phi_write_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0,
-                     stream, h->lg, h->col_logZ, h->phi, V, K, h->ldk);
+  if (h->f64)
+    hipLaunchKernelGGL(lda_phi_write_kernel<double>, dim3((unsigned)((total + 255) / 256)), dim3(256),
+                       0, stream, h->lg, h->col_logZ, h->phi64, V, K, h->ldk);
+  else
+    hipLaunchKernelGGL(lda_phi_write_kernel<float>, dim3((unsigned)((total + 255) / 256)), dim3(256),
+                       0, stream, h->lg, h->col_logZ, h->phi, V, K, h->ldk);
   AUGUR_HIP_TRY(hipGetLastError());
   return AUGUR_OK;
 }
@@ -2210,10 +2442,33 @@ int launch_loglik(hipStream_t stream, const int32_t* w, const int32_t* z, const 
   }
 #undef AUGUR_LL_CASE
 #undef AUGUR_LL_ARGS
-  hipLaunchKernelGGL(sum_log_kernel, dim3(kRedBlocks), dim3(256), 0, stream, theta, (int64_t)D, K,
-                     ldk, log_table, p_th);
-  hipLaunchKernelGGL(sum_log_kernel, dim3(kRedBlocks), dim3(256), 0, stream, phi, (int64_t)V, K, ldk,
-                     log_table, p_ph);
+  hipLaunchKernelGGL(sum_log_kernel<float>, dim3(kRedBlocks), dim3(256), 0, stream, theta, (int64_t)D,
+                     K, ldk, log_table, p_th);
+  hipLaunchKernelGGL(sum_log_kernel<float>, dim3(kRedBlocks), dim3(256), 0, stream, phi, (int64_t)V, K,
+                     ldk, log_table, p_ph);
+  const double c_theta = (double)D * (std::lgamma(K * alpha) - K * std::lgamma(alpha));
+  const double c_phi = (double)K * (std::lgamma(V * beta) - V * std::lgamma(beta));
+  hipLaunchKernelGGL(lda_loglik_finish_kernel, dim3(1), dim3(256), 0, stream, red, c_theta,
+                     alpha - 1.0, c_phi, beta - 1.0, out);
+  AUGUR_HIP_TRY(hipGetLastError());
+  return AUGUR_OK;
+}
+// The same for the fp64 state.
+int launch_loglik_f64(hipStream_t stream, const int32_t* w, const int32_t* z, const int64_t* doc_off,
+                      const int32_t* seg_base, int n_segs, const double* theta, const double* phi,
+                      int D, int V, int K, int ldk, double alpha, double beta,
+                      const double2* log_table, double* red, double* out) {
+  double* p_lik = red;
+  double* p_marg = red + kRedBlocks;
+  double* p_th = red + 2 * kRedBlocks;
+  double* p_ph = red + 3 * kRedBlocks;
+  hipLaunchKernelGGL(lda_loglik_tokens_f64_kernel, dim3(kRedBlocks), dim3(256),
+                     sizeof(double) * 4 * (size_t)ldk, stream, w, z, doc_off, seg_base, n_segs, theta,
+                     phi, D, V, K, ldk, log_table, p_lik, p_marg);
+  hipLaunchKernelGGL(sum_log_kernel<double>, dim3(kRedBlocks), dim3(256), 0, stream, theta, (int64_t)D,
+                     K, ldk, log_table, p_th);
+  hipLaunchKernelGGL(sum_log_kernel<double>, dim3(kRedBlocks), dim3(256), 0, stream, phi, (int64_t)V,
+                     K, ldk, log_table, p_ph);
   const double c_theta = (double)D * (std::lgamma(K * alpha) - K * std::lgamma(alpha));
   const double c_phi = (double)K * (std::lgamma(V * beta) - V * std::lgamma(beta));
   hipLaunchKernelGGL(lda_loglik_finish_kernel, dim3(1), dim3(256), 0, stream, red, c_theta,
@@ -2276,7 +2531,8 @@ int augur_lda_create(const augur_lda_config* cfg, const int32_t* doc_len, const 
   AUGUR_REQUIRE(std::isfinite(cfg->alpha) && cfg->alpha > 0.f && std::isfinite(cfg->beta) &&
                     cfg->beta > 0.f,
                 "alpha and beta must be positive and finite");
-  AUGUR_REQUIRE((cfg->flags & ~AUGUR_PTRS_DEVICE) == 0, "unknown flag bits 0x%x", cfg->flags);
+  AUGUR_REQUIRE((cfg->flags & ~(AUGUR_PTRS_DEVICE | AUGUR_STATE_F64)) == 0, "unknown flag bits 0x%x",
+                cfg->flags);
   AUGUR_REQUIRE(doc_len != nullptr, "doc_len is NULL");
   int ndev = 0;
   AUGUR_HIP_TRY(hipGetDeviceCount(&ndev));
@@ -2292,6 +2548,7 @@ int augur_lda_create(const augur_lda_config* cfg, const int32_t* doc_len, const 
   h->cfg = *cfg;
   h->stream = (hipStream_t)cfg->stream;
   h->use_graph = h->stream != nullptr;  // the default stream cannot be recorded
+  h->f64 = (cfg->flags & AUGUR_STATE_F64) != 0;
   h->alpha = (double)cfg->alpha;
   h->beta = (double)cfg->beta;
   h->ldk = row_stride(K);
@@ -2388,9 +2645,14 @@ int augur_lda_create(const augur_lda_config* cfg, const int32_t* doc_len, const 
   }
 
   const size_t dk = (size_t)D * h->ldk, vk = (size_t)V * h->ldk;
-  AUGUR_CREATE_TRY(hipMalloc(&h->theta, sizeof(float) * dk));
+  if (h->f64) {
+    AUGUR_CREATE_TRY(hipMalloc(&h->theta64, sizeof(double) * dk));
+    AUGUR_CREATE_TRY(hipMalloc(&h->phi64, sizeof(double) * vk));
+  } else {
+    AUGUR_CREATE_TRY(hipMalloc(&h->theta, sizeof(float) * dk));
+    AUGUR_CREATE_TRY(hipMalloc(&h->phi, sizeof(float) * vk));
+  }
   AUGUR_CREATE_TRY(hipMalloc(&h->n_dk, sizeof(int32_t) * dk));
-  AUGUR_CREATE_TRY(hipMalloc(&h->phi, sizeof(float) * vk));
   AUGUR_CREATE_TRY(hipMalloc(&h->n_wk, sizeof(int32_t) * vk));
   AUGUR_CREATE_TRY(hipMalloc(&h->lg, sizeof(double) * vk));
   AUGUR_CREATE_TRY(hipMalloc(&h->col_partial, sizeof(double2) * (size_t)h->phi_blocks * K));
@@ -2413,8 +2675,13 @@ int augur_lda_create(const augur_lda_config* cfg, const int32_t* doc_len, const 
   hipLaunchKernelGGL(shape_table_kernel, dim3(kShapeTable / 256), dim3(256), 0, h->stream,
                      h->shapes_beta, h->beta);
   AUGUR_CREATE_TRY(hipGetLastError());
-  AUGUR_CREATE_TRY(hipMemsetAsync(h->theta, 0, sizeof(float) * dk, h->stream));
-  AUGUR_CREATE_TRY(hipMemsetAsync(h->phi, 0, sizeof(float) * vk, h->stream));
+  if (h->f64) {
+    AUGUR_CREATE_TRY(hipMemsetAsync(h->theta64, 0, sizeof(double) * dk, h->stream));
+    AUGUR_CREATE_TRY(hipMemsetAsync(h->phi64, 0, sizeof(double) * vk, h->stream));
+  } else {
+    AUGUR_CREATE_TRY(hipMemsetAsync(h->theta, 0, sizeof(float) * dk, h->stream));
+    AUGUR_CREATE_TRY(hipMemsetAsync(h->phi, 0, sizeof(float) * vk, h->stream));
+  }
   AUGUR_CREATE_TRY(hipMemsetAsync(h->n_dk, 0, sizeof(int32_t) * dk, h->stream));
 
   {
@@ -2719,6 +2986,10 @@ int augur_lda_probe_gather(augur_lda* h, int32_t reps, double* ms_per_pass) {
   AUGUR_REQUIRE(reps > 0 && reps <= 4096 && ms_per_pass != nullptr,
                 "reps must lie in [1, 4096] and ms_per_pass must not be NULL");
   *ms_per_pass = 0.0;
+  if (h->f64) {
+    set_error("the gather probe covers the fp32 state only");
+    return AUGUR_ERR_UNIMPLEMENTED;
+  }
   if (h->N == 0) return AUGUR_OK;
   const dim3 grid((h->n_segs + 3) / 4), block(256);
   auto launch = [&]() -> int {
@@ -2769,9 +3040,14 @@ int augur_lda_probe_gather(augur_lda* h, int32_t reps, double* ms_per_pass) {
 int augur_lda_loglik(augur_lda* h, double* log_joint, double* log_marginal_w) {
   AUGUR_CHECK_HANDLE(h);
   double* out = h->red + 4 * kRedBlocks;
-  AUGUR_TRY(launch_loglik(h->stream, h->w, h->z, h->doc_off, h->seg_base, h->n_segs, h->theta, h->phi,
-                          h->cfg.D, h->cfg.V, h->cfg.K, h->ldk, h->alpha, h->beta, h->log_table,
-                          h->red, out));
+  if (h->f64)
+    AUGUR_TRY(launch_loglik_f64(h->stream, h->w, h->z, h->doc_off, h->seg_base, h->n_segs, h->theta64,
+                                h->phi64, h->cfg.D, h->cfg.V, h->cfg.K, h->ldk, h->alpha, h->beta,
+                                h->log_table, h->red, out));
+  else
+    AUGUR_TRY(launch_loglik(h->stream, h->w, h->z, h->doc_off, h->seg_base, h->n_segs, h->theta,
+                            h->phi, h->cfg.D, h->cfg.V, h->cfg.K, h->ldk, h->alpha, h->beta,
+                            h->log_table, h->red, out));
   double host[2] = {0.0, 0.0};
   AUGUR_HIP_TRY(hipMemcpyAsync(host, out, sizeof(host), hipMemcpyDeviceToHost, h->stream));
   AUGUR_HIP_TRY(hipStreamSynchronize(h->stream));
@@ -2788,22 +3064,24 @@ int augur_lda_loglik(augur_lda* h, double* log_joint, double* log_marginal_w) {
   return AUGUR_OK;
 }
 
-int augur_lda_get_state(augur_lda* h, int32_t* z, float* theta, float* phi, int64_t* sweep) {
-  AUGUR_CHECK_HANDLE(h);
+// theta and phi in the handle's own type (elem = its size in bytes).
+static int get_state_impl(augur_lda* h, int32_t* z, void* theta, void* phi, int64_t* sweep,
+                          size_t elem) {
   if (z && h->N > 0)
     AUGUR_HIP_TRY(hipMemcpyAsync(z, h->z, sizeof(int32_t) * (size_t)h->N,
                                  device_ptrs(h) ? hipMemcpyDeviceToDevice : hipMemcpyDeviceToHost,
                                  h->stream));
-  if (theta) AUGUR_TRY(copy_out(h, theta, h->theta, sizeof(float), h->cfg.D));
-  if (phi) AUGUR_TRY(copy_out(h, phi, h->phi, sizeof(float), h->cfg.V));
+  const void* th = h->f64 ? (const void*)h->theta64 : (const void*)h->theta;
+  const void* ph = h->f64 ? (const void*)h->phi64 : (const void*)h->phi;
+  if (theta) AUGUR_TRY(copy_out(h, theta, th, elem, h->cfg.D));
+  if (phi) AUGUR_TRY(copy_out(h, phi, ph, elem, h->cfg.V));
   AUGUR_HIP_TRY(hipStreamSynchronize(h->stream));
   if (sweep) *sweep = h->sweep;
   return AUGUR_OK;
 }
 
-int augur_lda_set_state(augur_lda* h, const int32_t* z, const float* theta, const float* phi,
-                        int64_t sweep) {
-  AUGUR_CHECK_HANDLE(h);
+static int set_state_impl(augur_lda* h, const int32_t* z, const void* theta, const void* phi,
+                          int64_t sweep, size_t elem) {
   if (z && h->N > 0) {
     if (!device_ptrs(h)) {
       for (int64_t i = 0; i < h->N; ++i)
@@ -2823,11 +3101,41 @@ int augur_lda_set_state(augur_lda* h, const int32_t* z, const float* theta, cons
     h->zb_current = false;  // the word table reads z itself until the next z step
     AUGUR_TRY(launch_count(h));
   }
-  if (theta) AUGUR_TRY(copy_in(h, h->theta, theta, sizeof(float), h->cfg.D));
-  if (phi) AUGUR_TRY(copy_in(h, h->phi, phi, sizeof(float), h->cfg.V));
+  void* th = h->f64 ? (void*)h->theta64 : (void*)h->theta;
+  void* ph = h->f64 ? (void*)h->phi64 : (void*)h->phi;
+  if (theta) AUGUR_TRY(copy_in(h, th, theta, elem, h->cfg.D));
+  if (phi) AUGUR_TRY(copy_in(h, ph, phi, elem, h->cfg.V));
   AUGUR_HIP_TRY(hipStreamSynchronize(h->stream));
   if (sweep >= 0) h->sweep = sweep;
   return AUGUR_OK;
+}
+
+int augur_lda_get_state(augur_lda* h, int32_t* z, float* theta, float* phi, int64_t* sweep) {
+  AUGUR_CHECK_HANDLE(h);
+  AUGUR_REQUIRE(!h->f64 || (theta == nullptr && phi == nullptr),
+                "this handle keeps theta and phi as fp64: use augur_lda_get_state_f64");
+  return get_state_impl(h, z, theta, phi, sweep, sizeof(float));
+}
+int augur_lda_get_state_f64(augur_lda* h, int32_t* z, double* theta, double* phi, int64_t* sweep) {
+  AUGUR_CHECK_HANDLE(h);
+  AUGUR_REQUIRE(h->f64 || (theta == nullptr && phi == nullptr),
+                "this handle keeps theta and phi as fp32: use augur_lda_get_state");
+  return get_state_impl(h, z, theta, phi, sweep, sizeof(double));
+}
+
+int augur_lda_set_state(augur_lda* h, const int32_t* z, const float* theta, const float* phi,
+                        int64_t sweep) {
+  AUGUR_CHECK_HANDLE(h);
+  AUGUR_REQUIRE(!h->f64 || (theta == nullptr && phi == nullptr),
+                "this handle keeps theta and phi as fp64: use augur_lda_set_state_f64");
+  return set_state_impl(h, z, theta, phi, sweep, sizeof(float));
+}
+int augur_lda_set_state_f64(augur_lda* h, const int32_t* z, const double* theta, const double* phi,
+                            int64_t sweep) {
+  AUGUR_CHECK_HANDLE(h);
+  AUGUR_REQUIRE(h->f64 || (theta == nullptr && phi == nullptr),
+                "this handle keeps theta and phi as fp32: use augur_lda_set_state");
+  return set_state_impl(h, z, theta, phi, sweep, sizeof(double));
 }
 
 int augur_lda_get_counts(augur_lda* h, int32_t* n_dk, int32_t* n_wk) {

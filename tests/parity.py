@@ -10,6 +10,11 @@ FLT_MIN = float(np.finfo(np.float32).tiny)
 Z_AGREE = 0.9999
 Z_BOUNDARY_RTOL = 1e-6
 REAL_RTOL = 1e-5
+# fp64 state: the two sides differ by the order of fp64 sums (z) and by the last bits of their
+# exp and log routines, amplified by the size of the exponent (theta, phi)
+DBL_MIN = float(np.finfo(np.float64).tiny)
+Z_BOUNDARY_RTOL_F64 = 1e-12
+REAL_RTOL_F64 = 1e-10
 
 # Topic counts of the parity tests, chosen to reach every instance of the two z kernels: the
 # quad kernel is compiled once per number of 16-topic stripes of the padded row (1..16, K up to
@@ -37,8 +42,10 @@ def assert_real_close(got, want, what, rtol=REAL_RTOL, floor=FLT_MIN):
     assert bad[0].size == 0, (what, bad[0].size, "worst rel", float((err / np.maximum(np.abs(want), floor)).max()))
 
 
-def assert_z_lda(z_gpu, z_orc, doc_off, w, theta, phi, seed, sweep):
-    """theta [D][K], phi [V][K]: the shared state both sides drew from."""
+def assert_z_lda(z_gpu, z_orc, doc_off, w, theta, phi, seed, sweep, f64=False,
+                 boundary_rtol=Z_BOUNDARY_RTOL):
+    """theta [D][K], phi [V][K]: the shared state both sides drew from (f64: held as doubles,
+    the running sums taken in fp64)."""
     z_gpu, z_orc = np.asarray(z_gpu), np.asarray(z_orc)
     N = z_orc.size
     K = theta.shape[1]
@@ -50,10 +57,10 @@ def assert_z_lda(z_gpu, z_orc, doc_off, w, theta, phi, seed, sweep):
     assert mism.size <= 1000, f"{mism.size} of {N} z differ"     # not rounding: do not walk them
     doc_of = np.searchsorted(doc_off, mism, side="right") - 1
     for i, d in zip(mism, doc_of):
-        cdf, t = O.lda_token_cdf(theta[d], phi[w[i]], seed, int(i), sweep)
+        cdf, t = O.lda_token_cdf(theta[d], phi[w[i]], seed, int(i), sweep, f64=f64)
         # the mass of the GPU's topic is its own product (a running sum in fp64 may absorb it)
         mass = float(theta[d, z_gpu[i]]) * float(phi[w[i], z_gpu[i]])
-        _assert_boundary(cdf, t, int(z_gpu[i]), int(z_orc[i]), f"token {i}", mass)
+        _assert_boundary(cdf, t, int(z_gpu[i]), int(z_orc[i]), f"token {i}", mass, boundary_rtol)
     _assert_agreement(mism.size, N)
     return mism.size
 
@@ -92,10 +99,10 @@ def assert_z_gmmuv(z_gpu, z_orc, x, pi, mu, var, seed, sweep):
     return mism.size
 
 
-def _assert_boundary(cdf, t, zg, zo, what, mass=None):
+def _assert_boundary(cdf, t, zg, zo, what, mass=None, rtol=Z_BOUNDARY_RTOL):
     lo, hi = min(zg, zo), max(zg, zo)
     between = cdf[lo:hi]                       # boundaries C_lo .. C_{hi-1} separate the answers
-    assert (np.abs(t - between) <= Z_BOUNDARY_RTOL * between).all(), (what, zg, zo, t, between)
+    assert (np.abs(t - between) <= rtol * between).all(), (what, zg, zo, t, between)
     if mass is None:
         mass = cdf[zg] - (cdf[zg - 1] if zg > 0 else 0.0)
     assert mass > 0.0, (what, "GPU chose a topic of zero mass", zg)
