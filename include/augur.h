@@ -47,8 +47,9 @@ extern "C" {
  * own experiments ran in, Sect. 5) instead of fp32.  The draws (Philox stream, Gamma variates,
  * normalisation in fp64) are the same; what changes is the rounding of the stored
  * probabilities (floored at DBL_MIN instead of FLT_MIN) and of the z step's products and
- * running sums.  The z step of such a handle is a plain kernel written for checking, several
- * times slower than the fp32 one; theta, phi, the counts and the log densities cost the same. */
+ * running sums.  The z step of such a handle is a plain kernel written for checking, about
+ * three times slower than the fp32 one (it moves twice the bytes); theta, phi, the counts and
+ * the log densities cost the same.  augur_lda_probe_gather is not available on such a handle. */
 #define AUGUR_STATE_F64 2u
 
 const char* augur_last_error(void); /* thread-local; valid until the next call on this thread */

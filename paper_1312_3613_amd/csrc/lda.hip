@@ -1081,12 +1081,18 @@ __global__ __launch_bounds__(256) void lda_gather_probe_row_kernel(
 // The same draw with theta and phi stored as doubles (the precision the paper's experiments
 // ran in): every product and sum in fp64, so the result differs from a sum in index order by
 // fp64 rounding only.  Written for any K up to 1024 and for checking rather than for speed:
-// a quad per token, theta_d as doubles in LDS, three walks over the row (the total; the
-// crossing stripe; the topic inside it), the row re-read from cache each time.
+// a quad per token, theta_d as doubles in LDS; one walk over the row leaves the running sum at
+// the end of every 16-topic stripe in LDS, the crossing stripe is found there, and that one
+// stripe is read again for the topic inside it.
 __device__ __forceinline__ double quad_sum_f64(double s) {
   s += __shfl_xor(s, 1, 64);
   s += __shfl_xor(s, 2, 64);
   return s;
+}
+// Dynamic LDS of a workgroup (four waves): per wave theta_d [ldk] doubles and the stripe ends
+// [ldk / 16][16 tokens] doubles, then per wave the histogram [ldk] ints.
+__host__ __device__ constexpr size_t z_f64_lds_bytes(int ldk) {
+  return 4 * ((size_t)ldk * (2 * sizeof(double) + sizeof(int32_t)));
 }
 template <bool kCountDocs>
 __global__ __launch_bounds__(256) void lda_sample_z_f64_kernel(
@@ -1095,7 +1101,7 @@ __global__ __launch_bounds__(256) void lda_sample_z_f64_kernel(
     const double* __restrict__ phi, int32_t* __restrict__ z, int32_t* __restrict__ n_dk, int D, int K,
     int ldk, uint64_t seed, SweepRef sweep_ref, unsigned long long* __restrict__ n_degenerate,
     uint8_t* __restrict__ zb) {
-  extern __shared__ __align__(16) double lds_f64[];  // per wave: theta_d [ldk16], then the histogram [ldk16] ints
+  extern __shared__ __align__(16) double lds_f64[];
   const uint32_t sweep = sweep_ref.get();
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int seg = blockIdx.x * 4 + wave;
@@ -1103,22 +1109,25 @@ __global__ __launch_bounds__(256) void lda_sample_z_f64_kernel(
   const Segment sg = segment_of(doc_off, seg_base, D, seg);
   const int d = sg.d;
   const int tq = lane >> 2, q = lane & 3;
-  const int ldk16 = (ldk + 15) & ~15;
-  const int stripes = ldk16 >> 4;
-  double* th = lds_f64 + (size_t)wave * ldk16;
-  int32_t* hist = reinterpret_cast<int32_t*>(lds_f64 + (size_t)4 * ldk16) + (size_t)wave * ldk16;
-  for (int k = lane; k < ldk16; k += 64) {
+  const int stripes = ldk >> 4;  // rows are padded to whole stripes
+  double* th = lds_f64 + (size_t)wave * 2 * ldk;
+  double* ends = th + ldk;  // [stripes][16]: running sum at the end of stripe c for token slot tq
+  int32_t* hist = reinterpret_cast<int32_t*>(lds_f64 + (size_t)8 * ldk) + (size_t)wave * ldk;
+  for (int k = lane; k < ldk; k += 64) {
     th[k] = k < K ? theta[(size_t)d * ldk + k] : 0.0;
     if (kCountDocs) hist[k] = 0;
   }
   wave_lds_fence();
   const double* th_q = th + 4 * q;
   // the lane's four entries of stripe c of row `row`; entries at or past column K count as zero
-  // (and are not read past the row's end)
   auto chunk = [&](const double* row, int c, double (&y)[4]) {
     const int col = 16 * c + 4 * q;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) y[e] = col + e < K ? row[col + e] : 0.0;
+    const double2 lo = *reinterpret_cast<const double2*>(row + col);
+    const double2 hi = *reinterpret_cast<const double2*>(row + col + 2);
+    y[0] = col + 0 < K ? lo.x : 0.0;
+    y[1] = col + 1 < K ? lo.y : 0.0;
+    y[2] = col + 2 < K ? hi.x : 0.0;
+    y[3] = col + 3 < K ? hi.y : 0.0;
   };
   const int64_t a = sg.first > sg.a ? sg.first : sg.a, b = sg.end;
   for (int64_t i0 = a; i0 < b; i0 += 16) {
@@ -1127,31 +1136,28 @@ __global__ __launch_bounds__(256) void lda_sample_z_f64_kernel(
     const int64_t ii = valid ? i : a;
     const double* row = phi + (size_t)w[ii] * ldk;
     const uint32_t r = word_of(random_block(seed, (uint64_t)(ii >> 2), sweep, kStreamZ, 0), (uint32_t)(ii & 3));
-    // walk 1: the total
+    // the walk: the lane's own running sum, the quad's sum of them at every stripe end
     double acc = 0.0;
+    wave_lds_fence();  // the previous tokens' stripe ends have been read
     for (int c = 0; c < stripes; ++c) {
       double y[4];
       chunk(row, c, y);
 #pragma unroll
       for (int e = 0; e < 4; ++e) acc = fma(th_q[16 * c + e], y[e], acc);
+      const double cum = quad_sum_f64(acc);
+      if (q == 0) ends[16 * c + tq] = cum;
     }
     const double S = quad_sum_f64(acc);
     const double t = (double)u24(r) * S;
-    // walk 2: the crossing stripe among all but the last, and the running sum before it
+    wave_lds_fence();
+    // the crossing stripe among all but the last: the stripe ends do not decrease, so it is the
+    // number of ends at or below t, and the running sum before it the last of those
     int cs = 0;
-    double cprev = 0.0;
-    acc = 0.0;
-    for (int c = 0; c < stripes - 1; ++c) {
-      double y[4];
-      chunk(row, c, y);
-#pragma unroll
-      for (int e = 0; e < 4; ++e) acc = fma(th_q[16 * c + e], y[e], acc);
-      const double cum = quad_sum_f64(acc);
-      const bool below = cum <= t;
-      cs += below ? 1 : 0;
-      cprev = below ? cum : cprev;
-    }
-    // walk 3: the topic inside stripe cs
+    for (int c = q; c < stripes - 1; c += 4) cs += ends[16 * c + tq] <= t ? 1 : 0;
+    cs += __shfl_xor(cs, 1, 64);
+    cs += __shfl_xor(cs, 2, 64);
+    const double cprev = cs > 0 ? ends[16 * (cs - 1) + tq] : 0.0;
+    // the topic inside stripe cs
     double y[4];
     chunk(row, cs, y);
     const double* t2 = th_q + 16 * cs;
@@ -1984,8 +1990,7 @@ int launch_sample_z(augur_lda* h, SweepRef sweep, bool fuse_doc_counts = false,
       const int rc = zero_split_rows(h, h->stream);
       if (rc != AUGUR_OK) return rc;
     }
-    // per wave: theta_d as doubles, then the histogram
-    const size_t shm = (sizeof(double) + sizeof(int32_t)) * 4 * (size_t)h->ldk;
+    const size_t shm = z_f64_lds_bytes(h->ldk);
     uint8_t* zb = h->ldk <= 256 ? h->zb : nullptr;
 #define AUGUR_ZD_ARGS                                                                             \
   grid, block, shm, h->stream, h->w, h->doc_off, h->seg_base, h->n_segs, h->theta64, h->phi64, h->z, \
@@ -2326,8 +2331,10 @@ int setup_resident_form(augur_lda* h) {
   if (rows < 8) return AUGUR_OK;
   h->hot_lds_bytes = (size_t)rows * row_lds + (size_t)waves_bytes;
   for (int cd = 0; cd < 2; ++cd)
+    // the limit belongs to the kernel, not to the handle: always the whole budget, so that a
+    // handle with fewer cached rows does not lower it under another handle's launches
     AUGUR_HIP_TRY(hipFuncSetAttribute(hot_kernel_ptr(ns16, cd != 0), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                      (int)h->hot_lds_bytes));
+                                      kHotLdsBudget));
   const int V = h->cfg.V;
   std::vector<uint8_t> slot_of;
   try {
@@ -2357,10 +2364,12 @@ int setup_resident_form(augur_lda* h) {
   return AUGUR_OK;
 }
 
-// Documents per wave in the theta step: about 1000 variables per wave (16 per
-// lane keeps the lanes' retry loops balanced) and the four waves' LDS strips
-// (rows * K doubles each) at 32 KiB, so several workgroups share a CU.
-int theta_rows_per_wave(int K) { return std::max(1, std::min(16, 1024 / K)); }
+// Documents per wave in the theta step: about 600 variables per wave, ten per lane (fewer
+// leave the lanes' retry loops unbalanced, more leave a corpus of 20,000 documents with too few
+// waves to fill the chip: 3M tokens at K = 100, 0.049 ms at 1000 variables per wave, 0.041 at
+// 300 to 600; 300,000 documents at K = 200: 0.71 ms at 1000, 0.66 at 600, 0.84 at 200), and
+// the four waves' LDS strips (rows * K doubles each) small enough for several workgroups per CU.
+int theta_rows_per_wave(int K) { return std::max(1, std::min(16, 640 / K)); }
 
 int launch_theta(augur_lda* h, SweepRef sweep) {
   const int D = h->cfg.D, K = h->cfg.K;
@@ -2728,6 +2737,16 @@ int augur_lda_create(const augur_lda_config* cfg, const int32_t* doc_len, const 
       delete h;
       return rc_hot;
     }
+  }
+
+  if (h->f64) {
+    // up to 80 KiB of LDS per workgroup at 1024 topics: above the 64 KiB a kernel gets unasked
+    // (the limit belongs to the kernel, not to the handle: always the most any handle needs)
+    const int lds = (int)z_f64_lds_bytes(1024);
+    AUGUR_CREATE_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&lda_sample_z_f64_kernel<true>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+    AUGUR_CREATE_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&lda_sample_z_f64_kernel<false>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, lds));
   }
 
   // initial state (sweep index 0)
