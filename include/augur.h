@@ -125,6 +125,17 @@ int augur_lda_set_graph(augur_lda* h, int32_t on);
  * 2: never.  Not to be changed while a sweep is in flight. */
 int augur_lda_set_z_cache(augur_lda* h, int32_t mode);
 
+/* Which kernels build the word table n_wk during sweeps and count steps (count_accumulate,
+ * Sect. 4.2; both give the same table).  The gathering kernel reads z through the word-major
+ * permutation; the staged form (up to 256 topics, after a z step) moves the one-byte copy of z
+ * into word-major order in two passes through LDS that read and write whole cache lines, which
+ * pays when the copy is larger than the caches and the word table has the chip to itself (beside
+ * the theta step of an overlapped sweep the gathering kernel hides better).  mode 0 (default):
+ * the library chooses (staged from 16M tokens on, when nothing runs beside it); 1: the staged
+ * form whenever it is available; 2: never.  Not to be changed
+ * while a sweep is in flight. */
+int augur_lda_set_word_table(augur_lda* h, int32_t mode);
+
 /* Same as sweep, but records events on the handle's stream around the steps and
  * returns the summed device time over the n_sweeps, in ms: ms[0] sample_z;
  * ms[1] count_accumulate (with overlap on: the document table only; the word

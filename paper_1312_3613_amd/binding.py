@@ -255,6 +255,9 @@ class LDA:
     def set_z_cache(self, mode):
         _check(lib().augur_lda_set_z_cache(self._h, int(mode)))
 
+    def set_word_table(self, mode):
+        _check(lib().augur_lda_set_word_table(self._h, int(mode)))
+
     def set_graph(self, on):
         _check(lib().augur_lda_set_graph(self._h, 1 if on else 0))
 

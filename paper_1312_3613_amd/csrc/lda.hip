@@ -1330,6 +1330,213 @@ __global__ __launch_bounds__(256) void lda_count_words_prepare_kernel(
   n_wk[(size_t)multi_words[m] * ldk + k] = 0;
 }
 
+// ---- word table, staged form (large corpora, K <= 256) ----
+// The gathers of the kernel above pull a 128-byte line for a byte of z whenever a word's
+// tokens lie far apart, which is the rule for all but the most frequent words (75M tokens:
+// 4.3 GB moved for 0.46 GB needed).  Here the bytes of z are instead *permuted* into
+// word-major order in two passes that read and write whole lines, through LDS; the
+// permutation is a property of the corpus and is planned once (build_staged_word_table):
+//   pass 1: a workgroup takes a tile of 65536 consecutive positions of zb into LDS and writes
+//           them out sorted by destination (the token's index in word-major order).  The
+//           destinations 0..N are cut into buckets of 49152; the tile's tokens of bucket b
+//           form one run, written to the bucket's part of the intermediate array, behind the
+//           runs of the earlier tiles.  (src: the local position of every output slot;
+//           ostart / istart: where a tile's run for bucket b starts among its slots / in the
+//           intermediate array.)
+//   pass 2: a workgroup takes a bucket of the intermediate array (whole lines again) and
+//           scatters it inside LDS to word-major order (dst: the local destination of every
+//           entry); each wave then owns a chunk of 3072 destinations, walks the words in it
+//           and turns each piece into a row with an LDS histogram.  A word that lies inside
+//           one chunk has its row stored; a word cut by a chunk border is listed in
+//           multi_words (rows zeroed first) and its pieces add their non-zero bins.
+constexpr int kWtTile = 65536;                   // positions per tile: a local index fits 16 bits
+constexpr int kWtChunk = 3072;                   // destinations per wave of pass 2
+constexpr int kWtWaves = 16;
+constexpr int kWtBucket = kWtWaves * kWtChunk;   // destinations per workgroup of pass 2
+constexpr int kWtMaxBuckets = 8000;              // pass 1 keeps two words per bucket in LDS
+__global__ __launch_bounds__(1024) void lda_wt_pass1_kernel(
+    const uint8_t* __restrict__ zb, const uint16_t* __restrict__ src, const uint32_t* __restrict__ ostart,
+    const uint32_t* __restrict__ istart, uint8_t* __restrict__ inter, int64_t N, int nb) {
+  extern __shared__ __align__(16) unsigned char wt_lds[];  // the tile, then ostart[nb + 1], then istart - ostart [nb]
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  // Workgroups go to the 8 XCDs in turn.  An XCD takes a run of consecutive tiles: their runs
+  // for a bucket lie one behind the other in the intermediate array, and meet in that XCD's L2
+  // as whole lines before they are written back.  (The grid is a multiple of 8.)
+  const int t = (int)(blockIdx.x % 8u) * (int)(gridDim.x / 8u) + (int)(blockIdx.x / 8u);
+  const int64_t base = (int64_t)t * kWtTile;
+  if (base >= N) return;
+  const int n = (int)(N - base < kWtTile ? N - base : kWtTile);
+  uint32_t* os = reinterpret_cast<uint32_t*>(wt_lds + kWtTile);
+  uint32_t* adj = os + (nb + 1);
+  for (int e = threadIdx.x * 16; e < n; e += 1024 * 16)  // (zb is padded: the last piece may pass N)
+    *reinterpret_cast<uint4*>(wt_lds + e) = *reinterpret_cast<const uint4*>(zb + base + e);
+  for (int b = threadIdx.x; b <= nb; b += 1024) os[b] = ostart[(size_t)t * (nb + 1) + b];
+  for (int b = threadIdx.x; b < nb; b += 1024)
+    adj[b] = istart[(size_t)t * nb + b] - ostart[(size_t)t * (nb + 1) + b];
+  __syncthreads();
+  // a wave takes a run of consecutive slots; a slot's bucket is found by walking on from the
+  // bucket of the slot before (the slots are sorted by bucket)
+  const int per = ((n + kWtWaves - 1) / kWtWaves + 63) & ~63;
+  const int s0 = wave * per, s1 = min(n, s0 + per);
+  if (s0 >= s1) return;
+  int b_cur = 0;  // the bucket of slot s0: os[b_cur] <= s0 < os[b_cur + 1]
+  {
+    int lo = 0, hi = nb;  // largest b with os[b] <= s0
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (os[mid] <= (uint32_t)s0) lo = mid; else hi = mid;
+    }
+    b_cur = lo;
+  }
+  constexpr int kDeep = 16;  // slots per lane and round: the loads of all of them are in flight together
+  for (int o0 = s0; o0 < s1; o0 += 64 * kDeep) {
+    uint32_t p[kDeep];
+#pragma unroll
+    for (int e = 0; e < kDeep; ++e) {
+      const int o = o0 + 64 * e + lane;
+      p[e] = o < s1 ? (uint32_t)src[base + o] : 0u;
+    }
+    int b = b_cur;
+#pragma unroll
+    for (int e = 0; e < kDeep; ++e) {
+      const int o = o0 + 64 * e + lane;
+      if (o < s1) {
+        while (os[b + 1] <= (uint32_t)o) ++b;  // ends: os[nb] = n > o
+        inter[adj[b] + (uint32_t)o] = wt_lds[p[e]];
+      }
+    }
+    // the bucket of the next round's first slot (the same for every lane)
+    const int o_next = o0 + 64 * kDeep;
+    if (o_next < s1)
+      while (os[b_cur + 1] <= (uint32_t)o_next) ++b_cur;
+  }
+}
+
+__global__ __launch_bounds__(1024) void lda_wt_pass2_kernel(
+    const uint8_t* __restrict__ inter, const uint16_t* __restrict__ dst,
+    const int32_t* __restrict__ word_off, const int32_t* __restrict__ chunk_word,
+    int32_t* __restrict__ n_wk, int ldk, int V, int64_t N) {
+  extern __shared__ __align__(16) unsigned char wt_lds[];  // the bucket in word-major order, then 16 histograms [ldk]
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t base = (int64_t)blockIdx.x * kWtBucket;
+  const int n = (int)(N - base < kWtBucket ? N - base : kWtBucket);
+  for (int e = threadIdx.x * 16; e < n; e += 1024 * 16) {  // (both arrays are padded past N)
+    const uint4 v = *reinterpret_cast<const uint4*>(inter + base + e);
+    const uint4 d0 = *reinterpret_cast<const uint4*>(dst + base + e);
+    const uint4 d1 = *reinterpret_cast<const uint4*>(dst + base + e + 8);
+    const uint32_t vb[4] = {v.x, v.y, v.z, v.w};
+    const uint32_t db[8] = {d0.x, d0.y, d0.z, d0.w, d1.x, d1.y, d1.z, d1.w};
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+      if (e + i < n)
+        wt_lds[(db[i >> 1] >> (16 * (i & 1))) & 0xFFFFu] = (unsigned char)(vb[i >> 2] >> (8 * (i & 3)));
+  }
+  __syncthreads();
+  const int c0 = wave * kWtChunk;
+  if (c0 >= n) return;
+  const int c1 = min(n, c0 + kWtChunk);
+  const int64_t g0 = base + c0, g1 = base + c1;  // the chunk's destinations
+  int32_t* hist = reinterpret_cast<int32_t*>(wt_lds + kWtBucket) + (size_t)wave * ldk;
+  for (int k = lane; k < ldk; k += 64) hist[k] = 0;
+  wave_lds_fence();
+  int v = chunk_word[blockIdx.x * kWtWaves + wave];  // the word that destination g0 belongs to
+  for (bool done = false; !done;) {
+    // the offsets of the next 64 words, then up to 63 words from them
+    const int64_t off_l = (int64_t)word_off[min(v + lane, V)];
+    for (int idx = 0; idx < 63 && !done; ++idx) {
+      const int64_t ws = __shfl(off_l, idx, 64), we = __shfl(off_l, idx + 1, 64);
+      if (v + idx >= V || ws >= g1) { done = true; break; }
+      const int64_t ps = ws > g0 ? ws : g0, pe = we < g1 ? we : g1;
+      if (pe > ps) {
+        const int a = (int)(ps - base), b = (int)(pe - base);
+        for (int o = a + lane; o < b; o += 64) atomicAdd(&hist[wt_lds[o]], 1);
+        wave_lds_fence();
+        int32_t* row = n_wk + (size_t)(v + idx) * ldk;
+        const bool whole = ws >= g0 && we <= g1;
+        for (int k = lane; k < ldk; k += 64) {
+          const int32_t c = hist[k];
+          hist[k] = 0;
+          if (whole) row[k] = c;
+          else if (c != 0) atomicAdd(&row[k], c);
+        }
+        wave_lds_fence();
+      }
+      if (we >= g1) done = true;
+    }
+    v += 63;
+  }
+}
+
+// ---- the plan of the staged word table (create) ----
+// key = tile of the token with destination j, val = j.
+__global__ __launch_bounds__(256) void wt_tile_keys_kernel(const int32_t* __restrict__ perm, int64_t N,
+                                                            uint32_t* __restrict__ key,
+                                                            uint32_t* __restrict__ val) {
+  const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= N) return;
+  key[j] = (uint32_t)perm[j] / (uint32_t)kWtTile;
+  val[j] = (uint32_t)j;
+}
+// sorted_j: the destinations in (tile, destination) order, i.e. by output slot of pass 1.
+// Writes every slot's local source position and counts the tokens of every (tile, bucket).
+__global__ __launch_bounds__(256) void wt_slots_kernel(const int32_t* __restrict__ perm,
+                                                        const uint32_t* __restrict__ sorted_j, int64_t N,
+                                                        int nb, uint16_t* __restrict__ src,
+                                                        uint32_t* __restrict__ cnt) {
+  const int64_t s = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (s >= N) return;
+  const uint32_t j = sorted_j[s];
+  src[s] = (uint16_t)((uint32_t)perm[j] % (uint32_t)kWtTile);
+  atomicAdd(&cnt[(size_t)(s / kWtTile) * (nb + 1) + j / (uint32_t)kWtBucket], 1u);
+}
+// istart[t][b] = b kWtBucket + the tokens of bucket b in tiles before t  (a thread per bucket).
+__global__ __launch_bounds__(256) void wt_prefix_buckets_kernel(const uint32_t* __restrict__ cnt, int nt,
+                                                                 int nb, uint32_t* __restrict__ istart) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= nb) return;
+  uint32_t run = (uint32_t)b * (uint32_t)kWtBucket;
+  for (int t = 0; t < nt; ++t) {
+    istart[(size_t)t * nb + b] = run;
+    run += cnt[(size_t)t * (nb + 1) + b];
+  }
+}
+// In place: cnt[t][0..nb] becomes ostart[t][0..nb], the exclusive sums over b  (a thread per tile).
+__global__ __launch_bounds__(256) void wt_prefix_tiles_kernel(uint32_t* __restrict__ cnt, int nt, int nb) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= nt) return;
+  uint32_t run = 0;
+  for (int b = 0; b <= nb; ++b) {
+    const uint32_t c = cnt[(size_t)t * (nb + 1) + b];
+    cnt[(size_t)t * (nb + 1) + b] = run;
+    run += c;
+  }
+}
+// dst[i] = local destination of the entry that pass 1 writes to intermediate index i.
+__global__ __launch_bounds__(256) void wt_dst_kernel(const uint32_t* __restrict__ sorted_j,
+                                                      const uint32_t* __restrict__ ostart,
+                                                      const uint32_t* __restrict__ istart, int64_t N, int nb,
+                                                      uint16_t* __restrict__ dst) {
+  const int64_t s = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (s >= N) return;
+  const uint32_t j = sorted_j[s];
+  const uint32_t t = (uint32_t)(s / kWtTile), b = j / (uint32_t)kWtBucket;
+  const uint32_t i = istart[(size_t)t * nb + b] + ((uint32_t)(s % kWtTile) - ostart[(size_t)t * (nb + 1) + b]);
+  dst[i] = (uint16_t)(j - b * (uint32_t)kWtBucket);
+}
+// chunk_word[c] = the word that destination c kWtChunk belongs to.
+__global__ __launch_bounds__(256) void wt_chunk_words_kernel(const int32_t* __restrict__ word_off, int V,
+                                                              int n_chunks, int32_t* __restrict__ chunk_word) {
+  const int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= n_chunks) return;
+  const int64_t g = (int64_t)c * kWtChunk;
+  int lo = 0, hi = V;  // largest v < V with word_off[v] <= g (word_off[0] = 0)
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if ((int64_t)word_off[mid] <= g) lo = mid; else hi = mid;
+  }
+  chunk_word[c] = lo;
+}
+
 // ---- one-time structure of the corpus (create) ----
 __global__ __launch_bounds__(256) void iota_kernel(int32_t* __restrict__ a, int64_t n) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -1903,6 +2110,16 @@ struct augur_lda {
   uint32_t* cw_next = nullptr;
   int32_t* multi_words = nullptr;  // words with more than one slice (rows zeroed, slices add)
   int n_multi = 0;
+  // the staged form of the word table (K <= 256, from the byte copy of z)
+  bool wt_ready = false;
+  int wt_mode = 0;                 // 0 automatic, 1 whenever available, 2 never
+  int wt_tiles = 0, wt_buckets = 0;
+  uint16_t *wt_src = nullptr, *wt_dst = nullptr;
+  uint32_t *wt_ostart = nullptr, *wt_istart = nullptr;
+  uint8_t* wt_inter = nullptr;
+  int32_t* wt_chunk_word = nullptr;
+  int32_t* wt_multi = nullptr;     // words cut by a chunk border, and words without tokens
+  int wt_n_multi = 0;
   uint8_t* zb = nullptr;    // z in bytes, written by the z kernel when K <= 256
   bool zb_current = false;  // zb holds the z of the last z step
   int32_t* seg_base = nullptr;  // NULL: every document is one segment
@@ -1961,6 +2178,9 @@ void free_all(augur_lda* h) {
   (void)hipFree(h->log_table); (void)hipFree(h->exp_table);
   (void)hipFree(h->hot_words); (void)hipFree(h->wz); (void)hipFree(h->ord);
   (void)hipFree(h->theta64); (void)hipFree(h->phi64);
+  (void)hipFree(h->wt_src); (void)hipFree(h->wt_dst); (void)hipFree(h->wt_ostart);
+  (void)hipFree(h->wt_istart); (void)hipFree(h->wt_inter); (void)hipFree(h->wt_chunk_word);
+  (void)hipFree(h->wt_multi);
   if (h->graph_exec) (void)hipGraphExecDestroy(h->graph_exec);
   if (h->graph) (void)hipGraphDestroy(h->graph);
   if (h->side) (void)hipStreamDestroy(h->side);
@@ -2091,8 +2311,35 @@ int launch_count_docs(augur_lda* h, hipStream_t stream) {
   return AUGUR_OK;
 }
 
-int launch_count_words(augur_lda* h, hipStream_t stream) {
+// Whether the word table is built by the staged kernels.  They read the byte copy of z.  Alone
+// on the chip they beat the gathering kernel where that one misses the caches (from about 16M
+// tokens on; below, the byte copy lies in the L2s): 75M tokens, 0.38 against 0.70 ms.  Beside
+// the theta step they lose: their workgroups need a CU's 16 wave slots and 64 to 76 KiB of
+// its LDS at once, which the theta step's small workgroups leave free only rarely, while the
+// gathering kernel's workgroups slip in anywhere and their time hides behind the theta step's
+// arithmetic (sweep 3.81 against 3.57 ms).  So by itself the library takes the staged form
+// only when the word table has the stream to itself.
+constexpr int64_t kWtMinTokens = 16 << 20;
+bool staged_word_table(const augur_lda* h, bool beside_theta) {
+  return h->wt_ready && h->zb_current && h->wt_mode != 2 &&
+         (h->wt_mode == 1 || (!beside_theta && h->N >= kWtMinTokens));
+}
+
+int launch_count_words(augur_lda* h, hipStream_t stream, bool beside_theta = false) {
   if (h->n_items == 0) return AUGUR_OK;
+  if (staged_word_table(h, beside_theta)) {
+    const int64_t cells = (int64_t)h->wt_n_multi * h->ldk;
+    hipLaunchKernelGGL(lda_count_words_prepare_kernel, dim3((unsigned)std::max<int64_t>(1, (cells + 255) / 256)),
+                       dim3(256), 0, stream, h->wt_multi, h->wt_n_multi, h->n_wk, h->ldk, h->cw_next);
+    hipLaunchKernelGGL(lda_wt_pass1_kernel, dim3((unsigned)round_up(h->wt_tiles, 8)), dim3(1024),
+                       (size_t)kWtTile + sizeof(uint32_t) * (2 * (size_t)h->wt_buckets + 1), stream, h->zb,
+                       h->wt_src, h->wt_ostart, h->wt_istart, h->wt_inter, h->N, h->wt_buckets);
+    hipLaunchKernelGGL(lda_wt_pass2_kernel, dim3(h->wt_buckets), dim3(1024),
+                       (size_t)kWtBucket + sizeof(int32_t) * kWtWaves * (size_t)h->ldk, stream, h->wt_inter,
+                       h->wt_dst, h->word_off, h->wt_chunk_word, h->n_wk, h->ldk, h->cfg.V, h->N);
+    AUGUR_HIP_TRY(hipGetLastError());
+    return AUGUR_OK;
+  }
   const size_t shm = sizeof(int32_t) * 4 * (size_t)h->ldk;
   {
     const int64_t cells = (int64_t)h->n_multi * h->ldk;
@@ -2297,6 +2544,97 @@ int build_word_major(augur_lda* h) {
   }
   (void)hipFree(temp); (void)hipFree(iota); (void)hipFree(sorted_w); (void)hipFree(d_heavy);
   (void)hipFree(d_border);
+  return rc;
+}
+
+// The plan of the staged word table (see lda_wt_pass1_kernel): made once on the device from
+// perm (destination -> position) and the word offsets.  Leaves wt_ready false where the form
+// does not apply (more than 256 topics, no tokens, more buckets than pass 1 has LDS for).
+int build_staged_word_table(augur_lda* h) {
+  h->wt_ready = false;
+  const int64_t N = h->N;
+  const int V = h->cfg.V;
+  if (h->ldk > 256 || N == 0) return AUGUR_OK;
+  const int nt = (int)((N + kWtTile - 1) / kWtTile), nb = (int)((N + kWtBucket - 1) / kWtBucket);
+  if (nb > kWtMaxBuckets) return AUGUR_OK;
+  const int n_chunks = nb * kWtWaves;
+  uint32_t *key = nullptr, *key2 = nullptr, *val = nullptr, *sorted_j = nullptr;
+  void* temp = nullptr;
+  int rc = AUGUR_OK;
+  auto check = [&](hipError_t e, const char* what) {
+    if (e != hipSuccess && rc == AUGUR_OK) {
+      set_error("%s failed: %s", what, hipGetErrorString(e));
+      (void)hipGetLastError();  // or the runtime hands the error to the next caller
+      rc = AUGUR_ERR_HIP;
+    }
+    return rc == AUGUR_OK;
+  };
+  try {
+  do {
+    // the words whose rows are zeroed first: cut by a chunk border, or without tokens
+    std::vector<int32_t> off((size_t)V + 1), multi;
+    if (!check(hipMemcpyAsync(off.data(), h->word_off, sizeof(int32_t) * off.size(), hipMemcpyDeviceToHost,
+                              h->stream), "hipMemcpyAsync")) break;
+    if (!check(hipStreamSynchronize(h->stream), "hipStreamSynchronize")) break;
+    for (int v = 0; v < V; ++v)
+      if (off[v + 1] == off[v] || off[v] / kWtChunk != (off[v + 1] - 1) / kWtChunk) multi.push_back(v);
+    h->wt_n_multi = (int)multi.size();
+    const size_t n_pad = (size_t)N + 64;  // the kernels read 16 entries at a time
+    if (!check(hipMalloc(&h->wt_multi, sizeof(int32_t) * std::max<size_t>(multi.size(), 1)), "hipMalloc(wt_multi)")) break;
+    if (!multi.empty() &&
+        !check(hipMemcpy(h->wt_multi, multi.data(), sizeof(int32_t) * multi.size(), hipMemcpyHostToDevice),
+               "hipMemcpy")) break;
+    if (!check(hipMalloc(&h->wt_src, sizeof(uint16_t) * n_pad), "hipMalloc(wt_src)")) break;
+    if (!check(hipMalloc(&h->wt_dst, sizeof(uint16_t) * n_pad), "hipMalloc(wt_dst)")) break;
+    if (!check(hipMalloc(&h->wt_inter, n_pad), "hipMalloc(wt_inter)")) break;
+    if (!check(hipMalloc(&h->wt_ostart, sizeof(uint32_t) * (size_t)nt * (nb + 1)), "hipMalloc(wt_ostart)")) break;
+    if (!check(hipMalloc(&h->wt_istart, sizeof(uint32_t) * (size_t)nt * nb), "hipMalloc(wt_istart)")) break;
+    if (!check(hipMalloc(&h->wt_chunk_word, sizeof(int32_t) * (size_t)n_chunks), "hipMalloc(wt_chunk_word)")) break;
+    if (!check(hipMalloc(&key, sizeof(uint32_t) * (size_t)N), "hipMalloc(keys)")) break;
+    if (!check(hipMalloc(&key2, sizeof(uint32_t) * (size_t)N), "hipMalloc(keys)")) break;
+    if (!check(hipMalloc(&val, sizeof(uint32_t) * (size_t)N), "hipMalloc(values)")) break;
+    if (!check(hipMalloc(&sorted_j, sizeof(uint32_t) * (size_t)N), "hipMalloc(values)")) break;
+    if (!check(hipMemsetAsync(h->wt_ostart, 0, sizeof(uint32_t) * (size_t)nt * (nb + 1), h->stream), "hipMemsetAsync")) break;
+    if (!check(hipMemsetAsync(h->wt_dst, 0, sizeof(uint16_t) * n_pad, h->stream), "hipMemsetAsync")) break;
+    if (!check(hipMemsetAsync(h->wt_src, 0, sizeof(uint16_t) * n_pad, h->stream), "hipMemsetAsync")) break;
+    if (!check(hipMemsetAsync(h->wt_inter, 0, n_pad, h->stream), "hipMemsetAsync")) break;
+    const dim3 grid_n((unsigned)((N + 255) / 256)), block(256);
+    hipLaunchKernelGGL(wt_tile_keys_kernel, grid_n, block, 0, h->stream, h->perm, N, key, val);
+    int end_bit = 1;
+    while ((1LL << end_bit) < nt) ++end_bit;
+    size_t temp_bytes = 0;
+    if (!check(hipcub::DeviceRadixSort::SortPairs(nullptr, temp_bytes, key, key2, val, sorted_j, (int)N, 0,
+                                                  end_bit, h->stream), "radix sort (size query)")) break;
+    if (!check(hipMalloc(&temp, std::max<size_t>(temp_bytes, 16)), "hipMalloc(sort temp)")) break;
+    if (!check(hipcub::DeviceRadixSort::SortPairs(temp, temp_bytes, key, key2, val, sorted_j, (int)N, 0,
+                                                  end_bit, h->stream), "radix sort")) break;
+    hipLaunchKernelGGL(wt_slots_kernel, grid_n, block, 0, h->stream, h->perm, sorted_j, N, nb, h->wt_src,
+                       h->wt_ostart);
+    hipLaunchKernelGGL(wt_prefix_buckets_kernel, dim3((nb + 255) / 256), block, 0, h->stream, h->wt_ostart, nt,
+                       nb, h->wt_istart);
+    hipLaunchKernelGGL(wt_prefix_tiles_kernel, dim3((nt + 255) / 256), block, 0, h->stream, h->wt_ostart, nt, nb);
+    hipLaunchKernelGGL(wt_dst_kernel, grid_n, block, 0, h->stream, sorted_j, h->wt_ostart, h->wt_istart, N, nb,
+                       h->wt_dst);
+    hipLaunchKernelGGL(wt_chunk_words_kernel, dim3((n_chunks + 255) / 256), block, 0, h->stream, h->word_off, V,
+                       n_chunks, h->wt_chunk_word);
+    if (!check(hipGetLastError(), "launch")) break;
+    if (!check(hipStreamSynchronize(h->stream), "hipStreamSynchronize")) break;
+    // pass 1 needs more LDS than a kernel gets unasked (the limit belongs to the kernel: always the most)
+    if (!check(hipFuncSetAttribute(reinterpret_cast<const void*>(&lda_wt_pass1_kernel),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   kWtTile + (int)sizeof(uint32_t) * (2 * kWtMaxBuckets + 1)), "hipFuncSetAttribute")) break;
+    if (!check(hipFuncSetAttribute(reinterpret_cast<const void*>(&lda_wt_pass2_kernel),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   kWtBucket + (int)sizeof(int32_t) * kWtWaves * 256), "hipFuncSetAttribute")) break;
+    h->wt_tiles = nt;
+    h->wt_buckets = nb;
+    h->wt_ready = true;
+  } while (false);
+  } catch (const std::exception& e) {  // the host-side list allocates; nothing may throw out of the C ABI
+    set_error("planning the staged word table failed: %s", e.what());
+    rc = AUGUR_ERR_INVALID_ARG;
+  }
+  (void)hipFree(temp); (void)hipFree(key); (void)hipFree(key2); (void)hipFree(val); (void)hipFree(sorted_j);
   return rc;
 }
 
@@ -2638,7 +2976,7 @@ int augur_lda_create(const augur_lda_config* cfg, const int32_t* doc_len, const 
   AUGUR_CREATE_TRY(hipMalloc(&h->w, sizeof(int32_t) * (n_alloc + 256)));
   AUGUR_CREATE_TRY(hipMemsetAsync(h->w, 0, sizeof(int32_t) * (n_alloc + 256), h->stream));
   AUGUR_CREATE_TRY(hipMalloc(&h->z, sizeof(int32_t) * n_alloc));
-  AUGUR_CREATE_TRY(hipMalloc(&h->zb, n_alloc));
+  AUGUR_CREATE_TRY(hipMalloc(&h->zb, n_alloc + 64));  // the staged word table reads 16 bytes at a time
   if (h->N > 0)
     AUGUR_CREATE_TRY(hipMemcpyAsync(h->w, w, sizeof(int32_t) * (size_t)h->N,
                                     dev ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice,
@@ -2699,6 +3037,15 @@ int augur_lda_create(const augur_lda_config* cfg, const int32_t* doc_len, const 
       free_all(h);
       delete h;
       return rc_w;
+    }
+  }
+
+  {
+    const int rc_s = build_staged_word_table(h);
+    if (rc_s != AUGUR_OK) {
+      free_all(h);
+      delete h;
+      return rc_s;
     }
   }
 
@@ -2845,7 +3192,7 @@ static int run_sweep(augur_lda* h, SweepRef t, hipEvent_t* ev) {
   }
   AUGUR_MARK(2);
   if (h->overlap) {
-    AUGUR_TRY(launch_count_words(h, h->side));
+    AUGUR_TRY(launch_count_words(h, h->side, true));
     AUGUR_TRY(launch_phi(h, t, h->side));
     AUGUR_HIP_TRY(hipEventRecord(h->ev_join, h->side));
   }
@@ -2869,7 +3216,7 @@ static void drop_graph(augur_lda* h) {
   h->graph = nullptr;
 }
 static int graph_key(const augur_lda* h) {
-  return (h->overlap ? 1 : 0) | (h->phi_observed ? 2 : 0) | (h->z_cache_mode << 2);
+  return (h->overlap ? 1 : 0) | (h->phi_observed ? 2 : 0) | (h->z_cache_mode << 2) | (h->wt_mode << 4);
 }
 static int record_graph(augur_lda* h) {
   drop_graph(h);
@@ -2951,6 +3298,13 @@ int augur_lda_set_z_cache(augur_lda* h, int32_t mode) {
   AUGUR_REQUIRE(h != nullptr, "handle is NULL");
   AUGUR_REQUIRE(mode >= 0 && mode <= 2, "mode must be 0 (automatic), 1 (always) or 2 (never), got %d", mode);
   h->z_cache_mode = mode;
+  return AUGUR_OK;
+}
+
+int augur_lda_set_word_table(augur_lda* h, int32_t mode) {
+  AUGUR_REQUIRE(h != nullptr, "handle is NULL");
+  AUGUR_REQUIRE(mode >= 0 && mode <= 2, "mode must be 0 (automatic), 1 (always) or 2 (never), got %d", mode);
+  h->wt_mode = mode;
   return AUGUR_OK;
 }
 

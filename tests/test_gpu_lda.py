@@ -130,6 +130,7 @@ def test_topic_counts_span_stripes_and_tails(B, K):
     results = []
     for mode in (2, 1):
         g.set_z_cache(mode)
+        g.set_word_table(mode)    # and the staged form of the word table (a no-op above 256 topics)
         g.set_state(z=o.z, theta=o.theta, phi=o.phi, sweep=o.sweep_index)
         g.sweep(1)
         results.append([np_(a).copy() for a in g.get_state()[:3] + g.get_counts()])
@@ -173,7 +174,48 @@ def test_word_table_plans(B, D, mean_len, V, K):
     check(z)
     g.sweep(2)                                                   # K <= 256: from the byte copy
     check(np_(g.get_state(theta=False, phi=False)[0]))
+    g.set_word_table(1)                                          # K <= 256: the staged form, forced
+    g.sweep(1)
+    check(np_(g.get_state(theta=False, phi=False)[0]))
+    g.step_sample_z(); g.step_count()
+    check(np_(g.get_state(theta=False, phi=False)[0]))
     g.close()
+
+
+@pytest.mark.parametrize("D,mean_len,V,K,zipf_s", [
+    (1, 200_000, 50, 8, 0.0),         # one document, 50 words of 4000 tokens: every word cut by chunk borders
+    (700, 300, 60_000, 16, 0.3),      # more words than tokens in most chunks: many empty words, pieces of one token
+    (3000, 100, 2000, 256, 1.1),      # 256 topics: the largest rows the form serves
+    (40, 49_152, 300, 5, 1.1),        # N close to a multiple of the bucket size
+    (3, 21_845, 9, 3, 1.5),           # one tile, two buckets
+])
+def test_staged_word_table_equals_histogram(B, D, mean_len, V, K, zipf_s):
+    """The staged form of the word table (the byte copy of z permuted to word-major order in
+    two passes through LDS), forced on corpora far below the size the library picks it for,
+    against numpy's histogram."""
+    rng = np.random.default_rng(D + V)
+    lens = np.full(D, mean_len, dtype=np.int32)
+    if D > 1:
+        lens = rng.poisson(mean_len, size=D).astype(np.int32)
+    zipf = np.arange(1, V + 1) ** -zipf_s
+    w = rng.choice(V, size=int(lens.sum()), p=zipf / zipf.sum()).astype(np.int32)
+    N = w.size
+    doc = np.repeat(np.arange(D), lens)
+    g = B.LDA(D, V, K, 0.3, 0.1, 9, lens, w)
+    g.set_word_table(1)
+    for _ in range(2):
+        g.sweep(1)
+        z = np_(g.get_state(theta=False, phi=False)[0])
+        n_dk, n_wk = (np_(a) for a in g.get_counts())
+        assert np.array_equal(n_wk, np.bincount(w.astype(np.int64) * K + z, minlength=V * K).reshape(V, K))
+        assert np.array_equal(n_dk, np.bincount(doc * K + z, minlength=D * K).reshape(D, K))
+    # and the same chain as with the gathering kernel
+    g2 = B.LDA(D, V, K, 0.3, 0.1, 9, lens, w)
+    g2.set_word_table(2)
+    g2.sweep(2)
+    for x, y in zip(g.get_state() + g.get_counts(), g2.get_state() + g2.get_counts()):
+        assert np.array_equal(np_(x), np_(y))
+    g.close(); g2.close()
 
 
 @pytest.mark.parametrize("K", [200, 700])
