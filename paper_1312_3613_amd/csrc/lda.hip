@@ -1894,6 +1894,179 @@ __global__ __launch_bounds__(256) void lda_loglik_tokens_kernel(
   block_partial_sum(marg, part_marg, smem);
 }
 
+// The same terms with the phi rows of the most frequent words read from LDS: the workgroup
+// shape, the cache, the processing order (wz, ord) and the LDS budget of the resident z kernel
+// (lda_sample_z_hot_kernel); per wave theta_d as doubles, then the chunk's wz and ord strips.
+// One trip of the inner loop issues the row loads of a 16-token iteration that reads memory,
+// runs an iteration that reads LDS only while they are on their way, then consumes them.
+// Blocks past the grid's size in the partial arrays are cleared here (the finishing kernel adds
+// all kRedBlocks of them).
+template <int NS16>
+__global__ __launch_bounds__(64 * kHotWaves) void lda_loglik_hot_kernel(
+    const int32_t* __restrict__ wz, const uint8_t* __restrict__ ord, const int32_t* __restrict__ z,
+    const int64_t* __restrict__ doc_off, const int32_t* __restrict__ seg_base, int n_segs,
+    const float* __restrict__ theta, const float* __restrict__ phi, int D, int K, int ldk,
+    const double2* __restrict__ log_table, double* __restrict__ part_lik,
+    double* __restrict__ part_marg, const int32_t* __restrict__ hot_words, int n_hot) {
+  extern __shared__ __align__(16) unsigned char lds[];
+  __shared__ double2 lt[kLogTableSize];
+  __shared__ double smem[kHotWaves];
+  constexpr int kRowLds = 64 * NS16 + hot_row_pad_bytes(NS16);
+  constexpr int kWaveBytes = hot_wave_bytes(NS16, true);  // the z kernel's strip: 128 NS16 + 1280 bytes are used
+  static_assert(128 * NS16 + 1024 + 256 <= kWaveBytes, "the strips of a wave must fit the z kernel's");
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  const uint32_t row_bytes = 4u * (uint32_t)ldk;  // 64 NS16
+  for (int i = threadIdx.x; i < kLogTableSize; i += blockDim.x) lt[i] = log_table[i];
+  {
+    const int pieces = 4 * NS16;
+    for (int e = threadIdx.x; e < n_hot * pieces; e += blockDim.x) {
+      const int s = e / pieces, pc = e - s * pieces;
+      const float4 v = *reinterpret_cast<const float4*>(reinterpret_cast<const char*>(phi) +
+                                                       ((size_t)(uint32_t)hot_words[s] * row_bytes + 16u * pc));
+      *reinterpret_cast<float4*>(lds + (size_t)s * kRowLds + 16 * pc) = v;
+    }
+  }
+  for (int i = (int)(gridDim.x + blockIdx.x * blockDim.x + threadIdx.x); i < kRedBlocks;
+       i += (int)(blockDim.x * gridDim.x)) {
+    part_lik[i] = 0.0;
+    part_marg[i] = 0.0;
+  }
+  __syncthreads();
+  unsigned char* mine = lds + (size_t)n_hot * kRowLds + (size_t)wave * kWaveBytes;
+  double* th = reinterpret_cast<double*>(mine);                          // [16 NS16]
+  uint32_t* strip_w = reinterpret_cast<uint32_t*>(mine + 128 * NS16);    // wz of the j-th token in order
+  uint8_t* strip_o = mine + 128 * NS16 + 1024;                           // its position in the chunk
+  const int tq = lane >> 2, q = lane & 3;
+  const char* phi_bytes = reinterpret_cast<const char*>(phi);
+  const uint32_t lane_off = 16u * (uint32_t)q;
+  double lik = 0.0, marg = 0.0;
+
+  // the three logarithms of a token, by three lanes of its quad
+  auto add_terms = [&](double s, int zi, double ph_z, bool valid) {
+    s += __shfl_xor(s, 1, 64);
+    s += __shfl_xor(s, 2, 64);
+    const double arg = q == 0 ? s : q == 1 ? th[zi] : q == 2 ? ph_z : 1.0;
+    const double lg = log_any(arg, lt);
+    marg += valid && q == 0 ? lg : 0.0;
+    lik += valid && (q == 1 || q == 2) ? lg : 0.0;
+  };
+
+  for (int seg = blockIdx.x * kHotWaves + wave; seg < n_segs; seg += gridDim.x * kHotWaves) {
+    const Segment sg = segment_of(doc_off, seg_base, D, seg);
+    wave_lds_fence();  // the previous segment's reads of theta are done
+    for (int k = lane; k < 16 * NS16; k += 64) th[k] = k < K ? (double)theta[(size_t)sg.d * ldk + k] : 0.0;
+    const int32_t* z_seg = z + sg.first;
+    const int rel_a = (int)(sg.a - sg.first);
+    const int rel_b = (int)(sg.end - sg.first);
+    for (int rbase = 0; rbase < rel_b; rbase += 256) {
+      const int lo = max(rel_a, rbase);
+      const int hi = min(rel_b, rbase + 256);
+      const int n_valid = hi - lo;
+      int n_cached = 0;
+      {
+        const int32_t* wz_c = wz + (sg.first + lo);
+        const uint8_t* ord_c = ord + (sg.first + lo);
+        uint32_t wv[4];
+        uint8_t ov[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int j = lane + 64 * e;
+          wv[e] = j < n_valid ? (uint32_t)wz_c[j] : 0u;
+          ov[e] = j < n_valid ? ord_c[j] : (uint8_t)0;
+        }
+        wave_lds_fence();  // earlier reads of the strips are done
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          strip_w[lane + 64 * e] = wv[e];
+          strip_o[lane + 64 * e] = ov[e];
+          n_cached += __popcll(__ballot((wv[e] >> 24) != 0u));
+        }
+        wave_lds_fence();
+      }
+      const int n_hot_iters = __builtin_amdgcn_readfirstlane(n_cached) >> 4;
+      const int cold0 = 16 * n_hot_iters;
+      const int n_cold_iters = (n_valid - cold0 + 15) >> 4;
+      const int n_trips = max(n_hot_iters, n_cold_iters);
+      for (int it = 0; it < n_trips; ++it) {
+        const bool do_cold = it < n_cold_iters, do_hot = it < n_hot_iters;
+        float4 ph[NS16];
+        float ph_z_c = 1.f;
+        int zi_c = 0;
+        bool valid_c = false;
+        if (do_cold) {
+          const int j0 = cold0 + 16 * it;
+          const int j = j0 + tq;
+          valid_c = j < n_valid;
+          const int jj = valid_c ? j : j0;  // a quad past the end redoes the iteration's first token; not counted
+          const uint32_t row_off = __umul24(strip_w[jj] & 0xFFFFFFu, row_bytes);
+          zi_c = min(max(z_seg[rbase + (int)strip_o[jj]], 0), K - 1);
+          const char* rowp = phi_bytes + (size_t)(row_off + lane_off);
+#pragma unroll
+          for (int c = 0; c < NS16; ++c) ph[c] = *reinterpret_cast<const float4*>(rowp + 64 * c);
+          ph_z_c = *reinterpret_cast<const float*>(phi_bytes + (size_t)(row_off + 4u * (uint32_t)zi_c));
+        }
+        asm volatile("" ::: "memory");  // the loads above are issued before anything below starts
+        if (do_hot) {
+          const int j = 16 * it + tq;
+          const uint32_t wv = strip_w[j];
+          const int zi = min(max(z_seg[rbase + (int)strip_o[j]], 0), K - 1);
+          const unsigned char* crow = lds + (size_t)((wv >> 24) - 1u) * kRowLds;
+          int theta_off = 4 * q;
+          asm volatile("" : "+v"(theta_off));  // or theta_d is read once and held in registers
+          const double* th_q = th + theta_off;
+          double s = 0.0;
+#pragma unroll
+          for (int c = 0; c < NS16; ++c) {
+            const float4 y = *reinterpret_cast<const float4*>(crow + 64 * c + 16 * q);
+            const double2 x01 = *reinterpret_cast<const double2*>(th_q + 16 * c);
+            const double2 x23 = *reinterpret_cast<const double2*>(th_q + 16 * c + 2);
+            s = fma(x01.x, (double)y.x, s);
+            s = fma(x01.y, (double)y.y, s);
+            s = fma(x23.x, (double)y.z, s);
+            s = fma(x23.y, (double)y.w, s);
+          }
+          add_terms(s, zi, (double)*reinterpret_cast<const float*>(crow + 4 * zi), true);
+        }
+        if (do_cold) {
+          int theta_off = 4 * q;
+          asm volatile("" : "+v"(theta_off));
+          const double* th_q = th + theta_off;
+          double s = 0.0;
+#pragma unroll
+          for (int c = 0; c < NS16; ++c) {
+            const double2 x01 = *reinterpret_cast<const double2*>(th_q + 16 * c);
+            const double2 x23 = *reinterpret_cast<const double2*>(th_q + 16 * c + 2);
+            s = fma(x01.x, (double)ph[c].x, s);
+            s = fma(x01.y, (double)ph[c].y, s);
+            s = fma(x23.x, (double)ph[c].z, s);
+            s = fma(x23.y, (double)ph[c].w, s);
+          }
+          add_terms(s, zi_c, (double)ph_z_c, valid_c);
+        }
+      }
+    }
+  }
+  // (the sum over a workgroup of 16 waves)
+  lik = wave_allreduce_sum(lik);
+  marg = wave_allreduce_sum(marg);
+  if (lane == 0) smem[wave] = lik;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double t = 0.0;
+    for (int i = 0; i < kHotWaves; ++i) t += smem[i];
+    part_lik[blockIdx.x] = t;
+  }
+  __syncthreads();
+  if (lane == 0) smem[wave] = marg;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double t = 0.0;
+    for (int i = 0; i < kHotWaves; ++i) t += smem[i];
+    part_marg[blockIdx.x] = t;
+  }
+}
+
 // The same per-token terms for the fp64 state: theta and phi are doubles, nothing is converted.
 __global__ __launch_bounds__(256) void lda_loglik_tokens_f64_kernel(
     const int32_t* __restrict__ w, const int32_t* __restrict__ z,
@@ -2197,6 +2370,17 @@ int zero_split_rows(augur_lda* h, hipStream_t stream) {
   return AUGUR_OK;
 }
 
+// Whether the kernels that walk the tokens (z step, log-likelihood) take their resident form.
+// By itself the library does when every wave of the chip gets at least 16 documents (fewer leave
+// the waves unevenly loaded and the copy of the cached rows unpaid for: 3M tokens in 20,000
+// documents at K = 100 take 0.081 against 0.075 ms) and rows are at least five stripes long
+// (shorter rows are too cheap to load for the detour to pay).
+bool resident_form(const augur_lda* h) {
+  return h->n_hot > 0 && h->z_cache_mode != 2 &&
+         (h->z_cache_mode == 1 ||
+          (h->n_segs >= 16 * kHotWaves * h->num_cus && h->ldk >= 16 * kHotMinStripes));
+}
+
 // fused: the kernel also writes the document table n_dk (K <= 256 only); returns
 // whether it did through *did_count.
 int launch_sample_z(augur_lda* h, SweepRef sweep, bool fuse_doc_counts = false,
@@ -2240,14 +2424,7 @@ int launch_sample_z(augur_lda* h, SweepRef sweep, bool fuse_doc_counts = false,
     break;
 #define AUGUR_Z_CASE(NSV) \
   case NSV: hipLaunchKernelGGL(lda_sample_z_kernel<NSV>, AUGUR_Z_ARGS); break;
-  // by itself the library takes the resident form when every wave of the chip gets at least 16
-  // documents (fewer leave the waves unevenly loaded and the copy of the cached rows unpaid
-  // for: 3M tokens in 20,000 documents at K = 100 take 0.081 against 0.075 ms) and rows are at
-  // least five stripes long (shorter rows are too cheap to load for the detour to pay)
-  const bool resident = h->n_hot > 0 && h->z_cache_mode != 2 &&
-                        (h->z_cache_mode == 1 ||
-                         (h->n_segs >= 16 * kHotWaves * h->num_cus && h->ldk >= 16 * kHotMinStripes));
-  if (resident) {
+  if (resident_form(h)) {
     // one workgroup per CU (fewer if there is not a segment for every wave), resident until done
     const dim3 hgrid((unsigned)std::min(h->num_cus, (h->n_segs + kHotWaves - 1) / kHotWaves));
 #define AUGUR_ZH_ARGS                                                                               \
@@ -2656,6 +2833,18 @@ const void* hot_kernel_ptr(int ns16, bool count_docs) {
 #undef AUGUR_HP_CASE
   return nullptr;
 }
+const void* hot_loglik_kernel_ptr(int ns16) {
+#define AUGUR_HL_CASE(N16) \
+  case N16: return reinterpret_cast<const void*>(&lda_loglik_hot_kernel<N16>);
+  switch (ns16) {
+    AUGUR_HL_CASE(1) AUGUR_HL_CASE(2) AUGUR_HL_CASE(3) AUGUR_HL_CASE(4) AUGUR_HL_CASE(5)
+    AUGUR_HL_CASE(6) AUGUR_HL_CASE(7) AUGUR_HL_CASE(8) AUGUR_HL_CASE(9) AUGUR_HL_CASE(10)
+    AUGUR_HL_CASE(11) AUGUR_HL_CASE(12) AUGUR_HL_CASE(13) AUGUR_HL_CASE(14) AUGUR_HL_CASE(15)
+    AUGUR_HL_CASE(16)
+  }
+#undef AUGUR_HL_CASE
+  return nullptr;
+}
 int setup_resident_form(augur_lda* h) {
   h->n_hot = 0;
   if (h->f64 || h->ldk > 256 || h->N == 0 || h->hot_host.empty()) return AUGUR_OK;
@@ -2673,6 +2862,8 @@ int setup_resident_form(augur_lda* h) {
     // handle with fewer cached rows does not lower it under another handle's launches
     AUGUR_HIP_TRY(hipFuncSetAttribute(hot_kernel_ptr(ns16, cd != 0), hipFuncAttributeMaxDynamicSharedMemorySize,
                                       kHotLdsBudget));
+  AUGUR_HIP_TRY(hipFuncSetAttribute(hot_loglik_kernel_ptr(ns16), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    kHotLdsBudget));
   const int V = h->cfg.V;
   std::vector<uint8_t> slot_of;
   try {
@@ -2765,16 +2956,27 @@ int launch_phi(augur_lda* h, SweepRef sweep, hipStream_t stream) {
 // The log joint and the log marginal of a state: three reduction kernels write block partials
 // into red ([4][kRedBlocks] doubles), a last one adds them and writes out[0], out[1] (device).
 // seg_base == NULL: one wave per document (n_segs = D).
+const void* hot_loglik_kernel_ptr(int ns16);
 int launch_loglik(hipStream_t stream, const int32_t* w, const int32_t* z, const int64_t* doc_off,
                   const int32_t* seg_base, int n_segs, const float* theta, const float* phi, int D,
                   int V, int K, int ldk, double alpha, double beta, const double2* log_table,
-                  double* red, double* out) {
+                  double* red, double* out, const augur_lda* resident = nullptr) {
   double* p_lik = red;
   double* p_marg = red + kRedBlocks;
   double* p_th = red + 2 * kRedBlocks;
   double* p_ph = red + 3 * kRedBlocks;
   const int stripes = (ldk + 15) / 16;
   const size_t shm = sizeof(double) * 4 * 16 * (size_t)stripes;
+  if (resident != nullptr) {
+    // the token terms by the kernel that keeps the rows of the most frequent words in LDS
+    const augur_lda* h = resident;
+    const dim3 hgrid((unsigned)std::min(h->num_cus, (n_segs + kHotWaves - 1) / kHotWaves));
+    void* args[] = {(void*)&h->wz, (void*)&h->ord, (void*)&z, (void*)&doc_off, (void*)&seg_base, (void*)&n_segs,
+                    (void*)&theta, (void*)&phi, (void*)&D, (void*)&K, (void*)&ldk, (void*)&log_table,
+                    (void*)&p_lik, (void*)&p_marg, (void*)&h->hot_words, (void*)&h->n_hot};
+    AUGUR_HIP_TRY(hipLaunchKernel(hot_loglik_kernel_ptr(ldk / 16), hgrid, dim3(64 * kHotWaves), args,
+                                  h->hot_lds_bytes, stream));
+  } else {
 #define AUGUR_LL_ARGS                                                                            \
   dim3(kRedBlocks), dim3(256), shm, stream, w, z, doc_off, seg_base, n_segs, theta, phi, D, V, K, \
       ldk, log_table, p_lik, p_marg
@@ -2789,6 +2991,7 @@ int launch_loglik(hipStream_t stream, const int32_t* w, const int32_t* z, const 
   }
 #undef AUGUR_LL_CASE
 #undef AUGUR_LL_ARGS
+  }
   hipLaunchKernelGGL(sum_log_kernel<float>, dim3(kRedBlocks), dim3(256), 0, stream, theta, (int64_t)D,
                      K, ldk, log_table, p_th);
   hipLaunchKernelGGL(sum_log_kernel<float>, dim3(kRedBlocks), dim3(256), 0, stream, phi, (int64_t)V, K,
@@ -3420,7 +3623,7 @@ int augur_lda_loglik(augur_lda* h, double* log_joint, double* log_marginal_w) {
   else
     AUGUR_TRY(launch_loglik(h->stream, h->w, h->z, h->doc_off, h->seg_base, h->n_segs, h->theta,
                             h->phi, h->cfg.D, h->cfg.V, h->cfg.K, h->ldk, h->alpha, h->beta,
-                            h->log_table, h->red, out));
+                            h->log_table, h->red, out, resident_form(h) ? h : nullptr));
   double host[2] = {0.0, 0.0};
   AUGUR_HIP_TRY(hipMemcpyAsync(host, out, sizeof(host), hipMemcpyDeviceToHost, h->stream));
   AUGUR_HIP_TRY(hipStreamSynchronize(h->stream));

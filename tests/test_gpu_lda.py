@@ -61,9 +61,13 @@ def lockstep_sweep(g, o, check_loglik=False):
     g.step_finish(); o.step_finish()
     if check_loglik:
         g.set_state(theta=o.theta, phi=o.phi)
-        lj, lm = g.loglik()
         olj, olm = o.loglik()
-        assert abs(lj - olj) <= P.REAL_RTOL * abs(olj) and abs(lm - olm) <= P.REAL_RTOL * abs(olm)
+        # both forms of the token kernel: rows from memory only, and (where the library has it:
+        # up to 256 topics) the rows of the most frequent words from LDS
+        for mode in (2, 1, 0):
+            g.set_z_cache(mode)
+            lj, lm = g.loglik()
+            assert abs(lj - olj) <= P.REAL_RTOL * abs(olj) and abs(lm - olm) <= P.REAL_RTOL * abs(olm)
     return nm
 
 
@@ -530,6 +534,15 @@ def test_full_size_config_sampled_parity(B, name):
     assert sw == 3 and np.array_equal(z2, z1) and np.array_equal(th2, th1) and np.array_equal(ph2, ph1)
     s_dk, s_wk = g.get_counts()
     assert np.array_equal(s_dk, n_dk) and np.array_equal(s_wk, n_wk)
+    # the log densities at full size: the form the library picks (rows of frequent words in LDS
+    # where it has them) against the plain one, which sums the same fp64 terms in another order
+    picked = g.loglik()
+    g.set_z_cache(2)
+    plain = g.loglik()
+    for a, b in zip(picked, plain):
+        assert abs(a - b) <= 1e-11 * abs(b)
+    lm_tokens = plain[1] / N
+    assert -12.0 < lm_tokens < -3.0
     g.close()
 
 
