@@ -257,6 +257,7 @@ __device__ __forceinline__ GammaShape gamma_shape(double a) {
 // per handle (the per-variable constants cost a square root, a division and a
 // logarithm otherwise); larger counts are computed on the spot.
 constexpr int kShapeTable = 1024;
+constexpr int kShapeLds = 32;  // entries that the theta and phi kernels copy into LDS
 __device__ __forceinline__ GammaShape gamma_shape_count(const GammaShape* __restrict__ table,
                                                         double a0, int n) {
   if (n < kShapeTable) return table[n];

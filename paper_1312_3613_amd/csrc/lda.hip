@@ -1613,30 +1613,46 @@ __global__ __launch_bounds__(256) void lda_resample_theta_kernel(
   const int total = nrows * K;
   double* lg = lg_all + (size_t)wave * rows * K;
 
-  int e = lane, r = 0, k = lane;  // variable e = row r, topic k
-  while (k >= K) { k -= K; ++r; }
+  // Variable e of the wave = row e / K, topic e % K.  The lanes do not own fixed lists: a lane
+  // whose draw is accepted takes the first variable that nobody has taken yet (the lanes that
+  // finish in the same trip take consecutive ones, in lane order), so that the wave runs dry
+  // only in its last trips, however the rejections fall.  Every variable's random numbers are
+  // keyed by its own index: which lane draws it does not matter.
+  const float inv_K = 1.0f / (float)K;
+  auto row_of = [&](int e_) {  // e_ / K for 0 <= e_ < 16384 (the quotient of the rounded floats is off by one at most)
+    int q = (int)(((float)e_ + 0.5f) * inv_K);
+    q -= q * K > e_ ? 1 : 0;
+    q += (q + 1) * K <= e_ ? 1 : 0;
+    return q;
+  };
+  int e = lane, r = row_of(lane), k = lane - r * K;
+  int next = 64;  // the first variable not yet taken (the same in every lane)
   uint32_t attempt = 0;
   bool capped = false;
   GammaShape g = gamma_shape_count(shapes, alpha, e < total ? n_dk[(size_t)(d0 + r) * ldk + k] : 0);
   while (__any(e < total)) {
+    bool done = false;
     if (e < total) {
       const uint64_t index = (uint64_t)(d0 + r) * (uint64_t)K + (uint64_t)k;
       double x;
-      bool done = gamma_attempt(g, random_block(seed, index, sweep, kStreamTheta, attempt), x, lt);
+      done = gamma_attempt(g, random_block(seed, index, sweep, kStreamTheta, attempt), x, lt);
       if (!done && ++attempt == (uint32_t)kGammaAttemptCap) {
         done = true;
         capped = true;
         x = g.ln_d;
       }
-      if (done) {
-        lg[e] = x;
-        e += 64;
-        k += 64;
-        while (k >= K) { k -= K; ++r; }
-        attempt = 0;
-        if (e < total) g = gamma_shape_count(shapes, alpha, n_dk[(size_t)(d0 + r) * ldk + k]);
-      }
+      if (done) lg[e] = x;
     }
+    const uint64_t finished = __ballot(done);
+    if (done) {
+      e = next + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(finished >> 32),
+                                                __builtin_amdgcn_mbcnt_lo((uint32_t)finished, 0u));
+      r = row_of(e);
+      k = e - r * K;
+      attempt = 0;
+      if (e < total) g = gamma_shape_count(shapes, alpha, n_dk[(size_t)(d0 + r) * ldk + k]);
+    }
+    next += __popcll(finished);
   }
   wave_lds_fence();
   for (int rr = 0; rr < nrows; ++rr) {
@@ -1668,7 +1684,7 @@ __global__ __launch_bounds__(256) void lda_resample_theta_kernel(
 // draws and keeps a running (max, sum) per column per block of rows, pass 2
 // merges the blocks, pass 3 writes exp(lg - L_k).  In pass 1 a thread owns one
 // column of its block of rows and retries on its own variable (see theta).
-__global__ __launch_bounds__(1024) void lda_phi_draw_kernel(
+__global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(6, 6))) void lda_phi_draw_kernel(
     const int32_t* __restrict__ n_wk, double* __restrict__ lg, double2* __restrict__ partial, int V,
     int K, int ldk, int rows_per_block, int groups, int n_row_blocks, int col_w, double beta,
     const GammaShape* __restrict__ shapes, const double2* __restrict__ log_table,
@@ -1677,8 +1693,10 @@ __global__ __launch_bounds__(1024) void lda_phi_draw_kernel(
   __shared__ double2 lt[kLogTableSize];
   const uint32_t sweep = sweep_ref.get();
   __shared__ double et[kExpTableSize];
+  __shared__ GammaShape small_shapes[kShapeLds];  // the constants of the smallest counts: most entries of the table
   for (int i = threadIdx.x; i < kLogTableSize; i += blockDim.x) lt[i] = log_table[i];
   for (int i = threadIdx.x; i < kExpTableSize; i += blockDim.x) et[i] = exp_table[i];
+  for (int i = threadIdx.x; i < kShapeLds; i += blockDim.x) small_shapes[i] = shapes[i];
   __syncthreads();
   // The workgroup covers columns [blockIdx.y col_w, +col_w) (all K of them unless K > 512).
   // thread t: column t % col_w of that range, row block blockIdx.x * groups + t / col_w.
@@ -1695,6 +1713,9 @@ __global__ __launch_bounds__(1024) void lda_phi_draw_kernel(
   double m = -INFINITY, s = 0.0;
   uint32_t attempt = 0;
   GammaShape g = gamma_shape_count(shapes, beta, v < v1 ? n_wk[(size_t)v * ldk + k] : 0);
+  // the count of the variable after the current one, asked for one variable ahead: when a draw
+  // is accepted the next one's constants are a table look-up away, not two dependent loads
+  int n_next = v + 1 < v1 ? n_wk[(size_t)(v + 1) * ldk + k] : 0;
   while (__any(v < v1)) {
     if (v < v1) {
       const size_t e = (size_t)v * ldk + k;
@@ -1717,7 +1738,8 @@ __global__ __launch_bounds__(1024) void lda_phi_draw_kernel(
         m = dx > 0.0 ? x : m;
         ++v;
         attempt = 0;
-        if (v < v1) g = gamma_shape_count(shapes, beta, n_wk[(size_t)v * ldk + k]);
+        if (v < v1) g = n_next < kShapeLds ? small_shapes[n_next] : gamma_shape_count(shapes, beta, n_next);
+        if (v + 1 < v1) n_next = n_wk[(size_t)(v + 1) * ldk + k];
       }
     }
   }
