@@ -56,6 +56,19 @@ def count_algorithmic_bytes(N, D, V, K):
     return words + docs
 
 
+LDA_SOURCES = ["common.hpp", "lda_device.hpp", "lda_sample_z.hpp", "lda_count.hpp", "lda_gamma.hpp",
+               "lda_loglik.hpp", "lda.hip"]
+
+
+def lda_source_digest():
+    """Digest of the sources of the LDA kernels: the traffic file names the one it was measured at."""
+    h = hashlib.sha256()
+    for name in LDA_SOURCES:
+        with open(os.path.join(ROOT, "paper_1312_3613_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
 def measured_counters(workload):
     """rocprofv3 figures of earlier runs (HBM bytes per sample_z launch, instruction counters),
     with the commit and the digest of the kernel source they were measured at.  They cannot be
@@ -69,11 +82,10 @@ def measured_counters(workload):
     entry = data.get("workloads", {}).get(workload)
     if entry is None:
         return None
-    with open(os.path.join(ROOT, "paper_1312_3613_amd", "csrc", "lda.hip"), "rb") as f:
-        digest = hashlib.sha256(f.read()).hexdigest()[:16]
+    digest = lda_source_digest()
     out = dict(entry)
     out["measured_at_commit"] = data.get("measured_at_commit")
-    out["kernel_source_changed_since"] = digest != data.get("lda_hip_sha256_16")
+    out["kernel_source_changed_since"] = digest != data.get("lda_sources_sha256_16")
     return out
 
 

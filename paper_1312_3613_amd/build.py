@@ -16,7 +16,8 @@ LIB = os.path.join(HERE, "libaugur_hip.so")
 DIGEST = LIB + ".digest"
 OBJDIR = os.path.join(HERE, "_build")
 SOURCES = ["api.cpp", "lda.hip", "probe.hip", "gmm.hip", "mh.hip"]
-HEADERS = ["common.hpp", os.path.join("..", "..", "include", "augur.h")]
+HEADERS = ["common.hpp", "lda_device.hpp", "lda_sample_z.hpp", "lda_count.hpp", "lda_gamma.hpp",
+           "lda_loglik.hpp", os.path.join("..", "..", "include", "augur.h")]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

@@ -35,7 +35,7 @@ def test_committed_traffic_file_names_its_commit_and_kernel_source():
     import bench
     with open(bench.TRAFFIC_FILE) as f:
         data = json.load(f)
-    assert len(data["measured_at_commit"]) >= 7 and len(data["lda_hip_sha256_16"]) == 16
+    assert len(data["measured_at_commit"]) >= 7 and len(data["lda_sources_sha256_16"]) == 16
     for wl in ("large", "medium", "widek"):
         e = data["workloads"][wl]
         assert e["sample_z_hbm_bytes"] > 0 and 0 < e["texture_addresser_busy"] <= 1
