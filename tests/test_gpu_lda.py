@@ -461,30 +461,33 @@ def test_medium_config_full_parity(B):
     g.close()
 
 
-def _oracle_z_on_ranges(c, off, theta, phi, seed, sweep, z_gpu, D, K, ranges):
+def _oracle_z_on_ranges(c, off, theta, phi, seed, sweep, z_gpu, D, K, ranges, f64=False):
     """The oracle redraws z for the documents of each range from (theta, phi) and the result is
-    compared with z_gpu under the boundary rule; returns the number of tokens checked."""
+    compared with z_gpu under the boundary rule; returns the number of tokens checked.  f64: theta
+    and phi are doubles, the oracle's fp64 state functions and the tighter boundary rule."""
     import ctypes as Ct
     lib = O.lib()
+    sample, real = (lib.orc_lda_sample_z_f64, Ct.c_double) if f64 else (lib.orc_lda_sample_z, Ct.c_float)
+    rtol = P.Z_BOUNDARY_RTOL_F64 if f64 else P.Z_BOUNDARY_RTOL
     checked = 0
     for d0, d1 in ranges:
         sub_off = off[d0:d1 + 1]
         zo = z_gpu.copy()
         # the oracle writes its draws for documents d0..d1-1 into zo at their global positions
-        lib.orc_lda_sample_z(Ct.c_int32(d1 - d0), Ct.c_int32(K), sub_off.ctypes.data_as(Ct.POINTER(Ct.c_int64)),
-                             c["w"].ctypes.data_as(Ct.POINTER(Ct.c_int32)),
-                             theta[d0:d1].ctypes.data_as(Ct.POINTER(Ct.c_float)),
-                             phi.ctypes.data_as(Ct.POINTER(Ct.c_float)), Ct.c_uint64(seed), Ct.c_uint32(sweep),
-                             zo.ctypes.data_as(Ct.POINTER(Ct.c_int32)))
+        sample(Ct.c_int32(d1 - d0), Ct.c_int32(K), sub_off.ctypes.data_as(Ct.POINTER(Ct.c_int64)),
+               c["w"].ctypes.data_as(Ct.POINTER(Ct.c_int32)),
+               np.ascontiguousarray(theta[d0:d1]).ctypes.data_as(Ct.POINTER(real)),
+               phi.ctypes.data_as(Ct.POINTER(real)), Ct.c_uint64(seed), Ct.c_uint32(sweep),
+               zo.ctypes.data_as(Ct.POINTER(Ct.c_int32)))
         lo, hi = int(off[d0]), int(off[d1])
         sub = np.arange(lo, hi)
         mism = sub[z_gpu[lo:hi] != zo[lo:hi]]
         assert mism.size <= (1 - P.Z_AGREE) * (hi - lo)
         doc_of = np.searchsorted(off, mism, side="right") - 1
         for i, d in zip(mism, doc_of):
-            cdf, t = O.lda_token_cdf(theta[d], phi[c["w"][i]], seed, int(i), sweep)
+            cdf, t = O.lda_token_cdf(theta[d], phi[c["w"][i]], seed, int(i), sweep, f64=f64)
             P._assert_boundary(cdf, t, int(z_gpu[i]), int(zo[i]), f"token {i}",
-                               float(theta[d, z_gpu[i]]) * float(phi[c["w"][i], z_gpu[i]]))
+                               float(theta[d, z_gpu[i]]) * float(phi[c["w"][i], z_gpu[i]]), rtol)
         checked += hi - lo
     return checked
 

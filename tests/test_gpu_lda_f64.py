@@ -12,7 +12,7 @@ import pytest
 from oracle import oracle as O
 from paper_1312_3613_amd import synth
 from tests import parity as P
-from tests.test_gpu_lda import ragged_corpus, np_
+from tests.test_gpu_lda import ragged_corpus, np_, _oracle_z_on_ranges
 
 pytestmark = pytest.mark.gpu
 
@@ -271,4 +271,37 @@ def test_medium_config_sample_z_and_counts(B):
                      c["doc_len"], c["w"])
     nm = lockstep_sweep(g, o, check_loglik=True)
     print("medium fp64: z mismatches", nm)
+    g.close()
+
+
+def test_full_size_config_sampled_parity(B):
+    """BASELINE's K=200 configuration (about 75M tokens) with the fp64 state, through sweep(): z of
+    the sweep on ranges of documents the oracle redoes one by one, both count tables in full,
+    theta on sampled ranges, phi in full."""
+    from scipy import special
+    cfg = synth.LDA_CONFIGS["large"]
+    c = synth.lda_corpus(**cfg)
+    D, V, K, N = cfg["D"], cfg["V"], cfg["K"], c["N"]
+    alpha, beta, seed = float(np.float32(cfg["alpha"])), float(np.float32(cfg["beta"])), cfg["seed"]
+    g = B.LDA(D, V, K, cfg["alpha"], cfg["beta"], seed, c["doc_len"], c["w"], state_f64=True)
+    off = O.doc_offsets(c["doc_len"])
+    g.sweep(1)
+    _, theta, phi, sw = g.get_state(z=False)
+    assert sw == 1 and theta.dtype == np.float64
+    g.sweep(1)                                   # the sweep under test: index 2
+    z1, th1, ph1, sw = g.get_state()
+    assert sw == 2 and z1.min() >= 0 and z1.max() < K
+    ranges = [(d0, d0 + 1000) for d0 in (0, D // 2 + 777, D - 1000)]
+    checked = _oracle_z_on_ranges(c, off, theta, phi, seed, 2, z1, D, K, ranges, f64=True)
+    print("fp64 large: z checked on", checked, "tokens")
+    n_dk, n_wk = g.get_counts()
+    o_dk, o_wk = O.lda_count(off, c["w"], z1, D, V, K)
+    assert np.array_equal(n_dk, o_dk) and np.array_equal(n_wk, o_wk)
+    del o_dk, o_wk
+    for d0 in (0, 2 * D // 3, D - 2000):
+        nd = np.ascontiguousarray(n_dk[d0:d0 + 2000])
+        lg = O.gamma_log_draws((alpha + nd).ravel(), seed, first=d0 * K, sweep=2, stream=O.STREAM_THETA).reshape(2000, K)
+        want = np.maximum(np.exp(lg - special.logsumexp(lg, axis=1, keepdims=True)), P.DBL_MIN)
+        P.assert_real_close(th1[d0:d0 + 2000], want, "theta rows", rtol=P.REAL_RTOL_F64, floor=P.DBL_MIN)
+    close64(ph1, O.lda_resample_phi(n_wk, beta, seed, 2, f64=True), "phi")
     g.close()
