@@ -469,8 +469,9 @@ def main():
                           "torch": torch.__version__, "cpu_model": host_description(),
                           "nproc": os.cpu_count()}
     if not args.no_cpu_baseline:
+        # a bounded sample: about ten seconds of oracle work at the default workload
         out["cpu_baseline"] = oracle_per_step(dict(cfg, K=K), corpus,
-                                              1_500_000 if K <= 256 else 300_000, z_reps=2)
+                                              10_000_000 if K <= 256 else 2_000_000, z_reps=2)
 
     if args.workload == "large" and args.topics is None and not args.no_k100:
         # the K = 100 half of the metric: LDA medium, its own sweep count, same protocol
@@ -489,7 +490,7 @@ def main():
         k100.update(mextra)
         k100["setup_s"]["generate_corpus"] = t_mgen
         if not args.no_cpu_baseline:
-            k100["cpu_baseline"] = oracle_per_step(mcfg, mcorpus, 500_000, z_reps=1)
+            k100["cpu_baseline"] = oracle_per_step(mcfg, mcorpus, 3_000_000, z_reps=2)
         out["k100"] = k100
     print(json.dumps(out))
 
