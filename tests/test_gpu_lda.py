@@ -241,6 +241,15 @@ def test_edge_corpora(B):
         g, o = make_pair(B, len(lens), V, K, 0.5, 0.5, 3, lens, w)
         lockstep_sweep(g, o, check_loglik=w.size > 0)
         g.sweep(2); o.sweep(2)
+        # the other forms of the kernels (staged word table, resident z kernel where it exists)
+        # on the same corner cases: the tables must be the histograms of the handle's own z
+        g.set_word_table(1); g.set_z_cache(1)
+        g.sweep(2)
+        z = np_(g.get_state(theta=False, phi=False)[0])
+        n_dk, n_wk = (np_(a) for a in g.get_counts())
+        doc = np.repeat(np.arange(len(lens)), lens)
+        assert np.array_equal(n_wk, np.bincount(w.astype(np.int64) * K + z, minlength=V * K).reshape(V, K))
+        assert np.array_equal(n_dk, np.bincount(doc * K + z, minlength=len(lens) * K).reshape(len(lens), K))
         g.close()
 
 
@@ -299,6 +308,7 @@ def test_long_documents_are_cut_into_segments(B, K):
     # the sweep entry point (fused / overlapped schedule) against the step-wise one
     g2 = B.LDA(D, V, K, 0.1, 0.01, 500 + K, lens, w)
     g2.set_z_cache(1)            # the resident form of the z kernel (a no-op above 256 topics)
+    g2.set_word_table(1)         # and the staged word table (likewise)
     g2.sweep(3)
     g3 = B.LDA(D, V, K, 0.1, 0.01, 500 + K, lens, w)
     g3.set_z_cache(2)
