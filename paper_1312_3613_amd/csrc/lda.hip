@@ -66,6 +66,7 @@ struct augur_lda {
   int4* slice_desc = nullptr;     // the slices in visiting order
   int32_t* item_off = nullptr;    // [n_items + 1] into slice_desc
   int n_items = 0;
+  int n_big = 0;                  // not looping: the slices of at least 64 tokens, listed first
   bool count_loops = false;       // the word-table kernel takes items from cw_next
   uint32_t* cw_next = nullptr;
   int32_t* multi_words = nullptr;  // words with more than one slice (rows zeroed, slices add)
@@ -310,6 +311,19 @@ int launch_count_words(augur_lda* h, hipStream_t stream, bool beside_theta = fal
     hipLaunchKernelGGL(lda_count_words_prepare_kernel, dim3((unsigned)std::max<int64_t>(1, (cells + 255) / 256)),
                        dim3(256), 0, stream, h->multi_words, h->n_multi, h->n_wk, h->ldk, h->cw_next);
   }
+  if (!h->count_loops) {
+    // a wave per slice of at least 64 tokens, four shorter slices per wave
+    const int big_blocks = (h->n_big + 3) / 4;
+    const dim3 qgrid((unsigned)(big_blocks + (h->n_items - h->n_big + 15) / 16));
+    if (h->zb_current)
+      hipLaunchKernelGGL(lda_count_words_mixed_kernel<uint8_t>, qgrid, dim3(256), 4 * shm, stream, h->zb,
+                         h->perm, h->slice_desc, h->n_wk, h->ldk, h->n_big, h->n_items, big_blocks);
+    else
+      hipLaunchKernelGGL(lda_count_words_mixed_kernel<int32_t>, qgrid, dim3(256), 4 * shm, stream, h->z,
+                         h->perm, h->slice_desc, h->n_wk, h->ldk, h->n_big, h->n_items, big_blocks);
+    AUGUR_HIP_TRY(hipGetLastError());
+    return AUGUR_OK;
+  }
   const int cw_blocks = h->count_loops ? kCountBlocks : (h->n_items + 3) / 4;
   uint32_t* next = h->count_loops ? h->cw_next : nullptr;
   if (h->zb_current)
@@ -385,8 +399,9 @@ int build_word_major(augur_lda* h) {
       by_freq.resize(keep);
       h->hot_host = std::move(by_freq);
     }
-    auto rare_pieces = [](int f) {
-      return std::max(1, std::min(kMaxSlicesPerWord, (f + kSliceTokens - 1) / kSliceTokens));
+    int slice_tokens = kSliceTokens;
+    auto rare_pieces = [&slice_tokens](int f) {
+      return std::max(1, std::min(kMaxSlicesPerWord, (f + slice_tokens - 1) / slice_tokens));
     };
     int64_t n_basic = 0;
     for (int v = 0; v < V; ++v) n_basic += rare_pieces(off[v + 1] - off[v]);
@@ -397,6 +412,9 @@ int build_word_major(augur_lda* h) {
     // the positions, and lets the theta step finish sooner (large workload, sweep: 4.73 ms at
     // 256 workgroups, 4.52 at 512, 4.64 at 768; one wave per item is slower still).
     const bool looping = n_basic > 4 * kCountBlocks && N / n_basic >= 256;
+    // a wave per slice: shorter slices, so that the most frequent words do not end the kernel alone
+    // (3M tokens: word table 0.034 ms with slices of 4096 tokens, 0.030 with 1024 to 2048, 0.036 with 256)
+    if (!looping) slice_tokens = kSliceTokens / 2;
     // parts of the positions for the frequent words: about 1 MiB of the gathered array each (a
     // quarter of an XCD's L2); none if the whole array is a few MiB anyway
     const int64_t gathered_bytes = N * (h->ldk <= 256 ? 1 : 4);
@@ -484,6 +502,11 @@ int build_word_major(augur_lda* h) {
     for (int v = 0; v < V; ++v)
       if (pieces_of[(size_t)v] > 1) multi.push_back(v);
     for (auto& d : desc) d.w = pieces_of[(size_t)d.z] > 1 ? 1 : 0;
+    if (!looping) {
+      // every item is one slice: the long ones first (a wave each), then the short ones (four a wave)
+      std::stable_partition(desc.begin(), desc.end(), [](const int4& d) { return d.y - d.x >= 64; });
+      h->n_big = (int)std::count_if(desc.begin(), desc.end(), [](const int4& d) { return d.y - d.x >= 64; });
+    }
     h->n_items = (int)item_off.size() - 1;
     h->count_loops = looping;
     h->n_multi = (int)multi.size();

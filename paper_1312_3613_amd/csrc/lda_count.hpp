@@ -110,6 +110,71 @@ __global__ __launch_bounds__(256) void lda_count_words_kernel(
   }
 }
 
+// The same for small corpora, where most slices have a few dozen tokens (3M tokens over 50,000 words:
+// 60 on average, most words far fewer) and a wave per slice spends its time waiting on chains of
+// dependent loads (perm, then z, then the LDS histogram, then the row).  Used when the kernel does
+// not loop; every item is then a single slice, and the plan lists the slices of at least 64 tokens
+// first.  Those keep a wave each (workgroups [0, big_blocks)).  The shorter ones are taken four
+// at a time by a wave, 16 lanes a slice: four times the loads in flight and a quarter of the
+// instructions per slice for clearing and writing out rows (16 bytes a lane).
+template <typename ZT>
+__global__ __launch_bounds__(256) void lda_count_words_mixed_kernel(
+    const ZT* __restrict__ z, const int32_t* __restrict__ perm, const int4* __restrict__ slice_desc,
+    int32_t* __restrict__ n_wk, int ldk, int n_big, int n_slices, int big_blocks) {
+  extern __shared__ __align__(16) int32_t hist_all[];  // [4 waves][4 quarters][ldk]; a whole wave uses its first
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if ((int)blockIdx.x < big_blocks) {
+    const int i = blockIdx.x * 4 + wave;
+    if (i >= n_big) return;
+    int32_t* hist = hist_all + (size_t)(wave * 4) * ldk;
+    const int4 d = slice_desc[i];
+    for (int k = lane; k < ldk; k += 64) hist[k] = 0;
+    wave_lds_fence();
+    const int end = d.y;
+    int j = d.x + lane;
+    for (; j + 192 < end; j += 256) {  // four gathers in flight per lane
+      const int p0 = perm[j], p1 = perm[j + 64], p2 = perm[j + 128], p3 = perm[j + 192];
+      const int z0 = (int)z[p0], z1 = (int)z[p1], z2 = (int)z[p2], z3 = (int)z[p3];
+      atomicAdd(&hist[z0], 1);
+      atomicAdd(&hist[z1], 1);
+      atomicAdd(&hist[z2], 1);
+      atomicAdd(&hist[z3], 1);
+    }
+    for (; j < end; j += 64) atomicAdd(&hist[(int)z[perm[j]]], 1);
+    wave_lds_fence();
+    int32_t* dst = n_wk + (size_t)d.z * ldk;
+    if (d.w == 0) {
+      for (int k = lane; k < ldk; k += 64) dst[k] = hist[k];
+    } else {
+      for (int k = lane; k < ldk; k += 64) {
+        const int32_t c = hist[k];
+        if (c != 0) atomicAdd(&dst[k], c);
+      }
+    }
+    return;
+  }
+  const int l16 = lane & 15, quarter = lane >> 4;
+  const int i = n_big + (((int)blockIdx.x - big_blocks) * 4 + wave) * 4 + quarter;
+  if (i >= n_slices) return;
+  int4* hist4 = reinterpret_cast<int4*>(hist_all + (size_t)(wave * 4 + quarter) * ldk);
+  int32_t* hist = reinterpret_cast<int32_t*>(hist4);
+  const int n4 = ldk >> 2;  // rows are multiples of 16 entries
+  const int4 d = slice_desc[i];
+  for (int k4 = l16; k4 < n4; k4 += 16) hist4[k4] = make_int4(0, 0, 0, 0);
+  wave_lds_fence();
+  for (int j = d.x + l16; j < d.y; j += 16) atomicAdd(&hist[(int)z[perm[j]]], 1);  // fewer than 64 tokens
+  wave_lds_fence();
+  int32_t* dst = n_wk + (size_t)d.z * ldk;
+  if (d.w == 0) {
+    for (int k4 = l16; k4 < n4; k4 += 16) reinterpret_cast<int4*>(dst)[k4] = hist4[k4];
+  } else {
+    for (int k = l16; k < ldk; k += 16) {
+      const int32_t c = hist[k];
+      if (c != 0) atomicAdd(&dst[k], c);
+    }
+  }
+}
+
 // Zeroes the counter of the looping word-table kernel and the rows of the words whose slices
 // add to them (listed in multi_words).
 __global__ __launch_bounds__(256) void lda_count_words_prepare_kernel(
