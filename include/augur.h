@@ -122,7 +122,8 @@ int augur_lda_set_graph(augur_lda* h, int32_t on);
  * words from there; it pays when there are several documents for every wave of
  * the chip.  mode 0 (default): the library chooses by the number of documents;
  * 1: the resident form whenever it is available (K <= 256, at least 8 rows fit);
- * 2: never.  Not to be changed while a sweep is in flight. */
+ * 2: never.  The same switch picks the form of loglik's token kernel, which has
+ * the same two.  Not to be changed while a sweep is in flight. */
 int augur_lda_set_z_cache(augur_lda* h, int32_t mode);
 
 /* Which kernels build the word table n_wk during sweeps and count steps (count_accumulate,
