@@ -636,7 +636,16 @@ __global__ __launch_bounds__(64 * kHotWaves) void lda_sample_z_hot_kernel(
       *reinterpret_cast<float4*>(lds + (size_t)s * kRowLds + 16 * pc) = v;
     }
   }
+  // A workgroup owns a run of consecutive segments; its waves take them one at a time from a
+  // counter in LDS, so that none idles while another still has documents waiting (with fixed
+  // shares of a few documents a wave, as in a corpus of 20,000 documents, the slowest wave
+  // sets the time).  Which wave draws a document does not matter to the result.
+  __shared__ int next_seg;
+  if (threadIdx.x == 0) next_seg = 0;
   __syncthreads();  // the only barrier: every wave passes it before it looks for work
+  const int segs_per_group = (n_segs + (int)gridDim.x - 1) / (int)gridDim.x;
+  const int seg_first = (int)blockIdx.x * segs_per_group;
+  const int seg_end = min(n_segs, seg_first + segs_per_group);
   unsigned char* mine = lds + (size_t)n_hot * kRowLds + (size_t)wave * kWaveBytes;
   uint32_t* strip_r = reinterpret_cast<uint32_t*>(mine);           // Philox word of position p
   uint32_t* strip_w = reinterpret_cast<uint32_t*>(mine + 1024);    // wz of the j-th token in order
@@ -655,7 +664,11 @@ __global__ __launch_bounds__(64 * kHotWaves) void lda_sample_z_hot_kernel(
   L.theta_q = theta_s + 4 * q;
   const unsigned char* cache_q = lds + 16 * q;
 
-  for (int seg = blockIdx.x * kHotWaves + wave; seg < n_segs; seg += gridDim.x * kHotWaves) {
+  for (;;) {
+    int taken = 0;
+    if (lane == 0) taken = atomicAdd(&next_seg, 1);
+    const int seg = seg_first + __builtin_amdgcn_readfirstlane(taken);
+    if (seg >= seg_end) break;
     const Segment sg = segment_of(doc_off, seg_base, D, seg);
     const int d = sg.d;
     wave_lds_fence();  // the previous segment's reads of theta and the histogram are done
