@@ -225,11 +225,25 @@ __device__ __forceinline__ double log_of(double x, const double2* __restrict__ l
   return lt != nullptr ? log_tab(x, lt) : log_pos(x);
 }
 
+// Square root of a positive normal double well inside the exponent range (the Box-Muller radicand
+// -2 ln u lies in (0, 45]): reciprocal square root estimate, one coupled Newton step for the root
+// and half its reciprocal, one correction of the root by its residual.  Within 1 ulp; a third of
+// the instructions of the general routine, which guards ranges that cannot occur here.
+__device__ __forceinline__ double sqrt_pos(double a) {
+  const double y = __builtin_amdgcn_rsq(a);
+  double s = a * y;
+  double h = 0.5 * y;
+  const double r = fma(-h, s, 0.5);
+  s = fma(s, r, s);
+  h = fma(h, r, h);
+  const double d = fma(-s, s, a);
+  return fma(d, h, s);
+}
 __device__ __forceinline__ double normal_from(const U4& b, const double2* __restrict__ lt) {
-  return sqrt(-2.0 * log_of(u32d(b.x), lt)) * cospi_0_2(2.0 * u32d(b.y));
+  return sqrt_pos(-2.0 * log_of(u32d(b.x), lt)) * cospi_0_2(2.0 * u32d(b.y));
 }
 __device__ __forceinline__ double normal_from(const U4& b) {
-  return sqrt(-2.0 * log_pos(u32d(b.x))) * cospi_0_2(2.0 * u32d(b.y));
+  return sqrt_pos(-2.0 * log_pos(u32d(b.x))) * cospi_0_2(2.0 * u32d(b.y));
 }
 
 constexpr int kGammaAttemptCap = 64;
